@@ -1,0 +1,266 @@
+#!/usr/bin/env python3
+"""Benchmark of the Indirect Convolution hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--no-shapes]
+
+A step is one icv_conv2d_nhwc call (the Indirect GEMM, epilogue included) on the headline workload
+(ResNet-style 3x3 bf16 convolution, N=32, 56x56, C=K=64).  As in the paper's protocol (section 3.1,
+"Protocol") the indirection buffer and the packed filter are built once, outside the timed region; the
+indirection build is timed on its own and reported under "setup".  The timed region rotates over enough
+distinct input / output / indirection buffer sets to exceed the 256 MB last-level cache, so every step reads
+its operands from HBM ("cold"); the same-buffers ("warm") figure is reported beside it.
+
+Prints ONE JSON line.  metric = effective TFLOP/s = 2*N*Hout*Wout*K*R*S*C / t.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"bf16": 2500.0, "u8i8": 5000.0, "f32": 157.3}      # TFLOP/s (TOP/s), dense, MI355X public figures
+HBM_PEAK_GBS = 8000.0
+LLC_BYTES = 256 << 20
+
+# HBM traffic of the dominant kernel per launch, bytes, measured with rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None until measured.
+MEASURED_TRAFFIC = {}
+
+
+def flops(s, Hout, Wout, c=None):
+    return 2.0 * s.N * Hout * Wout * s.K * s.R * s.S * (c or s.C)
+
+
+def algorithmic_bytes(s, Hout, Wout):
+    """Bytes one conv launch must move: input + packed filter + output + indirection entries, each once."""
+    esz = {"f32": 4, "bf16": 2, "u8i8": 1}[s.dtype]
+    M, T = s.N * Hout * Wout, s.R * s.S
+    return s.N * s.Hin * s.Win * s.C * esz + s.K * T * s.C * esz + M * s.K * 4 + M * T * 4
+
+
+class Problem:
+    """Device buffers of one shape, `sets` rotating copies of everything a launch touches."""
+
+    def __init__(self, icv, torch, s, sets=1, plan=0):
+        from paper_1907_02129_amd.workloads import make_tensors
+        self.icv, self.torch, self.s = icv, torch, s
+        x, w = make_tensors(s)
+        self.x_host, self.w_host = x, w
+        self.wd = icv.to_device(w)
+        self.bufs = [icv.prepare(s, self.wd, plan=plan) for _ in range(sets)]
+        x0 = icv.to_device(x)
+        self.xs = [x0] + [x0.clone() for _ in range(sets - 1)]
+        self.p = self.bufs[0].p
+        self.Hout, self.Wout = self.bufs[0].Hout, self.bufs[0].Wout
+        self.i = 0
+
+    def step(self):
+        b, x = self.bufs[self.i], self.xs[self.i]
+        self.i = (self.i + 1) % len(self.bufs)
+        self.icv.conv2d_nhwc(b.p, x, b.packed, b.indirection, b.zero_row, b.output)
+
+    def time_steps(self, steps, warmup):
+        """ms per step, HIP events on the launch stream around `steps` back-to-back launches."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            self.step()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    def time_quantiles(self, repeats=25, inner=20, warmup=5):
+        """Median and 20 % / 80 % quantiles over `repeats` timings (the paper's protocol), ms per launch."""
+        for _ in range(warmup):
+            self.step()
+        ts = [self.time_steps(inner, 0) for _ in range(repeats)]
+        return float(np.median(ts)), float(np.quantile(ts, 0.2)), float(np.quantile(ts, 0.8))
+
+    def time_setup(self, reps=20):
+        torch, b = self.torch, self.bufs[0]
+        self.icv.setup_indirection(b.p, b.indirection)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            bb = self.bufs[i % len(self.bufs)]
+            self.icv.setup_indirection(bb.p, bb.indirection)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def time_ablation(self, steps=20, warmup=3):
+        """im2col + GEMM through the same MFMA core: (total ms, im2col ms, gemm ms)."""
+        torch, icv, b, x = self.torch, self.icv, self.bufs[0], self.xs[0]
+        ws = torch.empty(icv.im2col_bytes(b.p), dtype=torch.uint8, device="cuda:0")
+        out = torch.empty_like(b.output)
+
+        def timed(fn):
+            for _ in range(warmup):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / steps
+
+        t_all = timed(lambda: icv.conv2d_nhwc_im2col(b.p, x, b.packed, ws, out))
+        t_i2c = timed(lambda: icv.im2col(b.p, x, ws))
+        t_gemm = timed(lambda: icv.gemm_nhwc(b.p, ws, b.packed, out))
+        return t_all, t_i2c, t_gemm
+
+
+def sets_for_cold(s, Hout, Wout):
+    per_set = algorithmic_bytes(s, Hout, Wout)
+    return min(32, max(2, int(np.ceil(2.5 * LLC_BYTES / per_set))))
+
+
+def cpu_baseline(s, x, w):
+    """The oracle as it stands, timed on this host's cores on the headline workload (one full pass)."""
+    import oracle
+    t0 = time.perf_counter()
+    if s.dtype == "u8i8":
+        oracle.conv2d_u8i8(s, x, w, s.zero_point)
+    else:
+        oracle.conv2d(s, x, w)
+    dt = time.perf_counter() - t0
+    Hout, Wout = oracle.out_extent(s)
+    return {"value": flops(s, Hout, Wout) / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(dt, 3),
+            "sample": f"one full pass of {s.name} (fp64 7-loop direct convolution, OpenMP over n,oy)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--no-shapes", action="store_true", help="skip the per-shape table and the ablation")
+    ap.add_argument("--workload", default=None, help="time another shape as the headline (tuning)")
+    ap.add_argument("--plan", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the path shards over the batch with no "
+              "exchange step; multi-GPU figures are not produced). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1907_02129_amd import binding as icv
+    from paper_1907_02129_amd.workloads import CONFIGS, HEADLINE
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    icv.load_library()
+    torch.cuda.set_device(0)
+
+    name = args.workload or HEADLINE
+    s = CONFIGS[name]
+    p0 = icv.make_params(s, plan=args.plan)
+    Hout, Wout = icv.output_size(p0)
+    prob = Problem(icv, torch, s, sets=sets_for_cold(s, Hout, Wout), plan=args.plan)
+    fl = flops(s, Hout, Wout, getattr(s, "c_logical", 0) or None)
+
+    # ---- the timed region: exactly --steps launches between two synchronisations
+    for _ in range(args.warmup):
+        prob.step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        prob.step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms = e0.elapsed_time(e1) / args.steps          # average launch duration of the conv kernel
+    value = fl / (ms * 1e-3) / 1e12
+
+    warm = Problem(icv, torch, s, sets=1, plan=args.plan)
+    ms_warm = warm.time_steps(args.steps, args.warmup)
+    med, q20, q80 = prob.time_quantiles()
+    t_setup = prob.time_setup()
+    ind_bytes = prob.bufs[0].M * s.R * s.S * 4
+
+    abytes = algorithmic_bytes(s, Hout, Wout)
+    hbm_time = abytes / (HBM_PEAK_GBS * 1e9)
+    mfma_time = fl / (PEAK[s.dtype] * 1e12)
+    if hbm_time >= mfma_time:
+        roof = {"bound": "hbm", "achieved": abytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": value, "peak": PEAK[s.dtype], "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = MEASURED_TRAFFIC.get(name)
+    roof["kernel"] = icv.plan_name(prob.p)
+    roof["algorithmic_bytes"] = abytes
+    roof["mfma_frac"] = value / PEAK[s.dtype]
+
+    out = {
+        "metric": "effective TFLOP/s (2*N*Hout*Wout*K*R*S*C / t)", "value": value, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"bf16": "bf16", "u8i8": "u8", "f32": "f32"}[s.dtype], "data": "synthetic",
+        "config": {"workload": f"{name}: N={s.N} {s.Hin}x{s.Win} C={s.C} K={s.K} {s.R}x{s.S} "
+                               f"stride {s.SY} dil {s.DY} pad {s.PT},{s.PL},{s.PB},{s.PR} {s.dtype}",
+                   "cache_regime": f"cold: rotation over {len(prob.bufs)} buffer sets",
+                   "kernel": icv.plan_name(prob.p)},
+        "roofline": roof,
+        "frac_of_mfma_peak": value / PEAK[s.dtype],
+        "wall_ms_per_step": wall_ms,
+        "warm": {"ms_per_step": ms_warm, "value": fl / (ms_warm * 1e-3) / 1e12},
+        "quantiles_ms": {"median": med, "q20": q20, "q80": q80, "repeats": 25, "launches_per_repeat": 20},
+        "setup": {"indirection_build_ms": t_setup, "indirection_bytes": ind_bytes,
+                  "indirection_GBps": ind_bytes / (t_setup * 1e-3) / 1e9,
+                  "frac_of_hbm_peak": ind_bytes / (t_setup * 1e-3) / 1e9 / HBM_PEAK_GBS},
+    }
+
+    if not args.no_shapes:
+        shapes = {}
+        for nm, sh in CONFIGS.items():
+            pp = icv.make_params(sh)
+            ho, wo = icv.output_size(pp)
+            pr = Problem(icv, torch, sh, sets=min(sets_for_cold(sh, ho, wo), 12))
+            m, a, b = pr.time_quantiles(repeats=15, inner=10, warmup=3)
+            f = flops(sh, ho, wo, getattr(sh, "c_logical", 0) or None)
+            ab = algorithmic_bytes(sh, ho, wo)
+            row = {"kernel": icv.plan_name(pp), "ms": m, "q20": a, "q80": b, "TFLOPs": f / (m * 1e-3) / 1e12,
+                   "frac_of_peak": f / (m * 1e-3) / 1e12 / PEAK[sh.dtype],
+                   "GBps_algorithmic": ab / (m * 1e-3) / 1e9,
+                   "frac_of_hbm_peak": ab / (m * 1e-3) / 1e9 / HBM_PEAK_GBS}
+            ts = pr.time_setup(reps=10)
+            ib = pr.bufs[0].M * sh.R * sh.S * 4
+            row["indirection_build_ms"] = ts
+            row["indirection_GBps"] = ib / (ts * 1e-3) / 1e9
+            if sh.dtype != "f32":
+                ta, ti, tg = pr.time_ablation()
+                row["im2col_gemm_ms"] = ta
+                row["im2col_ms"] = ti
+                row["gemm_only_ms"] = tg
+                row["speedup_vs_im2col_gemm"] = ta / m
+            shapes[nm] = row
+            del pr
+            torch.cuda.empty_cache()
+        out["shapes"] = shapes
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(s, prob.x_host, prob.w_host)
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

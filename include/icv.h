@@ -1,0 +1,145 @@
+/*
+ * icv -- Indirect Convolution for AMD MI355X (gfx950).  C ABI of libicv.so.
+ *
+ * The library implements the hot path of the Indirect Convolution algorithm
+ * (M. Dukhan, arXiv 1907.02129): an indirection buffer that names, for every
+ * output pixel and kernel element, the input pixel row to read (section 2.3),
+ * and an Indirect GEMM that accumulates output tiles over R*S*C by gathering
+ * rows of A through that buffer (section 2.2, Listing 3), so that no im2col
+ * matrix is ever written.
+ *
+ * Conventions that hold for every entry point
+ *  - Tensors: input NHWC, output NHWC, filter [K][R][S][C] (Listing 1).
+ *  - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *    allocates no memory, keeps no state between calls and is re-entrant.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls enqueue work on it and return without synchronising.
+ *  - Return value: ICV_OK or a negative icv_status; nothing aborts or throws.
+ *    Invalid arguments are detected on the host before anything is launched.
+ *  - Base pointers must be 16-byte aligned and pixel strides must make every
+ *    pixel row start 16-byte aligned (bf16 / u8i8 tensor-core paths).
+ */
+#ifndef ICV_H
+#define ICV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* exported from libicv.so (everything else in the library has hidden visibility) */
+#define ICV_API __attribute__((visibility("default")))
+
+typedef enum {
+    ICV_OK = 0,
+    ICV_ERR_INVALID_ARG = -1, /* null pointer, non-positive extent, misalignment, index overflow */
+    ICV_ERR_UNSUPPORTED = -2, /* a valid problem this build has no kernel for */
+    ICV_ERR_HIP = -3          /* a HIP call failed; see icv_last_hip_error() */
+} icv_status;
+
+/* Element types: input/filter -> accumulator/output. */
+typedef enum {
+    ICV_F32 = 0,  /* float  x float    -> float  (vector ALU path)                       */
+    ICV_BF16 = 1, /* bf16   x bf16     -> float  (MFMA, fp32 accumulate)                 */
+    ICV_U8I8 = 2  /* uint8  x int8     -> int32  (MFMA, out = sum (x - zero_point) * w)  */
+} icv_dtype;
+
+/*
+ * Problem statement, in the symbols of Listing 1 and section 2.3.
+ * Output extent (the paper leaves it undefined; the customary floor formula):
+ *   Hout = floor((Hin + PT + PB - DY*(R-1) - 1) / SY) + 1, Wout alike with PL, PR, DX, S, SX.
+ * A tap (ky,kx) of output pixel (oy,ox) reads input pixel
+ *   iy = oy*SY + ky*DY - PT,  ix = ox*SX + kx*DX - PL
+ * (the listing prints PL in the y formula and PT in the x formula; top pads y and
+ * left pads x here), or the zero row when that lies outside the input.
+ */
+typedef struct icv_conv_params {
+    int32_t N, Hin, Win, C, K, R, S;
+    int32_t SY, SX, DY, DX;
+    int32_t PT, PL, PB, PR;    /* implicit zero padding: top, left, bottom, right */
+    int32_t in_pixel_stride;   /* elements between input pixels;  0 means C ("rows can optionally be strided") */
+    int32_t out_pixel_stride;  /* elements between output pixels; 0 means K (ldc of Listing 3)                 */
+    int32_t dtype;             /* icv_dtype */
+    int32_t input_zero_point;  /* ICV_U8I8 only: the value the zero row holds, 0..255 */
+    int32_t plan;              /* 0: the library picks the tile shape; >0: force variant (tuning sweeps) */
+} icv_conv_params;
+
+/* Hout, Wout by the formula above.  ICV_ERR_INVALID_ARG when the parameters are not a valid problem. */
+ICV_API int icv_output_size(const icv_conv_params* p, int32_t* Hout, int32_t* Wout);
+
+/*
+ * Buffer sizes in bytes (0 when the parameters are invalid).
+ *  indirection  : int32 entries, M rounded up to whole row tiles, times R*S (independent of C, section 1.1)
+ *  packed filter: the [K][R][S][C] filter re-laid as the tiles the GEMM kernel reads, K padded to the tile
+ *  zero row     : C elements (section 2.3's explicit zero vector), rounded up to 16 bytes
+ *  im2col       : the [M][R*S*C] patch matrix of the ablation path
+ */
+ICV_API size_t icv_indirection_bytes(const icv_conv_params* p);
+ICV_API size_t icv_packed_filter_bytes(const icv_conv_params* p);
+ICV_API size_t icv_zero_row_bytes(const icv_conv_params* p);
+ICV_API size_t icv_im2col_bytes(const icv_conv_params* p);
+
+/*
+ * Where the entry of output pixel m = (n*Hout + oy)*Wout + ox and kernel element tap = ky*S + kx sits in
+ * the indirection buffer (index in int32 units).  The physical order is [row tile][tap][row in tile], the
+ * order in which Listing 3 consumes pointers (*ppa++: all rows of the tile for one tap, then the next tap).
+ * Rows past M in the last tile hold -1.  Returns -1 on invalid arguments.
+ */
+ICV_API int64_t icv_indirection_index(const icv_conv_params* p, int64_t m, int32_t tap);
+
+/* Fill the explicit zero vector of section 2.3: zeros, or input_zero_point bytes for ICV_U8I8. */
+ICV_API int icv_init_zero_row(const icv_conv_params* p, void* zero_row, void* stream);
+
+/*
+ * Repack the filter once, off the timed path (section 3.1, "Implementation": matrix B is repacked into a
+ * contiguous region because weights never change at inference time).
+ *   filter_krsc: [K][R][S][C] device, packed: icv_packed_filter_bytes() device.
+ */
+ICV_API int icv_pack_filter(const icv_conv_params* p, const void* filter_krsc, void* packed, void* stream);
+
+/*
+ * Build the indirection buffer (section 2.3).  Entry = index of the input pixel (n*Hin + iy)*Win + ix, so
+ * that the row starts at input + entry * in_pixel_stride elements, or -1 for "the zero row".  Storing an
+ * index instead of the paper's raw pointer keeps the buffer valid when the input or zero-row pointers
+ * change (the paper's fourth invalidation rule then never applies); it must be rebuilt only when the shape,
+ * stride, dilation, padding or batch size change.  Requires N*Hin*Win < 2^31.
+ *   indirection: icv_indirection_bytes() device.
+ */
+ICV_API int icv_setup_indirection(const icv_conv_params* p, void* indirection, void* stream);
+
+/*
+ * The Indirect GEMM (section 2.2): output = conv(input, filter) with rows of A gathered through the
+ * indirection buffer; entries < 0 read `zero_row`.  alpha = 1, beta = 0: the output is overwritten.
+ *   input        : [N][Hin][Win] pixels of in_pixel_stride elements (first C used)
+ *   packed_filter: from icv_pack_filter with the same params
+ *   indirection  : from icv_setup_indirection with the same params
+ *   zero_row     : from icv_init_zero_row
+ *   output       : [N][Hout][Wout] pixels of out_pixel_stride elements (first K written), float or int32
+ */
+ICV_API int icv_conv2d_nhwc(const icv_conv_params* p, const void* input, const void* packed_filter,
+                    const void* indirection, const void* zero_row, void* output, void* stream);
+
+/*
+ * Ablation, not the method: the GEMM-based algorithm the paper compares against (section 1, "GEMM-based
+ * algorithms"): write the [M][R*S*C] patch matrix (im2col), then a plain constant-stride GEMM with the same
+ * tensor-core inner loop.  icv_im2col and icv_gemm_nhwc are its two halves; icv_conv2d_nhwc_im2col runs both.
+ */
+ICV_API int icv_im2col(const icv_conv_params* p, const void* input, void* im2col_ws, void* stream);
+ICV_API int icv_gemm_nhwc(const icv_conv_params* p, const void* im2col_ws, const void* packed_filter, void* output,
+                  void* stream);
+ICV_API int icv_conv2d_nhwc_im2col(const icv_conv_params* p, const void* input, const void* packed_filter,
+                           void* im2col_ws, void* output, void* stream);
+
+/* Name of the kernel variant icv_conv2d_nhwc would launch for p (static string; "" when invalid). */
+ICV_API const char* icv_plan_name(const icv_conv_params* p);
+
+ICV_API const char* icv_status_string(int status);
+/* hipError_t of the last failed HIP call on this thread (0 when none). */
+ICV_API int icv_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ICV_H */

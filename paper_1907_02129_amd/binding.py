@@ -1,0 +1,243 @@
+"""ctypes binding of libicv.so: the same names as include/icv.h, argument marshalling only.
+
+torch is used for device memory and streams; every step of the path runs in the
+library's kernels.  There is no CPU fallback: when the library is missing or a
+call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libicv.so")
+
+ICV_OK = 0
+ICV_ERR_INVALID_ARG = -1
+ICV_ERR_UNSUPPORTED = -2
+ICV_ERR_HIP = -3
+ICV_F32, ICV_BF16, ICV_U8I8 = 0, 1, 2
+DTYPES = {"f32": ICV_F32, "bf16": ICV_BF16, "u8i8": ICV_U8I8}
+
+# every symbol include/icv.h declares
+EXPORTS = (
+    "icv_output_size", "icv_indirection_bytes", "icv_packed_filter_bytes", "icv_zero_row_bytes",
+    "icv_im2col_bytes", "icv_indirection_index", "icv_init_zero_row", "icv_pack_filter",
+    "icv_setup_indirection", "icv_conv2d_nhwc", "icv_im2col", "icv_gemm_nhwc", "icv_conv2d_nhwc_im2col",
+    "icv_plan_name", "icv_status_string", "icv_last_hip_error",
+)
+
+
+class IcvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = f"{where}: {status_string(status)} ({status})"
+        if status == ICV_ERR_HIP:
+            msg += f", hipError {_lib.icv_last_hip_error()}"
+        super().__init__(msg)
+
+
+class icv_conv_params(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "N", "Hin", "Win", "C", "K", "R", "S", "SY", "SX", "DY", "DX", "PT", "PL", "PB", "PR",
+        "in_pixel_stride", "out_pixel_stride", "dtype", "input_zero_point", "plan")]
+
+
+_lib = None
+
+
+def load_library(path: str | None = None):
+    """Load libicv.so (built in-tree by `python -m paper_1907_02129_amd.build`)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} not found: build it with `python -m paper_1907_02129_amd.build`")
+    lib = ctypes.CDLL(path)
+    P = ctypes.POINTER(icv_conv_params)
+    vp, i32p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32)
+    sig = {
+        "icv_output_size": (ctypes.c_int, [P, i32p, i32p]),
+        "icv_indirection_bytes": (ctypes.c_size_t, [P]),
+        "icv_packed_filter_bytes": (ctypes.c_size_t, [P]),
+        "icv_zero_row_bytes": (ctypes.c_size_t, [P]),
+        "icv_im2col_bytes": (ctypes.c_size_t, [P]),
+        "icv_indirection_index": (ctypes.c_int64, [P, ctypes.c_int64, ctypes.c_int32]),
+        "icv_init_zero_row": (ctypes.c_int, [P, vp, vp]),
+        "icv_pack_filter": (ctypes.c_int, [P, vp, vp, vp]),
+        "icv_setup_indirection": (ctypes.c_int, [P, vp, vp]),
+        "icv_conv2d_nhwc": (ctypes.c_int, [P, vp, vp, vp, vp, vp, vp]),
+        "icv_im2col": (ctypes.c_int, [P, vp, vp, vp]),
+        "icv_gemm_nhwc": (ctypes.c_int, [P, vp, vp, vp, vp]),
+        "icv_conv2d_nhwc_im2col": (ctypes.c_int, [P, vp, vp, vp, vp, vp]),
+        "icv_plan_name": (ctypes.c_char_p, [P]),
+        "icv_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+        "icv_last_hip_error": (ctypes.c_int, []),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+def make_params(shape, plan: int = 0, in_pixel_stride: int = 0, out_pixel_stride: int = 0) -> icv_conv_params:
+    """icv_conv_params from a workloads.ConvShape-like object."""
+    return icv_conv_params(
+        shape.N, shape.Hin, shape.Win, shape.C, shape.K, shape.R, shape.S, shape.SY, shape.SX, shape.DY,
+        shape.DX, shape.PT, shape.PL, shape.PB, shape.PR, in_pixel_stride, out_pixel_stride,
+        DTYPES[shape.dtype], getattr(shape, "zero_point", 0), plan)
+
+
+def _check(status: int, where: str):
+    if status != ICV_OK:
+        raise IcvError(status, where)
+
+
+def _ptr(t) -> ctypes.c_void_p:
+    if t is None:
+        return ctypes.c_void_p(0)
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    if not t.is_cuda:
+        raise ValueError("icv takes device tensors")
+    if not t.is_contiguous():
+        raise ValueError("icv takes contiguous tensors")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None) -> ctypes.c_void_p:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+# ---------------------------------------------------------------- thin wrappers, same names as the header
+def status_string(status: int) -> str:
+    return load_library().icv_status_string(status).decode()
+
+
+def plan_name(p: icv_conv_params) -> str:
+    return load_library().icv_plan_name(ctypes.byref(p)).decode()
+
+
+def output_size(p: icv_conv_params):
+    h, w = ctypes.c_int32(), ctypes.c_int32()
+    _check(load_library().icv_output_size(ctypes.byref(p), ctypes.byref(h), ctypes.byref(w)), "icv_output_size")
+    return h.value, w.value
+
+
+def indirection_bytes(p) -> int:
+    return load_library().icv_indirection_bytes(ctypes.byref(p))
+
+
+def packed_filter_bytes(p) -> int:
+    return load_library().icv_packed_filter_bytes(ctypes.byref(p))
+
+
+def zero_row_bytes(p) -> int:
+    return load_library().icv_zero_row_bytes(ctypes.byref(p))
+
+
+def im2col_bytes(p) -> int:
+    return load_library().icv_im2col_bytes(ctypes.byref(p))
+
+
+def indirection_index(p, m: int, tap: int) -> int:
+    return load_library().icv_indirection_index(ctypes.byref(p), m, tap)
+
+
+def init_zero_row(p, zero_row, stream=None):
+    _check(load_library().icv_init_zero_row(ctypes.byref(p), _ptr(zero_row), _stream(stream)), "icv_init_zero_row")
+
+
+def pack_filter(p, filter_krsc, packed, stream=None):
+    _check(load_library().icv_pack_filter(ctypes.byref(p), _ptr(filter_krsc), _ptr(packed), _stream(stream)),
+           "icv_pack_filter")
+
+
+def setup_indirection(p, indirection, stream=None):
+    _check(load_library().icv_setup_indirection(ctypes.byref(p), _ptr(indirection), _stream(stream)),
+           "icv_setup_indirection")
+
+
+def conv2d_nhwc(p, input, packed_filter, indirection, zero_row, output, stream=None):
+    _check(load_library().icv_conv2d_nhwc(ctypes.byref(p), _ptr(input), _ptr(packed_filter), _ptr(indirection),
+                                          _ptr(zero_row), _ptr(output), _stream(stream)), "icv_conv2d_nhwc")
+
+
+def im2col(p, input, ws, stream=None):
+    _check(load_library().icv_im2col(ctypes.byref(p), _ptr(input), _ptr(ws), _stream(stream)), "icv_im2col")
+
+
+def gemm_nhwc(p, ws, packed_filter, output, stream=None):
+    _check(load_library().icv_gemm_nhwc(ctypes.byref(p), _ptr(ws), _ptr(packed_filter), _ptr(output),
+                                        _stream(stream)), "icv_gemm_nhwc")
+
+
+def conv2d_nhwc_im2col(p, input, packed_filter, ws, output, stream=None):
+    _check(load_library().icv_conv2d_nhwc_im2col(ctypes.byref(p), _ptr(input), _ptr(packed_filter), _ptr(ws),
+                                                 _ptr(output), _stream(stream)), "icv_conv2d_nhwc_im2col")
+
+
+# ---------------------------------------------------------------- convenience: buffers for one problem
+def to_device(a: np.ndarray, device="cuda:0") -> torch.Tensor:
+    """numpy -> device tensor; uint16 arrays are bfloat16 bit patterns."""
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)
+
+
+@dataclass
+class ConvBuffers:
+    """Device buffers of one convolution problem (allocated through torch, filled by the library)."""
+    p: icv_conv_params
+    Hout: int
+    Wout: int
+    zero_row: torch.Tensor
+    packed: torch.Tensor
+    indirection: torch.Tensor
+    output: torch.Tensor
+
+    @property
+    def M(self) -> int:
+        return self.p.N * self.Hout * self.Wout
+
+
+def prepare(shape, filter_dev: torch.Tensor, plan: int = 0, device="cuda:0", in_pixel_stride: int = 0,
+            out_pixel_stride: int = 0) -> ConvBuffers:
+    """Set-up phase: zero row, packed filter, indirection buffer, output tensor."""
+    p = make_params(shape, plan, in_pixel_stride, out_pixel_stride)
+    Hout, Wout = output_size(p)
+    zero_row = torch.empty(zero_row_bytes(p), dtype=torch.uint8, device=device)
+    packed = torch.empty(packed_filter_bytes(p), dtype=torch.uint8, device=device)
+    ind = torch.empty(indirection_bytes(p) // 4, dtype=torch.int32, device=device)
+    out_dtype = torch.int32 if shape.dtype == "u8i8" else torch.float32
+    ostride = out_pixel_stride or shape.K
+    out = torch.empty((shape.N, Hout, Wout, ostride), dtype=out_dtype, device=device)
+    init_zero_row(p, zero_row)
+    pack_filter(p, filter_dev, packed)
+    setup_indirection(p, ind)
+    return ConvBuffers(p, Hout, Wout, zero_row, packed, ind, out)
+
+
+def run(buf: ConvBuffers, input_dev: torch.Tensor) -> torch.Tensor:
+    conv2d_nhwc(buf.p, input_dev, buf.packed, buf.indirection, buf.zero_row, buf.output)
+    return buf.output
+
+
+def logical_indirection(buf: ConvBuffers) -> np.ndarray:
+    """The buffer re-ordered to [M][R*S] through icv_indirection_index (host side, for tests)."""
+    p = buf.p
+    T = p.R * p.S
+    phys = buf.indirection.cpu().numpy()
+    # the layout is [tile][tap][MR]; recover MR from the index function instead of assuming it
+    mr = indirection_index(p, 0, 1) if T > 1 else len(phys)
+    tiles = len(phys) // (mr * T)
+    assert indirection_index(p, mr, 0) in (-1, mr * T) and indirection_index(p, 1, 0) == 1
+    logical = phys.reshape(tiles, T, mr).transpose(0, 2, 1).reshape(tiles * mr, T)
+    return logical[:buf.M], logical[buf.M:]

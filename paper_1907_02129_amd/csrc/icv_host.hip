@@ -1,0 +1,260 @@
+// Host side of libicv.so: argument validation, geometry / plan selection and the C entry points.
+#include "icv_internal.h"
+
+namespace icv {
+
+static thread_local int g_last_hip_error = 0;
+void set_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+
+// Tile variants of the tensor-core kernel: workgroup tile MR x NR, split over a WM x WN grid of
+// wavefronts.  Index + 1 is what icv_conv_params::plan selects.
+const TileVariant kTileVariants[] = {
+    {128, 64, 2, 2, "128x64_w2x2"},
+    {128, 128, 2, 2, "128x128_w2x2"},
+    {128, 64, 4, 1, "128x64_w4x1"},
+    {256, 64, 4, 1, "256x64_w4x1"},
+    {256, 128, 2, 2, "256x128_w2x2"},
+    {64, 64, 2, 2, "64x64_w2x2"},
+};
+const int kNumTileVariants = (int)(sizeof(kTileVariants) / sizeof(kTileVariants[0]));
+
+static int64_t out_extent(int64_t in, int64_t lo, int64_t hi, int64_t dil, int64_t k, int64_t stride)
+{
+    const int64_t span = in + lo + hi - dil * (k - 1) - 1;
+    return span < 0 ? 0 : span / stride + 1;
+}
+
+static const char* plan_names[3][8] = {
+    {"generic_f32"},
+    {"generic_bf16", "mfma_bf16_128x64_w2x2", "mfma_bf16_128x128_w2x2", "mfma_bf16_128x64_w4x1",
+     "mfma_bf16_256x64_w4x1", "mfma_bf16_256x128_w2x2", "mfma_bf16_64x64_w2x2"},
+    {"generic_u8i8", "mfma_i8_128x64_w2x2", "mfma_i8_128x128_w2x2", "mfma_i8_128x64_w4x1",
+     "mfma_i8_256x64_w4x1", "mfma_i8_256x128_w2x2", "mfma_i8_64x64_w2x2"},
+};
+
+int make_geometry(const icv_conv_params* p, Geometry* g)
+{
+    if (!p || !g) return ICV_ERR_INVALID_ARG;
+    if (p->N < 1 || p->Hin < 1 || p->Win < 1 || p->C < 1 || p->K < 1 || p->R < 1 || p->S < 1) return ICV_ERR_INVALID_ARG;
+    if (p->SY < 1 || p->SX < 1 || p->DY < 1 || p->DX < 1) return ICV_ERR_INVALID_ARG;
+    if (p->PT < 0 || p->PL < 0 || p->PB < 0 || p->PR < 0) return ICV_ERR_INVALID_ARG;
+    if (p->dtype != ICV_F32 && p->dtype != ICV_BF16 && p->dtype != ICV_U8I8) return ICV_ERR_INVALID_ARG;
+    if (p->in_pixel_stride < 0 || p->out_pixel_stride < 0) return ICV_ERR_INVALID_ARG;
+    if (p->in_pixel_stride != 0 && p->in_pixel_stride < p->C) return ICV_ERR_INVALID_ARG;
+    if (p->out_pixel_stride != 0 && p->out_pixel_stride < p->K) return ICV_ERR_INVALID_ARG;
+    if (p->dtype == ICV_U8I8 && (p->input_zero_point < 0 || p->input_zero_point > 255)) return ICV_ERR_INVALID_ARG;
+    if (p->plan < 0 || p->plan > kNumTileVariants + 1) return ICV_ERR_INVALID_ARG;
+
+    const int64_t Hout = out_extent(p->Hin, p->PT, p->PB, p->DY, p->R, p->SY);
+    const int64_t Wout = out_extent(p->Win, p->PL, p->PR, p->DX, p->S, p->SX);
+    if (Hout < 1 || Wout < 1) return ICV_ERR_INVALID_ARG;
+    // entries are int32 pixel indices; sizes below stay far from int64 limits once these hold
+    if ((int64_t)p->N * p->Hin * p->Win >= (1ll << 31)) return ICV_ERR_INVALID_ARG;
+    const int64_t M = (int64_t)p->N * Hout * Wout;
+    const int64_t T = (int64_t)p->R * p->S;
+    if (M >= (1ll << 31) || T > 4096 || M * T >= (1ll << 40)) return ICV_ERR_INVALID_ARG;
+    if ((int64_t)T * p->C >= (1ll << 31)) return ICV_ERR_INVALID_ARG;
+
+    g->Hout = (int32_t)Hout;
+    g->Wout = (int32_t)Wout;
+    g->M = M;
+    g->T = (int32_t)T;
+    g->elem_bytes = p->dtype == ICV_F32 ? 4 : (p->dtype == ICV_BF16 ? 2 : 1);
+    g->in_stride = p->in_pixel_stride ? p->in_pixel_stride : p->C;
+    g->out_stride = p->out_pixel_stride ? p->out_pixel_stride : p->K;
+
+    // ---- plan: which kernel, which tile
+    const int64_t row_bytes = (int64_t)p->C * g->elem_bytes;        // bytes of one gathered A row
+    const int64_t stride_bytes = (int64_t)g->in_stride * g->elem_bytes;
+    bool mfma_ok = p->dtype != ICV_F32 && row_bytes % 64 == 0 && stride_bytes % 16 == 0;
+    if (p->dtype == ICV_U8I8 && p->input_zero_point != 128) mfma_ok = false;   // x ^ 0x80 == x - 128 only
+    if (p->plan == 1) mfma_ok = false;                                          // forced vector-ALU kernel
+    int variant = -1;
+    if (mfma_ok) {
+        if (p->plan >= 2) {
+            variant = p->plan - 2;
+        } else {
+            variant = p->K <= 64 ? 0 : 1;
+        }
+        // the workgroup keeps its tile's entries in LDS: MR*T int32
+        if ((int64_t)kTileVariants[variant].MR * T * 4 > 48 * 1024) mfma_ok = false;
+    }
+    if (mfma_ok) {
+        const TileVariant& tv = kTileVariants[variant];
+        g->kind = PLAN_MFMA;
+        g->variant = variant;
+        g->MR = tv.MR;
+        g->NR = tv.NR;
+        g->KCB = row_bytes % 128 == 0 ? 128 : 64;
+        g->stages_per_tap = (int32_t)(row_bytes / g->KCB);
+        g->taps_per_stage = 1;
+        g->n_stages = g->T * g->stages_per_tap;
+        g->name = plan_names[p->dtype][1 + variant];
+    } else {
+        g->kind = PLAN_GENERIC;
+        g->variant = -1;
+        g->MR = 64;
+        g->NR = 64;
+        g->KCB = 0;
+        g->stages_per_tap = 1;
+        g->taps_per_stage = 1;
+        g->n_stages = g->T;
+        g->name = plan_names[p->dtype][0];
+    }
+    g->m_tiles = (M + g->MR - 1) / g->MR;
+    g->n_tiles = (p->K + g->NR - 1) / g->NR;
+    return ICV_OK;
+}
+
+static bool aligned16(const void* ptr) { return ((uintptr_t)ptr & 15u) == 0; }
+
+}  // namespace icv
+
+using namespace icv;
+
+extern "C" {
+
+int icv_output_size(const icv_conv_params* p, int32_t* Hout, int32_t* Wout)
+{
+    Geometry g;
+    const int st = make_geometry(p, &g);
+    if (st != ICV_OK) return st;
+    if (Hout) *Hout = g.Hout;
+    if (Wout) *Wout = g.Wout;
+    return ICV_OK;
+}
+
+size_t icv_indirection_bytes(const icv_conv_params* p)
+{
+    Geometry g;
+    if (make_geometry(p, &g) != ICV_OK) return 0;
+    return (size_t)g.m_tiles * g.MR * g.T * sizeof(int32_t);
+}
+
+size_t icv_packed_filter_bytes(const icv_conv_params* p)
+{
+    Geometry g;
+    if (make_geometry(p, &g) != ICV_OK) return 0;
+    return (size_t)g.n_tiles * g.NR * g.T * p->C * g.elem_bytes;
+}
+
+size_t icv_zero_row_bytes(const icv_conv_params* p)
+{
+    Geometry g;
+    if (make_geometry(p, &g) != ICV_OK) return 0;
+    return (((size_t)p->C * g.elem_bytes) + 15) / 16 * 16;
+}
+
+size_t icv_im2col_bytes(const icv_conv_params* p)
+{
+    Geometry g;
+    if (make_geometry(p, &g) != ICV_OK) return 0;
+    // rows padded to whole tiles so the GEMM kernel may read (and discard) the rows past M
+    return (size_t)g.m_tiles * g.MR * g.T * p->C * g.elem_bytes;
+}
+
+int64_t icv_indirection_index(const icv_conv_params* p, int64_t m, int32_t tap)
+{
+    Geometry g;
+    if (make_geometry(p, &g) != ICV_OK) return -1;
+    if (m < 0 || m >= g.m_tiles * g.MR || tap < 0 || tap >= g.T) return -1;
+    return (m / g.MR) * ((int64_t)g.T * g.MR) + (int64_t)tap * g.MR + m % g.MR;
+}
+
+int icv_init_zero_row(const icv_conv_params* p, void* zero_row, void* stream)
+{
+    Geometry g;
+    const int st = make_geometry(p, &g);
+    if (st != ICV_OK) return st;
+    if (!zero_row || !aligned16(zero_row)) return ICV_ERR_INVALID_ARG;
+    return launch_zero_row(p, g, zero_row, (hipStream_t)stream);
+}
+
+int icv_pack_filter(const icv_conv_params* p, const void* filter_krsc, void* packed, void* stream)
+{
+    Geometry g;
+    const int st = make_geometry(p, &g);
+    if (st != ICV_OK) return st;
+    if (!filter_krsc || !packed || !aligned16(packed)) return ICV_ERR_INVALID_ARG;
+    return launch_pack_filter(p, g, filter_krsc, packed, (hipStream_t)stream);
+}
+
+int icv_setup_indirection(const icv_conv_params* p, void* indirection, void* stream)
+{
+    Geometry g;
+    const int st = make_geometry(p, &g);
+    if (st != ICV_OK) return st;
+    if (!indirection || !aligned16(indirection)) return ICV_ERR_INVALID_ARG;
+    return launch_build_indirection(p, g, (int32_t*)indirection, (hipStream_t)stream);
+}
+
+static int conv_common(const icv_conv_params* p, const Geometry& g, const void* a, const void* packed,
+                       const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s)
+{
+    if (g.kind == PLAN_MFMA) return launch_igemm_mfma(p, g, a, packed, ind, zero_row, out, a_direct, s);
+    return launch_igemm_generic(p, g, a, packed, ind, zero_row, out, a_direct, s);
+}
+
+int icv_conv2d_nhwc(const icv_conv_params* p, const void* input, const void* packed_filter,
+                    const void* indirection, const void* zero_row, void* output, void* stream)
+{
+    Geometry g;
+    const int st = make_geometry(p, &g);
+    if (st != ICV_OK) return st;
+    if (!input || !packed_filter || !indirection || !zero_row || !output) return ICV_ERR_INVALID_ARG;
+    if (!aligned16(input) || !aligned16(packed_filter) || !aligned16(indirection) || !aligned16(zero_row) ||
+        !aligned16(output))
+        return ICV_ERR_INVALID_ARG;
+    return conv_common(p, g, input, packed_filter, (const int32_t*)indirection, zero_row, output, false,
+                       (hipStream_t)stream);
+}
+
+int icv_im2col(const icv_conv_params* p, const void* input, void* im2col_ws, void* stream)
+{
+    Geometry g;
+    const int st = make_geometry(p, &g);
+    if (st != ICV_OK) return st;
+    if (!input || !im2col_ws || !aligned16(input) || !aligned16(im2col_ws)) return ICV_ERR_INVALID_ARG;
+    return launch_im2col(p, g, input, im2col_ws, (hipStream_t)stream);
+}
+
+int icv_gemm_nhwc(const icv_conv_params* p, const void* im2col_ws, const void* packed_filter, void* output,
+                  void* stream)
+{
+    Geometry g;
+    const int st = make_geometry(p, &g);
+    if (st != ICV_OK) return st;
+    if (!im2col_ws || !packed_filter || !output) return ICV_ERR_INVALID_ARG;
+    if (!aligned16(im2col_ws) || !aligned16(packed_filter) || !aligned16(output)) return ICV_ERR_INVALID_ARG;
+    return conv_common(p, g, im2col_ws, packed_filter, nullptr, nullptr, output, true, (hipStream_t)stream);
+}
+
+int icv_conv2d_nhwc_im2col(const icv_conv_params* p, const void* input, const void* packed_filter,
+                           void* im2col_ws, void* output, void* stream)
+{
+    const int st = icv_im2col(p, input, im2col_ws, stream);
+    if (st != ICV_OK) return st;
+    return icv_gemm_nhwc(p, im2col_ws, packed_filter, output, stream);
+}
+
+const char* icv_plan_name(const icv_conv_params* p)
+{
+    Geometry g;
+    if (make_geometry(p, &g) != ICV_OK) return "";
+    return g.name;
+}
+
+const char* icv_status_string(int status)
+{
+    switch (status) {
+        case ICV_OK: return "ok";
+        case ICV_ERR_INVALID_ARG: return "invalid argument";
+        case ICV_ERR_UNSUPPORTED: return "unsupported problem";
+        case ICV_ERR_HIP: return "HIP call failed";
+        default: return "unknown status";
+    }
+}
+
+int icv_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,72 @@
+// Internal declarations shared by the translation units of libicv.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "icv.h"
+
+namespace icv {
+
+// Which inner kernel serves a problem.
+enum PlanKind : int32_t {
+    PLAN_INVALID = 0,
+    PLAN_GENERIC = 1,   // vector-ALU kernel, any C, any dtype
+    PLAN_MFMA = 2,      // tensor-core indirect GEMM, C a multiple of the k-granule
+    PLAN_MFMA_LOWC = 3  // tensor-core indirect GEMM for C*elem = 8 bytes (several taps per k-step)
+};
+
+// Geometry derived once per call from icv_conv_params (host side).
+struct Geometry {
+    int32_t Hout, Wout;
+    int64_t M;            // N*Hout*Wout, GEMM rows
+    int32_t T;            // R*S kernel elements ("taps")
+    int32_t elem_bytes;   // input / filter element size
+    int32_t in_stride;    // elements between input pixels
+    int32_t out_stride;   // elements between output pixels
+    // plan
+    int32_t kind;         // PlanKind
+    int32_t variant;      // index into the tile-variant table (MFMA kinds)
+    int32_t MR, NR;       // workgroup tile: rows (output pixels) x columns (output channels)
+    int32_t KCB;          // bytes of one A/B row per pipeline stage
+    int32_t stages_per_tap;  // C*elem_bytes / KCB (MFMA)        | 1
+    int32_t taps_per_stage;  // 1                                | KCB / 8 (LOWC)
+    int32_t n_stages;        // pipeline stages in the reduction
+    int64_t m_tiles, n_tiles;
+    const char* name;
+};
+
+// Fills g; returns ICV_OK / ICV_ERR_INVALID_ARG / ICV_ERR_UNSUPPORTED.
+int make_geometry(const icv_conv_params* p, Geometry* g);
+
+void set_hip_error(hipError_t e);
+
+#define ICV_HIP_CHECK(expr)                        \
+    do {                                           \
+        hipError_t e_ = (expr);                    \
+        if (e_ != hipSuccess) {                    \
+            ::icv::set_hip_error(e_);              \
+            return ICV_ERR_HIP;                    \
+        }                                          \
+    } while (0)
+
+// Kernel launchers (each returns an icv_status).
+int launch_zero_row(const icv_conv_params* p, const Geometry& g, void* zero_row, hipStream_t s);
+int launch_pack_filter(const icv_conv_params* p, const Geometry& g, const void* filt, void* packed, hipStream_t s);
+int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_t* ind, hipStream_t s);
+int launch_im2col(const icv_conv_params* p, const Geometry& g, const void* input, void* ws, hipStream_t s);
+
+// a_direct = false: rows of A come from the indirection buffer (the method);
+// a_direct = true : A is the dense [M][T*C] patch matrix with constant row stride (ablation GEMM).
+int launch_igemm_mfma(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
+                      const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s);
+int launch_igemm_generic(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
+                         const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s);
+
+// Tile variants of the tensor-core kernel (host-visible table).
+struct TileVariant {
+    int32_t MR, NR, WM, WN;
+    const char* tag;
+};
+extern const TileVariant kTileVariants[];
+extern const int kNumTileVariants;
+
+}  // namespace icv

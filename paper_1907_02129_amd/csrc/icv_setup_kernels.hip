@@ -1,0 +1,217 @@
+// Set-up kernels: zero row, filter pre-pack, indirection build, and the im2col of the ablation path.
+#include "icv_internal.h"
+
+namespace icv {
+
+// ------------------------------------------------------------------ zero row (section 2.3)
+__global__ void k_fill_bytes(uint8_t* dst, int n, uint8_t v)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = v;
+}
+
+int launch_zero_row(const icv_conv_params* p, const Geometry& g, void* zero_row, hipStream_t s)
+{
+    const int n = (int)((((size_t)p->C * g.elem_bytes) + 15) / 16 * 16);
+    const uint8_t v = p->dtype == ICV_U8I8 ? (uint8_t)p->input_zero_point : 0;
+    hipLaunchKernelGGL(k_fill_bytes, dim3((n + 255) / 256), dim3(256), 0, s, (uint8_t*)zero_row, n, v);
+    ICV_HIP_CHECK(hipGetLastError());
+    return ICV_OK;
+}
+
+// ------------------------------------------------------------------ filter pre-pack
+// Source  [K][T][C] elements.
+// Packed  [n_tile][stage][NR][KCB bytes], stage = (tap, C-chunk): the tile one pipeline stage of the GEMM
+//         kernel copies into LDS is one contiguous block.  Rows past K are zero.
+// One thread moves 16 bytes (KCB and C*elem are multiples of 16 for the tensor-core plans); the generic
+// plan (KCB == 0) keeps [K padded][T][C] and moves single elements.
+struct PackArgs {
+    const uint8_t* src;
+    uint8_t* dst;
+    int32_t K, T, CB;  // CB = C * elem bytes
+    int32_t NR, KCB, stages_per_tap, n_stages;
+    int64_t total_vec;  // number of 16-byte vectors in dst
+};
+
+__global__ void k_pack_filter_vec(PackArgs a)
+{
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= a.total_vec) return;
+    const int32_t q = a.KCB / 16;  // vectors per row per stage
+    const int32_t chunk = (int32_t)(v % q);
+    int64_t r = v / q;
+    const int32_t row = (int32_t)(r % a.NR);
+    r /= a.NR;
+    const int32_t stage = (int32_t)(r % a.n_stages);
+    const int32_t ntile = (int32_t)(r / a.n_stages);
+    const int32_t tap = stage / a.stages_per_tap, cc = stage % a.stages_per_tap;
+    const int32_t oc = ntile * a.NR + row;
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (oc < a.K)
+        val = *(const uint4*)(a.src + ((int64_t)oc * a.T + tap) * a.CB + (int64_t)cc * a.KCB + chunk * 16);
+    *(uint4*)(a.dst + v * 16) = val;
+}
+
+__global__ void k_pack_filter_plain(const uint8_t* src, uint8_t* dst, int64_t valid_bytes, int64_t total_bytes)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < total_bytes) dst[i] = i < valid_bytes ? src[i] : (uint8_t)0;
+}
+
+int launch_pack_filter(const icv_conv_params* p, const Geometry& g, const void* filt, void* packed, hipStream_t s)
+{
+    const int64_t CB = (int64_t)p->C * g.elem_bytes;
+    if (g.kind == PLAN_MFMA) {
+        PackArgs a;
+        a.src = (const uint8_t*)filt;
+        a.dst = (uint8_t*)packed;
+        a.K = p->K; a.T = g.T; a.CB = (int32_t)CB;
+        a.NR = g.NR; a.KCB = g.KCB; a.stages_per_tap = g.stages_per_tap; a.n_stages = g.n_stages;
+        a.total_vec = g.n_tiles * g.NR * (int64_t)g.T * CB / 16;
+        hipLaunchKernelGGL(k_pack_filter_vec, dim3((unsigned)((a.total_vec + 255) / 256)), dim3(256), 0, s, a);
+    } else {
+        const int64_t valid = (int64_t)p->K * g.T * CB, total = g.n_tiles * g.NR * (int64_t)g.T * CB;
+        hipLaunchKernelGGL(k_pack_filter_plain, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                           (const uint8_t*)filt, (uint8_t*)packed, valid, total);
+    }
+    ICV_HIP_CHECK(hipGetLastError());
+    return ICV_OK;
+}
+
+// ------------------------------------------------------------------ indirection build (section 2.3)
+// Entry (m, tap): iy = oy*SY + ky*DY - PT, ix = ox*SX + kx*DX - PL (Listing 1's index arithmetic);
+// inside the input -> (n*Hin + iy)*Win + ix, else -1 (the zero row).  Physical order [m tile][tap][MR].
+// One thread owns four consecutive rows m0..m0+3 (MR is a multiple of 4, so they share a tile) and walks
+// all taps, writing one int4 per tap: consecutive threads write consecutive 16-byte pieces of a
+// (tile, tap) run of MR*4 bytes.  The two integer divisions per thread are amortised over 4*T entries.
+struct IndArgs {
+    int32_t* ind;
+    int64_t M, m_padded;
+    int32_t Hin, Win, Hout, Wout, R, S, SY, SX, DY, DX, PT, PL, MR, T;
+};
+
+__global__ __launch_bounds__(256) void k_build_indirection(IndArgs a)
+{
+    const int64_t m0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (m0 >= a.m_padded) return;
+    // decompose the four rows
+    int32_t n[4], oy[4], ox[4];
+    bool live[4];
+    {
+        const uint32_t mm = (uint32_t)(m0 < a.M ? m0 : 0);
+        const uint32_t q = mm / (uint32_t)a.Wout;
+        int32_t x = (int32_t)(mm - q * (uint32_t)a.Wout);
+        const uint32_t nn = q / (uint32_t)a.Hout;
+        int32_t y = (int32_t)(q - nn * (uint32_t)a.Hout);
+        int32_t b = (int32_t)nn;
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            n[j] = b; oy[j] = y; ox[j] = x;
+            live[j] = m0 + j < a.M;
+            if (++x == a.Wout) { x = 0; if (++y == a.Hout) { y = 0; ++b; } }
+        }
+    }
+    const int64_t tile = m0 / a.MR;
+    const int32_t r = (int32_t)(m0 - tile * a.MR);
+    int4* dst = (int4*)(a.ind + tile * ((int64_t)a.T * a.MR) + r);
+    const int32_t mr4 = a.MR / 4;
+    for (int32_t ky = 0; ky < a.R; ky++) {
+        for (int32_t kx = 0; kx < a.S; kx++) {
+            int32_t e[4];
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const int32_t iy = oy[j] * a.SY + ky * a.DY - a.PT;
+                const int32_t ix = ox[j] * a.SX + kx * a.DX - a.PL;
+                const bool in = live[j] && (uint32_t)iy < (uint32_t)a.Hin && (uint32_t)ix < (uint32_t)a.Win;
+                e[j] = in ? (n[j] * a.Hin + iy) * a.Win + ix : -1;
+            }
+            *dst = make_int4(e[0], e[1], e[2], e[3]);
+            dst += mr4;
+        }
+    }
+}
+
+int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_t* ind, hipStream_t s)
+{
+    IndArgs a;
+    a.ind = ind;
+    a.M = g.M; a.m_padded = g.m_tiles * g.MR;
+    a.Hin = p->Hin; a.Win = p->Win; a.Hout = g.Hout; a.Wout = g.Wout;
+    a.R = p->R; a.S = p->S; a.SY = p->SY; a.SX = p->SX; a.DY = p->DY; a.DX = p->DX;
+    a.PT = p->PT; a.PL = p->PL; a.MR = g.MR; a.T = g.T;
+    const int64_t threads = a.m_padded / 4;
+    hipLaunchKernelGGL(k_build_indirection, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, a);
+    ICV_HIP_CHECK(hipGetLastError());
+    return ICV_OK;
+}
+
+// ------------------------------------------------------------------ im2col (ablation; section 1, "GEMM-based algorithms")
+// ws[m][tap][C]: the patch of input pixels behind output pixel m copied into row m; taps outside the input
+// become zeros (the zero point for u8i8).  Rows past M (tile padding) are filled like padding.
+// One thread moves `VB` bytes of one (m, tap) pixel row.
+struct Im2colArgs {
+    const uint8_t* in;
+    uint8_t* ws;
+    int64_t M, m_padded;
+    int32_t Hin, Win, Hout, Wout, S, SY, SX, DY, DX, PT, PL, T;
+    int32_t CB;             // bytes of one pixel row copied (C * elem)
+    int64_t stride_bytes;   // input pixel stride in bytes
+    uint32_t fill;          // padding pattern, replicated per byte
+};
+
+template <int VB>
+__global__ __launch_bounds__(256) void k_im2col(Im2colArgs a)
+{
+    const int32_t vec_per_row = a.CB / VB;
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t total = a.m_padded * a.T * vec_per_row;
+    if (v >= total) return;
+    const int32_t c = (int32_t)(v % vec_per_row);
+    const int64_t mt = v / vec_per_row;
+    const int32_t tap = (int32_t)(mt % a.T);
+    const int64_t m = mt / a.T;
+    const int32_t ky = tap / a.S, kx = tap - ky * a.S;
+    const int32_t ox = (int32_t)(m % a.Wout);
+    const int64_t q = m / a.Wout;
+    const int32_t oy = (int32_t)(q % a.Hout);
+    const int32_t n = (int32_t)(q / a.Hout);
+    const int32_t iy = oy * a.SY + ky * a.DY - a.PT;
+    const int32_t ix = ox * a.SX + kx * a.DX - a.PL;
+    const bool in = m < a.M && (uint32_t)iy < (uint32_t)a.Hin && (uint32_t)ix < (uint32_t)a.Win;
+    uint8_t* d = a.ws + v * VB;
+    if constexpr (VB == 16) {
+        uint4 val = make_uint4(a.fill, a.fill, a.fill, a.fill);
+        if (in) val = *(const uint4*)(a.in + (((int64_t)n * a.Hin + iy) * a.Win + ix) * a.stride_bytes + c * 16);
+        *(uint4*)d = val;
+    } else {
+        for (int b = 0; b < VB; b++)
+            d[b] = in ? a.in[(((int64_t)n * a.Hin + iy) * a.Win + ix) * a.stride_bytes + c * VB + b]
+                      : (uint8_t)(a.fill & 0xff);
+    }
+}
+
+int launch_im2col(const icv_conv_params* p, const Geometry& g, const void* input, void* ws, hipStream_t s)
+{
+    Im2colArgs a;
+    a.in = (const uint8_t*)input;
+    a.ws = (uint8_t*)ws;
+    a.M = g.M; a.m_padded = g.m_tiles * g.MR;
+    a.Hin = p->Hin; a.Win = p->Win; a.Hout = g.Hout; a.Wout = g.Wout;
+    a.S = p->S; a.SY = p->SY; a.SX = p->SX; a.DY = p->DY; a.DX = p->DX; a.PT = p->PT; a.PL = p->PL; a.T = g.T;
+    a.CB = p->C * g.elem_bytes;
+    a.stride_bytes = (int64_t)g.in_stride * g.elem_bytes;
+    const uint32_t zp = p->dtype == ICV_U8I8 ? (uint32_t)p->input_zero_point : 0u;
+    a.fill = zp * 0x01010101u;
+    const bool vec16 = a.CB % 16 == 0 && a.stride_bytes % 16 == 0;
+    const int vb = vec16 ? 16 : g.elem_bytes;
+    const int64_t total = a.m_padded * a.T * (a.CB / vb);
+    const dim3 grid((unsigned)((total + 255) / 256));
+    if (vec16) hipLaunchKernelGGL(k_im2col<16>, grid, dim3(256), 0, s, a);
+    else if (vb == 4) hipLaunchKernelGGL(k_im2col<4>, grid, dim3(256), 0, s, a);
+    else if (vb == 2) hipLaunchKernelGGL(k_im2col<2>, grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(k_im2col<1>, grid, dim3(256), 0, s, a);
+    ICV_HIP_CHECK(hipGetLastError());
+    return ICV_OK;
+}
+
+}  // namespace icv

@@ -1,0 +1,245 @@
+"""GPU parity: the HIP path against the CPU oracle on the same seeded inputs, through the C ABI.
+
+Tolerances (stated by the task's correctness bar):
+  u8i8 : bit-exact int32
+  bf16 : max |y - r| / max |r| <= 1e-2 against the double-precision oracle
+  f32  : same measure <= 1e-4
+and, stricter, a rounding bound that holds for any summation order of an fp32 accumulator:
+  |y - r| <= 2 * n * 2^-24 * sum |x*w|   (n = R*S*C terms; bf16 products are exact in fp32).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1907_02129_amd import binding as icv
+from paper_1907_02129_amd.workloads import CONFIGS, ConvShape, make_tensors
+
+pytestmark = pytest.mark.gpu
+TOL = {"bf16": 1e-2, "f32": 1e-4}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    icv.load_library()
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def check_against_oracle(s: ConvShape, got: np.ndarray, x: np.ndarray, w: np.ndarray):
+    if s.dtype == "u8i8":
+        want = oracle.conv2d_u8i8(s, x, w, s.zero_point, centred=True)
+        assert got.dtype == np.int32
+        assert np.array_equal(got, want), f"{s.name}: {(got != want).sum()} of {want.size} differ"
+        return
+    want, mag = oracle.conv2d_abs(s, x, w)
+    err = np.abs(got.astype(np.float64) - want)
+    rel = err.max() / np.abs(want).max()
+    assert rel <= TOL[s.dtype], f"{s.name}: max rel err {rel:.3e}"
+    n_terms = s.R * s.S * s.C
+    bound = 2.0 * n_terms * 2.0 ** -24 * mag + 1e-30
+    worst = (err / bound).max()
+    assert worst <= 1.0, f"{s.name}: error is {worst:.2f}x the fp32 accumulation bound"
+
+
+def run_indirect(s: ConvShape, x, w, plan=0, out_pixel_stride=0):
+    xd, wd = icv.to_device(x), icv.to_device(w)
+    buf = icv.prepare(s, wd, plan=plan, out_pixel_stride=out_pixel_stride)
+    buf.output.fill_(-7)
+    icv.run(buf, xd)
+    torch.cuda.synchronize()
+    return buf, xd
+
+
+def run_im2col(s: ConvShape, buf, xd):
+    ws = torch.empty(icv.im2col_bytes(buf.p), dtype=torch.uint8, device="cuda:0")
+    out = torch.full_like(buf.output, -7)
+    icv.conv2d_nhwc_im2col(buf.p, xd, buf.packed, ws, out)
+    torch.cuda.synchronize()
+    return out, ws
+
+
+# ---------------------------------------------------------------- indirection buffer
+@pytest.mark.parametrize("name", list(CONFIGS))
+def test_indirection_matches_oracle_entry_by_entry(name):
+    s = CONFIGS[name]
+    _say("indirection", name)
+    p = icv.make_params(s)
+    Hout, Wout = icv.output_size(p)
+    ind = torch.full((icv.indirection_bytes(p) // 4,), 12345, dtype=torch.int32, device="cuda:0")
+    icv.setup_indirection(p, ind)
+    torch.cuda.synchronize()
+    buf = icv.ConvBuffers(p, Hout, Wout, None, None, ind, None)
+    got, tail = icv.logical_indirection(buf)
+    assert np.array_equal(got, oracle.indirection(s))
+    assert np.all(tail == -1)                                   # rows past M read the zero row
+
+
+SMALL_IND = [
+    ConvShape("i1", 2, 9, 7, 3, 2, 3, 4, SY=2, SX=1, DY=1, DX=2, PT=3, PL=1, PB=0, PR=2, dtype="f32"),
+    ConvShape("i2", 3, 13, 11, 64, 8, 5, 2, SY=1, SX=3, DY=2, DX=1, PT=0, PL=2, PB=4, PR=0),
+    ConvShape("i3", 1, 1, 1, 64, 8, 1, 1),
+    ConvShape("i4", 5, 6, 40, 64, 8, 1, 1, SY=2, SX=3),
+    ConvShape("i5", 1, 30, 30, 64, 8, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, dtype="u8i8", zero_point=128),
+]
+
+
+@pytest.mark.parametrize("s", SMALL_IND, ids=lambda s: s.name)
+def test_indirection_small_shapes(s):
+    _say("indirection", s)
+    p = icv.make_params(s)
+    Hout, Wout = icv.output_size(p)
+    ind = torch.full((icv.indirection_bytes(p) // 4,), 12345, dtype=torch.int32, device="cuda:0")
+    icv.setup_indirection(p, ind)
+    torch.cuda.synchronize()
+    got, tail = icv.logical_indirection(icv.ConvBuffers(p, Hout, Wout, None, None, ind, None))
+    assert np.array_equal(got, oracle.indirection(s))
+    assert np.all(tail == -1)
+
+
+# ---------------------------------------------------------------- full-size benchmark shapes, every element
+@pytest.mark.parametrize("name", list(CONFIGS))
+def test_benchmark_shape_matches_oracle(name):
+    s = CONFIGS[name]
+    _say("conv", name, icv.plan_name(icv.make_params(s)))
+    x, w = make_tensors(s)
+    buf, xd = run_indirect(s, x, w)
+    check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+
+
+# ---------------------------------------------------------------- small shapes: several tiles, ragged tails
+def _small_shapes():
+    out = []
+    # bf16: ragged M (not a multiple of any tile), ragged K, C giving one / several stages per tap
+    out.append(ConvShape("s_bf16_c64_k96", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=21))
+    out.append(ConvShape("s_bf16_c32_k40", 1, 37, 11, 32, 40, 5, 5, PT=2, PL=2, PB=1, PR=1, seed=22))
+    out.append(ConvShape("s_bf16_c96_k130", 3, 15, 17, 96, 130, 3, 2, SY=2, SX=1, DY=1, DX=2, PT=1, PL=0, PB=2, PR=3, seed=23))
+    out.append(ConvShape("s_bf16_c256_k64_1x1", 2, 21, 13, 256, 64, 1, 1, seed=24))
+    out.append(ConvShape("s_bf16_c128_s2", 2, 22, 26, 128, 72, 3, 3, SY=2, SX=2, PT=1, PL=1, PB=1, PR=1, seed=25))
+    out.append(ConvShape("s_bf16_one_pixel", 1, 1, 1, 64, 8, 1, 1, seed=26))
+    out.append(ConvShape("s_bf16_all_padding_rows", 1, 2, 2, 32, 16, 3, 3, DY=2, DX=2, PT=4, PL=4, PB=4, PR=4, seed=27))
+    # int8
+    out.append(ConvShape("s_i8_c64_k96", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=31))
+    out.append(ConvShape("s_i8_c192_k200", 1, 17, 9, 192, 200, 3, 3, DY=2, DX=2, PT=2, PL=2, PB=2, PR=2, dtype="u8i8", zero_point=128, seed=32))
+    out.append(ConvShape("s_i8_c128_s2", 3, 14, 14, 128, 64, 5, 3, SY=2, SX=2, PT=2, PL=1, PB=2, PR=1, dtype="u8i8", zero_point=128, seed=33))
+    # vector-ALU fallback: odd channel counts, fp32, other zero points
+    out.append(ConvShape("s_f32_odd", 2, 9, 10, 5, 7, 3, 3, SY=2, SX=1, PT=1, PL=2, PB=0, PR=1, dtype="f32", dist="uniform", seed=41))
+    out.append(ConvShape("s_bf16_c3", 1, 12, 12, 3, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=42))
+    out.append(ConvShape("s_i8_zp7", 1, 9, 9, 64, 16, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=7, seed=43))
+    out.append(ConvShape("s_i8_c5", 1, 9, 9, 5, 16, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=44))
+    return out
+
+
+@pytest.mark.parametrize("s", _small_shapes(), ids=lambda s: s.name)
+def test_small_shapes_match_oracle(s):
+    _say("conv", s.name, icv.plan_name(icv.make_params(s)))
+    x, w = make_tensors(s)
+    buf, xd = run_indirect(s, x, w)
+    check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+
+
+N_PLANS = 7     # plan 1 = vector ALU, 2.. = tensor-core tile variants
+
+
+@pytest.mark.parametrize("plan", range(1, N_PLANS + 1))
+@pytest.mark.parametrize("dtype", ["bf16", "u8i8"])
+def test_every_tile_variant(plan, dtype):
+    zp = 128 if dtype == "u8i8" else 0
+    for s in (ConvShape("v_a", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype=dtype, zero_point=zp, seed=51),
+              ConvShape("v_b", 1, 20, 33, 128, 200, 2, 3, SY=1, SX=2, PT=0, PL=1, PB=1, PR=1, dtype=dtype, zero_point=zp, seed=52),
+              ConvShape("v_c", 3, 11, 9, 32 if dtype == "bf16" else 64, 33, 3, 3, DY=2, DX=1, PT=2, PL=1, PB=2, PR=1,
+                        dtype=dtype, zero_point=zp, seed=53)):
+        _say("variant", plan, icv.plan_name(icv.make_params(s, plan=plan)), s.name)
+        x, w = make_tensors(s)
+        buf, xd = run_indirect(s, x, w, plan=plan)
+        check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+
+
+# ---------------------------------------------------------------- properties of the path
+def test_output_pixel_stride_and_untouched_gaps():
+    s = ConvShape("ostride", 2, 10, 12, 64, 40, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=61)
+    x, w = make_tensors(s)
+    buf, xd = run_indirect(s, x, w, out_pixel_stride=48)
+    out = buf.output.cpu().numpy()
+    assert out.shape[-1] == 48 and np.all(out[..., 40:] == -7)        # only the first K of each pixel written
+    check_against_oracle(s, np.ascontiguousarray(out[..., :40]), x, w)
+
+
+def test_padded_channel_layout():
+    # 3 real channels stored with a pixel stride of 4 (fourth input / filter channel zero)
+    s4 = CONFIGS["cfg5b_7x7_s2"].with_(N=2, Hin=40, Win=36)
+    x, w = make_tensors(s4)
+    buf, xd = run_indirect(s4, x, w)
+    s3 = s4.with_(C=3)
+    want3 = oracle.conv2d(s3, x, np.ascontiguousarray(w[..., :3]))
+    got = buf.output.cpu().numpy().astype(np.float64)
+    assert np.abs(got - want3).max() / np.abs(want3).max() <= 1e-2
+
+
+@pytest.mark.parametrize("name", ["cfg2_3x3_c64", "cfg3a_3x3_s2", "cfg4_int8_3x3", "cfg3c_5x5_asym"])
+def test_im2col_gemm_ablation_agrees_with_indirect_path(name):
+    # "fused im2col + GEMM" (section 2.2): both paths compute the same thing
+    s = CONFIGS[name].with_(N=2)
+    _say("ablation", name)
+    x, w = make_tensors(s)
+    buf, xd = run_indirect(s, x, w)
+    out2, ws = run_im2col(s, buf, xd)
+    got1, got2 = buf.output.cpu().numpy(), out2.cpu().numpy()
+    check_against_oracle(s, got2, x, w)
+    if s.dtype == "u8i8":
+        assert np.array_equal(got1, got2)
+    else:
+        assert np.abs(got1 - got2).max() <= 2e-2 * np.abs(got1).max()
+    # the patch matrix itself: row m, tap t holds the pixel row the indirection entry names
+    M, T = buf.M, s.R * s.S
+    esz = 1 if s.dtype == "u8i8" else 2
+    rows = ws.cpu().numpy()[:M * T * s.C * esz].reshape(M, T, s.C * esz)
+    ent = oracle.indirection(s)
+    xb = x.reshape(-1, s.C).view(np.uint8).reshape(-1, s.C * esz)
+    fill = np.full(s.C * esz, s.zero_point if s.dtype == "u8i8" else 0, dtype=np.uint8)
+    src = np.concatenate([xb, fill[None]], axis=0)
+    assert np.array_equal(rows, src[ent])          # entry -1 indexes the appended fill row
+
+
+def test_small_generic_im2col_path():
+    s = ConvShape("g_im2col", 2, 9, 10, 5, 7, 3, 3, SY=2, SX=1, PT=1, PL=2, PB=0, PR=1, dtype="f32", dist="uniform", seed=71)
+    x, w = make_tensors(s)
+    buf, xd = run_indirect(s, x, w)
+    out2, _ = run_im2col(s, buf, xd)
+    check_against_oracle(s, out2.cpu().numpy(), x, w)
+
+
+def test_determinism_and_buffer_reuse_with_new_input_pointer():
+    s = CONFIGS["cfg2_3x3_c64"].with_(N=4)
+    x, w = make_tensors(s)
+    buf, xd = run_indirect(s, x, w)
+    first = buf.output.clone()
+    icv.run(buf, xd)
+    torch.cuda.synchronize()
+    assert torch.equal(first, buf.output)
+    # entries are indices, so the same buffer serves an input tensor at another address
+    pad = torch.empty(4096, dtype=torch.uint8, device="cuda:0")   # shifts the next allocation
+    xd2 = xd.clone()
+    assert xd2.data_ptr() != xd.data_ptr()
+    icv.run(buf, xd2)
+    torch.cuda.synchronize()
+    assert torch.equal(first, buf.output)
+    del pad
+
+
+def test_runs_on_a_side_stream():
+    s = CONFIGS["cfg2_3x3_c64"].with_(N=2)
+    x, w = make_tensors(s)
+    buf, xd = run_indirect(s, x, w)
+    want = buf.output.clone()
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    buf.output.zero_()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(st):
+        icv.run(buf, xd)
+    st.synchronize()
+    assert torch.equal(want, buf.output)

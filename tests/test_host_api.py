@@ -1,0 +1,128 @@
+"""Host-side checks that need no GPU: the library loads, exports what the header declares, and its
+geometry / validation logic agrees with the oracle's statement of the problem."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1907_02129_amd import binding as icv
+from paper_1907_02129_amd.workloads import CONFIGS, ConvShape, random_small_shape
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return icv.load_library()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "icv.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(icv_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(icv.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_params_struct_matches_header():
+    header = open(os.path.join(ROOT, "include", "icv.h")).read()
+    body = re.search(r"typedef struct icv_conv_params \{(.*?)\} icv_conv_params;", header, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = [n.strip() for decl in re.findall(r"int32_t([^;]*);", body) for n in decl.split(",")]
+    assert names == [f[0] for f in icv.icv_conv_params._fields_]
+
+
+@pytest.mark.parametrize("name", list(CONFIGS))
+def test_output_size_and_buffer_sizes(lib, name):
+    s = CONFIGS[name]
+    p = icv.make_params(s)
+    Hout, Wout = icv.output_size(p)
+    assert (Hout, Wout) == oracle.out_extent(s)
+    M, T = s.N * Hout * Wout, s.R * s.S
+    nbytes = icv.indirection_bytes(p)
+    assert nbytes % (4 * T) == 0 and nbytes >= 4 * M * T
+    assert nbytes < 4 * (M + 256) * T                       # padding is less than one row tile
+    # the indirection buffer does not depend on the number of input channels (section 1.1)
+    assert icv.indirection_bytes(icv.make_params(s.with_(C=s.C * 2))) == nbytes or s.dtype == "f32"
+    esz = {"f32": 4, "bf16": 2, "u8i8": 1}[s.dtype]
+    assert icv.packed_filter_bytes(p) >= s.K * T * s.C * esz
+    assert icv.zero_row_bytes(p) >= s.C * esz and icv.zero_row_bytes(p) % 16 == 0
+    assert icv.im2col_bytes(p) >= M * T * s.C * esz
+    assert icv.plan_name(p) != ""
+
+
+def test_output_size_random_shapes(lib):
+    rng = np.random.default_rng(3)
+    for _ in range(200):
+        s = random_small_shape(rng)
+        assert icv.output_size(icv.make_params(s)) == oracle.out_extent(s)
+
+
+def test_indirection_index_is_tile_tap_row_order(lib):
+    s = CONFIGS["cfg2_3x3_c64"]
+    p = icv.make_params(s)
+    T = 9
+    mr = icv.indirection_index(p, 0, 1)            # tap stride = rows per tile
+    assert mr >= 32 and mr % 32 == 0
+    assert icv.indirection_index(p, 0, 0) == 0 and icv.indirection_index(p, 1, 0) == 1
+    assert icv.indirection_index(p, mr, 0) == mr * T
+    seen = {icv.indirection_index(p, m, t) for m in range(2 * mr) for t in range(T)}
+    assert seen == set(range(2 * mr * T))          # a bijection onto the first two tiles
+    assert icv.indirection_index(p, -1, 0) == -1 and icv.indirection_index(p, 0, T) == -1
+
+
+def _status(lib, s, **over):
+    p = icv.make_params(s)
+    for k, v in over.items():
+        setattr(p, k, v)
+    return lib.icv_output_size(ctypes.byref(p), None, None)
+
+
+def test_invalid_arguments_are_rejected(lib):
+    s = CONFIGS["cfg2_3x3_c64"]
+    assert _status(lib, s) == icv.ICV_OK
+    for field in ("N", "Hin", "Win", "C", "K", "R", "S", "SY", "SX", "DY", "DX"):
+        assert _status(lib, s, **{field: 0}) == icv.ICV_ERR_INVALID_ARG, field      # empty problems
+        assert _status(lib, s, **{field: -3}) == icv.ICV_ERR_INVALID_ARG, field
+    for field in ("PT", "PL", "PB", "PR"):
+        assert _status(lib, s, **{field: -1}) == icv.ICV_ERR_INVALID_ARG, field
+    assert _status(lib, s, dtype=7) == icv.ICV_ERR_INVALID_ARG
+    assert _status(lib, s, in_pixel_stride=32) == icv.ICV_ERR_INVALID_ARG           # stride < C
+    assert _status(lib, s, out_pixel_stride=8) == icv.ICV_ERR_INVALID_ARG           # stride < K
+    assert _status(lib, s, R=80, PT=0, PB=0) == icv.ICV_ERR_INVALID_ARG             # kernel larger than input
+    assert _status(lib, s, N=1 << 20) == icv.ICV_ERR_INVALID_ARG                    # pixel index overflows int32
+    assert _status(lib, s, plan=99) == icv.ICV_ERR_INVALID_ARG
+    assert _status(lib, CONFIGS["cfg4_int8_3x3"], input_zero_point=300) == icv.ICV_ERR_INVALID_ARG
+    assert lib.icv_output_size(None, None, None) == icv.ICV_ERR_INVALID_ARG
+    assert icv.indirection_bytes(icv.make_params(s.with_(N=0))) == 0
+
+
+def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
+    p = icv.make_params(CONFIGS["cfg2_3x3_c64"])
+    vp = ctypes.c_void_p
+    assert lib.icv_setup_indirection(ctypes.byref(p), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
+    assert lib.icv_setup_indirection(ctypes.byref(p), vp(0x1004), vp(0)) == icv.ICV_ERR_INVALID_ARG
+    assert lib.icv_conv2d_nhwc(ctypes.byref(p), vp(0), vp(0), vp(0), vp(0), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
+    assert lib.icv_pack_filter(ctypes.byref(p), vp(0), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
+    assert lib.icv_init_zero_row(ctypes.byref(p), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
+    assert lib.icv_im2col(ctypes.byref(p), vp(0), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
+    assert lib.icv_gemm_nhwc(ctypes.byref(p), vp(0), vp(0), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
+
+
+def test_status_strings(lib):
+    assert icv.status_string(0) == "ok"
+    assert "invalid" in icv.status_string(icv.ICV_ERR_INVALID_ARG)
+    assert icv.status_string(-99) == "unknown status"
+
+
+def test_plans(lib):
+    assert icv.plan_name(icv.make_params(CONFIGS["cfg1_tiny_f32"])).startswith("generic")
+    assert icv.plan_name(icv.make_params(CONFIGS["cfg2_3x3_c64"])).startswith("mfma_bf16")
+    assert icv.plan_name(icv.make_params(CONFIGS["cfg4_int8_3x3"])).startswith("mfma_i8")
+    # odd channel counts fall back to the vector-ALU kernel instead of failing
+    odd = ConvShape("odd", 1, 8, 8, 5, 3, 3, 3)
+    assert icv.plan_name(icv.make_params(odd)).startswith("generic")
