@@ -68,32 +68,64 @@ __device__ inline typename Acc<I8>::type mfma32(const uint4& a, const uint4& b, 
     }
 }
 
-template <bool I8, int MR, int NR, int WM, int WN, int KCB, bool DIRECT>
+// 16-byte global -> LDS copy without a register stop (global_load_lds_dwordx4): lane l of the wavefront
+// writes LDS bytes [lds_base + 16*l, +16).  Written as inline assembly on purpose: the compiler does not see
+// a memory instruction, so it inserts no waits of its own for it, and the kernel counts outstanding copies
+// itself with wait_vmcnt<>.  While such copies are in flight the kernel issues no other vector-memory
+// instruction, which keeps the compiler's own counter bookkeeping valid.
+__device__ inline void copy16_global_to_lds(const void* gptr, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n"
+                 :
+                 : "v"(gptr), "s"(lds_base)
+                 : "memory", "m0");
+}
+
+template <int N>
+__device__ inline void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+// XCD-aware block -> tile map.  Workgroups are dealt round-robin to the 8 XCDs (block b lands on XCD b % 8),
+// each with its own L2.  Giving every XCD one contiguous range of tiles keeps neighbouring row tiles --
+// which for a 3x3 kernel share most of their input rows -- and all column tiles of a row tile in one L2.
+__device__ inline int64_t xcd_tile(int64_t b, int64_t n_blocks)
+{
+    const int64_t chunk = n_blocks >> 3, rem = n_blocks & 7, x = b & 7;
+    return x * chunk + (x < rem ? x : rem) + (b >> 3);
+}
+
+template <bool I8, int MR, int NR, int WM, int WN, int KCB, int NSTAGE, bool DIRECT>
 __global__ __launch_bounds__(256) void k_igemm_mfma(IgemmArgs g)
 {
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
+    static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring depth");
     constexpr int Q = KCB / 16;          // 16-byte chunks per row per stage
     constexpr int P = 256 / KCB;         // rows per 256 bytes of LDS
-    constexpr int ROWS_PER_PASS = 256 / Q;
-    constexpr int A_VEC = MR / ROWS_PER_PASS;
-    constexpr int B_VEC = NR / ROWS_PER_PASS;
+    constexpr int RPB = 1024 / KCB;      // rows one wavefront-wide copy (64 x 16 B) covers
+    constexpr int A_VEC = MR * KCB / 4096;   // copies per wavefront per stage, A tile
+    constexpr int B_VEC = NR * KCB / 4096;   // ... B tile
+    constexpr int L = A_VEC + B_VEC;
     constexpr int MRW = MR / WM, NRW = NR / WN;
     constexpr int MB = MRW / 32, NB = NRW / 32;
     constexpr int KSTEPS = KCB / 32;
+    constexpr int SLOT = (MR + NR) * KCB;    // bytes of one ring slot: A tile then B tile
     static_assert(A_VEC >= 1 && B_VEC >= 1 && MB >= 1 && NB >= 1, "tile too small");
+    static_assert((NSTAGE - 1) * L <= 63, "vmcnt is a 6-bit counter");
     using acc_t = typename Acc<I8>::type;
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    uint8_t* ldsA = lds;                          // [2][MR*KCB]
-    uint8_t* ldsB = lds + 2 * MR * KCB;           // [2][NR*KCB]
-    int32_t* ldsE = (int32_t*)(lds + 2 * (MR + NR) * KCB);   // [T][MR]
+    int32_t* ldsE = (int32_t*)(lds + NSTAGE * SLOT);          // [T][MR]
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
-    const int64_t bid = blockIdx.x;
-    const int32_t nt = (int32_t)(bid % g.n_tiles);
-    const int64_t mt = bid / g.n_tiles;
+    const int64_t tile = xcd_tile(blockIdx.x, gridDim.x);
+    const int32_t nt = (int32_t)(tile % g.n_tiles);
+    const int64_t mt = tile / g.n_tiles;
 
     // ---- tile's indirection entries -> LDS (Listing 3 reads them in exactly this order)
     if constexpr (!DIRECT) {
@@ -103,57 +135,43 @@ __global__ __launch_bounds__(256) void k_igemm_mfma(IgemmArgs g)
         __syncthreads();
     }
 
-    // ---- per-thread load slots
-    const int chunk = tid % Q;
-    const int row0 = tid / Q;
-    uint32_t a_lds_off[A_VEC], b_lds_off[B_VEC];
-#pragma unroll
-    for (int j = 0; j < A_VEC; j++) {
-        const int row = row0 + j * ROWS_PER_PASS;
-        a_lds_off[j] = row * KCB + ((chunk ^ ((row / P) % Q)) << 4);
-    }
-#pragma unroll
-    for (int j = 0; j < B_VEC; j++) {
-        const int row = row0 + j * ROWS_PER_PASS;
-        b_lds_off[j] = row * KCB + ((chunk ^ ((row / P) % Q)) << 4);
-    }
-    const uint8_t* wtile = g.w + ((int64_t)nt * g.n_stages) * (NR * KCB) + tid * 16;
-    const uint8_t* a_direct_base = g.a + (mt * MR + row0) * g.row_stride_bytes + chunk * 16;
+    // ---- copy slots of this lane: wavefront w moves 1 KB blocks b = w, w+4, ... of a stage tile; block b is
+    // rows [b*RPB, +RPB); lane l fills LDS chunk (l % Q) of row b*RPB + l/Q, which must hold source chunk
+    // (l % Q) ^ swizzle(row).  swizzle(row) = (row / P) % Q is the same for every block of a wavefront.
+    const int lrow_in_blk = lane / Q;
+    const int row0 = wave * RPB + lrow_in_blk;                 // first row this lane copies (A and B alike)
+    const int src_chunk_off = ((lane % Q) ^ ((row0 / P) % Q)) << 4;
+    const uint8_t* wsrc = g.w + ((int64_t)nt * g.n_stages) * (NR * KCB) + row0 * KCB + src_chunk_off;
+    const uint8_t* a_direct_src = g.a + (mt * MR + row0) * g.row_stride_bytes + src_chunk_off;
+    const uint32_t lds_wave = lds_base + wave * 1024;
 
-    uint4 ra[A_VEC], rb[B_VEC];
-    auto gload = [&](int s) {
+    auto issue = [&](int s) {
+        const uint32_t slot = lds_wave + (uint32_t)(s % NSTAGE) * SLOT;
         const int tap = s / g.stages_per_tap;
         const int cc = s - tap * g.stages_per_tap;
+        const uint8_t* asrc[A_VEC];      // all addresses first: the copies below are opaque to the scheduler
 #pragma unroll
         for (int j = 0; j < A_VEC; j++) {
-            const uint8_t* src;
             if constexpr (DIRECT) {
-                src = a_direct_base + (int64_t)(j * ROWS_PER_PASS) * g.row_stride_bytes + (int64_t)s * KCB;
+                asrc[j] = a_direct_src + (int64_t)(j * 4 * RPB) * g.row_stride_bytes + (int64_t)s * KCB;
             } else {
-                const int32_t e = ldsE[tap * MR + row0 + j * ROWS_PER_PASS];
+                const int32_t e = ldsE[tap * MR + row0 + j * 4 * RPB];
                 const uint8_t* rowp = e < 0 ? g.zero_row : g.a + (int64_t)e * g.row_stride_bytes;
-                src = rowp + cc * KCB + chunk * 16;
+                asrc[j] = rowp + cc * KCB + src_chunk_off;
             }
-            ra[j] = *(const uint4*)src;
         }
-        const uint8_t* ws = wtile + (int64_t)s * (NR * KCB);
 #pragma unroll
-        for (int j = 0; j < B_VEC; j++) rb[j] = *(const uint4*)(ws + j * 4096);
-    };
-    auto lstore = [&](int buf) {
-        uint8_t* A = ldsA + buf * (MR * KCB);
-        uint8_t* B = ldsB + buf * (NR * KCB);
+        for (int j = 0; j < A_VEC; j++) copy16_global_to_lds(asrc[j], slot + j * 4096);
+        const uint8_t* ws = wsrc + (int64_t)s * (NR * KCB);
 #pragma unroll
-        for (int j = 0; j < A_VEC; j++) *(uint4*)(A + a_lds_off[j]) = ra[j];
-#pragma unroll
-        for (int j = 0; j < B_VEC; j++) *(uint4*)(B + b_lds_off[j]) = rb[j];
+        for (int j = 0; j < B_VEC; j++) copy16_global_to_lds(ws + j * (4 * RPB * KCB), slot + MR * KCB + j * 4096);
     };
 
     // ---- fragment read offsets (per lane)
     const int lrow = lane & 31, lhalf = lane >> 5;
     const int swz = (lrow / P) % Q;          // tile bases are multiples of 32 rows, and 32 % (P*Q) == 0
     const uint32_t a_frag_base = (wm * MRW + lrow) * KCB;
-    const uint32_t b_frag_base = (wn * NRW + lrow) * KCB;
+    const uint32_t b_frag_base = MR * KCB + (wn * NRW + lrow) * KCB;
 
     acc_t acc[MB][NB];
 #pragma unroll
@@ -163,31 +181,31 @@ __global__ __launch_bounds__(256) void k_igemm_mfma(IgemmArgs g)
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[i][j][r] = 0;
 
-    gload(0);
-    lstore(0);
-    __syncthreads();
+    const int n_stages = g.n_stages;
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; s++)
+        if (s < n_stages) issue(s);
 
-    for (int s = 0; s < g.n_stages; s++) {
-        const int buf = s & 1;
-        const bool more = s + 1 < g.n_stages;
-        if (more) gload(s + 1);
-        const uint8_t* A = ldsA + buf * (MR * KCB);
-        const uint8_t* B = ldsB + buf * (NR * KCB);
+    for (int s = 0; s < n_stages; s++) {
+        // stage s has landed once at most the copies of the (up to NSTAGE-2) younger stages are outstanding
+        if (s + NSTAGE - 2 < n_stages) wait_vmcnt<(NSTAGE - 2) * L>();
+        else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();        // every wavefront's part of stage s is in LDS, and all are done with s-1
+        if (s + NSTAGE - 1 < n_stages) issue(s + NSTAGE - 1);      // refills the slot stage s-1 used
+        const uint8_t* S = lds + (s % NSTAGE) * SLOT;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ks++) {
             const uint32_t coff = (uint32_t)(((2 * ks + lhalf) ^ swz) << 4);
             uint4 af[MB], bf[NB];
 #pragma unroll
-            for (int i = 0; i < MB; i++) af[i] = *(const uint4*)(A + a_frag_base + i * 32 * KCB + coff);
+            for (int i = 0; i < MB; i++) af[i] = *(const uint4*)(S + a_frag_base + i * 32 * KCB + coff);
 #pragma unroll
-            for (int j = 0; j < NB; j++) bf[j] = *(const uint4*)(B + b_frag_base + j * 32 * KCB + coff);
+            for (int j = 0; j < NB; j++) bf[j] = *(const uint4*)(S + b_frag_base + j * 32 * KCB + coff);
 #pragma unroll
             for (int i = 0; i < MB; i++)
 #pragma unroll
                 for (int j = 0; j < NB; j++) acc[i][j] = mfma32<I8>(af[i], bf[j], acc[i][j]);
         }
-        if (more) lstore(buf ^ 1);
-        __syncthreads();
     }
 
     // ---- epilogue: accumulator register r of lane l holds row 8*(r/4) + 4*(l>>5) + (r&3), column l&31
@@ -209,10 +227,12 @@ __global__ __launch_bounds__(256) void k_igemm_mfma(IgemmArgs g)
 }
 
 // ------------------------------------------------------------------ launch
+constexpr int kRingDepth = 3;
+
 template <bool I8, int MR, int NR, int WM, int WN, int KCB, bool DIRECT>
 static int launch_one(const IgemmArgs& a, int64_t blocks, size_t lds_bytes, hipStream_t s)
 {
-    auto kern = k_igemm_mfma<I8, MR, NR, WM, WN, KCB, DIRECT>;
+    auto kern = k_igemm_mfma<I8, MR, NR, WM, WN, KCB, kRingDepth, DIRECT>;
     if (lds_bytes > 64 * 1024) {
         static bool raised = false;   // idempotent attribute; a race only repeats the call
         if (!raised) {
@@ -230,7 +250,7 @@ template <bool I8, int MR, int NR, int WM, int WN>
 static int launch_tile(const Geometry& g, const IgemmArgs& a, int64_t blocks, bool direct, hipStream_t s)
 {
     const size_t ent = direct ? 0 : (size_t)g.T * MR * 4;
-    const size_t lds = (size_t)2 * (MR + NR) * g.KCB + ent;
+    const size_t lds = (size_t)kRingDepth * (MR + NR) * g.KCB + ent;
     if (lds > 160 * 1024) return ICV_ERR_UNSUPPORTED;
     if (g.KCB == 128) {
         return direct ? launch_one<I8, MR, NR, WM, WN, 128, true>(a, blocks, lds, s)
