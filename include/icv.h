@@ -63,7 +63,10 @@ typedef struct icv_conv_params {
     int32_t out_pixel_stride;  /* elements between output pixels; 0 means K (ldc of Listing 3)                 */
     int32_t dtype;             /* icv_dtype */
     int32_t input_zero_point;  /* ICV_U8I8 only: the value the zero row holds, 0..255 */
-    int32_t plan;              /* 0: the library picks the tile shape; >0: force variant (tuning sweeps) */
+    int32_t plan;              /* 0: the library picks kernel, tile and pipeline shape.  For tuning sweeps:
+                                  bits 0-3 kernel (1 vector ALU, 2.. tile variant), bits 4-7 LDS ring depth (2..6),
+                                  bits 8-9 workgroups per CU (1, 2), bits 10-11 stage width (1: 64 B, 2: 128 B).
+                                  All set-up calls and the conv call of one problem must use the same value. */
 } icv_conv_params;
 
 /* Hout, Wout by the formula above.  ICV_ERR_INVALID_ARG when the parameters are not a valid problem. */

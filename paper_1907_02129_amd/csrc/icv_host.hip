@@ -43,7 +43,13 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     if (p->in_pixel_stride != 0 && p->in_pixel_stride < p->C) return ICV_ERR_INVALID_ARG;
     if (p->out_pixel_stride != 0 && p->out_pixel_stride < p->K) return ICV_ERR_INVALID_ARG;
     if (p->dtype == ICV_U8I8 && (p->input_zero_point < 0 || p->input_zero_point > 255)) return ICV_ERR_INVALID_ARG;
-    if (p->plan < 0 || p->plan > kNumTileVariants + 1) return ICV_ERR_INVALID_ARG;
+    // plan: bits 0-3 kernel (0 auto, 1 vector ALU, 2.. tile variant), bits 4-7 ring depth, bits 8-9 workgroups
+    // per CU, bits 10-11 stage width (1: 64 bytes, 2: 128 bytes); 0 in a field leaves the choice to the library
+    const int plan_kernel = p->plan & 15, plan_ring = (p->plan >> 4) & 15, plan_per_cu = (p->plan >> 8) & 3,
+              plan_kcb = (p->plan >> 10) & 3;
+    if (p->plan < 0 || p->plan >= (1 << 12) || plan_kernel > kNumTileVariants + 1 || plan_ring == 1 || plan_ring > 6 ||
+        plan_per_cu > 2 || plan_kcb > 2)
+        return ICV_ERR_INVALID_ARG;
 
     const int64_t Hout = out_extent(p->Hin, p->PT, p->PB, p->DY, p->R, p->SY);
     const int64_t Wout = out_extent(p->Win, p->PL, p->PR, p->DX, p->S, p->SX);
@@ -68,16 +74,16 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     const int64_t stride_bytes = (int64_t)g->in_stride * g->elem_bytes;
     bool mfma_ok = p->dtype != ICV_F32 && row_bytes % 64 == 0 && stride_bytes % 16 == 0;
     if (p->dtype == ICV_U8I8 && p->input_zero_point != 128) mfma_ok = false;   // x ^ 0x80 == x - 128 only
-    if (p->plan == 1) mfma_ok = false;                                          // forced vector-ALU kernel
+    if (plan_kernel == 1) mfma_ok = false;                                      // forced vector-ALU kernel
     int variant = -1;
     if (mfma_ok) {
-        if (p->plan >= 2) {
-            variant = p->plan - 2;
+        if (plan_kernel >= 2) {
+            variant = plan_kernel - 2;
         } else {
             variant = p->K <= 64 ? 0 : 1;
         }
-        // the workgroup keeps its tile's entries in LDS: MR*T int32
-        if ((int64_t)kTileVariants[variant].MR * T * 4 > 48 * 1024) mfma_ok = false;
+        // a workgroup keeps two tiles' worth of entries in LDS: 2 * MR*T int32 (plus padding)
+        if ((int64_t)kTileVariants[variant].MR * T * 4 > 24 * 1024) mfma_ok = false;
     }
     if (mfma_ok) {
         const TileVariant& tv = kTileVariants[variant];
@@ -86,6 +92,9 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         g->MR = tv.MR;
         g->NR = tv.NR;
         g->KCB = row_bytes % 128 == 0 ? 128 : 64;
+        if (plan_kcb == 1) g->KCB = 64;
+        g->ring = plan_ring;
+        g->blocks_per_cu = plan_per_cu;
         g->stages_per_tap = (int32_t)(row_bytes / g->KCB);
         g->taps_per_stage = 1;
         g->n_stages = g->T * g->stages_per_tap;
@@ -96,6 +105,8 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         g->MR = 64;
         g->NR = 64;
         g->KCB = 0;
+        g->ring = 0;
+        g->blocks_per_cu = 0;
         g->stages_per_tap = 1;
         g->taps_per_stage = 1;
         g->n_stages = g->T;

@@ -1,24 +1,34 @@
 // Tensor-core Indirect GEMM for gfx950 (section 2.2, Listing 3, re-designed around MFMA).
 //
-// A workgroup of four wavefronts owns an MR x NR output tile (MR output pixels x NR output channels, the
-// paper's micro-kernel tile scaled to a compute unit).  As in Listing 3 the reduction is two nested loops:
-// the outer one walks the R*S kernel elements and fetches the MR row pointers of the tile from the
-// indirection buffer, the inner one walks the C channels.  One pipeline stage covers one kernel element and
-// KCB bytes of its channels:
+// Listing 3 is kept as the shape of the computation: an MR x NR output tile (MR output pixels x NR output
+// channels, the paper's micro-kernel tile scaled up to a compute unit) accumulates over two nested loops --
+// the outer one walks the R*S kernel elements and fetches the tile's MR row pointers from the indirection
+// buffer, the inner one walks the C channels of the rows they name.  What changes is how it is executed:
 //
-//   A stage tile: MR gathered rows x KCB bytes.  Each row is read from the input tensor (or the zero row)
-//                 with coalesced 16-byte loads, lanes running along the channels first, and laid into LDS.
-//   B stage tile: NR filter rows x KCB bytes, one contiguous block of the pre-packed filter.
-//
-// Both tiles keep the reduction dimension contiguous, which is exactly the operand layout of
-// v_mfma_f32_32x32x16_bf16 / v_mfma_i32_32x32x32_i8: lane l supplies 16 contiguous bytes of row (l & 31),
-// byte offset 16*(l >> 5) inside a 32-byte k-step.  LDS rows are XOR-swizzled in 16-byte units so that the
-// ds_read_b128 fragment reads of 32 different rows spread over all banks.
-//
-// Pipeline: global loads of stage s+1 are issued into registers before the MFMAs of stage s and written to
-// the other LDS buffer after them; one barrier per stage.  The tile's indirection entries (MR * T int32,
-// contiguous thanks to the [tile][tap][row] order) are copied to LDS once at the start, so the
-// pointer -> data dependency never waits on HBM inside the loop.
+//  * Persistent workgroups.  The grid is sized to the chip (one or two workgroups per compute unit) and every
+//    workgroup walks a list of tiles.  The stages of all its tiles form one stream, so the next tile's
+//    operands are already in flight while the current tile is multiplied and stored; a convolution layer is
+//    a few microseconds of work, and per-tile start-up latency would otherwise dominate it.
+//  * Producer / consumer wavefronts.  A workgroup is eight wavefronts: four producers move data, four
+//    consumers run MFMA and store results.  A pipeline stage covers one kernel element and KCB bytes of its
+//    channels:
+//       A stage tile: MR gathered rows x KCB bytes, each row read from the input tensor (or the zero row)
+//                     with 16-byte pieces, lanes running along the channels first;
+//       B stage tile: NR filter rows x KCB bytes, one contiguous block of the pre-packed filter.
+//    Producers copy both straight from global memory into a ring of LDS slots (global_load_lds_dwordx4, no
+//    register stop) and run up to `ring - 1` stages ahead.  They count their own outstanding copies with
+//    s_waitcnt vmcnt; consumers never wait on memory except LDS, and their output stores never delay a load.
+//    One s_barrier per stage hands a filled slot to the consumers and a drained one back to the producers.
+//  * Both tiles keep the reduction dimension contiguous, which is the operand layout of
+//    v_mfma_f32_32x32x16_bf16 / v_mfma_i32_32x32x32_i8: lane l supplies 16 contiguous bytes of row (l & 31),
+//    byte offset 16*(l >> 5) inside a 32-byte k-step.  LDS rows are XOR-swizzled in 16-byte units so the
+//    ds_read_b128 fragment reads of 32 different rows spread over all banks; the swizzle is applied by
+//    choosing which source piece each lane copies, since a wavefront-wide copy fills 1 KB of LDS linearly.
+//  * The indirection entries of a tile (MR * T int32, contiguous thanks to the [tile][tap][row] order) are
+//    themselves copied to LDS one tile ahead, each producer fetching the quarter of the rows it serves, so the
+//    pointer -> data dependency of Listing 3 never waits on HBM inside the loop.
+//  * XCD-aware tile order: every XCD (own L2) gets one contiguous range of tiles, and its workgroups sweep it
+//    side by side, so neighbouring row tiles -- which share most input rows for a 3x3 kernel -- meet in L2.
 //
 // uint8 activations: MFMA multiplies signed bytes, so every A fragment is XORed with 0x80, which turns
 // x into x - 128 exactly; the zero row (filled with the zero point 128) becomes a row of zeros.
@@ -40,9 +50,13 @@ struct IgemmArgs {
     void* out;
     int64_t M;
     int64_t row_stride_bytes;  // input pixel stride | im2col row stride
+    int64_t total_tiles;       // m_tiles * n_tiles
     int32_t K, T, out_stride;
     int32_t stages_per_tap, n_stages;
     int32_t n_tiles;
+    int32_t ring;              // LDS slots in the ring, 2..6
+    int32_t ent_copies;        // wavefront-wide copies per producer per tile of entries
+    int32_t xcd_mode;          // 1: grid is a multiple of 8 and tiles are dealt per XCD
 };
 
 template <bool I8>
@@ -68,208 +82,329 @@ __device__ inline typename Acc<I8>::type mfma32(const uint4& a, const uint4& b, 
     }
 }
 
-// 16-byte global -> LDS copy without a register stop (global_load_lds_dwordx4): lane l of the wavefront
-// writes LDS bytes [lds_base + 16*l, +16).  Written as inline assembly on purpose: the compiler does not see
-// a memory instruction, so it inserts no waits of its own for it, and the kernel counts outstanding copies
-// itself with wait_vmcnt<>.  While such copies are in flight the kernel issues no other vector-memory
-// instruction, which keeps the compiler's own counter bookkeeping valid.
+// 16-byte global -> LDS copy without a register stop: lane l of the wavefront writes LDS bytes
+// [lds_base + 16*l, +16).  Inline assembly on purpose: the compiler does not see a memory instruction, so it
+// inserts no waits of its own for it, and the producers count outstanding copies themselves (wait_vmcnt).
+// A producer issues no other vector-memory instruction while copies are in flight.
 __device__ inline void copy16_global_to_lds(const void* gptr, uint32_t lds_base)
 {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n"
                  :
                  : "v"(gptr), "s"(lds_base)
-                 : "memory", "m0");
+                 : "memory");
 }
 
 template <int N>
 __device__ inline void wait_vmcnt()
 {
+    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
-// XCD-aware block -> tile map.  Workgroups are dealt round-robin to the 8 XCDs (block b lands on XCD b % 8),
-// each with its own L2.  Giving every XCD one contiguous range of tiles keeps neighbouring row tiles --
-// which for a 3x3 kernel share most of their input rows -- and all column tiles of a row tile in one L2.
-__device__ inline int64_t xcd_tile(int64_t b, int64_t n_blocks)
+// Wait until at most `stages` x LP of this wavefront's copies are outstanding (copies retire in order).
+template <int LP>
+__device__ inline void wait_all_but_stages(int stages)
 {
-    const int64_t chunk = n_blocks >> 3, rem = n_blocks & 7, x = b & 7;
-    return x * chunk + (x < rem ? x : rem) + (b >> 3);
+    switch (stages) {
+        case 0: wait_vmcnt<0>(); break;
+        case 1: wait_vmcnt<LP>(); break;
+        case 2: wait_vmcnt<2 * LP>(); break;
+        case 3: wait_vmcnt<3 * LP>(); break;
+        default: wait_vmcnt<4 * LP>(); break;
+    }
 }
 
-template <bool I8, int MR, int NR, int WM, int WN, int KCB, int NSTAGE, bool DIRECT>
-__global__ __launch_bounds__(256) void k_igemm_mfma(IgemmArgs g)
+// Tile list of a persistent workgroup.  Workgroups are dealt round-robin to the 8 XCDs (block b runs on
+// XCD b % 8).  In XCD mode XCD x owns the contiguous tile range [first, first + count) and its G/8 workgroups
+// take tiles first + i, first + i + G/8, ... ; otherwise block b takes b, b + G, ...
+struct TileList {
+    int64_t first, step, count;   // tiles first + k*step for k < count
+};
+
+__device__ inline TileList my_tiles(int64_t total, int xcd_mode)
 {
-    static_assert(WM * WN == 4, "four wavefronts per workgroup");
-    static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring depth");
-    constexpr int Q = KCB / 16;          // 16-byte chunks per row per stage
-    constexpr int P = 256 / KCB;         // rows per 256 bytes of LDS
-    constexpr int RPB = 1024 / KCB;      // rows one wavefront-wide copy (64 x 16 B) covers
-    constexpr int A_VEC = MR * KCB / 4096;   // copies per wavefront per stage, A tile
+    const int64_t b = blockIdx.x, G = gridDim.x;
+    TileList t;
+    if (xcd_mode) {
+        const int64_t chunk = total >> 3, rem = total & 7, x = b & 7;
+        const int64_t start = x * chunk + (x < rem ? x : rem);
+        const int64_t len = chunk + (x < rem ? 1 : 0);
+        const int64_t i = b >> 3;
+        t.step = G >> 3;
+        t.first = start + i;
+        t.count = i < len ? (len - i + t.step - 1) / t.step : 0;
+    } else {
+        t.step = G;
+        t.first = b;
+        t.count = b < total ? (total - b + G - 1) / G : 0;
+    }
+    return t;
+}
+
+template <bool I8, int MR, int NR, int WM, int WN, int KCB, bool DIRECT>
+__global__ __launch_bounds__(512) void k_igemm_mfma(IgemmArgs g)
+{
+    static_assert(WM * WN == 4, "four consumer wavefronts per workgroup");
+    constexpr int Q = KCB / 16;              // 16-byte chunks per row per stage
+    constexpr int P = 256 / KCB;             // rows per 256 bytes of LDS
+    constexpr int RPB = 1024 / KCB;          // rows one wavefront-wide copy (64 x 16 B) covers
+    constexpr int A_VEC = MR * KCB / 4096;   // copies per producer per stage, A tile (a quarter of its rows)
     constexpr int B_VEC = NR * KCB / 4096;   // ... B tile
-    constexpr int L = A_VEC + B_VEC;
+    constexpr int LP = A_VEC + B_VEC;
     constexpr int MRW = MR / WM, NRW = NR / WN;
     constexpr int MB = MRW / 32, NB = NRW / 32;
     constexpr int KSTEPS = KCB / 32;
     constexpr int SLOT = (MR + NR) * KCB;    // bytes of one ring slot: A tile then B tile
+    constexpr int EQ = MR / 4;               // rows (entries per tap) one producer serves
+    constexpr int TPC = 256 / EQ;            // taps one wavefront-wide entry copy covers (EQ*4 bytes per tap)
     static_assert(A_VEC >= 1 && B_VEC >= 1 && MB >= 1 && NB >= 1, "tile too small");
-    static_assert((NSTAGE - 1) * L <= 63, "vmcnt is a 6-bit counter");
+    static_assert(4 * LP <= 63, "vmcnt is a 6-bit counter");
+    static_assert(EQ % 16 == 0, "a producer's rows must keep the swizzle phase");
     using acc_t = typename Acc<I8>::type;
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    int32_t* ldsE = (int32_t*)(lds + NSTAGE * SLOT);          // [T][MR]
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
+    const int D = g.ring;
+    const int ent_bytes_per_producer = g.ent_copies * 1024;          // one parity
+    const int ent_base = D * SLOT;                                   // [parity][producer][tap][EQ] int32
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WN, wn = wave % WN;
-    const int64_t tile = xcd_tile(blockIdx.x, gridDim.x);
-    const int32_t nt = (int32_t)(tile % g.n_tiles);
-    const int64_t mt = tile / g.n_tiles;
+    const TileList tl = my_tiles(g.total_tiles, g.xcd_mode);
+    const int n_stages = g.n_stages;
+    const int64_t total_stages = tl.count * n_stages;                // same value in every wavefront
 
-    // ---- tile's indirection entries -> LDS (Listing 3 reads them in exactly this order)
-    if constexpr (!DIRECT) {
-        const int4* src = (const int4*)(g.ind + mt * ((int64_t)g.T * MR));
-        const int n4 = g.T * MR / 4;
-        for (int i = tid; i < n4; i += 256) ((int4*)ldsE)[i] = src[i];
-        __syncthreads();
-    }
+    if (wave >= 4) {
+        // =============================================================== producer
+        const int p = wave - 4;
+        const int lrow_in_blk = lane / Q;
+        const uint32_t my_ent = ent_base + p * ent_bytes_per_producer;     // parity 0; parity 1 is 4x further
+        const int ent_parity_stride = 4 * ent_bytes_per_producer;
 
-    // ---- copy slots of this lane: wavefront w moves 1 KB blocks b = w, w+4, ... of a stage tile; block b is
-    // rows [b*RPB, +RPB); lane l fills LDS chunk (l % Q) of row b*RPB + l/Q, which must hold source chunk
-    // (l % Q) ^ swizzle(row).  swizzle(row) = (row / P) % Q is the same for every block of a wavefront.
-    const int lrow_in_blk = lane / Q;
-    const int row0 = wave * RPB + lrow_in_blk;                 // first row this lane copies (A and B alike)
-    const int src_chunk_off = ((lane % Q) ^ ((row0 / P) % Q)) << 4;
-    const uint8_t* wsrc = g.w + ((int64_t)nt * g.n_stages) * (NR * KCB) + row0 * KCB + src_chunk_off;
-    const uint8_t* a_direct_src = g.a + (mt * MR + row0) * g.row_stride_bytes + src_chunk_off;
-    const uint32_t lds_wave = lds_base + wave * 1024;
-
-    auto issue = [&](int s) {
-        const uint32_t slot = lds_wave + (uint32_t)(s % NSTAGE) * SLOT;
-        const int tap = s / g.stages_per_tap;
-        const int cc = s - tap * g.stages_per_tap;
-        const uint8_t* asrc[A_VEC];      // all addresses first: the copies below are opaque to the scheduler
+        // source piece of each copy: LDS chunk (lane % Q) of row r must hold source chunk (lane % Q) ^ swz(r)
+        int a_src_off[A_VEC];
 #pragma unroll
         for (int j = 0; j < A_VEC; j++) {
-            if constexpr (DIRECT) {
-                asrc[j] = a_direct_src + (int64_t)(j * 4 * RPB) * g.row_stride_bytes + (int64_t)s * KCB;
-            } else {
-                const int32_t e = ldsE[tap * MR + row0 + j * 4 * RPB];
-                const uint8_t* rowp = e < 0 ? g.zero_row : g.a + (int64_t)e * g.row_stride_bytes;
-                asrc[j] = rowp + cc * KCB + src_chunk_off;
-            }
+            const int row = p * EQ + j * RPB + lrow_in_blk;
+            a_src_off[j] = ((lane % Q) ^ ((row / P) % Q)) << 4;
         }
+        int b_src_off[B_VEC];
 #pragma unroll
-        for (int j = 0; j < A_VEC; j++) copy16_global_to_lds(asrc[j], slot + j * 4096);
-        const uint8_t* ws = wsrc + (int64_t)s * (NR * KCB);
-#pragma unroll
-        for (int j = 0; j < B_VEC; j++) copy16_global_to_lds(ws + j * (4 * RPB * KCB), slot + MR * KCB + j * 4096);
-    };
+        for (int j = 0; j < B_VEC; j++) {
+            const int row = (p * B_VEC + j) * RPB + lrow_in_blk;
+            b_src_off[j] = row * KCB + (((lane % Q) ^ ((row / P) % Q)) << 4);
+        }
 
-    // ---- fragment read offsets (per lane)
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    const int swz = (lrow / P) % Q;          // tile bases are multiples of 32 rows, and 32 % (P*Q) == 0
-    const uint32_t a_frag_base = (wm * MRW + lrow) * KCB;
-    const uint32_t b_frag_base = MR * KCB + (wn * NRW + lrow) * KCB;
+        auto fetch_entries = [&](int64_t k) {      // entries of my k-th tile -> ENT[k & 1]
+            if constexpr (!DIRECT) {
+                if (k >= tl.count) return;
+                const int64_t mt = (tl.first + k * tl.step) / g.n_tiles;
+                const int32_t* src = g.ind + mt * ((int64_t)g.T * MR) + p * EQ + (lane % (EQ / 4)) * 4;
+                const uint32_t dst = lds_base + my_ent + (uint32_t)(k & 1) * ent_parity_stride;
+                for (int c = 0; c < g.ent_copies; c++) {
+                    const int tap = c * TPC + lane / (EQ / 4);
+                    if (tap < g.T) copy16_global_to_lds(src + (int64_t)tap * MR, dst + c * 1024);
+                }
+            }
+        };
 
-    acc_t acc[MB][NB];
+        // issue cursor: next stage to copy
+        int64_t ik = 0;          // tile index in my list
+        int is = 0;              // stage within the tile
+        int islot = 0;
+        auto issue_next = [&]() {
+            if (ik >= tl.count) return;
+            const int64_t tile = tl.first + ik * tl.step;
+            const int32_t nt = (int32_t)(tile % g.n_tiles);
+            const int64_t mt = tile / g.n_tiles;
+            const uint32_t slot = lds_base + (uint32_t)islot * SLOT;
+            const uint8_t* asrc[A_VEC];
+            if constexpr (DIRECT) {
 #pragma unroll
-    for (int i = 0; i < MB; i++)
+                for (int j = 0; j < A_VEC; j++)
+                    asrc[j] = g.a + (mt * MR + p * EQ + j * RPB + lrow_in_blk) * g.row_stride_bytes +
+                              (int64_t)is * KCB + a_src_off[j];
+            } else {
+                const int tap = is / g.stages_per_tap;
+                const int cc = is - tap * g.stages_per_tap;
+                const int32_t* ent = (const int32_t*)(lds + my_ent + (int)(ik & 1) * ent_parity_stride) + tap * EQ;
 #pragma unroll
-        for (int j = 0; j < NB; j++)
+                for (int j = 0; j < A_VEC; j++) {
+                    const int32_t e = ent[j * RPB + lrow_in_blk];
+                    const uint8_t* rowp = e < 0 ? g.zero_row : g.a + (int64_t)e * g.row_stride_bytes;
+                    asrc[j] = rowp + cc * KCB + a_src_off[j];
+                }
+            }
 #pragma unroll
-            for (int r = 0; r < 16; r++) acc[i][j][r] = 0;
+            for (int j = 0; j < A_VEC; j++) copy16_global_to_lds(asrc[j], slot + (p * A_VEC + j) * 1024);
+            const uint8_t* ws = g.w + ((int64_t)nt * n_stages + is) * (NR * KCB);
+#pragma unroll
+            for (int j = 0; j < B_VEC; j++)
+                copy16_global_to_lds(ws + b_src_off[j], slot + MR * KCB + (p * B_VEC + j) * 1024);
+            islot = islot + 1 == D ? 0 : islot + 1;
+            if (++is == n_stages) {
+                // all stages of tile ik are issued: its entry buffer is free for the tile after next
+                is = 0;
+                fetch_entries(ik + 2);
+                ++ik;
+                // entries of tile ik were fetched a whole tile of stages ago; only a reduction shorter than
+                // the ring can get here before a later wait has covered them
+                if (n_stages < D - 1) wait_vmcnt<0>();
+            }
+        };
 
-    const int n_stages = g.n_stages;
-#pragma unroll
-    for (int s = 0; s < NSTAGE - 1; s++)
-        if (s < n_stages) issue(s);
+        fetch_entries(0);
+        wait_vmcnt<0>();
+        fetch_entries(1);
+        for (int q = 0; q < D - 1; q++) issue_next();
+        for (int64_t q = 0; q < total_stages; q++) {
+            // stage q has landed once only the copies of younger stages (at most D-2 of them) are outstanding
+            const int64_t younger = total_stages - 1 - q;
+            wait_all_but_stages<LP>(younger < D - 2 ? (int)younger : D - 2);
+            __builtin_amdgcn_s_barrier();     // hand stage q to the consumers; they are done with stage q-1
+            issue_next();                     // stage q + D - 1 refills the slot stage q - 1 used
+        }
+        wait_vmcnt<0>();
+    } else {
+        // =============================================================== consumer
+        const int wm = wave / WN, wn = wave % WN;
+        const int lrow = lane & 31, lhalf = lane >> 5;
+        const int swz = (lrow / P) % Q;          // tile bases are multiples of 32 rows, and 32 % (P*Q) == 0
+        const uint32_t a_frag_base = (wm * MRW + lrow) * KCB;
+        const uint32_t b_frag_base = MR * KCB + (wn * NRW + lrow) * KCB;
+        using out_t = typename std::conditional<I8, int32_t, float>::type;
+        out_t* out = (out_t*)g.out;
 
-    for (int s = 0; s < n_stages; s++) {
-        // stage s has landed once at most the copies of the (up to NSTAGE-2) younger stages are outstanding
-        if (s + NSTAGE - 2 < n_stages) wait_vmcnt<(NSTAGE - 2) * L>();
-        else wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();        // every wavefront's part of stage s is in LDS, and all are done with s-1
-        if (s + NSTAGE - 1 < n_stages) issue(s + NSTAGE - 1);      // refills the slot stage s-1 used
-        const uint8_t* S = lds + (s % NSTAGE) * SLOT;
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ks++) {
-            const uint32_t coff = (uint32_t)(((2 * ks + lhalf) ^ swz) << 4);
-            uint4 af[MB], bf[NB];
-#pragma unroll
-            for (int i = 0; i < MB; i++) af[i] = *(const uint4*)(S + a_frag_base + i * 32 * KCB + coff);
-#pragma unroll
-            for (int j = 0; j < NB; j++) bf[j] = *(const uint4*)(S + b_frag_base + j * 32 * KCB + coff);
+        int slot = 0;
+        for (int64_t k = 0; k < tl.count; k++) {
+            acc_t acc[MB][NB];
 #pragma unroll
             for (int i = 0; i < MB; i++)
 #pragma unroll
-                for (int j = 0; j < NB; j++) acc[i][j] = mfma32<I8>(af[i], bf[j], acc[i][j]);
+                for (int j = 0; j < NB; j++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) acc[i][j][r] = 0;
+
+            for (int s = 0; s < n_stages; s++) {
+                __builtin_amdgcn_s_barrier();
+                const uint8_t* S = lds + slot * SLOT;
+                slot = slot + 1 == D ? 0 : slot + 1;
+#pragma unroll
+                for (int ks = 0; ks < KSTEPS; ks++) {
+                    const uint32_t coff = (uint32_t)(((2 * ks + lhalf) ^ swz) << 4);
+                    uint4 af[MB], bf[NB];
+#pragma unroll
+                    for (int i = 0; i < MB; i++) af[i] = *(const uint4*)(S + a_frag_base + i * 32 * KCB + coff);
+#pragma unroll
+                    for (int j = 0; j < NB; j++) bf[j] = *(const uint4*)(S + b_frag_base + j * 32 * KCB + coff);
+#pragma unroll
+                    for (int i = 0; i < MB; i++)
+#pragma unroll
+                        for (int j = 0; j < NB; j++) acc[i][j] = mfma32<I8>(af[i], bf[j], acc[i][j]);
+                }
+            }
+
+            // epilogue: accumulator register r of lane l holds row 8*(r/4) + 4*(l>>5) + (r&3), column l&31
+            const int64_t tile = tl.first + k * tl.step;
+            const int32_t nt = (int32_t)(tile % g.n_tiles);
+            const int64_t mt = tile / g.n_tiles;
+            const int64_t m_base = mt * MR + wm * MRW + 4 * lhalf;
+            const int32_t n_base = nt * NR + wn * NRW + lrow;
+#pragma unroll
+            for (int i = 0; i < MB; i++)
+#pragma unroll
+                for (int j = 0; j < NB; j++) {
+                    const int32_t col = n_base + j * 32;
+#pragma unroll
+                    for (int r = 0; r < 16; r++) {
+                        const int64_t row = m_base + i * 32 + 8 * (r >> 2) + (r & 3);
+                        if (row < g.M && col < g.K) out[row * g.out_stride + col] = acc[i][j][r];
+                    }
+                }
         }
     }
-
-    // ---- epilogue: accumulator register r of lane l holds row 8*(r/4) + 4*(l>>5) + (r&3), column l&31
-    using out_t = typename std::conditional<I8, int32_t, float>::type;
-    out_t* out = (out_t*)g.out;
-    const int64_t m_base = mt * MR + wm * MRW + 4 * lhalf;
-    const int32_t n_base = nt * NR + wn * NRW + lrow;
-#pragma unroll
-    for (int i = 0; i < MB; i++)
-#pragma unroll
-        for (int j = 0; j < NB; j++) {
-            const int32_t col = n_base + j * 32;
-#pragma unroll
-            for (int r = 0; r < 16; r++) {
-                const int64_t row = m_base + i * 32 + 8 * (r >> 2) + (r & 3);
-                if (row < g.M && col < g.K) out[row * g.out_stride + col] = acc[i][j][r];
-            }
-        }
 }
 
 // ------------------------------------------------------------------ launch
-constexpr int kRingDepth = 3;
+static int device_cu_count()
+{
+    static int cached[64] = {0};      // per device ordinal; filled on first use, the value never changes
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+constexpr size_t kLdsPerCu = 160 * 1024;
 
 template <bool I8, int MR, int NR, int WM, int WN, int KCB, bool DIRECT>
-static int launch_one(const IgemmArgs& a, int64_t blocks, size_t lds_bytes, hipStream_t s)
+static int launch_one(const Geometry& g, IgemmArgs a, hipStream_t s)
 {
-    auto kern = k_igemm_mfma<I8, MR, NR, WM, WN, KCB, kRingDepth, DIRECT>;
+    auto kern = k_igemm_mfma<I8, MR, NR, WM, WN, KCB, DIRECT>;
+    constexpr size_t slot = (size_t)(MR + NR) * KCB;
+    constexpr int tpc = 256 / (MR / 4);
+    a.ent_copies = DIRECT ? 0 : (g.T + tpc - 1) / tpc;
+    const size_t ent = (size_t)2 * 4 * a.ent_copies * 1024;
+    // ring depth and workgroups per CU: two co-resident workgroups when each can still have >= 3 slots,
+    // otherwise one workgroup with as deep a ring as fits (at most 6 slots)
+    int per_cu = g.blocks_per_cu, ring = g.ring;
+    if (per_cu == 0) per_cu = (kLdsPerCu / 2 >= ent + 3 * slot) ? 2 : 1;
+    const size_t budget = kLdsPerCu / per_cu;
+    if (budget < ent + 2 * slot) return ICV_ERR_UNSUPPORTED;
+    const int fit = (int)((budget - ent) / slot);
+    if (ring == 0) ring = fit;
+    if (ring > fit) ring = fit;
+    if (ring > 6) ring = 6;
+    if (ring < 2) return ICV_ERR_UNSUPPORTED;
+    a.ring = ring;
+    const size_t lds_bytes = ent + (size_t)ring * slot;
+
+    int64_t grid = (int64_t)device_cu_count() * per_cu;
+    if (grid > a.total_tiles) grid = a.total_tiles;
+    a.xcd_mode = 0;
+    if (grid >= 8 && a.total_tiles >= 8) {
+        grid -= grid % 8;
+        a.xcd_mode = 1;
+    }
     if (lds_bytes > 64 * 1024) {
         static bool raised = false;   // idempotent attribute; a race only repeats the call
         if (!raised) {
             ICV_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                              160 * 1024));
+                                              (int)kLdsPerCu));
             raised = true;
         }
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds_bytes, s, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), lds_bytes, s, a);
     ICV_HIP_CHECK(hipGetLastError());
     return ICV_OK;
 }
 
 template <bool I8, int MR, int NR, int WM, int WN>
-static int launch_tile(const Geometry& g, const IgemmArgs& a, int64_t blocks, bool direct, hipStream_t s)
+static int launch_tile(const Geometry& g, const IgemmArgs& a, bool direct, hipStream_t s)
 {
-    const size_t ent = direct ? 0 : (size_t)g.T * MR * 4;
-    const size_t lds = (size_t)kRingDepth * (MR + NR) * g.KCB + ent;
-    if (lds > 160 * 1024) return ICV_ERR_UNSUPPORTED;
     if (g.KCB == 128) {
-        return direct ? launch_one<I8, MR, NR, WM, WN, 128, true>(a, blocks, lds, s)
-                      : launch_one<I8, MR, NR, WM, WN, 128, false>(a, blocks, lds, s);
+        return direct ? launch_one<I8, MR, NR, WM, WN, 128, true>(g, a, s)
+                      : launch_one<I8, MR, NR, WM, WN, 128, false>(g, a, s);
     }
-    return direct ? launch_one<I8, MR, NR, WM, WN, 64, true>(a, blocks, lds, s)
-                  : launch_one<I8, MR, NR, WM, WN, 64, false>(a, blocks, lds, s);
+    return direct ? launch_one<I8, MR, NR, WM, WN, 64, true>(g, a, s)
+                  : launch_one<I8, MR, NR, WM, WN, 64, false>(g, a, s);
 }
 
 template <bool I8>
-static int launch_dtype(const Geometry& g, const IgemmArgs& a, int64_t blocks, bool direct, hipStream_t s)
+static int launch_dtype(const Geometry& g, const IgemmArgs& a, bool direct, hipStream_t s)
 {
     switch (g.variant) {
-        case 0: return launch_tile<I8, 128, 64, 2, 2>(g, a, blocks, direct, s);
-        case 1: return launch_tile<I8, 128, 128, 2, 2>(g, a, blocks, direct, s);
-        case 2: return launch_tile<I8, 128, 64, 4, 1>(g, a, blocks, direct, s);
-        case 3: return launch_tile<I8, 256, 64, 4, 1>(g, a, blocks, direct, s);
-        case 4: return launch_tile<I8, 256, 128, 2, 2>(g, a, blocks, direct, s);
-        case 5: return launch_tile<I8, 64, 64, 2, 2>(g, a, blocks, direct, s);
+        case 0: return launch_tile<I8, 128, 64, 2, 2>(g, a, direct, s);
+        case 1: return launch_tile<I8, 128, 128, 2, 2>(g, a, direct, s);
+        case 2: return launch_tile<I8, 128, 64, 4, 1>(g, a, direct, s);
+        case 3: return launch_tile<I8, 256, 64, 4, 1>(g, a, direct, s);
+        case 4: return launch_tile<I8, 256, 128, 2, 2>(g, a, direct, s);
+        case 5: return launch_tile<I8, 64, 64, 2, 2>(g, a, direct, s);
         default: return ICV_ERR_UNSUPPORTED;
     }
 }
@@ -288,13 +423,12 @@ int launch_igemm_mfma(const icv_conv_params* p, const Geometry& g, const void* i
     a.out = out;
     a.M = g.M;
     a.row_stride_bytes = a_direct ? (int64_t)g.T * p->C * g.elem_bytes : (int64_t)g.in_stride * g.elem_bytes;
+    a.total_tiles = g.m_tiles * g.n_tiles;
     a.K = p->K; a.T = g.T; a.out_stride = g.out_stride;
     a.stages_per_tap = g.stages_per_tap; a.n_stages = g.n_stages;
     a.n_tiles = (int32_t)g.n_tiles;
-    const int64_t blocks = g.m_tiles * g.n_tiles;
-    if (blocks > 0x7fffffffll) return ICV_ERR_UNSUPPORTED;
-    return p->dtype == ICV_U8I8 ? launch_dtype<true>(g, a, blocks, a_direct, s)
-                                : launch_dtype<false>(g, a, blocks, a_direct, s);
+    a.ring = 0; a.ent_copies = 0; a.xcd_mode = 0;
+    return p->dtype == ICV_U8I8 ? launch_dtype<true>(g, a, a_direct, s) : launch_dtype<false>(g, a, a_direct, s);
 }
 
 }  // namespace icv

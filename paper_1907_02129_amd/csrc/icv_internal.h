@@ -31,6 +31,8 @@ struct Geometry {
     int32_t taps_per_stage;  // 1                                | KCB / 8 (LOWC)
     int32_t n_stages;        // pipeline stages in the reduction
     int64_t m_tiles, n_tiles;
+    int32_t ring;            // forced LDS ring depth (0: launcher decides)
+    int32_t blocks_per_cu;   // forced co-resident workgroups per CU (0: launcher decides)
     const char* name;
 };
 
