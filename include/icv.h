@@ -88,7 +88,7 @@ ICV_API size_t icv_im2col_bytes(const icv_conv_params* p);
  * Where the entry of output pixel m = (n*Hout + oy)*Wout + ox and kernel element tap = ky*S + kx sits in
  * the indirection buffer (index in int32 units).  The physical order is [row tile][tap][row in tile], the
  * order in which Listing 3 consumes pointers (*ppa++: all rows of the tile for one tap, then the next tap).
- * Rows past M in the last tile hold -1.  Returns -1 on invalid arguments.
+ * Rows past M in the last tile name the zero row.  Returns -1 on invalid arguments.
  */
 ICV_API int64_t icv_indirection_index(const icv_conv_params* p, int64_t m, int32_t tap);
 
@@ -103,18 +103,19 @@ ICV_API int icv_init_zero_row(const icv_conv_params* p, void* zero_row, void* st
 ICV_API int icv_pack_filter(const icv_conv_params* p, const void* filter_krsc, void* packed, void* stream);
 
 /*
- * Build the indirection buffer (section 2.3).  Entry = index of the input pixel (n*Hin + iy)*Win + ix, so
- * that the row starts at input + entry * in_pixel_stride elements, or -1 for "the zero row".  Storing an
- * index instead of the paper's raw pointer keeps the buffer valid when the input or zero-row pointers
- * change (the paper's fourth invalidation rule then never applies); it must be rebuilt only when the shape,
- * stride, dilation, padding or batch size change.  Requires N*Hin*Win < 2^31.
+ * Build the indirection buffer (section 2.3).  Entry = byte offset of the input pixel's row from the input
+ * base, ((n*Hin + iy)*Win + ix) * in_pixel_stride * sizeof(element), or INT32_MIN for "the zero row": the
+ * paper's row pointer minus the tensor's base pointer.  Storing offsets keeps the buffer valid when the
+ * input or zero-row pointers change (the paper's fourth invalidation rule then never applies); it must be
+ * rebuilt only when the shape, stride, dilation, padding, pixel stride, element type or batch size change.
+ * The input tensor must be smaller than 2 GiB (ICV_ERR_INVALID_ARG otherwise).
  *   indirection: icv_indirection_bytes() device.
  */
 ICV_API int icv_setup_indirection(const icv_conv_params* p, void* indirection, void* stream);
 
 /*
  * The Indirect GEMM (section 2.2): output = conv(input, filter) with rows of A gathered through the
- * indirection buffer; entries < 0 read `zero_row`.  alpha = 1, beta = 0: the output is overwritten.
+ * indirection buffer; negative entries read `zero_row`.  alpha = 1, beta = 0: the output is overwritten.
  *   input        : [N][Hin][Win] pixels of in_pixel_stride elements (first C used)
  *   packed_filter: from icv_pack_filter with the same params
  *   indirection  : from icv_setup_indirection with the same params

@@ -231,7 +231,8 @@ def run(buf: ConvBuffers, input_dev: torch.Tensor) -> torch.Tensor:
 
 
 def logical_indirection(buf: ConvBuffers) -> np.ndarray:
-    """The buffer re-ordered to [M][R*S] through icv_indirection_index (host side, for tests)."""
+    """The buffer re-ordered to [M][R*S] through icv_indirection_index, with the byte offsets turned back
+    into pixel indices (-1 = zero row); host side, for tests.  Returns (rows < M, tile-padding rows)."""
     p = buf.p
     T = p.R * p.S
     phys = buf.indirection.cpu().numpy()
@@ -240,4 +241,8 @@ def logical_indirection(buf: ConvBuffers) -> np.ndarray:
     tiles = len(phys) // (mr * T)
     assert indirection_index(p, mr, 0) in (-1, mr * T) and indirection_index(p, 1, 0) == 1
     logical = phys.reshape(tiles, T, mr).transpose(0, 2, 1).reshape(tiles * mr, T)
+    stride_bytes = (p.in_pixel_stride or p.C) * {ICV_F32: 4, ICV_BF16: 2, ICV_U8I8: 1}[p.dtype]
+    assert np.all((logical >= 0) | (logical == np.iinfo(np.int32).min))
+    assert np.all(logical[logical >= 0] % stride_bytes == 0)
+    logical = np.where(logical < 0, -1, logical // stride_bytes).astype(np.int32)
     return logical[:buf.M], logical[buf.M:]

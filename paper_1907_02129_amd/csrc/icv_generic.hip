@@ -2,7 +2,7 @@
 // multiple of the MFMA k-granule, unaligned pixel strides, zero points other than 128).
 //
 // It is Listing 3 with one output element per thread: for each kernel element load the row pointer from
-// the indirection buffer (entry < 0 -> the zero row), take the C-long dot product with the filter row,
+// the indirection buffer (entry = byte offset from the input base; < 0 -> the zero row), take the C-long dot product with the filter row,
 // accumulate.  A block is 4 output pixels x 64 output channels; the 64 lanes of a wavefront share the
 // A row (a broadcast read) and differ in the filter row.
 #include <type_traits>
@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256) void k_igemm_generic(GenericArgs g)
             row = in + (m * g.T + t) * (int64_t)g.C;
         } else {
             const int32_t e = ent[(int64_t)t * 64];
-            row = e < 0 ? (const TIn*)g.zero_row : in + (int64_t)e * g.in_stride;
+            row = e < 0 ? (const TIn*)g.zero_row : (const TIn*)((const uint8_t*)in + e);   // byte offset entry
         }
         const TW* wr = w + (int64_t)t * g.C;
         for (int32_t c = 0; c < g.C; c++) {

@@ -9,12 +9,16 @@ void set_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
 // Tile variants of the tensor-core kernel: workgroup tile MR x NR, split over a WM x WN grid of
 // wavefronts.  Index + 1 is what icv_conv_params::plan selects.
 const TileVariant kTileVariants[] = {
-    {128, 64, 2, 2, "128x64_w2x2"},
-    {128, 128, 2, 2, "128x128_w2x2"},
-    {128, 64, 4, 1, "128x64_w4x1"},
-    {256, 64, 4, 1, "256x64_w4x1"},
-    {256, 128, 2, 2, "256x128_w2x2"},
-    {64, 64, 2, 2, "64x64_w2x2"},
+    {128, 64, 2, 2, "128x64_c2x2_p4"},
+    {128, 128, 2, 2, "128x128_c2x2_p4"},
+    {128, 64, 4, 2, "128x64_c4x2_p4"},
+    {256, 64, 4, 2, "256x64_c4x2_p8"},
+    {256, 128, 2, 2, "256x128_c2x2_p4"},
+    {64, 64, 2, 2, "64x64_c2x2_p4"},
+    {256, 128, 4, 2, "256x128_c4x2_p8"},
+    {128, 128, 4, 2, "128x128_c4x2_p8"},
+    {256, 128, 4, 2, "256x128_c4x2_p4"},
+    {128, 128, 2, 2, "128x128_c2x2_p8"},
 };
 const int kNumTileVariants = (int)(sizeof(kTileVariants) / sizeof(kTileVariants[0]));
 
@@ -24,12 +28,14 @@ static int64_t out_extent(int64_t in, int64_t lo, int64_t hi, int64_t dil, int64
     return span < 0 ? 0 : span / stride + 1;
 }
 
-static const char* plan_names[3][8] = {
-    {"generic_f32"},
-    {"generic_bf16", "mfma_bf16_128x64_w2x2", "mfma_bf16_128x128_w2x2", "mfma_bf16_128x64_w4x1",
-     "mfma_bf16_256x64_w4x1", "mfma_bf16_256x128_w2x2", "mfma_bf16_64x64_w2x2"},
-    {"generic_u8i8", "mfma_i8_128x64_w2x2", "mfma_i8_128x128_w2x2", "mfma_i8_128x64_w4x1",
-     "mfma_i8_256x64_w4x1", "mfma_i8_256x128_w2x2", "mfma_i8_64x64_w2x2"},
+static const char* kGenericNames[3] = {"generic_f32", "generic_bf16", "generic_u8i8"};
+static const char* kMfmaNames[2][10] = {
+    {"mfma_bf16_128x64_c2x2_p4", "mfma_bf16_128x128_c2x2_p4", "mfma_bf16_128x64_c4x2_p4", "mfma_bf16_256x64_c4x2_p8",
+     "mfma_bf16_256x128_c2x2_p4", "mfma_bf16_64x64_c2x2_p4", "mfma_bf16_256x128_c4x2_p8", "mfma_bf16_128x128_c4x2_p8",
+     "mfma_bf16_256x128_c4x2_p4", "mfma_bf16_128x128_c2x2_p8"},
+    {"mfma_i8_128x64_c2x2_p4", "mfma_i8_128x128_c2x2_p4", "mfma_i8_128x64_c4x2_p4", "mfma_i8_256x64_c4x2_p8",
+     "mfma_i8_256x128_c2x2_p4", "mfma_i8_64x64_c2x2_p4", "mfma_i8_256x128_c4x2_p8", "mfma_i8_128x128_c4x2_p8",
+     "mfma_i8_256x128_c4x2_p4", "mfma_i8_128x128_c2x2_p8"},
 };
 
 int make_geometry(const icv_conv_params* p, Geometry* g)
@@ -54,8 +60,12 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     const int64_t Hout = out_extent(p->Hin, p->PT, p->PB, p->DY, p->R, p->SY);
     const int64_t Wout = out_extent(p->Win, p->PL, p->PR, p->DX, p->S, p->SX);
     if (Hout < 1 || Wout < 1) return ICV_ERR_INVALID_ARG;
-    // entries are int32 pixel indices; sizes below stay far from int64 limits once these hold
-    if ((int64_t)p->N * p->Hin * p->Win >= (1ll << 31)) return ICV_ERR_INVALID_ARG;
+    // entries are int32 byte offsets into the input tensor, so it must be smaller than 2 GiB
+    {
+        const int64_t esz = p->dtype == ICV_F32 ? 4 : (p->dtype == ICV_BF16 ? 2 : 1);
+        const int64_t stride = p->in_pixel_stride ? p->in_pixel_stride : p->C;
+        if ((int64_t)p->N * p->Hin * p->Win * stride * esz >= (1ll << 31)) return ICV_ERR_INVALID_ARG;
+    }
     const int64_t M = (int64_t)p->N * Hout * Wout;
     const int64_t T = (int64_t)p->R * p->S;
     if (M >= (1ll << 31) || T > 4096 || M * T >= (1ll << 40)) return ICV_ERR_INVALID_ARG;
@@ -98,7 +108,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         g->stages_per_tap = (int32_t)(row_bytes / g->KCB);
         g->taps_per_stage = 1;
         g->n_stages = g->T * g->stages_per_tap;
-        g->name = plan_names[p->dtype][1 + variant];
+        g->name = kMfmaNames[p->dtype == ICV_U8I8 ? 1 : 0][variant];
     } else {
         g->kind = PLAN_GENERIC;
         g->variant = -1;
@@ -110,7 +120,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         g->stages_per_tap = 1;
         g->taps_per_stage = 1;
         g->n_stages = g->T;
-        g->name = plan_names[p->dtype][0];
+        g->name = kGenericNames[p->dtype];
     }
     g->m_tiles = (M + g->MR - 1) / g->MR;
     g->n_tiles = (p->K + g->NR - 1) / g->NR;

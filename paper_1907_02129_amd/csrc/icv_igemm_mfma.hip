@@ -141,32 +141,31 @@ __device__ inline TileList my_tiles(int64_t total, int xcd_mode)
     return t;
 }
 
-template <bool I8, int MR, int NR, int WM, int WN, int KCB, bool DIRECT>
-__global__ __launch_bounds__(512) void k_igemm_mfma(IgemmArgs g)
+template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool DIRECT>
+__global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
 {
-    static_assert(WM * WN == 4, "four consumer wavefronts per workgroup");
+    constexpr int NC = WM * WN;              // consumer wavefronts; NP producer wavefronts follow them
     constexpr int Q = KCB / 16;              // 16-byte chunks per row per stage
     constexpr int P = 256 / KCB;             // rows per 256 bytes of LDS
     constexpr int RPB = 1024 / KCB;          // rows one wavefront-wide copy (64 x 16 B) covers
-    constexpr int A_VEC = MR * KCB / 4096;   // copies per producer per stage, A tile (a quarter of its rows)
-    constexpr int B_VEC = NR * KCB / 4096;   // ... B tile
+    constexpr int A_VEC = MR * KCB / 1024 / NP;   // copies per producer per stage, A tile (MR/NP of its rows)
+    constexpr int B_VEC = NR * KCB / 1024 / NP;   // ... B tile
     constexpr int LP = A_VEC + B_VEC;
     constexpr int MRW = MR / WM, NRW = NR / WN;
     constexpr int MB = MRW / 32, NB = NRW / 32;
     constexpr int KSTEPS = KCB / 32;
     constexpr int SLOT = (MR + NR) * KCB;    // bytes of one ring slot: A tile then B tile
-    constexpr int EQ = MR / 4;               // rows (entries per tap) one producer serves
-    constexpr int TPC = 256 / EQ;            // taps one wavefront-wide entry copy covers (EQ*4 bytes per tap)
-    static_assert(A_VEC >= 1 && B_VEC >= 1 && MB >= 1 && NB >= 1, "tile too small");
+    static_assert(A_VEC >= 1 && B_VEC >= 1 && MB >= 1 && NB >= 1, "tile too small for this wavefront split");
+    static_assert(A_VEC * NP * 1024 == MR * KCB && B_VEC * NP * 1024 == NR * KCB, "copies must divide evenly");
     static_assert(4 * LP <= 63, "vmcnt is a 6-bit counter");
-    static_assert(EQ % 16 == 0, "a producer's rows must keep the swizzle phase");
+    static_assert((MR / NP) % RPB == 0, "a producer's rows are whole copy blocks");
     using acc_t = typename Acc<I8>::type;
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
     const int D = g.ring;
-    const int ent_bytes_per_producer = g.ent_copies * 1024;          // one parity
-    const int ent_base = D * SLOT;                                   // [parity][producer][tap][EQ] int32
+    const int ent_base = D * SLOT;                       // [parity][tap][MR] int32, each parity ent_bytes long
+    const int ent_bytes = g.ent_copies * 1024;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -175,19 +174,18 @@ __global__ __launch_bounds__(512) void k_igemm_mfma(IgemmArgs g)
     const int n_stages = g.n_stages;
     const int64_t total_stages = tl.count * n_stages;                // same value in every wavefront
 
-    if (wave >= 4) {
+    if (wave >= NC) {
         // =============================================================== producer
-        const int p = wave - 4;
+        const int p = wave - NC;
         const int lrow_in_blk = lane / Q;
-        const uint32_t my_ent = ent_base + p * ent_bytes_per_producer;     // parity 0; parity 1 is 4x further
-        const int ent_parity_stride = 4 * ent_bytes_per_producer;
 
         // source piece of each copy: LDS chunk (lane % Q) of row r must hold source chunk (lane % Q) ^ swz(r)
-        int a_src_off[A_VEC];
+        int a_lane_off[A_VEC];       // byte offset inside the KCB bytes of the row
+        int a_row[A_VEC];            // row of the tile this lane copies
 #pragma unroll
         for (int j = 0; j < A_VEC; j++) {
-            const int row = p * EQ + j * RPB + lrow_in_blk;
-            a_src_off[j] = ((lane % Q) ^ ((row / P) % Q)) << 4;
+            a_row[j] = (p * A_VEC + j) * RPB + lrow_in_blk;
+            a_lane_off[j] = ((lane % Q) ^ ((a_row[j] / P) % Q)) << 4;
         }
         int b_src_off[B_VEC];
 #pragma unroll
@@ -196,67 +194,84 @@ __global__ __launch_bounds__(512) void k_igemm_mfma(IgemmArgs g)
             b_src_off[j] = row * KCB + (((lane % Q) ^ ((row / P) % Q)) << 4);
         }
 
-        auto fetch_entries = [&](int64_t k) {      // entries of my k-th tile -> ENT[k & 1]
+        // entries of my k-th tile -> ENT[k & 1]; the T*MR int32 are one contiguous run, the producers share it
+        // in 1 KB pieces.  A piece issued here is complete, and visible to every wavefront, once its issuer has
+        // passed ring-1 more stage waits and barriers; the host keeps ring - 1 <= n_stages, so that is always
+        // before the first stage of tile k is copied.
+        auto fetch_entries = [&](int64_t k) {
             if constexpr (!DIRECT) {
                 if (k >= tl.count) return;
                 const int64_t mt = (tl.first + k * tl.step) / g.n_tiles;
-                const int32_t* src = g.ind + mt * ((int64_t)g.T * MR) + p * EQ + (lane % (EQ / 4)) * 4;
-                const uint32_t dst = lds_base + my_ent + (uint32_t)(k & 1) * ent_parity_stride;
-                for (int c = 0; c < g.ent_copies; c++) {
-                    const int tap = c * TPC + lane / (EQ / 4);
-                    if (tap < g.T) copy16_global_to_lds(src + (int64_t)tap * MR, dst + c * 1024);
+                const int32_t* src = g.ind + mt * ((int64_t)g.T * MR);
+                const uint32_t dst = lds_base + ent_base + (uint32_t)(k & 1) * ent_bytes;
+                const int n_chunks = g.T * MR / 4;
+                for (int u = p; u < g.ent_copies; u += NP) {
+                    const int c = u * 64 + lane;
+                    if (c < n_chunks) copy16_global_to_lds(src + c * 4, dst + u * 1024);
                 }
             }
         };
 
-        // issue cursor: next stage to copy
+        // issue cursor: next stage to copy.  Everything that only changes per tile or per kernel element is
+        // carried along incrementally so that one stage costs a handful of vector instructions per copy.
         int64_t ik = 0;          // tile index in my list
         int is = 0;              // stage within the tile
+        int itap = 0, icc = 0;   // kernel element and channel chunk of stage `is`
         int islot = 0;
-        auto issue_next = [&]() {
+        const uint8_t* wstage = nullptr;     // B tile of the stage, before the per-lane offset
+        const uint8_t* adirect = nullptr;    // DIRECT: this lane's first row of the tile, at the stage's column
+        auto enter_tile = [&]() {
             if (ik >= tl.count) return;
             const int64_t tile = tl.first + ik * tl.step;
             const int32_t nt = (int32_t)(tile % g.n_tiles);
             const int64_t mt = tile / g.n_tiles;
+            wstage = g.w + ((int64_t)nt * n_stages) * (NR * KCB);
+            if constexpr (DIRECT) adirect = g.a + (mt * MR + a_row[0]) * g.row_stride_bytes;
+        };
+        enter_tile();
+        auto issue_next = [&]() {
+            if (ik >= tl.count) return;
             const uint32_t slot = lds_base + (uint32_t)islot * SLOT;
             const uint8_t* asrc[A_VEC];
             if constexpr (DIRECT) {
 #pragma unroll
                 for (int j = 0; j < A_VEC; j++)
-                    asrc[j] = g.a + (mt * MR + p * EQ + j * RPB + lrow_in_blk) * g.row_stride_bytes +
-                              (int64_t)is * KCB + a_src_off[j];
+                    asrc[j] = adirect + (int64_t)(j * RPB) * g.row_stride_bytes + (int64_t)is * KCB + a_lane_off[j];
             } else {
-                const int tap = is / g.stages_per_tap;
-                const int cc = is - tap * g.stages_per_tap;
-                const int32_t* ent = (const int32_t*)(lds + my_ent + (int)(ik & 1) * ent_parity_stride) + tap * EQ;
+                const int32_t* ent = (const int32_t*)(lds + ent_base + (int)(ik & 1) * ent_bytes) + itap * MR;
+                int32_t e[A_VEC];
+#pragma unroll
+                for (int j = 0; j < A_VEC; j++) e[j] = ent[a_row[j]];     // all LDS reads first
+                const uint8_t* zsrc = g.zero_row + icc * KCB;
+                const uint8_t* abase = g.a + icc * KCB;
 #pragma unroll
                 for (int j = 0; j < A_VEC; j++) {
-                    const int32_t e = ent[j * RPB + lrow_in_blk];
-                    const uint8_t* rowp = e < 0 ? g.zero_row : g.a + (int64_t)e * g.row_stride_bytes;
-                    asrc[j] = rowp + cc * KCB + a_src_off[j];
+                    // entry = byte offset of the pixel row from the input base; negative = the zero row
+                    const uint32_t off = (uint32_t)(e[j] + a_lane_off[j]);
+                    asrc[j] = e[j] < 0 ? zsrc + a_lane_off[j] : abase + off;
                 }
             }
 #pragma unroll
             for (int j = 0; j < A_VEC; j++) copy16_global_to_lds(asrc[j], slot + (p * A_VEC + j) * 1024);
-            const uint8_t* ws = g.w + ((int64_t)nt * n_stages + is) * (NR * KCB);
 #pragma unroll
             for (int j = 0; j < B_VEC; j++)
-                copy16_global_to_lds(ws + b_src_off[j], slot + MR * KCB + (p * B_VEC + j) * 1024);
+                copy16_global_to_lds(wstage + b_src_off[j], slot + MR * KCB + (p * B_VEC + j) * 1024);
+            wstage += NR * KCB;
             islot = islot + 1 == D ? 0 : islot + 1;
+            if (++icc == g.stages_per_tap) { icc = 0; ++itap; }
             if (++is == n_stages) {
                 // all stages of tile ik are issued: its entry buffer is free for the tile after next
-                is = 0;
+                is = 0; itap = 0; icc = 0;
                 fetch_entries(ik + 2);
                 ++ik;
-                // entries of tile ik were fetched a whole tile of stages ago; only a reduction shorter than
-                // the ring can get here before a later wait has covered them
-                if (n_stages < D - 1) wait_vmcnt<0>();
+                enter_tile();
             }
         };
 
         fetch_entries(0);
-        wait_vmcnt<0>();
         fetch_entries(1);
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();         // entries of the first two tiles are visible to all producers
         for (int q = 0; q < D - 1; q++) issue_next();
         for (int64_t q = 0; q < total_stages; q++) {
             // stage q has landed once only the copies of younger stages (at most D-2 of them) are outstanding
@@ -276,6 +291,7 @@ __global__ __launch_bounds__(512) void k_igemm_mfma(IgemmArgs g)
         using out_t = typename std::conditional<I8, int32_t, float>::type;
         out_t* out = (out_t*)g.out;
 
+        __builtin_amdgcn_s_barrier();         // pairs with the producers' start-up barrier
         int slot = 0;
         for (int64_t k = 0; k < tl.count; k++) {
             acc_t acc[MB][NB];
@@ -311,17 +327,29 @@ __global__ __launch_bounds__(512) void k_igemm_mfma(IgemmArgs g)
             const int64_t mt = tile / g.n_tiles;
             const int64_t m_base = mt * MR + wm * MRW + 4 * lhalf;
             const int32_t n_base = nt * NR + wn * NRW + lrow;
+            const bool full = (mt + 1) * MR <= g.M && (nt + 1) * NR <= g.K;     // no row or column tail
+            if (full) {
+                out_t* o = out + m_base * g.out_stride + n_base;
 #pragma unroll
-            for (int i = 0; i < MB; i++)
+                for (int i = 0; i < MB; i++)
 #pragma unroll
-                for (int j = 0; j < NB; j++) {
-                    const int32_t col = n_base + j * 32;
+                    for (int j = 0; j < NB; j++)
 #pragma unroll
-                    for (int r = 0; r < 16; r++) {
-                        const int64_t row = m_base + i * 32 + 8 * (r >> 2) + (r & 3);
-                        if (row < g.M && col < g.K) out[row * g.out_stride + col] = acc[i][j][r];
+                        for (int r = 0; r < 16; r++)
+                            o[(int64_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * g.out_stride + j * 32] = acc[i][j][r];
+            } else {
+#pragma unroll
+                for (int i = 0; i < MB; i++)
+#pragma unroll
+                    for (int j = 0; j < NB; j++) {
+                        const int32_t col = n_base + j * 32;
+#pragma unroll
+                        for (int r = 0; r < 16; r++) {
+                            const int64_t row = m_base + i * 32 + 8 * (r >> 2) + (r & 3);
+                            if (row < g.M && col < g.K) out[row * g.out_stride + col] = acc[i][j][r];
+                        }
                     }
-                }
+            }
         }
     }
 }
@@ -342,24 +370,27 @@ static int device_cu_count()
 
 constexpr size_t kLdsPerCu = 160 * 1024;
 
-template <bool I8, int MR, int NR, int WM, int WN, int KCB, bool DIRECT>
+template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool DIRECT>
 static int launch_one(const Geometry& g, IgemmArgs a, hipStream_t s)
 {
-    auto kern = k_igemm_mfma<I8, MR, NR, WM, WN, KCB, DIRECT>;
+    auto kern = k_igemm_mfma<I8, MR, NR, WM, WN, NP, KCB, DIRECT>;
+    constexpr int threads = 64 * (WM * WN + NP);
     constexpr size_t slot = (size_t)(MR + NR) * KCB;
-    constexpr int tpc = 256 / (MR / 4);
-    a.ent_copies = DIRECT ? 0 : (g.T + tpc - 1) / tpc;
-    const size_t ent = (size_t)2 * 4 * a.ent_copies * 1024;
+    a.ent_copies = DIRECT ? 0 : (int32_t)(((size_t)g.T * MR * 4 + 1023) / 1024);
+    const size_t ent = (size_t)2 * a.ent_copies * 1024;
     // ring depth and workgroups per CU: two co-resident workgroups when each can still have >= 3 slots,
-    // otherwise one workgroup with as deep a ring as fits (at most 6 slots)
+    // otherwise one workgroup with as deep a ring as fits (at most 6 slots).  The ring never runs further
+    // ahead than one tile's worth of stages (ring - 1 <= n_stages): the entry prefetch relies on it.
     int per_cu = g.blocks_per_cu, ring = g.ring;
-    if (per_cu == 0) per_cu = (kLdsPerCu / 2 >= ent + 3 * slot) ? 2 : 1;
+    if (per_cu == 0) per_cu = (threads <= 512 && kLdsPerCu / 2 >= ent + 3 * slot) ? 2 : 1;
+    if (threads > 512) per_cu = 1;
     const size_t budget = kLdsPerCu / per_cu;
     if (budget < ent + 2 * slot) return ICV_ERR_UNSUPPORTED;
     const int fit = (int)((budget - ent) / slot);
     if (ring == 0) ring = fit;
     if (ring > fit) ring = fit;
     if (ring > 6) ring = 6;
+    if (ring > g.n_stages + 1) ring = g.n_stages + 1;
     if (ring < 2) return ICV_ERR_UNSUPPORTED;
     a.ring = ring;
     const size_t lds_bytes = ent + (size_t)ring * slot;
@@ -379,32 +410,41 @@ static int launch_one(const Geometry& g, IgemmArgs a, hipStream_t s)
             raised = true;
         }
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), lds_bytes, s, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(threads), lds_bytes, s, a);
     ICV_HIP_CHECK(hipGetLastError());
     return ICV_OK;
 }
 
-template <bool I8, int MR, int NR, int WM, int WN>
+template <bool I8, int MR, int NR, int WM, int WN, int NP>
 static int launch_tile(const Geometry& g, const IgemmArgs& a, bool direct, hipStream_t s)
 {
     if (g.KCB == 128) {
-        return direct ? launch_one<I8, MR, NR, WM, WN, 128, true>(g, a, s)
-                      : launch_one<I8, MR, NR, WM, WN, 128, false>(g, a, s);
+        return direct ? launch_one<I8, MR, NR, WM, WN, NP, 128, true>(g, a, s)
+                      : launch_one<I8, MR, NR, WM, WN, NP, 128, false>(g, a, s);
     }
-    return direct ? launch_one<I8, MR, NR, WM, WN, 64, true>(g, a, s)
-                  : launch_one<I8, MR, NR, WM, WN, 64, false>(g, a, s);
+    if constexpr (NR * 64 / 1024 >= NP) {      // a 64-byte stage of the B tile must still split over NP producers
+        return direct ? launch_one<I8, MR, NR, WM, WN, NP, 64, true>(g, a, s)
+                      : launch_one<I8, MR, NR, WM, WN, NP, 64, false>(g, a, s);
+    } else {
+        return direct ? launch_one<I8, MR, NR, WM, WN, 4, 64, true>(g, a, s)
+                      : launch_one<I8, MR, NR, WM, WN, 4, 64, false>(g, a, s);
+    }
 }
 
 template <bool I8>
 static int launch_dtype(const Geometry& g, const IgemmArgs& a, bool direct, hipStream_t s)
 {
     switch (g.variant) {
-        case 0: return launch_tile<I8, 128, 64, 2, 2>(g, a, direct, s);
-        case 1: return launch_tile<I8, 128, 128, 2, 2>(g, a, direct, s);
-        case 2: return launch_tile<I8, 128, 64, 4, 1>(g, a, direct, s);
-        case 3: return launch_tile<I8, 256, 64, 4, 1>(g, a, direct, s);
-        case 4: return launch_tile<I8, 256, 128, 2, 2>(g, a, direct, s);
-        case 5: return launch_tile<I8, 64, 64, 2, 2>(g, a, direct, s);
+        case 0: return launch_tile<I8, 128, 64, 2, 2, 4>(g, a, direct, s);
+        case 1: return launch_tile<I8, 128, 128, 2, 2, 4>(g, a, direct, s);
+        case 2: return launch_tile<I8, 128, 64, 4, 2, 4>(g, a, direct, s);
+        case 3: return launch_tile<I8, 256, 64, 4, 2, 8>(g, a, direct, s);
+        case 4: return launch_tile<I8, 256, 128, 2, 2, 4>(g, a, direct, s);
+        case 5: return launch_tile<I8, 64, 64, 2, 2, 4>(g, a, direct, s);
+        case 6: return launch_tile<I8, 256, 128, 4, 2, 8>(g, a, direct, s);
+        case 7: return launch_tile<I8, 128, 128, 4, 2, 8>(g, a, direct, s);
+        case 8: return launch_tile<I8, 256, 128, 4, 2, 4>(g, a, direct, s);
+        case 9: return launch_tile<I8, 128, 128, 2, 2, 8>(g, a, direct, s);
         default: return ICV_ERR_UNSUPPORTED;
     }
 }

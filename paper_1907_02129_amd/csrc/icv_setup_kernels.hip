@@ -80,7 +80,8 @@ int launch_pack_filter(const icv_conv_params* p, const Geometry& g, const void* 
 
 // ------------------------------------------------------------------ indirection build (section 2.3)
 // Entry (m, tap): iy = oy*SY + ky*DY - PT, ix = ox*SX + kx*DX - PL (Listing 1's index arithmetic);
-// inside the input -> (n*Hin + iy)*Win + ix, else -1 (the zero row).  Physical order [m tile][tap][MR].
+// inside the input -> byte offset of pixel (n*Hin + iy)*Win + ix from the input base, else INT32_MIN (the
+// zero row).  Physical order [m tile][tap][MR].
 // One thread owns four consecutive rows m0..m0+3 (MR is a multiple of 4, so they share a tile) and walks
 // all taps, writing one int4 per tap: consecutive threads write consecutive 16-byte pieces of a
 // (tile, tap) run of MR*4 bytes.  The two integer divisions per thread are amortised over 4*T entries.
@@ -88,6 +89,7 @@ struct IndArgs {
     int32_t* ind;
     int64_t M, m_padded;
     int32_t Hin, Win, Hout, Wout, R, S, SY, SX, DY, DX, PT, PL, MR, T;
+    int32_t stride_bytes;   // bytes between input pixels
 };
 
 __global__ __launch_bounds__(256) void k_build_indirection(IndArgs a)
@@ -123,7 +125,7 @@ __global__ __launch_bounds__(256) void k_build_indirection(IndArgs a)
                 const int32_t iy = oy[j] * a.SY + ky * a.DY - a.PT;
                 const int32_t ix = ox[j] * a.SX + kx * a.DX - a.PL;
                 const bool in = live[j] && (uint32_t)iy < (uint32_t)a.Hin && (uint32_t)ix < (uint32_t)a.Win;
-                e[j] = in ? (n[j] * a.Hin + iy) * a.Win + ix : -1;
+                e[j] = in ? ((n[j] * a.Hin + iy) * a.Win + ix) * a.stride_bytes : INT32_MIN;
             }
             *dst = make_int4(e[0], e[1], e[2], e[3]);
             dst += mr4;
@@ -139,6 +141,7 @@ int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_
     a.Hin = p->Hin; a.Win = p->Win; a.Hout = g.Hout; a.Wout = g.Wout;
     a.R = p->R; a.S = p->S; a.SY = p->SY; a.SX = p->SX; a.DY = p->DY; a.DX = p->DX;
     a.PT = p->PT; a.PL = p->PL; a.MR = g.MR; a.T = g.T;
+    a.stride_bytes = g.in_stride * g.elem_bytes;
     const int64_t threads = a.m_padded / 4;
     hipLaunchKernelGGL(k_build_indirection, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, a);
     ICV_HIP_CHECK(hipGetLastError());

@@ -141,7 +141,7 @@ def test_small_shapes_match_oracle(s):
     check_against_oracle(s, buf.output.cpu().numpy(), x, w)
 
 
-N_PLANS = 7     # plan 1 = vector ALU, 2.. = tensor-core tile variants
+N_PLANS = 11    # plan 1 = vector ALU, 2.. = tensor-core tile variants
 
 
 @pytest.mark.parametrize("plan", range(1, N_PLANS + 1))

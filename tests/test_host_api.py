@@ -94,7 +94,7 @@ def test_invalid_arguments_are_rejected(lib):
     assert _status(lib, s, in_pixel_stride=32) == icv.ICV_ERR_INVALID_ARG           # stride < C
     assert _status(lib, s, out_pixel_stride=8) == icv.ICV_ERR_INVALID_ARG           # stride < K
     assert _status(lib, s, R=80, PT=0, PB=0) == icv.ICV_ERR_INVALID_ARG             # kernel larger than input
-    assert _status(lib, s, N=1 << 20) == icv.ICV_ERR_INVALID_ARG                    # pixel index overflows int32
+    assert _status(lib, s, N=1 << 20) == icv.ICV_ERR_INVALID_ARG                    # input of 2 GiB or more
     assert _status(lib, s, plan=1 << 12) == icv.ICV_ERR_INVALID_ARG
     assert _status(lib, s, plan=15) == icv.ICV_ERR_INVALID_ARG                      # no such tile variant
     assert _status(lib, s, plan=2 | (1 << 4)) == icv.ICV_ERR_INVALID_ARG            # a ring needs two slots
