@@ -29,6 +29,7 @@ static int64_t out_extent(int64_t in, int64_t lo, int64_t hi, int64_t dil, int64
 }
 
 static const char* kGenericNames[3] = {"generic_f32", "generic_bf16", "generic_u8i8"};
+static const char* kLowcNames[2] = {"mfma_bf16_lowc_64x64", "mfma_i8_lowc_64x64"};
 static const char* kMfmaNames[2][10] = {
     {"mfma_bf16_128x64_c2x2_p4", "mfma_bf16_128x128_c2x2_p4", "mfma_bf16_128x64_c4x2_p4", "mfma_bf16_256x64_c4x2_p8",
      "mfma_bf16_256x128_c2x2_p4", "mfma_bf16_64x64_c2x2_p4", "mfma_bf16_256x128_c4x2_p8", "mfma_bf16_128x128_c4x2_p8",
@@ -95,7 +96,23 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         // a workgroup keeps two tiles' worth of entries in LDS: 2 * MR*T int32 (plus padding)
         if ((int64_t)kTileVariants[variant].MR * T * 4 > 24 * 1024) mfma_ok = false;
     }
-    if (mfma_ok) {
+    // very short rows (first-layer convolutions): the whole reduction of a tile is gathered at once
+    const bool lowc_ok = p->dtype != ICV_F32 && plan_kernel == 0 &&
+                         (row_bytes == 8 || row_bytes == 16 || row_bytes == 32) && stride_bytes % row_bytes == 0 &&
+                         T * row_bytes <= 608 && !(p->dtype == ICV_U8I8 && p->input_zero_point != 128);
+    if (lowc_ok) {
+        g->kind = PLAN_MFMA_LOWC;
+        g->variant = -1;
+        g->MR = 64;
+        g->NR = 64;
+        g->KCB = (int32_t)((T * row_bytes + 31) / 32 * 32);
+        g->ring = 0;
+        g->blocks_per_cu = 0;
+        g->stages_per_tap = 1;
+        g->taps_per_stage = g->T;
+        g->n_stages = 1;
+        g->name = kLowcNames[p->dtype == ICV_U8I8 ? 1 : 0];
+    } else if (mfma_ok) {
         const TileVariant& tv = kTileVariants[variant];
         g->kind = PLAN_MFMA;
         g->variant = variant;
@@ -156,6 +173,7 @@ size_t icv_packed_filter_bytes(const icv_conv_params* p)
 {
     Geometry g;
     if (make_geometry(p, &g) != ICV_OK) return 0;
+    if (g.kind == PLAN_MFMA_LOWC) return (size_t)g.n_tiles * g.NR * g.KCB;
     return (size_t)g.n_tiles * g.NR * g.T * p->C * g.elem_bytes;
 }
 
@@ -171,6 +189,7 @@ size_t icv_im2col_bytes(const icv_conv_params* p)
     Geometry g;
     if (make_geometry(p, &g) != ICV_OK) return 0;
     // rows padded to whole tiles so the GEMM kernel may read (and discard) the rows past M
+    if (g.kind == PLAN_MFMA_LOWC) return (size_t)g.m_tiles * g.MR * g.KCB;
     return (size_t)g.m_tiles * g.MR * g.T * p->C * g.elem_bytes;
 }
 
@@ -213,6 +232,7 @@ static int conv_common(const icv_conv_params* p, const Geometry& g, const void* 
                        const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s)
 {
     if (g.kind == PLAN_MFMA) return launch_igemm_mfma(p, g, a, packed, ind, zero_row, out, a_direct, s);
+    if (g.kind == PLAN_MFMA_LOWC) return launch_igemm_lowc(p, g, a, packed, ind, zero_row, out, a_direct, s);
     return launch_igemm_generic(p, g, a, packed, ind, zero_row, out, a_direct, s);
 }
 

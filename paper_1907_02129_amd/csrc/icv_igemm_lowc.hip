@@ -1,0 +1,187 @@
+// Tensor-core Indirect GEMM for very few input channels (first-layer convolutions: C*sizeof(element) of
+// 8, 16 or 32 bytes per pixel row).
+//
+// With so short rows one kernel element is less than an MFMA k-step, so the two nested loops of Listing 3
+// (kernel elements outside, channels inside) are flattened: the reduction index is k = tap*C + c, the whole
+// reduction of a tile (R*S*C elements, zero-padded to a multiple of the 32-byte k-step) is gathered into LDS at
+// once, one U-byte load per (output pixel, kernel element) through the indirection buffer, and the tile is then
+// multiplied in one sweep of MFMAs.  The packed filter slice of the workgroup's column tile stays in LDS for
+// all the row tiles the (persistent) workgroup walks, because it is as large as the gathered A tile.
+//
+// LDS rows are padded by 16 bytes (odd number of 16-byte units per row) instead of swizzled: ds_write_b64
+// from the gather and ds_read_b128 for the fragments are then both spread over the banks.
+#include <type_traits>
+#include "icv_internal.h"
+
+namespace icv {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+typedef int i32x16_t __attribute__((ext_vector_type(16)));
+
+struct LowcArgs {
+    const uint8_t* a;
+    const uint8_t* zero_row;
+    const uint8_t* w;       // packed filter [n tile][64][KP]
+    const int32_t* ind;     // [m tile][tap][64], byte offsets, negative = zero row
+    void* out;
+    int64_t M, m_tiles;
+    int32_t K, T, out_stride, n_tiles;
+    int32_t KP;             // padded reduction bytes per row, multiple of 32
+    int32_t direct;         // 1: `a` is the dense patch matrix [rows][KP] of the ablation path
+};
+
+template <int U>
+struct Piece;
+template <>
+struct Piece<8> { using type = uint2; };
+template <>
+struct Piece<16> { using type = uint4; };
+template <>
+struct Piece<32> { using type = uint4; };   // moved as two 16-byte halves
+
+// One workgroup (4 wavefronts) per 64 x 64 output tile; wavefront w owns the 32 x 32 block (w / 2, w % 2).
+template <bool I8, int U>
+__global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
+{
+    constexpr int MR = 64, NR = 64;
+    using acc_t = typename std::conditional<I8, i32x16_t, f32x16_t>::type;
+    using out_t = typename std::conditional<I8, int32_t, float>::type;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int pitch = g.KP + 16;
+    uint8_t* ldsB = lds;                    // [NR][pitch]
+    uint8_t* ldsA = lds + NR * pitch;       // [MR][pitch]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nt = blockIdx.y;
+
+    // ---- filter slice of this column tile -> LDS, once
+    {
+        const uint8_t* src = g.w + (int64_t)nt * NR * g.KP;
+        const int vec_per_row = g.KP / 16;
+        for (int v = tid; v < NR * vec_per_row; v += 256) {
+            const int row = v / vec_per_row, c = v - row * vec_per_row;
+            *(uint4*)(ldsB + row * pitch + c * 16) = *(const uint4*)(src + (int64_t)row * g.KP + c * 16);
+        }
+    }
+    // zero the k padding of the A rows once (those columns are never written by the gather)
+    {
+        const int pad_from = g.T * U;             // multiple of 8
+        const int pad8 = (g.KP - pad_from) / 8;
+        for (int v = tid; v < MR * pad8; v += 256) {
+            const int row = v / pad8, c = v - row * pad8;
+            *(uint2*)(ldsA + row * pitch + pad_from + c * 8) = make_uint2(0, 0);
+        }
+    }
+
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const uint8_t* a_frag = ldsA + (wm * 32 + lrow) * pitch + lhalf * 16;
+    const uint8_t* b_frag = ldsB + (wn * 32 + lrow) * pitch + lhalf * 16;
+    const int ksteps = g.KP / 32;
+    out_t* out = (out_t*)g.out;
+
+    for (int64_t mt = blockIdx.x; mt < g.m_tiles; mt += gridDim.x) {
+        __syncthreads();      // previous tile's fragment reads are done (first pass: filter and padding are in)
+        // ---- gather: thread -> (row = tid % 64, taps tid / 64, +4, ...); the 64 entries of a tap are contiguous
+        if (g.direct) {
+            const uint8_t* src = g.a + mt * MR * (int64_t)g.KP;
+            const int vec_per_row = g.KP / 16;
+            for (int v = tid; v < MR * vec_per_row; v += 256) {
+                const int row = v / vec_per_row, c = v - row * vec_per_row;
+                *(uint4*)(ldsA + row * pitch + c * 16) = *(const uint4*)(src + (int64_t)row * g.KP + c * 16);
+            }
+        }
+        const int32_t* ent = g.ind + mt * ((int64_t)g.T * MR) + (tid & 63);
+        uint8_t* dstrow = ldsA + (tid & 63) * pitch;
+        for (int tap = tid >> 6; tap < (g.direct ? 0 : g.T); tap += 4) {
+            const int32_t e = ent[tap * MR];
+            const uint8_t* src = e < 0 ? g.zero_row : g.a + (uint32_t)e;
+            if constexpr (U == 32) {
+                const uint4 lo = *(const uint4*)src, hi = *(const uint4*)(src + 16);
+                *(uint4*)(dstrow + tap * 32) = lo;
+                *(uint4*)(dstrow + tap * 32 + 16) = hi;
+            } else {
+                using piece_t = typename Piece<U>::type;
+                *(piece_t*)(dstrow + tap * U) = *(const piece_t*)src;
+            }
+        }
+        __syncthreads();
+        // ---- multiply
+        acc_t acc;
+#pragma unroll
+        for (int r = 0; r < 16; r++) acc[r] = 0;
+        for (int ks = 0; ks < ksteps; ks++) {
+            const uint4 av = *(const uint4*)(a_frag + ks * 32);
+            const uint4 bv = *(const uint4*)(b_frag + ks * 32);
+            if constexpr (I8) {
+                i32x4_t ai = {(int)(av.x ^ 0x80808080u), (int)(av.y ^ 0x80808080u), (int)(av.z ^ 0x80808080u),
+                              (int)(av.w ^ 0x80808080u)};
+                i32x4_t bi = {(int)bv.x, (int)bv.y, (int)bv.z, (int)bv.w};
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(ai, bi, acc, 0, 0, 0);
+            } else {
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av),
+                                                              __builtin_bit_cast(bf16x8_t, bv), acc, 0, 0, 0);
+            }
+        }
+        // ---- store: register r of lane l holds row 8*(r/4) + 4*(l>>5) + (r&3), column l&31
+        const int64_t m_base = mt * MR + wm * 32 + 4 * lhalf;
+        const int32_t col = nt * NR + wn * 32 + lrow;
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+            const int64_t row = m_base + 8 * (r >> 2) + (r & 3);
+            if (row < g.M && col < g.K) out[row * g.out_stride + col] = acc[r];
+        }
+    }
+}
+
+int launch_igemm_lowc(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
+                      const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s)
+{
+    LowcArgs a;
+    a.a = (const uint8_t*)input;
+    a.zero_row = (const uint8_t*)zero_row;
+    a.w = (const uint8_t*)packed;
+    a.ind = ind;
+    a.out = out;
+    a.M = g.M; a.m_tiles = g.m_tiles;
+    a.K = p->K; a.T = g.T; a.out_stride = g.out_stride; a.n_tiles = (int32_t)g.n_tiles;
+    a.KP = g.KCB;
+    a.direct = a_direct ? 1 : 0;
+    const size_t lds_bytes = (size_t)128 * (a.KP + 16);
+    if (lds_bytes > 80 * 1024 || g.n_tiles > 65535) return ICV_ERR_UNSUPPORTED;
+    int cus = 256, dev = 0;
+    if (hipGetDevice(&dev) == hipSuccess) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
+    }
+    int64_t gx = (int64_t)cus * 2 / g.n_tiles;      // two workgroups per CU, shared among the column tiles
+    if (gx < 1) gx = 1;
+    if (gx > g.m_tiles) gx = g.m_tiles;
+    const dim3 grid((unsigned)gx, (unsigned)g.n_tiles);
+    const int unit = p->C * g.elem_bytes;
+    const bool i8 = p->dtype == ICV_U8I8;
+#define ICV_LOWC_LAUNCH(I8, U)                                                                                  \
+    do {                                                                                                        \
+        auto kern = k_igemm_lowc<I8, U>;                                                                        \
+        if (lds_bytes > 64 * 1024) {                                                                            \
+            static bool raised = false;                                                                         \
+            if (!raised) {                                                                                      \
+                ICV_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                                  160 * 1024));                                                 \
+                raised = true;                                                                                  \
+            }                                                                                                   \
+        }                                                                                                       \
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds_bytes, s, a);                                             \
+    } while (0)
+    if (unit == 8) { if (i8) ICV_LOWC_LAUNCH(true, 8); else ICV_LOWC_LAUNCH(false, 8); }
+    else if (unit == 16) { if (i8) ICV_LOWC_LAUNCH(true, 16); else ICV_LOWC_LAUNCH(false, 16); }
+    else if (unit == 32) { if (i8) ICV_LOWC_LAUNCH(true, 32); else ICV_LOWC_LAUNCH(false, 32); }
+    else return ICV_ERR_UNSUPPORTED;
+#undef ICV_LOWC_LAUNCH
+    ICV_HIP_CHECK(hipGetLastError());
+    return ICV_OK;
+}
+
+}  // namespace icv

@@ -212,14 +212,17 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
             }
         };
 
-        // issue cursor: next stage to copy.  Everything that only changes per tile or per kernel element is
-        // carried along incrementally so that one stage costs a handful of vector instructions per copy.
-        int64_t ik = 0;          // tile index in my list
+        // Copy cursor.  A stage is handled in two steps: `prepare` turns its indirection entries into source
+        // addresses (kept in registers), `issue` fires the copies.  The addresses of the next stage are prepared
+        // right after the copies of the current one were issued, so that work overlaps with the memory pipeline
+        // draining instead of delaying the next burst of copies.  Everything that only changes per tile or per
+        // kernel element is carried along incrementally.
+        int64_t ik = 0;          // tile index in my list (of the stage to prepare next)
         int is = 0;              // stage within the tile
         int itap = 0, icc = 0;   // kernel element and channel chunk of stage `is`
-        int islot = 0;
-        const uint8_t* wstage = nullptr;     // B tile of the stage, before the per-lane offset
-        const uint8_t* adirect = nullptr;    // DIRECT: this lane's first row of the tile, at the stage's column
+        int islot = 0;           // ring slot the next issued stage goes to
+        const uint8_t* wstage = nullptr;     // B tile of the stage to prepare, before the per-lane offset
+        const uint8_t* adirect = nullptr;    // DIRECT: this lane's first row of the tile
         auto enter_tile = [&]() {
             if (ik >= tl.count) return;
             const int64_t tile = tl.first + ik * tl.step;
@@ -229,10 +232,13 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
             if constexpr (DIRECT) adirect = g.a + (mt * MR + a_row[0]) * g.row_stride_bytes;
         };
         enter_tile();
-        auto issue_next = [&]() {
-            if (ik >= tl.count) return;
-            const uint32_t slot = lds_base + (uint32_t)islot * SLOT;
-            const uint8_t* asrc[A_VEC];
+
+        const uint8_t* asrc[A_VEC];          // prepared source addresses of the next stage to issue
+        const uint8_t* bsrc = nullptr;
+        bool prepared = false;
+        auto prepare = [&]() {
+            prepared = ik < tl.count;
+            if (!prepared) return;
             if constexpr (DIRECT) {
 #pragma unroll
                 for (int j = 0; j < A_VEC; j++)
@@ -251,34 +257,41 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
                     asrc[j] = e[j] < 0 ? zsrc + a_lane_off[j] : abase + off;
                 }
             }
-#pragma unroll
-            for (int j = 0; j < A_VEC; j++) copy16_global_to_lds(asrc[j], slot + (p * A_VEC + j) * 1024);
-#pragma unroll
-            for (int j = 0; j < B_VEC; j++)
-                copy16_global_to_lds(wstage + b_src_off[j], slot + MR * KCB + (p * B_VEC + j) * 1024);
+            bsrc = wstage;
             wstage += NR * KCB;
-            islot = islot + 1 == D ? 0 : islot + 1;
             if (++icc == g.stages_per_tap) { icc = 0; ++itap; }
             if (++is == n_stages) {
-                // all stages of tile ik are issued: its entry buffer is free for the tile after next
+                // every stage of tile ik has its addresses: its entry buffer is free for the tile after next
                 is = 0; itap = 0; icc = 0;
                 fetch_entries(ik + 2);
                 ++ik;
                 enter_tile();
             }
         };
+        auto issue = [&]() {
+            if (!prepared) return;
+            const uint32_t slot = lds_base + (uint32_t)islot * SLOT;
+#pragma unroll
+            for (int j = 0; j < A_VEC; j++) copy16_global_to_lds(asrc[j], slot + (p * A_VEC + j) * 1024);
+#pragma unroll
+            for (int j = 0; j < B_VEC; j++)
+                copy16_global_to_lds(bsrc + b_src_off[j], slot + MR * KCB + (p * B_VEC + j) * 1024);
+            islot = islot + 1 == D ? 0 : islot + 1;
+        };
 
         fetch_entries(0);
         fetch_entries(1);
         wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();         // entries of the first two tiles are visible to all producers
-        for (int q = 0; q < D - 1; q++) issue_next();
+        prepare();
+        for (int q = 0; q < D - 1; q++) { issue(); prepare(); }
         for (int64_t q = 0; q < total_stages; q++) {
             // stage q has landed once only the copies of younger stages (at most D-2 of them) are outstanding
             const int64_t younger = total_stages - 1 - q;
             wait_all_but_stages<LP>(younger < D - 2 ? (int)younger : D - 2);
             __builtin_amdgcn_s_barrier();     // hand stage q to the consumers; they are done with stage q-1
-            issue_next();                     // stage q + D - 1 refills the slot stage q - 1 used
+            issue();                          // stage q + D - 1 refills the slot stage q - 1 used
+            prepare();                        // addresses of stage q + D, while those copies are in flight
         }
         wait_vmcnt<0>();
     } else {

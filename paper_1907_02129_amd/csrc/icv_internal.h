@@ -11,7 +11,7 @@ enum PlanKind : int32_t {
     PLAN_INVALID = 0,
     PLAN_GENERIC = 1,   // vector-ALU kernel, any C, any dtype
     PLAN_MFMA = 2,      // tensor-core indirect GEMM, C a multiple of the k-granule
-    PLAN_MFMA_LOWC = 3  // tensor-core indirect GEMM for C*elem = 8 bytes (several taps per k-step)
+    PLAN_MFMA_LOWC = 3  // tensor-core indirect GEMM for pixel rows of 8, 16 or 32 bytes (first-layer convolutions)
 };
 
 // Geometry derived once per call from icv_conv_params (host side).
@@ -26,7 +26,7 @@ struct Geometry {
     int32_t kind;         // PlanKind
     int32_t variant;      // index into the tile-variant table (MFMA kinds)
     int32_t MR, NR;       // workgroup tile: rows (output pixels) x columns (output channels)
-    int32_t KCB;          // bytes of one A/B row per pipeline stage
+    int32_t KCB;          // bytes of one A/B row per pipeline stage | LOWC: padded reduction bytes per row
     int32_t stages_per_tap;  // C*elem_bytes / KCB (MFMA)        | 1
     int32_t taps_per_stage;  // 1                                | KCB / 8 (LOWC)
     int32_t n_stages;        // pipeline stages in the reduction
@@ -59,6 +59,8 @@ int launch_im2col(const icv_conv_params* p, const Geometry& g, const void* input
 // a_direct = false: rows of A come from the indirection buffer (the method);
 // a_direct = true : A is the dense [M][T*C] patch matrix with constant row stride (ablation GEMM).
 int launch_igemm_mfma(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
+                      const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s);
+int launch_igemm_lowc(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                       const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s);
 int launch_igemm_generic(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                          const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s);

@@ -58,9 +58,29 @@ __global__ void k_pack_filter_plain(const uint8_t* src, uint8_t* dst, int64_t va
     if (i < total_bytes) dst[i] = i < valid_bytes ? src[i] : (uint8_t)0;
 }
 
+// Low-C plan: [n tile][64][KP]; row oc is the filter's own [R][S][C] run followed by zeros up to KP bytes.
+__global__ void k_pack_filter_lowc(const uint8_t* src, uint8_t* dst, int K, int row_bytes, int KP, int64_t total_rows)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;     // one thread per 8 bytes
+    const int per_row = KP / 8;
+    if (i >= total_rows * per_row) return;
+    const int64_t row = i / per_row;
+    const int b = (int)(i - row * per_row) * 8;
+    uint2 v = make_uint2(0, 0);
+    if (row < K && b < row_bytes) v = *(const uint2*)(src + row * (int64_t)row_bytes + b);
+    *(uint2*)(dst + row * (int64_t)KP + b) = v;
+}
+
 int launch_pack_filter(const icv_conv_params* p, const Geometry& g, const void* filt, void* packed, hipStream_t s)
 {
     const int64_t CB = (int64_t)p->C * g.elem_bytes;
+    if (g.kind == PLAN_MFMA_LOWC) {
+        const int64_t rows = g.n_tiles * g.NR, threads = rows * (g.KCB / 8);
+        hipLaunchKernelGGL(k_pack_filter_lowc, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
+                           (const uint8_t*)filt, (uint8_t*)packed, p->K, (int)(g.T * CB), g.KCB, rows);
+        ICV_HIP_CHECK(hipGetLastError());
+        return ICV_OK;
+    }
     if (g.kind == PLAN_MFMA) {
         PackArgs a;
         a.src = (const uint8_t*)filt;
@@ -193,6 +213,31 @@ __global__ __launch_bounds__(256) void k_im2col(Im2colArgs a)
     }
 }
 
+// Low-C plan: rows of KP bytes, [tap][C] followed by zeros; one thread per 8 bytes.
+__global__ __launch_bounds__(256) void k_im2col_lowc(Im2colArgs a, int KP)
+{
+    const int per_row = KP / 8;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= a.m_padded * per_row) return;
+    const int64_t m = i / per_row;
+    const int b = (int)(i - m * per_row) * 8;
+    const int32_t tap = b / a.CB, within = b - tap * a.CB;
+    uint2 val = make_uint2(0, 0);
+    if (tap < a.T) {
+        const int32_t ky = tap / a.S, kx = tap - ky * a.S;
+        const int32_t ox = (int32_t)(m % a.Wout);
+        const int64_t q = m / a.Wout;
+        const int32_t oy = (int32_t)(q % a.Hout);
+        const int32_t n = (int32_t)(q / a.Hout);
+        const int32_t iy = oy * a.SY + ky * a.DY - a.PT;
+        const int32_t ix = ox * a.SX + kx * a.DX - a.PL;
+        const bool in = m < a.M && (uint32_t)iy < (uint32_t)a.Hin && (uint32_t)ix < (uint32_t)a.Win;
+        val = make_uint2(a.fill, a.fill);
+        if (in) val = *(const uint2*)(a.in + (((int64_t)n * a.Hin + iy) * a.Win + ix) * a.stride_bytes + within);
+    }
+    *(uint2*)(a.ws + i * 8) = val;
+}
+
 int launch_im2col(const icv_conv_params* p, const Geometry& g, const void* input, void* ws, hipStream_t s)
 {
     Im2colArgs a;
@@ -205,6 +250,12 @@ int launch_im2col(const icv_conv_params* p, const Geometry& g, const void* input
     a.stride_bytes = (int64_t)g.in_stride * g.elem_bytes;
     const uint32_t zp = p->dtype == ICV_U8I8 ? (uint32_t)p->input_zero_point : 0u;
     a.fill = zp * 0x01010101u;
+    if (g.kind == PLAN_MFMA_LOWC) {
+        const int64_t threads = a.m_padded * (g.KCB / 8);
+        hipLaunchKernelGGL(k_im2col_lowc, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, a, g.KCB);
+        ICV_HIP_CHECK(hipGetLastError());
+        return ICV_OK;
+    }
     const bool vec16 = a.CB % 16 == 0 && a.stride_bytes % 16 == 0;
     const int vb = vec16 ? 16 : g.elem_bytes;
     const int64_t total = a.m_padded * a.T * (a.CB / vb);

@@ -125,6 +125,12 @@ def _small_shapes():
     out.append(ConvShape("s_i8_c64_k96", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=31))
     out.append(ConvShape("s_i8_c192_k200", 1, 17, 9, 192, 200, 3, 3, DY=2, DX=2, PT=2, PL=2, PB=2, PR=2, dtype="u8i8", zero_point=128, seed=32))
     out.append(ConvShape("s_i8_c128_s2", 3, 14, 14, 128, 64, 5, 3, SY=2, SX=2, PT=2, PL=1, PB=2, PR=1, dtype="u8i8", zero_point=128, seed=33))
+    # short pixel rows (8, 16, 32 bytes): the flattened-reduction tensor-core kernel
+    out.append(ConvShape("s_bf16_c4_7x7", 2, 30, 26, 4, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=34))
+    out.append(ConvShape("s_bf16_c8_3x3", 3, 13, 17, 8, 40, 3, 3, DY=2, DX=1, PT=2, PL=1, PB=2, PR=1, seed=35))
+    out.append(ConvShape("s_bf16_c16_5x5", 1, 21, 9, 16, 64, 5, 5, SY=1, SX=2, PT=2, PL=2, PB=2, PR=2, seed=36))
+    out.append(ConvShape("s_i8_c8_5x5", 2, 11, 23, 8, 33, 5, 5, PT=2, PL=2, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=37))
+    out.append(ConvShape("s_i8_c32_3x3", 1, 16, 16, 32, 64, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=38))
     # vector-ALU fallback: odd channel counts, fp32, other zero points
     out.append(ConvShape("s_f32_odd", 2, 9, 10, 5, 7, 3, 3, SY=2, SX=1, PT=1, PL=2, PB=0, PR=1, dtype="f32", dist="uniform", seed=41))
     out.append(ConvShape("s_bf16_c3", 1, 12, 12, 3, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=42))
@@ -179,7 +185,7 @@ def test_padded_channel_layout():
     assert np.abs(got - want3).max() / np.abs(want3).max() <= 1e-2
 
 
-@pytest.mark.parametrize("name", ["cfg2_3x3_c64", "cfg3a_3x3_s2", "cfg4_int8_3x3", "cfg3c_5x5_asym"])
+@pytest.mark.parametrize("name", ["cfg2_3x3_c64", "cfg3a_3x3_s2", "cfg4_int8_3x3", "cfg3c_5x5_asym", "cfg5b_7x7_s2"])
 def test_im2col_gemm_ablation_agrees_with_indirect_path(name):
     # "fused im2col + GEMM" (section 2.2): both paths compute the same thing
     s = CONFIGS[name].with_(N=2)
@@ -196,7 +202,10 @@ def test_im2col_gemm_ablation_agrees_with_indirect_path(name):
     # the patch matrix itself: row m, tap t holds the pixel row the indirection entry names
     M, T = buf.M, s.R * s.S
     esz = 1 if s.dtype == "u8i8" else 2
-    rows = ws.cpu().numpy()[:M * T * s.C * esz].reshape(M, T, s.C * esz)
+    kp = icv.im2col_bytes(buf.p) // (len(buf.indirection) // T)       # bytes per patch row (padded for short rows)
+    rows = ws.cpu().numpy()[:M * kp].reshape(M, kp)
+    assert not rows[:, T * s.C * esz:].any()
+    rows = rows[:, :T * s.C * esz].reshape(M, T, s.C * esz)
     ent = oracle.indirection(s)
     xb = x.reshape(-1, s.C).view(np.uint8).reshape(-1, s.C * esz)
     fill = np.full(s.C * esz, s.zero_point if s.dtype == "u8i8" else 0, dtype=np.uint8)
