@@ -153,6 +153,8 @@ def main():
     ap.add_argument("--no-shapes", action="store_true", help="skip the per-shape table and the ablation")
     ap.add_argument("--workload", default=None, help="time another shape as the headline (tuning)")
     ap.add_argument("--plan", type=int, default=0)
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: a 256 MiB device copy (calibration) then 10 conv launches")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the path shards over the batch with no "
@@ -170,6 +172,21 @@ def main():
 
     name = args.workload or HEADLINE
     s = CONFIGS[name]
+    if args.traffic_probe:
+        # FETCH_SIZE / WRITE_SIZE calibration: a plain copy of known size (reads 256 MiB, writes 256 MiB),
+        # then the conv kernel on rotating buffers; the counters of both are read from the same rocprofv3 run
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        pr = Problem(icv, torch, s, sets=sets_for_cold(s, *icv.output_size(icv.make_params(s, plan=args.plan))),
+                     plan=args.plan)
+        for _ in range(10):
+            pr.step()
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": name, "kernel": icv.plan_name(pr.p), "copy_bytes": 256 << 20}))
+        return
     p0 = icv.make_params(s, plan=args.plan)
     Hout, Wout = icv.output_size(p0)
     prob = Problem(icv, torch, s, sets=sets_for_cold(s, Hout, Wout), plan=args.plan)

@@ -19,6 +19,10 @@ const TileVariant kTileVariants[] = {
     {128, 128, 4, 2, "128x128_c4x2_p8"},
     {256, 128, 4, 2, "256x128_c4x2_p4"},
     {128, 128, 2, 2, "128x128_c2x2_p8"},
+    {256, 128, 4, 2, "256x128_u4x2"},
+    {128, 128, 4, 2, "128x128_u4x2"},
+    {256, 64, 4, 2, "256x64_u4x2"},
+    {128, 64, 4, 2, "128x64_u4x2"},
 };
 const int kNumTileVariants = (int)(sizeof(kTileVariants) / sizeof(kTileVariants[0]));
 
@@ -30,13 +34,15 @@ static int64_t out_extent(int64_t in, int64_t lo, int64_t hi, int64_t dil, int64
 
 static const char* kGenericNames[3] = {"generic_f32", "generic_bf16", "generic_u8i8"};
 static const char* kLowcNames[2] = {"mfma_bf16_lowc_64x64", "mfma_i8_lowc_64x64"};
-static const char* kMfmaNames[2][10] = {
+static const char* kMfmaNames[2][14] = {
     {"mfma_bf16_128x64_c2x2_p4", "mfma_bf16_128x128_c2x2_p4", "mfma_bf16_128x64_c4x2_p4", "mfma_bf16_256x64_c4x2_p8",
      "mfma_bf16_256x128_c2x2_p4", "mfma_bf16_64x64_c2x2_p4", "mfma_bf16_256x128_c4x2_p8", "mfma_bf16_128x128_c4x2_p8",
-     "mfma_bf16_256x128_c4x2_p4", "mfma_bf16_128x128_c2x2_p8"},
+     "mfma_bf16_256x128_c4x2_p4", "mfma_bf16_128x128_c2x2_p8", "mfma_bf16_256x128_u4x2", "mfma_bf16_128x128_u4x2",
+     "mfma_bf16_256x64_u4x2", "mfma_bf16_128x64_u4x2"},
     {"mfma_i8_128x64_c2x2_p4", "mfma_i8_128x128_c2x2_p4", "mfma_i8_128x64_c4x2_p4", "mfma_i8_256x64_c4x2_p8",
      "mfma_i8_256x128_c2x2_p4", "mfma_i8_64x64_c2x2_p4", "mfma_i8_256x128_c4x2_p8", "mfma_i8_128x128_c4x2_p8",
-     "mfma_i8_256x128_c4x2_p4", "mfma_i8_128x128_c2x2_p8"},
+     "mfma_i8_256x128_c4x2_p4", "mfma_i8_128x128_c2x2_p8", "mfma_i8_256x128_u4x2", "mfma_i8_128x128_u4x2",
+     "mfma_i8_256x64_u4x2", "mfma_i8_128x64_u4x2"},
 };
 
 int make_geometry(const icv_conv_params* p, Geometry* g)

@@ -367,6 +367,210 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
     }
 }
 
+// Unified variant: no producer / consumer split.  Every wavefront copies its share of each stage and
+// multiplies its block of the tile; the address arithmetic of the next stage is ordinary code between the
+// copy burst and the next wait, so the compiler can spread it among the MFMAs of the current stage, and two
+// wavefronts per SIMD cover each other's LDS and issue latencies.  The ring, the entry prefetch, the tile list
+// and the per-stage barrier are those of the split kernel above.  Output stores share the vmcnt counter with
+// the copies here: after a tile's epilogue the next waits also drain those stores (safe, merely conservative).
+template <bool I8, int MR, int NR, int WM, int WN, int KCB, bool DIRECT>
+__global__ __launch_bounds__(64 * WM * WN) void k_igemm_uni(IgemmArgs g)
+{
+    constexpr int NW = WM * WN;              // wavefronts; all copy and all multiply
+    constexpr int Q = KCB / 16;
+    constexpr int P = 256 / KCB;
+    constexpr int RPB = 1024 / KCB;
+    constexpr int A_VEC = MR * KCB / 1024 / NW;
+    constexpr int B_VEC = NR * KCB / 1024 / NW;
+    constexpr int LP = A_VEC + B_VEC;
+    constexpr int MRW = MR / WM, NRW = NR / WN;
+    constexpr int MB = MRW / 32, NB = NRW / 32;
+    constexpr int KSTEPS = KCB / 32;
+    constexpr int SLOT = (MR + NR) * KCB;
+    static_assert(A_VEC >= 1 && B_VEC >= 1 && MB >= 1 && NB >= 1, "tile too small for this wavefront split");
+    static_assert(A_VEC * NW * 1024 == MR * KCB && B_VEC * NW * 1024 == NR * KCB, "copies must divide evenly");
+    static_assert(4 * LP <= 63, "vmcnt is a 6-bit counter");
+    using acc_t = typename Acc<I8>::type;
+    using out_t = typename std::conditional<I8, int32_t, float>::type;
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
+    const int D = g.ring;
+    const int ent_base = D * SLOT;
+    const int ent_bytes = g.ent_copies * 1024;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const TileList tl = my_tiles(g.total_tiles, g.xcd_mode);
+    const int n_stages = g.n_stages;
+    const int64_t total_stages = tl.count * n_stages;
+
+    // ---- copy side (this wavefront is "producer" p = wave of NW)
+    const int p = wave;
+    const int lrow_in_blk = lane / Q;
+    int a_lane_off[A_VEC], a_row[A_VEC], b_src_off[B_VEC];
+#pragma unroll
+    for (int j = 0; j < A_VEC; j++) {
+        a_row[j] = (p * A_VEC + j) * RPB + lrow_in_blk;
+        a_lane_off[j] = ((lane % Q) ^ ((a_row[j] / P) % Q)) << 4;
+    }
+#pragma unroll
+    for (int j = 0; j < B_VEC; j++) {
+        const int row = (p * B_VEC + j) * RPB + lrow_in_blk;
+        b_src_off[j] = row * KCB + (((lane % Q) ^ ((row / P) % Q)) << 4);
+    }
+    auto fetch_entries = [&](int64_t k) {
+        if constexpr (!DIRECT) {
+            if (k >= tl.count) return;
+            const int64_t mt = (tl.first + k * tl.step) / g.n_tiles;
+            const int32_t* src = g.ind + mt * ((int64_t)g.T * MR);
+            const uint32_t dst = lds_base + ent_base + (uint32_t)(k & 1) * ent_bytes;
+            const int n_chunks = g.T * MR / 4;
+            for (int u = p; u < g.ent_copies; u += NW) {
+                const int c = u * 64 + lane;
+                if (c < n_chunks) copy16_global_to_lds(src + c * 4, dst + u * 1024);
+            }
+        }
+    };
+    int64_t ik = 0;
+    int is = 0, itap = 0, icc = 0, islot = 0;
+    const uint8_t* wstage = nullptr;
+    const uint8_t* adirect = nullptr;
+    auto enter_tile = [&]() {
+        if (ik >= tl.count) return;
+        const int64_t tile = tl.first + ik * tl.step;
+        const int32_t nt = (int32_t)(tile % g.n_tiles);
+        const int64_t mt = tile / g.n_tiles;
+        wstage = g.w + ((int64_t)nt * n_stages) * (NR * KCB);
+        if constexpr (DIRECT) adirect = g.a + (mt * MR + a_row[0]) * g.row_stride_bytes;
+    };
+    enter_tile();
+    const uint8_t* asrc[A_VEC];
+    const uint8_t* bsrc = nullptr;
+    bool prepared = false;
+    auto prepare = [&]() {
+        prepared = ik < tl.count;
+        if (!prepared) return;
+        if constexpr (DIRECT) {
+#pragma unroll
+            for (int j = 0; j < A_VEC; j++)
+                asrc[j] = adirect + (int64_t)(j * RPB) * g.row_stride_bytes + (int64_t)is * KCB + a_lane_off[j];
+        } else {
+            const int32_t* ent = (const int32_t*)(lds + ent_base + (int)(ik & 1) * ent_bytes) + itap * MR;
+            int32_t e[A_VEC];
+#pragma unroll
+            for (int j = 0; j < A_VEC; j++) e[j] = ent[a_row[j]];
+            const uint8_t* zsrc = g.zero_row + icc * KCB;
+            const uint8_t* abase = g.a + icc * KCB;
+#pragma unroll
+            for (int j = 0; j < A_VEC; j++) {
+                const uint32_t off = (uint32_t)(e[j] + a_lane_off[j]);
+                asrc[j] = e[j] < 0 ? zsrc + a_lane_off[j] : abase + off;
+            }
+        }
+        bsrc = wstage;
+        wstage += NR * KCB;
+        if (++icc == g.stages_per_tap) { icc = 0; ++itap; }
+        if (++is == n_stages) {
+            is = 0; itap = 0; icc = 0;
+            fetch_entries(ik + 2);
+            ++ik;
+            enter_tile();
+        }
+    };
+    auto issue = [&]() {
+        if (!prepared) return;
+        const uint32_t slot = lds_base + (uint32_t)islot * SLOT;
+#pragma unroll
+        for (int j = 0; j < A_VEC; j++) copy16_global_to_lds(asrc[j], slot + (p * A_VEC + j) * 1024);
+#pragma unroll
+        for (int j = 0; j < B_VEC; j++)
+            copy16_global_to_lds(bsrc + b_src_off[j], slot + MR * KCB + (p * B_VEC + j) * 1024);
+        islot = islot + 1 == D ? 0 : islot + 1;
+    };
+
+    // ---- multiply side
+    const int wm = wave / WN, wn = wave % WN;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int swz = (lrow / P) % Q;
+    const uint32_t a_frag_base = (wm * MRW + lrow) * KCB;
+    const uint32_t b_frag_base = MR * KCB + (wn * NRW + lrow) * KCB;
+    out_t* out = (out_t*)g.out;
+
+    fetch_entries(0);
+    fetch_entries(1);
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    prepare();
+    for (int q = 0; q < D - 1; q++) { issue(); prepare(); }
+
+    int cslot = 0;
+    int64_t q = 0;
+    for (int64_t k = 0; k < tl.count; k++) {
+        acc_t acc[MB][NB];
+#pragma unroll
+        for (int i = 0; i < MB; i++)
+#pragma unroll
+            for (int j = 0; j < NB; j++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) acc[i][j][r] = 0;
+
+        for (int s = 0; s < n_stages; s++, q++) {
+            const int64_t younger = total_stages - 1 - q;
+            wait_all_but_stages<LP>(younger < D - 2 ? (int)younger : D - 2);
+            __builtin_amdgcn_s_barrier();
+            issue();
+            prepare();
+            const uint8_t* S = lds + cslot * SLOT;
+            cslot = cslot + 1 == D ? 0 : cslot + 1;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ks++) {
+                const uint32_t coff = (uint32_t)(((2 * ks + lhalf) ^ swz) << 4);
+                uint4 af[MB], bf[NB];
+#pragma unroll
+                for (int i = 0; i < MB; i++) af[i] = *(const uint4*)(S + a_frag_base + i * 32 * KCB + coff);
+#pragma unroll
+                for (int j = 0; j < NB; j++) bf[j] = *(const uint4*)(S + b_frag_base + j * 32 * KCB + coff);
+#pragma unroll
+                for (int i = 0; i < MB; i++)
+#pragma unroll
+                    for (int j = 0; j < NB; j++) acc[i][j] = mfma32<I8>(af[i], bf[j], acc[i][j]);
+            }
+        }
+
+        const int64_t tile = tl.first + k * tl.step;
+        const int32_t nt = (int32_t)(tile % g.n_tiles);
+        const int64_t mt = tile / g.n_tiles;
+        const int64_t m_base = mt * MR + wm * MRW + 4 * lhalf;
+        const int32_t n_base = nt * NR + wn * NRW + lrow;
+        const bool full = (mt + 1) * MR <= g.M && (nt + 1) * NR <= g.K;
+        if (full) {
+            out_t* o = out + m_base * g.out_stride + n_base;
+#pragma unroll
+            for (int i = 0; i < MB; i++)
+#pragma unroll
+                for (int j = 0; j < NB; j++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++)
+                        o[(int64_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * g.out_stride + j * 32] = acc[i][j][r];
+        } else {
+#pragma unroll
+            for (int i = 0; i < MB; i++)
+#pragma unroll
+                for (int j = 0; j < NB; j++) {
+                    const int32_t col = n_base + j * 32;
+#pragma unroll
+                    for (int r = 0; r < 16; r++) {
+                        const int64_t row = m_base + i * 32 + 8 * (r >> 2) + (r & 3);
+                        if (row < g.M && col < g.K) out[row * g.out_stride + col] = acc[i][j][r];
+                    }
+                }
+        }
+    }
+    wait_vmcnt<0>();
+}
+
 // ------------------------------------------------------------------ launch
 static int device_cu_count()
 {
@@ -386,8 +590,10 @@ constexpr size_t kLdsPerCu = 160 * 1024;
 template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool DIRECT>
 static int launch_one(const Geometry& g, IgemmArgs a, hipStream_t s)
 {
-    auto kern = k_igemm_mfma<I8, MR, NR, WM, WN, NP, KCB, DIRECT>;
     constexpr int threads = 64 * (WM * WN + NP);
+    void (*kern)(IgemmArgs);
+    if constexpr (NP == 0) kern = k_igemm_uni<I8, MR, NR, WM, WN, KCB, DIRECT>;
+    else kern = k_igemm_mfma<I8, MR, NR, WM, WN, NP, KCB, DIRECT>;
     constexpr size_t slot = (size_t)(MR + NR) * KCB;
     a.ent_copies = DIRECT ? 0 : (int32_t)(((size_t)g.T * MR * 4 + 1023) / 1024);
     const size_t ent = (size_t)2 * a.ent_copies * 1024;
@@ -435,12 +641,13 @@ static int launch_tile(const Geometry& g, const IgemmArgs& a, bool direct, hipSt
         return direct ? launch_one<I8, MR, NR, WM, WN, NP, 128, true>(g, a, s)
                       : launch_one<I8, MR, NR, WM, WN, NP, 128, false>(g, a, s);
     }
-    if constexpr (NR * 64 / 1024 >= NP) {      // a 64-byte stage of the B tile must still split over NP producers
+    if constexpr (NR * 64 / 1024 >= (NP == 0 ? WM * WN : NP)) {      // a 64-byte stage of the B tile must still split over the copying wavefronts
         return direct ? launch_one<I8, MR, NR, WM, WN, NP, 64, true>(g, a, s)
                       : launch_one<I8, MR, NR, WM, WN, NP, 64, false>(g, a, s);
     } else {
-        return direct ? launch_one<I8, MR, NR, WM, WN, 4, 64, true>(g, a, s)
-                      : launch_one<I8, MR, NR, WM, WN, 4, 64, false>(g, a, s);
+        if constexpr (NP == 0) return ICV_ERR_UNSUPPORTED;
+        else return direct ? launch_one<I8, MR, NR, WM, WN, 4, 64, true>(g, a, s)
+                           : launch_one<I8, MR, NR, WM, WN, 4, 64, false>(g, a, s);
     }
 }
 
@@ -458,6 +665,10 @@ static int launch_dtype(const Geometry& g, const IgemmArgs& a, bool direct, hipS
         case 7: return launch_tile<I8, 128, 128, 4, 2, 8>(g, a, direct, s);
         case 8: return launch_tile<I8, 256, 128, 4, 2, 4>(g, a, direct, s);
         case 9: return launch_tile<I8, 128, 128, 2, 2, 8>(g, a, direct, s);
+        case 10: return launch_tile<I8, 256, 128, 4, 2, 0>(g, a, direct, s);
+        case 11: return launch_tile<I8, 128, 128, 4, 2, 0>(g, a, direct, s);
+        case 12: return launch_tile<I8, 256, 64, 4, 2, 0>(g, a, direct, s);
+        case 13: return launch_tile<I8, 128, 64, 4, 2, 0>(g, a, direct, s);
         default: return ICV_ERR_UNSUPPORTED;
     }
 }

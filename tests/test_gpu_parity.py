@@ -147,7 +147,7 @@ def test_small_shapes_match_oracle(s):
     check_against_oracle(s, buf.output.cpu().numpy(), x, w)
 
 
-N_PLANS = 11    # plan 1 = vector ALU, 2.. = tensor-core tile variants
+N_PLANS = 15    # plan 1 = vector ALU, 2.. = tensor-core tile variants
 
 
 @pytest.mark.parametrize("plan", range(1, N_PLANS + 1))
@@ -160,7 +160,13 @@ def test_every_tile_variant(plan, dtype):
                         dtype=dtype, zero_point=zp, seed=53)):
         _say("variant", plan, icv.plan_name(icv.make_params(s, plan=plan)), s.name)
         x, w = make_tensors(s)
-        buf, xd = run_indirect(s, x, w, plan=plan)
+        try:
+            buf, xd = run_indirect(s, x, w, plan=plan)
+        except icv.IcvError as e:
+            # a forced variant may decline a stage width it cannot split over its wavefronts -- loudly, not wrongly
+            row_bytes = s.C * (1 if dtype == "u8i8" else 2)
+            assert e.status == icv.ICV_ERR_UNSUPPORTED and row_bytes % 128 != 0, (plan, s.name, e)
+            continue
         check_against_oracle(s, buf.output.cpu().numpy(), x, w)
 
 

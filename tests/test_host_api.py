@@ -96,7 +96,7 @@ def test_invalid_arguments_are_rejected(lib):
     assert _status(lib, s, R=80, PT=0, PB=0) == icv.ICV_ERR_INVALID_ARG             # kernel larger than input
     assert _status(lib, s, N=1 << 20) == icv.ICV_ERR_INVALID_ARG                    # input of 2 GiB or more
     assert _status(lib, s, plan=1 << 12) == icv.ICV_ERR_INVALID_ARG
-    assert _status(lib, s, plan=15) == icv.ICV_ERR_INVALID_ARG                      # no such tile variant
+    assert _status(lib, s, plan=2 | (7 << 4)) == icv.ICV_ERR_INVALID_ARG            # ring deeper than 6
     assert _status(lib, s, plan=2 | (1 << 4)) == icv.ICV_ERR_INVALID_ARG            # a ring needs two slots
     assert _status(lib, CONFIGS["cfg4_int8_3x3"], input_zero_point=300) == icv.ICV_ERR_INVALID_ARG
     assert lib.icv_output_size(None, None, None) == icv.ICV_ERR_INVALID_ARG
