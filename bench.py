@@ -31,7 +31,10 @@ LLC_BYTES = 256 << 20
 
 # HBM traffic of the dominant kernel per launch, bytes, measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None until measured.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/igemm_cfg2_hbm_traffic.md: FETCH 8430.8 KiB x 1.99975 + WRITE 25101.4 KiB x 1.0
+    "cfg2_3x3_c64": int((8430.8 * 1.99975 + 25101.4) * 1024),
+}
 
 
 def flops(s, Hout, Wout, c=None):

@@ -97,7 +97,10 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         if (plan_kernel >= 2) {
             variant = plan_kernel - 2;
         } else {
-            variant = p->K <= 64 ? 0 : 1;
+            // measured on MI355X: a 64-wide filter is served best by 256-row tiles with 8 + 8 wavefronts (when a
+            // tile's entries still fit their LDS budget), wider filters by 128 x 128 tiles
+            if (p->K <= 64) variant = (int64_t)256 * T * 4 <= 24 * 1024 ? 3 : 0;
+            else variant = 1;
         }
         // a workgroup keeps two tiles' worth of entries in LDS: 2 * MR*T int32 (plus padding)
         if ((int64_t)kTileVariants[variant].MR * T * 4 > 24 * 1024) mfma_ok = false;

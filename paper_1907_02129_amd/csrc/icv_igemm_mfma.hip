@@ -349,7 +349,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
                     for (int j = 0; j < NB; j++)
 #pragma unroll
                         for (int r = 0; r < 16; r++)
-                            o[(int64_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * g.out_stride + j * 32] = acc[i][j][r];
+                            __builtin_nontemporal_store(acc[i][j][r], &o[(int64_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * g.out_stride + j * 32]);
             } else {
 #pragma unroll
                 for (int i = 0; i < MB; i++)
@@ -553,7 +553,7 @@ __global__ __launch_bounds__(64 * WM * WN) void k_igemm_uni(IgemmArgs g)
                 for (int j = 0; j < NB; j++)
 #pragma unroll
                     for (int r = 0; r < 16; r++)
-                        o[(int64_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * g.out_stride + j * 32] = acc[i][j][r];
+                        __builtin_nontemporal_store(acc[i][j][r], &o[(int64_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * g.out_stride + j * 32]);
         } else {
 #pragma unroll
             for (int i = 0; i < MB; i++)
