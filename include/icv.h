@@ -64,9 +64,10 @@ typedef struct icv_conv_params {
     int32_t dtype;             /* icv_dtype */
     int32_t input_zero_point;  /* ICV_U8I8 only: the value the zero row holds, 0..255 */
     int32_t plan;              /* 0: the library picks kernel, tile and pipeline shape.  For tuning sweeps:
-                                  bits 0-3 kernel (1 vector ALU, 2.. tile variant), bits 4-7 LDS ring depth (2..6),
-                                  bits 8-9 workgroups per CU (1, 2), bits 10-11 stage width (1: 64 B, 2: 128 B).
-                                  All set-up calls and the conv call of one problem must use the same value. */
+                                  bits 0-3 kernel (1 vector ALU, 2.. tile variant), bits 4-7 LDS ring depth (2..12),
+                                  bits 8-9 workgroups per CU (1, 2), bits 10-11 stage width (1: 64 B, 2: 128 B),
+                                  bits 12-13 row staging (1: rows gathered per kernel element, 2: the tile's
+                                  input pixel range kept in LDS).  All set-up calls and the conv call of one problem must use the same value. */
 } icv_conv_params;
 
 /* Hout, Wout by the formula above.  ICV_ERR_INVALID_ARG when the parameters are not a valid problem. */
@@ -74,7 +75,9 @@ ICV_API int icv_output_size(const icv_conv_params* p, int32_t* Hout, int32_t* Wo
 
 /*
  * Buffer sizes in bytes (0 when the parameters are invalid).
- *  indirection  : int32 entries, M rounded up to whole row tiles, times R*S (independent of C, section 1.1)
+ *  indirection  : int32 entries, M rounded up to whole row tiles, times R*S (independent of C, section 1.1);
+ *                 kernels that keep a tile's input pixels in LDS append one 16-byte record per row tile:
+ *                 {smallest valid entry of the tile, pixels from there to the largest one, 0, 0}
  *  packed filter: the [K][R][S][C] filter re-laid as the tiles the GEMM kernel reads, K padded to the tile
  *  zero row     : C elements (section 2.3's explicit zero vector), rounded up to 16 bytes
  *  im2col       : the [M][R*S*C] patch matrix of the ablation path
@@ -91,6 +94,13 @@ ICV_API size_t icv_im2col_bytes(const icv_conv_params* p);
  * Rows past M in the last tile name the zero row.  Returns -1 on invalid arguments.
  */
 ICV_API int64_t icv_indirection_index(const icv_conv_params* p, int64_t m, int32_t tap);
+
+/*
+ * Upper bound on the number of consecutive input pixels that the valid entries of any `rows` consecutive
+ * output pixels span (the entries of neighbouring output pixels overlap, section 3.4's re-use of input rows);
+ * the library sizes its LDS input patch with it.  Host arithmetic only.  Returns -1 on invalid arguments.
+ */
+ICV_API int64_t icv_tile_span_bound(const icv_conv_params* p, int32_t rows);
 
 /* Fill the explicit zero vector of section 2.3: zeros, or input_zero_point bytes for ICV_U8I8. */
 ICV_API int icv_init_zero_row(const icv_conv_params* p, void* zero_row, void* stream);

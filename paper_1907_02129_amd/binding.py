@@ -26,7 +26,7 @@ DTYPES = {"f32": ICV_F32, "bf16": ICV_BF16, "u8i8": ICV_U8I8}
 # every symbol include/icv.h declares
 EXPORTS = (
     "icv_output_size", "icv_indirection_bytes", "icv_packed_filter_bytes", "icv_zero_row_bytes",
-    "icv_im2col_bytes", "icv_indirection_index", "icv_init_zero_row", "icv_pack_filter",
+    "icv_im2col_bytes", "icv_indirection_index", "icv_tile_span_bound", "icv_init_zero_row", "icv_pack_filter",
     "icv_setup_indirection", "icv_conv2d_nhwc", "icv_im2col", "icv_gemm_nhwc", "icv_conv2d_nhwc_im2col",
     "icv_plan_name", "icv_status_string", "icv_last_hip_error",
 )
@@ -68,6 +68,7 @@ def load_library(path: str | None = None):
         "icv_zero_row_bytes": (ctypes.c_size_t, [P]),
         "icv_im2col_bytes": (ctypes.c_size_t, [P]),
         "icv_indirection_index": (ctypes.c_int64, [P, ctypes.c_int64, ctypes.c_int32]),
+        "icv_tile_span_bound": (ctypes.c_int64, [P, ctypes.c_int32]),
         "icv_init_zero_row": (ctypes.c_int, [P, vp, vp]),
         "icv_pack_filter": (ctypes.c_int, [P, vp, vp, vp]),
         "icv_setup_indirection": (ctypes.c_int, [P, vp, vp]),
@@ -151,6 +152,10 @@ def indirection_index(p, m: int, tap: int) -> int:
     return load_library().icv_indirection_index(ctypes.byref(p), m, tap)
 
 
+def tile_span_bound(p, rows: int) -> int:
+    return load_library().icv_tile_span_bound(ctypes.byref(p), rows)
+
+
 def init_zero_row(p, zero_row, stream=None):
     _check(load_library().icv_init_zero_row(ctypes.byref(p), _ptr(zero_row), _stream(stream)), "icv_init_zero_row")
 
@@ -230,15 +235,30 @@ def run(buf: ConvBuffers, input_dev: torch.Tensor) -> torch.Tensor:
     return buf.output
 
 
+def tile_ranges(buf: ConvBuffers):
+    """Range records appended to the buffer by the plans that keep pixel ranges in LDS: (tiles, 4) int32 or None."""
+    p = buf.p
+    T = p.R * p.S
+    phys = buf.indirection.cpu().numpy()
+    mr = indirection_index(p, 0, 1) if T > 1 else None
+    if mr is None:
+        return None
+    tiles = -(-buf.M // mr)
+    rest = phys[tiles * mr * T:]
+    return rest.reshape(tiles, 4) if len(rest) == tiles * 4 else None
+
+
 def logical_indirection(buf: ConvBuffers) -> np.ndarray:
     """The buffer re-ordered to [M][R*S] through icv_indirection_index, with the byte offsets turned back
     into pixel indices (-1 = zero row); host side, for tests.  Returns (rows < M, tile-padding rows)."""
     p = buf.p
     T = p.R * p.S
     phys = buf.indirection.cpu().numpy()
-    # the layout is [tile][tap][MR]; recover MR from the index function instead of assuming it
+    # the layout is [tile][tap][MR] (range records may follow); recover MR from the index function
+    # (with a single kernel element the order is the identity and no records follow)
     mr = indirection_index(p, 0, 1) if T > 1 else len(phys)
-    tiles = len(phys) // (mr * T)
+    tiles = -(-buf.M // mr)
+    phys = phys[:tiles * mr * T]
     assert indirection_index(p, mr, 0) in (-1, mr * T) and indirection_index(p, 1, 0) == 1
     logical = phys.reshape(tiles, T, mr).transpose(0, 2, 1).reshape(tiles * mr, T)
     stride_bytes = (p.in_pixel_stride or p.C) * {ICV_F32: 4, ICV_BF16: 2, ICV_U8I8: 1}[p.dtype]

@@ -32,8 +32,35 @@ static int64_t out_extent(int64_t in, int64_t lo, int64_t hi, int64_t dil, int64
     return span < 0 ? 0 : span / stride + 1;
 }
 
+int64_t tile_span_bound(const icv_conv_params* p, int64_t Hout, int64_t Wout, int64_t rows)
+{
+    // Pixel index of entry (m, tap) before clipping: q(m) + ky*DY*Win + kx*DX with
+    // q(m) = (n*Hin + oy*SY - PT)*Win + ox*SX - PL.  Along consecutive m, q moves by SX inside an output row, by
+    // `rw` at the end of a row and by `iw` at the end of an image; max q - min q over a window is at most the sum
+    // of the absolute steps.  Clipped (padding) entries only remove pixels from the set.
+    const int64_t Win = p->Win, Hin = p->Hin, SX = p->SX, SY = p->SY;
+    const int64_t rw = SY * Win - (Wout - 1) * SX;
+    const int64_t iw = Hin * Win - (Hout - 1) * SY * Win - (Wout - 1) * SX;
+    const int64_t arw = rw < 0 ? -rw : rw, aiw = iw < 0 ? -iw : iw;
+    int64_t nrw = 0, niw = 0;
+    if (rows >= 2) {
+        nrw = (rows - 2) / Wout + 1;
+        niw = (rows - 2) / (Hout * Wout) + 1;
+        if (nrw > rows - 1) nrw = rows - 1;
+        if (niw > rows - 1) niw = rows - 1;
+    }
+    const int64_t walk = SX * (rows - 1) + nrw * (arw > SX ? arw - SX : 0) + niw * (aiw > SX ? aiw - SX : 0);
+    return walk + (int64_t)(p->R - 1) * p->DY * Win + (int64_t)(p->S - 1) * p->DX + 1;
+}
+
 static const char* kGenericNames[3] = {"generic_f32", "generic_bf16", "generic_u8i8"};
 static const char* kLowcNames[2] = {"mfma_bf16_lowc_64x64", "mfma_i8_lowc_64x64"};
+static const char* kPatchNames[2][14] = {
+    {"mfma_bf16_128x64_c2x2_patch", "mfma_bf16_128x128_c2x2_patch", "", "mfma_bf16_256x64_c4x2_patch", "", "",
+     "mfma_bf16_256x128_c4x2_patch", "mfma_bf16_128x128_c4x2_patch", "", "", "", "", "", ""},
+    {"mfma_i8_128x64_c2x2_patch", "mfma_i8_128x128_c2x2_patch", "", "mfma_i8_256x64_c4x2_patch", "", "",
+     "mfma_i8_256x128_c4x2_patch", "mfma_i8_128x128_c4x2_patch", "", "", "", "", "", ""},
+};
 static const char* kMfmaNames[2][14] = {
     {"mfma_bf16_128x64_c2x2_p4", "mfma_bf16_128x128_c2x2_p4", "mfma_bf16_128x64_c4x2_p4", "mfma_bf16_256x64_c4x2_p8",
      "mfma_bf16_256x128_c2x2_p4", "mfma_bf16_64x64_c2x2_p4", "mfma_bf16_256x128_c4x2_p8", "mfma_bf16_128x128_c4x2_p8",
@@ -57,11 +84,12 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     if (p->out_pixel_stride != 0 && p->out_pixel_stride < p->K) return ICV_ERR_INVALID_ARG;
     if (p->dtype == ICV_U8I8 && (p->input_zero_point < 0 || p->input_zero_point > 255)) return ICV_ERR_INVALID_ARG;
     // plan: bits 0-3 kernel (0 auto, 1 vector ALU, 2.. tile variant), bits 4-7 ring depth, bits 8-9 workgroups
-    // per CU, bits 10-11 stage width (1: 64 bytes, 2: 128 bytes); 0 in a field leaves the choice to the library
+    // per CU, bits 10-11 stage width (1: 64 bytes, 2: 128 bytes), bits 12-13 row staging (1: rows gathered per
+    // kernel element, 2: the tile's pixel range kept in LDS); 0 in a field leaves the choice to the library
     const int plan_kernel = p->plan & 15, plan_ring = (p->plan >> 4) & 15, plan_per_cu = (p->plan >> 8) & 3,
-              plan_kcb = (p->plan >> 10) & 3;
-    if (p->plan < 0 || p->plan >= (1 << 12) || plan_kernel > kNumTileVariants + 1 || plan_ring == 1 || plan_ring > 6 ||
-        plan_per_cu > 2 || plan_kcb > 2)
+              plan_kcb = (p->plan >> 10) & 3, plan_staging = (p->plan >> 12) & 3;
+    if (p->plan < 0 || p->plan >= (1 << 14) || plan_kernel > kNumTileVariants + 1 || plan_ring == 1 || plan_ring > 12 ||
+        plan_per_cu > 2 || plan_kcb > 2 || plan_staging > 2)
         return ICV_ERR_INVALID_ARG;
 
     const int64_t Hout = out_extent(p->Hin, p->PT, p->PB, p->DY, p->R, p->SY);
@@ -85,6 +113,8 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     g->elem_bytes = p->dtype == ICV_F32 ? 4 : (p->dtype == ICV_BF16 ? 2 : 1);
     g->in_stride = p->in_pixel_stride ? p->in_pixel_stride : p->C;
     g->out_stride = p->out_pixel_stride ? p->out_pixel_stride : p->K;
+    g->patch_rows = 0;
+    g->cc_major = 0;
 
     // ---- plan: which kernel, which tile
     const int64_t row_bytes = (int64_t)p->C * g->elem_bytes;        // bytes of one gathered A row
@@ -93,9 +123,43 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     if (p->dtype == ICV_U8I8 && p->input_zero_point != 128) mfma_ok = false;   // x ^ 0x80 == x - 128 only
     if (plan_kernel == 1) mfma_ok = false;                                      // forced vector-ALU kernel
     int variant = -1;
+    int patch_rows = 0, patch_kcb = 0;
+    // LDS-resident pixel range: worthwhile when several kernel elements re-read the rows, possible when the pixel
+    // stride is a power of two (entry -> LDS row is a shift) and two patch buffers fit beside the other buffers
+    auto try_patch = [&](int v, bool forced) {
+        if (plan_staging == 1 || T < 4 || !patch_variant_supported(v)) return false;
+        if ((stride_bytes & (stride_bytes - 1)) != 0) return false;
+        const TileVariant& tv = kTileVariants[v];
+        if ((int64_t)tv.MR * T * 4 > 24 * 1024) return false;
+        const int64_t rows = tile_span_bound(p, Hout, Wout, tv.MR);
+        const int ent_copies = (int)((tv.MR * T * 4 + 1023) / 1024);
+        // Measured on MI355X: the per-stage synchronisation is only amortised with 128-byte stages, so unless the
+        // plan is forced the pixel-range kernel is taken when two patches of 128-byte rows fit.
+        const int kcb_max = (row_bytes % 128 == 0 && plan_kcb != 1) ? 128 : 64;
+        const int kcb_min = forced ? 64 : 128;
+        for (int kcb = kcb_max; kcb >= kcb_min; kcb -= 64) {
+            const int64_t cap_units = (rows * kcb + 1023) / 1024;
+            if (cap_units < 4096 && patch_lds_bytes(tv.NR, kcb, 2, (int)cap_units, ent_copies) <= 160 * 1024) {
+                variant = v; patch_rows = (int)rows; patch_kcb = kcb;
+                return true;
+            }
+        }
+        return false;
+    };
+    // wide filters: 256-row tiles when they still give every compute unit a tile, else 128-row tiles
+    const int wide = ((M + 255) / 256) * ((p->K + 127) / 128) >= 256 ? 6 : 7;
     if (mfma_ok) {
         if (plan_kernel >= 2) {
             variant = plan_kernel - 2;
+            if (!try_patch(variant, plan_staging == 2) && plan_staging == 2) return ICV_ERR_UNSUPPORTED;
+        } else if (p->K <= 64 ? (try_patch(3, false) || try_patch(0, false))
+                              : (try_patch(wide, false) || try_patch(wide == 6 ? 7 : 1, false))) {
+            // a pixel-range plan fits
+        } else if (plan_staging == 2 && (p->K <= 64 ? (try_patch(3, true) || try_patch(0, true))
+                                                    : (try_patch(wide, true) || try_patch(1, true)))) {
+            // a pixel-range plan fits
+        } else if (plan_staging == 2) {
+            return ICV_ERR_UNSUPPORTED;
         } else {
             // measured on MI355X: a 64-wide filter is served best by 256-row tiles with 8 + 8 wavefronts (when a
             // tile's entries still fit their LDS budget), wider filters by 128 x 128 tiles
@@ -129,12 +193,15 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         g->NR = tv.NR;
         g->KCB = row_bytes % 128 == 0 ? 128 : 64;
         if (plan_kcb == 1) g->KCB = 64;
+        if (patch_rows) g->KCB = patch_kcb;
+        g->patch_rows = patch_rows;
+        g->cc_major = patch_rows ? 1 : 0;
         g->ring = plan_ring;
         g->blocks_per_cu = plan_per_cu;
         g->stages_per_tap = (int32_t)(row_bytes / g->KCB);
         g->taps_per_stage = 1;
         g->n_stages = g->T * g->stages_per_tap;
-        g->name = kMfmaNames[p->dtype == ICV_U8I8 ? 1 : 0][variant];
+        g->name = (patch_rows ? kPatchNames : kMfmaNames)[p->dtype == ICV_U8I8 ? 1 : 0][variant];
     } else {
         g->kind = PLAN_GENERIC;
         g->variant = -1;
@@ -175,7 +242,8 @@ size_t icv_indirection_bytes(const icv_conv_params* p)
 {
     Geometry g;
     if (make_geometry(p, &g) != ICV_OK) return 0;
-    return (size_t)g.m_tiles * g.MR * g.T * sizeof(int32_t);
+    // entries, then (pixel-range plans) one 16-byte range record per row tile
+    return (size_t)g.m_tiles * g.MR * g.T * sizeof(int32_t) + (g.patch_rows ? (size_t)g.m_tiles * 16 : 0);
 }
 
 size_t icv_packed_filter_bytes(const icv_conv_params* p)
@@ -210,6 +278,13 @@ int64_t icv_indirection_index(const icv_conv_params* p, int64_t m, int32_t tap)
     return (m / g.MR) * ((int64_t)g.T * g.MR) + (int64_t)tap * g.MR + m % g.MR;
 }
 
+int64_t icv_tile_span_bound(const icv_conv_params* p, int32_t rows)
+{
+    Geometry g;
+    if (make_geometry(p, &g) != ICV_OK || rows < 1) return -1;
+    return tile_span_bound(p, g.Hout, g.Wout, rows);
+}
+
 int icv_init_zero_row(const icv_conv_params* p, void* zero_row, void* stream)
 {
     Geometry g;
@@ -240,6 +315,7 @@ int icv_setup_indirection(const icv_conv_params* p, void* indirection, void* str
 static int conv_common(const icv_conv_params* p, const Geometry& g, const void* a, const void* packed,
                        const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s)
 {
+    if (g.kind == PLAN_MFMA && g.patch_rows && !a_direct) return launch_igemm_patch(p, g, a, packed, ind, out, s);
     if (g.kind == PLAN_MFMA) return launch_igemm_mfma(p, g, a, packed, ind, zero_row, out, a_direct, s);
     if (g.kind == PLAN_MFMA_LOWC) return launch_igemm_lowc(p, g, a, packed, ind, zero_row, out, a_direct, s);
     return launch_igemm_generic(p, g, a, packed, ind, zero_row, out, a_direct, s);

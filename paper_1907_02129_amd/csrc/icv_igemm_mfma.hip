@@ -32,15 +32,9 @@
 //
 // uint8 activations: MFMA multiplies signed bytes, so every A fragment is XORed with 0x80, which turns
 // x into x - 128 exactly; the zero row (filled with the zero point 128) becomes a row of zeros.
-#include <type_traits>
-#include "icv_internal.h"
+#include "icv_mfma_common.h"
 
 namespace icv {
-
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
-typedef int i32x4_t __attribute__((ext_vector_type(4)));
-typedef int i32x16_t __attribute__((ext_vector_type(16)));
 
 struct IgemmArgs {
     const uint8_t* a;         // input tensor | im2col matrix
@@ -57,89 +51,9 @@ struct IgemmArgs {
     int32_t ring;              // LDS slots in the ring, 2..6
     int32_t ent_copies;        // wavefront-wide copies per producer per tile of entries
     int32_t xcd_mode;          // 1: grid is a multiple of 8 and tiles are dealt per XCD
+    int32_t cc_major;          // packed filter stage order: 1 = chunk * T + tap, 0 = tap * stages_per_tap + chunk
+    int32_t row_bytes;         // C * element size
 };
-
-template <bool I8>
-struct Acc {
-    using type = f32x16_t;
-};
-template <>
-struct Acc<true> {
-    using type = i32x16_t;
-};
-
-template <bool I8>
-__device__ inline typename Acc<I8>::type mfma32(const uint4& a, const uint4& b, typename Acc<I8>::type c)
-{
-    if constexpr (I8) {
-        i32x4_t av = {(int)(a.x ^ 0x80808080u), (int)(a.y ^ 0x80808080u), (int)(a.z ^ 0x80808080u),
-                      (int)(a.w ^ 0x80808080u)};
-        i32x4_t bv = {(int)b.x, (int)b.y, (int)b.z, (int)b.w};
-        return __builtin_amdgcn_mfma_i32_32x32x32_i8(av, bv, c, 0, 0, 0);
-    } else {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
-    }
-}
-
-// 16-byte global -> LDS copy without a register stop: lane l of the wavefront writes LDS bytes
-// [lds_base + 16*l, +16).  Inline assembly on purpose: the compiler does not see a memory instruction, so it
-// inserts no waits of its own for it, and the producers count outstanding copies themselves (wait_vmcnt).
-// A producer issues no other vector-memory instruction while copies are in flight.
-__device__ inline void copy16_global_to_lds(const void* gptr, uint32_t lds_base)
-{
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n"
-                 :
-                 : "v"(gptr), "s"(lds_base)
-                 : "memory");
-}
-
-template <int N>
-__device__ inline void wait_vmcnt()
-{
-    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-
-// Wait until at most `stages` x LP of this wavefront's copies are outstanding (copies retire in order).
-template <int LP>
-__device__ inline void wait_all_but_stages(int stages)
-{
-    switch (stages) {
-        case 0: wait_vmcnt<0>(); break;
-        case 1: wait_vmcnt<LP>(); break;
-        case 2: wait_vmcnt<2 * LP>(); break;
-        case 3: wait_vmcnt<3 * LP>(); break;
-        default: wait_vmcnt<4 * LP>(); break;
-    }
-}
-
-// Tile list of a persistent workgroup.  Workgroups are dealt round-robin to the 8 XCDs (block b runs on
-// XCD b % 8).  In XCD mode XCD x owns the contiguous tile range [first, first + count) and its G/8 workgroups
-// take tiles first + i, first + i + G/8, ... ; otherwise block b takes b, b + G, ...
-struct TileList {
-    int64_t first, step, count;   // tiles first + k*step for k < count
-};
-
-__device__ inline TileList my_tiles(int64_t total, int xcd_mode)
-{
-    const int64_t b = blockIdx.x, G = gridDim.x;
-    TileList t;
-    if (xcd_mode) {
-        const int64_t chunk = total >> 3, rem = total & 7, x = b & 7;
-        const int64_t start = x * chunk + (x < rem ? x : rem);
-        const int64_t len = chunk + (x < rem ? 1 : 0);
-        const int64_t i = b >> 3;
-        t.step = G >> 3;
-        t.first = start + i;
-        t.count = i < len ? (len - i + t.step - 1) / t.step : 0;
-    } else {
-        t.step = G;
-        t.first = b;
-        t.count = b < total ? (total - b + G - 1) / G : 0;
-    }
-    return t;
-}
 
 template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool DIRECT>
 __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
@@ -240,9 +154,12 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
             prepared = ik < tl.count;
             if (!prepared) return;
             if constexpr (DIRECT) {
+                // byte offset of this stage inside a patch-matrix row ([tap][C])
+                const int64_t koff = g.cc_major ? (int64_t)(is % g.T) * g.row_bytes + (int64_t)(is / g.T) * KCB
+                                                : (int64_t)is * KCB;
 #pragma unroll
                 for (int j = 0; j < A_VEC; j++)
-                    asrc[j] = adirect + (int64_t)(j * RPB) * g.row_stride_bytes + (int64_t)is * KCB + a_lane_off[j];
+                    asrc[j] = adirect + (int64_t)(j * RPB) * g.row_stride_bytes + koff + a_lane_off[j];
             } else {
                 const int32_t* ent = (const int32_t*)(lds + ent_base + (int)(ik & 1) * ent_bytes) + itap * MR;
                 int32_t e[A_VEC];
@@ -453,9 +370,11 @@ __global__ __launch_bounds__(64 * WM * WN) void k_igemm_uni(IgemmArgs g)
         prepared = ik < tl.count;
         if (!prepared) return;
         if constexpr (DIRECT) {
+            const int64_t koff = g.cc_major ? (int64_t)(is % g.T) * g.row_bytes + (int64_t)(is / g.T) * KCB
+                                            : (int64_t)is * KCB;
 #pragma unroll
             for (int j = 0; j < A_VEC; j++)
-                asrc[j] = adirect + (int64_t)(j * RPB) * g.row_stride_bytes + (int64_t)is * KCB + a_lane_off[j];
+                asrc[j] = adirect + (int64_t)(j * RPB) * g.row_stride_bytes + koff + a_lane_off[j];
         } else {
             const int32_t* ent = (const int32_t*)(lds + ent_base + (int)(ik & 1) * ent_bytes) + itap * MR;
             int32_t e[A_VEC];
@@ -572,21 +491,6 @@ __global__ __launch_bounds__(64 * WM * WN) void k_igemm_uni(IgemmArgs g)
 }
 
 // ------------------------------------------------------------------ launch
-static int device_cu_count()
-{
-    static int cached[64] = {0};      // per device ordinal; filled on first use, the value never changes
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
-    }
-    return cached[dev];
-}
-
-constexpr size_t kLdsPerCu = 160 * 1024;
-
 template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool DIRECT>
 static int launch_one(const Geometry& g, IgemmArgs a, hipStream_t s)
 {
@@ -692,6 +596,7 @@ int launch_igemm_mfma(const icv_conv_params* p, const Geometry& g, const void* i
     a.stages_per_tap = g.stages_per_tap; a.n_stages = g.n_stages;
     a.n_tiles = (int32_t)g.n_tiles;
     a.ring = 0; a.ent_copies = 0; a.xcd_mode = 0;
+    a.cc_major = g.cc_major; a.row_bytes = p->C * g.elem_bytes;
     return p->dtype == ICV_U8I8 ? launch_dtype<true>(g, a, a_direct, s) : launch_dtype<false>(g, a, a_direct, s);
 }
 

@@ -1,0 +1,393 @@
+// Tensor-core Indirect GEMM with the gathered rows kept in LDS across kernel elements.
+//
+// Listing 3 reads, for every kernel element, the MR rows its indirection entries name.  For a convolution the
+// R*S entries of neighbouring output pixels name mostly the same input pixels (section 3.4 counts on the cache
+// for that re-use); here the re-use is made explicit.  The valid entries of a tile of MR consecutive output
+// pixels all fall into one short range of consecutive input pixels -- the set-up phase records each tile's first
+// byte offset and pixel count next to the entries -- so that range ("patch") is copied to LDS once per tile and
+// channel chunk, and every kernel element then takes its MR rows from the patch by looking its entries up:
+//
+//     LDS row of entry e  =  (e - first offset of the tile) / pixel stride      (zero row: one extra LDS row)
+//
+// The loop nest is Listing 3's with the channel chunks outermost (chunk, kernel element, channels of the chunk);
+// only the filter tile of a stage (NR rows x KCB bytes, contiguous in the packed filter) still streams through a
+// small LDS ring.  Compared with gathering the rows of every kernel element separately this moves R*S times
+// fewer input bytes into LDS, and LDS bandwidth -- fragment reads plus fills -- is what bounds these kernels.
+//
+// Execution model (same as the streamed kernel): persistent workgroups, NC consumer wavefronts running MFMA and
+// NP producer wavefronts issuing global -> LDS copies, one s_barrier per stage, producers counting their own
+// outstanding copies with s_waitcnt vmcnt.  Per stage every producer issues a share of the next patch and of the
+// next tile's entries, then its part of the filter tile of stage q + ring - 1; the wait before stage q is "at
+// most the filter copies of ring - 2 stages outstanding", which is conservative for the shares in between.
+//
+// Patch rows are XOR-swizzled like the stage tiles of the streamed kernel (LDS row r holds source piece
+// c ^ swz(r) at piece c), the consumer applies swz(r) of the row its entry names.
+#include "icv_mfma_common.h"
+
+namespace icv {
+
+struct PatchArgs {
+    const uint8_t* a;          // input tensor
+    const uint8_t* w;          // packed filter [n tile][channel chunk][tap][NR][KCB]
+    const int32_t* ind;        // [m tile][tap][MR]
+    const int4* ranges;        // per m tile: {first byte offset, pixel rows, 0, 0}
+    void* out;
+    int64_t M;
+    int64_t total_tiles;       // m_tiles * n_tiles
+    int32_t stride_bytes, stride_shift;   // bytes between input pixels, a power of two
+    int32_t K, T, NCC, out_stride, n_tiles;
+    int32_t ring;              // filter-tile slots
+    int32_t ent_copies;        // 1 KB pieces of one tile's entries
+    int32_t cap_units;         // 1 KB pieces of one patch buffer (the zero row follows them)
+    int32_t a_share, e_share;  // copies per producer per stage: next patch, next entries
+    int32_t xcd_mode;
+};
+
+template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB>
+__global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g)
+{
+    constexpr int NC = WM * WN;
+    constexpr int Q = KCB / 16;              // 16-byte pieces per row per stage
+    constexpr int P = 256 / KCB;             // rows per 256 bytes of LDS
+    constexpr int RPB = 1024 / KCB;          // rows one wavefront-wide copy covers
+    constexpr int B_VEC = NR * KCB / 1024 / NP;
+    constexpr int MRW = MR / WM, NRW = NR / WN;
+    constexpr int MB = MRW / 32, NB = NRW / 32;
+    constexpr int KSTEPS = KCB / 32;
+    constexpr int BS = NR * KCB;             // bytes of one filter-tile slot
+    static_assert(B_VEC >= 1 && B_VEC * NP * 1024 == NR * KCB, "filter tile must split over the producers");
+    static_assert(MB >= 1 && NB >= 1, "tile too small for this wavefront split");
+    using acc_t = typename Acc<I8>::type;
+    using out_t = typename std::conditional<I8, int32_t, float>::type;
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
+    const int D = g.ring;
+    const int pbytes = (g.cap_units + 1) * 1024;          // patch buffer: cap_units pieces, then the zero row
+    const int zoff = g.cap_units * 1024;
+    const int patch_base = D * BS;
+    const int ent_base = patch_base + 2 * pbytes;
+    const int ent_bytes = g.ent_copies * 1024;
+    const int hdr_base = ent_base + 2 * ent_bytes;        // [parity] int4 copy of the tile's range record
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const TileList tl = my_tiles(g.total_tiles, g.xcd_mode);
+    const int T = g.T, NCC = g.NCC;
+    const int n_st = NCC * T;                             // stages per tile, stage = chunk * T + tap
+    const int64_t total_stages = tl.count * n_st;
+
+    if (wave >= NC) {
+        // =============================================================== producer
+        // The per-stage body below is the critical path of a stage whenever the consumers have little to do (one
+        // wavefront issues an instruction every few cycles only), so everything that can be is precomputed,
+        // uniform values stay in scalar registers, and per-lane addresses are 32-bit offsets from uniform bases.
+        const int p = wave - NC;
+        const int lrow_in_blk = lane / Q, lchunk = lane % Q;
+        uint32_t b_src_off[B_VEC];
+#pragma unroll
+        for (int j = 0; j < B_VEC; j++) {
+            const int row = (p * B_VEC + j) * RPB + lrow_in_blk;
+            b_src_off[j] = row * KCB + ((lchunk ^ ((row / P) % Q)) << 4);
+        }
+        const uint32_t n_tiles = (uint32_t)g.n_tiles;
+        auto m_tile_of = [&](int k) { return (uint32_t)(tl.first + k * tl.step) / n_tiles; };
+        auto n_tile_of = [&](int k) { return (uint32_t)(tl.first + k * tl.step) % n_tiles; };
+        const int count = (int)tl.count;
+        // range record {first byte offset, pixel rows} of my k-th tile, read through the constant address space:
+        // a scalar load, which neither touches the vector-memory counter the copies are tracked with nor makes the
+        // compiler wait on it
+        auto load_range = [&](int k) {
+            int2 r = make_int2(0, 1);
+            if (k < count) {
+                typedef const int32_t __attribute__((address_space(4))) * const_int_ptr;
+                const_int_ptr rec = (const_int_ptr)(uintptr_t)(g.ranges + m_tile_of(k));
+                r = make_int2(rec[0], rec[1]);
+            }
+            return r;
+        };
+        // piece u of a patch: LDS rows u*RPB .. +RPB hold pixels first + row (clamped to the tile's range, so the
+        // read stays inside the tensor), channel chunk cc, piece c of row r taken from source piece c ^ swz(r)
+        auto copy_patch_piece = [&](int u, const uint8_t* src, int nrows, uint32_t dst) {
+            const uint32_t r = (uint32_t)(u * RPB + lrow_in_blk);
+            const uint32_t rc = r < (uint32_t)nrows ? r : (uint32_t)nrows - 1;
+            const uint32_t off = (rc << g.stride_shift) + ((lchunk ^ ((r / P) % Q)) << 4);
+            copy16_global_to_lds(src, off, dst + u * 1024);
+        };
+        // piece u of a tile's entries; piece ent_copies is the tile's range record (16 bytes, one lane)
+        const int ent_chunks = T * MR / 4;
+        auto copy_ent_piece = [&](int u, const int32_t* src, const int4* rec, uint32_t par) {
+            if (u < g.ent_copies) {
+                const int c = u * 64 + lane;
+                if (c < ent_chunks) copy16_global_to_lds(src, (uint32_t)c * 16u, lds_base + ent_base + par * ent_bytes + u * 1024);
+            } else if (u == g.ent_copies) {
+                if (lane == 0) copy16_global_to_lds(rec, 0u, lds_base + hdr_base + par * 16);
+            }
+        };
+
+        // filter-tile cursor: the next stage to issue is stage bs of my tile bk, into slot bslot
+        int bk = 0, bs = 0, bslot = 0;
+        const uint8_t* wsrc = g.w + (int64_t)(count > 0 ? n_tile_of(0) : 0) * n_st * BS;
+        auto issue_b = [&]() {
+            if (bk >= count) return;
+            const uint32_t slot = lds_base + (uint32_t)bslot * BS;
+#pragma unroll
+            for (int j = 0; j < B_VEC; j++) copy16_global_to_lds(wsrc, b_src_off[j], slot + (p * B_VEC + j) * 1024);
+            wsrc += BS;
+            bslot = bslot + 1 == D ? 0 : bslot + 1;
+            if (++bs == n_st) {
+                bs = 0;
+                if (++bk < count) wsrc = g.w + (int64_t)n_tile_of(bk) * n_st * BS;
+            }
+        };
+
+        int2 rng_k = load_range(0), rng_k1 = load_range(1);
+        if (count > 0) {
+            const uint32_t mt = m_tile_of(0);
+            for (int u = p; u <= g.ent_copies; u += NP)
+                copy_ent_piece(u, g.ind + (int64_t)mt * T * MR, g.ranges + mt, 0);
+            int units = (rng_k.y + RPB - 1) / RPB;
+            if (units > g.cap_units) units = g.cap_units;
+            for (int u = p; u < units; u += NP) copy_patch_piece(u, g.a + rng_k.x, rng_k.y, lds_base + patch_base);
+        }
+        for (int q = 0; q < D - 1; q++) issue_b();
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();         // first tile's entries, patch and filter stages are in LDS
+
+        // Shares go out before the stage's filter tile.  Copies retire in order, so "at most (ring-2) * B_VEC copies
+        // outstanding" then implies: the filter tile issued ring-1 stages ago has landed, and so has every share
+        // issued ring-1 or more stages ago -- which is why shares stop ring-1 stages before their data is needed.
+        const int a_last = T - D + 1, e_last = n_st - D + 1;     // last tap / stage that still carries a share
+        int younger = (int)total_stages - 1;                     // stages after the one being handed over
+        for (int k = 0; k < count; k++) {
+            const bool next_tile = k + 1 < count;
+            const uint32_t mt1 = next_tile ? m_tile_of(k + 1) : 0;
+            const int32_t* ent_src = g.ind + (int64_t)mt1 * T * MR;
+            const int4* rec_src = g.ranges + mt1;
+            const uint32_t ent_par = (uint32_t)((k + 1) & 1);
+            int s = 0;
+            for (int cc = 0; cc < NCC; cc++) {
+                // the patch after this one: (k, cc+1) or (k+1, 0); its buffer was last read in the patch before this one
+                const bool same_tile = cc + 1 < NCC;
+                const int2 rng = same_tile ? rng_k : rng_k1;
+                const bool next_patch = same_tile || next_tile;
+                const uint8_t* psrc = g.a + rng.x + (same_tile ? cc + 1 : 0) * KCB;
+                int units = next_patch ? (rng.y + RPB - 1) / RPB : 0;
+                if (units > g.cap_units) units = g.cap_units;
+                const uint32_t pdst = lds_base + patch_base + (uint32_t)((k * NCC + cc + 1) & 1) * pbytes;
+                for (int tap = 0; tap < T; tap++, s++) {
+                    // (towards the end fewer filter tiles follow the one waited for)
+                    wait_all_but_stages<B_VEC>(younger < D - 2 ? younger : D - 2);
+                    --younger;
+                    __builtin_amdgcn_s_barrier();     // hand this stage to the consumers; they are done with the one before
+                    if (tap <= a_last) {
+                        int u = tap * g.a_share * NP + p;
+                        for (int j = 0; j < g.a_share; j++, u += NP)
+                            if (u < units) copy_patch_piece(u, psrc, rng.y, pdst);
+                    }
+                    if (next_tile && s <= e_last) {
+                        int u = s * g.e_share * NP + p;
+                        for (int j = 0; j < g.e_share; j++, u += NP) copy_ent_piece(u, ent_src, rec_src, ent_par);
+                    }
+                    issue_b();
+                }
+            }
+            rng_k = rng_k1;
+            rng_k1 = load_range(k + 2);
+        }
+        wait_vmcnt<0>();
+    } else {
+        // =============================================================== consumer
+        const int wm = wave / WN, wn = wave % WN;
+        const int lrow = lane & 31, lhalf = lane >> 5;
+        const int bswz = (lrow / P) % Q;
+        const uint32_t b_frag_base = (wn * NRW + lrow) * KCB;
+        out_t* out = (out_t*)g.out;
+
+        // the zero row of both patch buffers (bytes that multiply as zero: 0x80 for centred uint8)
+        {
+            const uint32_t zv = I8 ? 0x80808080u : 0u;
+            for (int i = tid; i < 2 * 256; i += 64 * NC)
+                *(uint32_t*)(lds + patch_base + (i >> 8) * pbytes + zoff + (i & 255) * 4) = zv;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+        __builtin_amdgcn_s_barrier();         // pairs with the producers' start-up barrier
+        int slot = 0;
+        for (int64_t k = 0; k < tl.count; k++) {
+            acc_t acc[MB][NB];
+#pragma unroll
+            for (int i = 0; i < MB; i++)
+#pragma unroll
+                for (int j = 0; j < NB; j++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) acc[i][j][r] = 0;
+
+            const int32_t* ent = (const int32_t*)(lds + ent_base + (int)(k & 1) * ent_bytes) + wm * MRW + lrow;
+            int32_t first = 0;
+            for (int cc = 0; cc < NCC; cc++) {
+                const uint32_t pb = patch_base + (uint32_t)((k * NCC + cc) & 1) * pbytes;
+                for (int tap = 0; tap < T; tap++) {
+                    __builtin_amdgcn_s_barrier();
+                    if (cc == 0 && tap == 0) first = *(const int32_t*)(lds + hdr_base + (int)(k & 1) * 16);
+                    // entry -> LDS row of the patch (or the zero row) and that row's swizzle
+                    uint32_t abase[MB], aswz[MB];
+#pragma unroll
+                    for (int i = 0; i < MB; i++) {
+                        const int32_t e = ent[tap * MR + i * 32];
+                        const uint32_t r = (uint32_t)(e - first) >> g.stride_shift;
+                        abase[i] = pb + (e < 0 ? (uint32_t)zoff : r * KCB);
+                        aswz[i] = e < 0 ? 0u : ((r / P) % Q) << 4;
+                    }
+                    const uint8_t* S = lds + slot * BS;
+                    slot = slot + 1 == D ? 0 : slot + 1;
+#pragma unroll
+                    for (int ks = 0; ks < KSTEPS; ks++) {
+                        const uint32_t piece = (uint32_t)(2 * ks + lhalf) << 4;
+                        uint4 af[MB], bf[NB];
+#pragma unroll
+                        for (int i = 0; i < MB; i++) af[i] = *(const uint4*)(lds + abase[i] + (piece ^ aswz[i]));
+#pragma unroll
+                        for (int j = 0; j < NB; j++)
+                            bf[j] = *(const uint4*)(S + b_frag_base + j * 32 * KCB + (piece ^ (uint32_t)(bswz << 4)));
+#pragma unroll
+                        for (int i = 0; i < MB; i++)
+#pragma unroll
+                            for (int j = 0; j < NB; j++) acc[i][j] = mfma32<I8>(af[i], bf[j], acc[i][j]);
+                    }
+                }
+            }
+
+            // epilogue: accumulator register r of lane l holds row 8*(r/4) + 4*(l>>5) + (r&3), column l&31
+            const int64_t tile = tl.first + k * tl.step;
+            const int32_t nt = (int32_t)(tile % g.n_tiles);
+            const int64_t mt = tile / g.n_tiles;
+            const int64_t m_base = mt * MR + wm * MRW + 4 * lhalf;
+            const int32_t n_base = nt * NR + wn * NRW + lrow;
+            const bool full = (mt + 1) * MR <= g.M && (nt + 1) * NR <= g.K;
+            if (full) {
+                out_t* o = out + m_base * g.out_stride + n_base;
+#pragma unroll
+                for (int i = 0; i < MB; i++)
+#pragma unroll
+                    for (int j = 0; j < NB; j++)
+#pragma unroll
+                        for (int r = 0; r < 16; r++)
+                            __builtin_nontemporal_store(acc[i][j][r], &o[(int64_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * g.out_stride + j * 32]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < MB; i++)
+#pragma unroll
+                    for (int j = 0; j < NB; j++) {
+                        const int32_t col = n_base + j * 32;
+#pragma unroll
+                        for (int r = 0; r < 16; r++) {
+                            const int64_t row = m_base + i * 32 + 8 * (r >> 2) + (r & 3);
+                            if (row < g.M && col < g.K) out[row * g.out_stride + col] = acc[i][j][r];
+                        }
+                    }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ launch
+size_t patch_lds_bytes(int NR, int KCB, int ring, int cap_units, int ent_copies)
+{
+    return (size_t)ring * NR * KCB + (size_t)2 * (cap_units + 1) * 1024 + (size_t)2 * ent_copies * 1024 + 2048;
+}
+
+template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB>
+static int launch_one(const Geometry& g, PatchArgs a, hipStream_t s)
+{
+    constexpr int threads = 64 * (WM * WN + NP);
+    constexpr int B_VEC = NR * KCB / 1024 / NP;
+    auto kern = k_igemm_patch<I8, MR, NR, WM, WN, NP, KCB>;
+    const int n_st = a.NCC * a.T;
+    a.ent_copies = (int32_t)(((size_t)a.T * MR * 4 + 1023) / 1024);
+    a.cap_units = (int32_t)(((size_t)g.patch_rows * KCB + 1023) / 1024);
+    // Ring depth.  A copy takes on the order of a microsecond from issue to completion under load, a stage far
+    // less, and a stage's filter tile must be issued ring - 1 stages ahead: as deep as fits (LDS, the 6-bit copy
+    // counter, enough stages left to spread the shares over), at most 8.
+    int ring = g.ring ? g.ring : 8;
+    for (;; --ring) {
+        if (ring < 2) return ICV_ERR_UNSUPPORTED;
+        if (a.T - ring + 2 < 1 || n_st - ring + 2 < 1) continue;
+        a.a_share = (a.cap_units + NP * (a.T - ring + 2) - 1) / (NP * (a.T - ring + 2));
+        a.e_share = (a.ent_copies + 1 + NP * (n_st - ring + 2) - 1) / (NP * (n_st - ring + 2));
+        if ((ring - 2) * B_VEC > 63) continue;
+        if (patch_lds_bytes(NR, KCB, ring, a.cap_units, a.ent_copies) > kLdsPerCu) continue;
+        break;
+    }
+    a.ring = ring;
+    const size_t lds_bytes = patch_lds_bytes(NR, KCB, ring, a.cap_units, a.ent_copies);
+    int per_cu = g.blocks_per_cu ? g.blocks_per_cu : 1;
+    if (per_cu == 2 && (lds_bytes > kLdsPerCu / 2 || threads > 512)) per_cu = 1;
+
+    int64_t grid = (int64_t)device_cu_count() * per_cu;
+    if (grid > a.total_tiles) grid = a.total_tiles;
+    a.xcd_mode = 0;
+    if (grid >= 8 && a.total_tiles >= 8) {
+        grid -= grid % 8;
+        a.xcd_mode = 1;
+    }
+    if (lds_bytes > 64 * 1024) {
+        static bool raised = false;   // idempotent attribute; a race only repeats the call
+        if (!raised) {
+            ICV_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                              (int)kLdsPerCu));
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(threads), lds_bytes, s, a);
+    ICV_HIP_CHECK(hipGetLastError());
+    return ICV_OK;
+}
+
+template <bool I8, int MR, int NR, int WM, int WN>
+static int launch_tile(const Geometry& g, const PatchArgs& a, hipStream_t s)
+{
+    if (g.KCB == 128) return launch_one<I8, MR, NR, WM, WN, 4, 128>(g, a, s);
+    return launch_one<I8, MR, NR, WM, WN, 4, 64>(g, a, s);
+}
+
+template <bool I8>
+static int launch_dtype(const Geometry& g, const PatchArgs& a, hipStream_t s)
+{
+    switch (g.variant) {
+        case 0: return launch_tile<I8, 128, 64, 2, 2>(g, a, s);
+        case 1: return launch_tile<I8, 128, 128, 2, 2>(g, a, s);
+        case 3: return launch_tile<I8, 256, 64, 4, 2>(g, a, s);
+        case 6: return launch_tile<I8, 256, 128, 4, 2>(g, a, s);
+        case 7: return launch_tile<I8, 128, 128, 4, 2>(g, a, s);
+        default: return ICV_ERR_UNSUPPORTED;
+    }
+}
+
+bool patch_variant_supported(int variant) { return variant == 0 || variant == 1 || variant == 3 || variant == 6 || variant == 7; }
+
+int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
+                       const int32_t* ind, void* out, hipStream_t s)
+{
+    const TileVariant& tv = kTileVariants[g.variant];
+    if (tv.MR != g.MR || tv.NR != g.NR || !g.patch_rows) return ICV_ERR_UNSUPPORTED;
+    const int64_t stride_bytes = (int64_t)g.in_stride * g.elem_bytes;
+    int shift = 0;
+    while ((1ll << shift) < stride_bytes) ++shift;
+    if ((1ll << shift) != stride_bytes) return ICV_ERR_UNSUPPORTED;
+    PatchArgs a;
+    a.a = (const uint8_t*)input;
+    a.w = (const uint8_t*)packed;
+    a.ind = ind;
+    a.ranges = (const int4*)(ind + g.m_tiles * g.MR * (int64_t)g.T);
+    a.out = out;
+    a.M = g.M;
+    a.total_tiles = g.m_tiles * g.n_tiles;
+    a.stride_bytes = (int32_t)stride_bytes; a.stride_shift = shift;
+    a.K = p->K; a.T = g.T; a.NCC = g.stages_per_tap; a.out_stride = g.out_stride;
+    a.n_tiles = (int32_t)g.n_tiles;
+    a.ring = 0; a.ent_copies = 0; a.cap_units = 0; a.a_share = 0; a.e_share = 0; a.xcd_mode = 0;
+    return p->dtype == ICV_U8I8 ? launch_dtype<true>(g, a, s) : launch_dtype<false>(g, a, s);
+}
+
+}  // namespace icv

@@ -33,8 +33,14 @@ struct Geometry {
     int64_t m_tiles, n_tiles;
     int32_t ring;            // forced LDS ring depth (0: launcher decides)
     int32_t blocks_per_cu;   // forced co-resident workgroups per CU (0: launcher decides)
+    int32_t patch_rows;      // > 0: the tile's input pixel range is kept in LDS, this many pixel rows reserved
+    int32_t cc_major;        // 1: stage = chunk * T + tap (channel chunks outermost), 0: stage = tap * chunks + chunk
     const char* name;
 };
+
+// Upper bound on the number of consecutive input pixels spanned by the valid indirection entries of any
+// `rows` consecutive output pixels.
+int64_t tile_span_bound(const icv_conv_params* p, int64_t Hout, int64_t Wout, int64_t rows);
 
 // Fills g; returns ICV_OK / ICV_ERR_INVALID_ARG / ICV_ERR_UNSUPPORTED.
 int make_geometry(const icv_conv_params* p, Geometry* g);
@@ -60,6 +66,10 @@ int launch_im2col(const icv_conv_params* p, const Geometry& g, const void* input
 // a_direct = true : A is the dense [M][T*C] patch matrix with constant row stride (ablation GEMM).
 int launch_igemm_mfma(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                       const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s);
+int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
+                       const int32_t* ind, void* out, hipStream_t s);
+bool patch_variant_supported(int variant);
+size_t patch_lds_bytes(int NR, int KCB, int ring, int cap_units, int ent_copies);
 int launch_igemm_lowc(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                       const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s);
 int launch_igemm_generic(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,

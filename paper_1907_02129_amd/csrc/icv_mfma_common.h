@@ -1,0 +1,123 @@
+// Device helpers shared by the tensor-core Indirect GEMM kernels (MFMA wrappers, global -> LDS copies, manual
+// vmcnt waits, the persistent workgroups' tile lists).
+#pragma once
+#include <type_traits>
+#include "icv_internal.h"
+
+namespace icv {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+typedef int i32x16_t __attribute__((ext_vector_type(16)));
+
+template <bool I8>
+struct Acc {
+    using type = f32x16_t;
+};
+template <>
+struct Acc<true> {
+    using type = i32x16_t;
+};
+
+template <bool I8>
+__device__ inline typename Acc<I8>::type mfma32(const uint4& a, const uint4& b, typename Acc<I8>::type c)
+{
+    if constexpr (I8) {
+        i32x4_t av = {(int)(a.x ^ 0x80808080u), (int)(a.y ^ 0x80808080u), (int)(a.z ^ 0x80808080u),
+                      (int)(a.w ^ 0x80808080u)};
+        i32x4_t bv = {(int)b.x, (int)b.y, (int)b.z, (int)b.w};
+        return __builtin_amdgcn_mfma_i32_32x32x32_i8(av, bv, c, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+}
+
+// 16-byte global -> LDS copy without a register stop: lane l of the wavefront writes LDS bytes
+// [lds_base + 16*l, +16).  Inline assembly on purpose: the compiler does not see a memory instruction, so it
+// inserts no waits of its own for it, and the producers count outstanding copies themselves (wait_vmcnt).
+// A producer issues no other vector-memory instruction while copies are in flight.
+__device__ inline void copy16_global_to_lds(const void* gptr, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n"
+                 :
+                 : "v"(gptr), "s"(lds_base)
+                 : "memory");
+}
+
+// Same copy with the address split into a uniform 64-bit base and a per-lane unsigned 32-bit byte offset, which
+// keeps the per-lane address arithmetic in 32 bits.
+__device__ inline void copy16_global_to_lds(const void* sbase, uint32_t voff, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n"
+                 :
+                 : "v"(voff), "s"(sbase), "s"(lds_base)
+                 : "memory");
+}
+
+template <int N>
+__device__ inline void wait_vmcnt()
+{
+    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+// Wait until at most `stages` x LP of this wavefront's copies are outstanding (copies retire in order).
+template <int LP>
+__device__ inline void wait_all_but_stages(int stages)
+{
+    switch (stages) {
+        case 0: wait_vmcnt<0>(); break;
+        case 1: wait_vmcnt<LP>(); break;
+        case 2: wait_vmcnt<2 * LP>(); break;
+        case 3: wait_vmcnt<3 * LP>(); break;
+        case 4: wait_vmcnt<(4 * LP <= 63 ? 4 * LP : 63)>(); break;
+        case 5: wait_vmcnt<(5 * LP <= 63 ? 5 * LP : 63)>(); break;
+        default: wait_vmcnt<(6 * LP <= 63 ? 6 * LP : 63)>(); break;
+    }
+}
+
+// Tile list of a persistent workgroup.  Workgroups are dealt round-robin to the 8 XCDs (block b runs on
+// XCD b % 8).  In XCD mode XCD x owns the contiguous tile range [first, first + count) and its G/8 workgroups
+// take tiles first + i, first + i + G/8, ... ; otherwise block b takes b, b + G, ...
+struct TileList {
+    int64_t first, step, count;   // tiles first + k*step for k < count
+};
+
+__device__ inline TileList my_tiles(int64_t total, int xcd_mode)
+{
+    const int64_t b = blockIdx.x, G = gridDim.x;
+    TileList t;
+    if (xcd_mode) {
+        const int64_t chunk = total >> 3, rem = total & 7, x = b & 7;
+        const int64_t start = x * chunk + (x < rem ? x : rem);
+        const int64_t len = chunk + (x < rem ? 1 : 0);
+        const int64_t i = b >> 3;
+        t.step = G >> 3;
+        t.first = start + i;
+        t.count = i < len ? (len - i + t.step - 1) / t.step : 0;
+    } else {
+        t.step = G;
+        t.first = b;
+        t.count = b < total ? (total - b + G - 1) / G : 0;
+    }
+    return t;
+}
+
+inline int device_cu_count()
+{
+    static int cached[64] = {0};      // per device ordinal; filled on first use, the value never changes
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+constexpr size_t kLdsPerCu = 160 * 1024;
+
+}  // namespace icv

@@ -21,8 +21,9 @@ int launch_zero_row(const icv_conv_params* p, const Geometry& g, void* zero_row,
 
 // ------------------------------------------------------------------ filter pre-pack
 // Source  [K][T][C] elements.
-// Packed  [n_tile][stage][NR][KCB bytes], stage = (tap, C-chunk): the tile one pipeline stage of the GEMM
-//         kernel copies into LDS is one contiguous block.  Rows past K are zero.
+// Packed  [n_tile][stage][NR][KCB bytes], stage = (tap, C-chunk), or (C-chunk, tap) for the plans that keep the
+//         tile's pixel range in LDS: the tile one pipeline stage of the GEMM kernel copies into LDS is one
+//         contiguous block.  Rows past K are zero.
 // One thread moves 16 bytes (KCB and C*elem are multiples of 16 for the tensor-core plans); the generic
 // plan (KCB == 0) keeps [K padded][T][C] and moves single elements.
 struct PackArgs {
@@ -30,6 +31,7 @@ struct PackArgs {
     uint8_t* dst;
     int32_t K, T, CB;  // CB = C * elem bytes
     int32_t NR, KCB, stages_per_tap, n_stages;
+    int32_t cc_major;   // stage = chunk * T + tap instead of tap * stages_per_tap + chunk
     int64_t total_vec;  // number of 16-byte vectors in dst
 };
 
@@ -44,7 +46,8 @@ __global__ void k_pack_filter_vec(PackArgs a)
     r /= a.NR;
     const int32_t stage = (int32_t)(r % a.n_stages);
     const int32_t ntile = (int32_t)(r / a.n_stages);
-    const int32_t tap = stage / a.stages_per_tap, cc = stage % a.stages_per_tap;
+    const int32_t tap = a.cc_major ? stage % a.T : stage / a.stages_per_tap;
+    const int32_t cc = a.cc_major ? stage / a.T : stage % a.stages_per_tap;
     const int32_t oc = ntile * a.NR + row;
     uint4 val = make_uint4(0, 0, 0, 0);
     if (oc < a.K)
@@ -87,6 +90,7 @@ int launch_pack_filter(const icv_conv_params* p, const Geometry& g, const void* 
         a.dst = (uint8_t*)packed;
         a.K = p->K; a.T = g.T; a.CB = (int32_t)CB;
         a.NR = g.NR; a.KCB = g.KCB; a.stages_per_tap = g.stages_per_tap; a.n_stages = g.n_stages;
+        a.cc_major = g.cc_major;
         a.total_vec = g.n_tiles * g.NR * (int64_t)g.T * CB / 16;
         hipLaunchKernelGGL(k_pack_filter_vec, dim3((unsigned)((a.total_vec + 255) / 256)), dim3(256), 0, s, a);
     } else {
@@ -153,6 +157,32 @@ __global__ __launch_bounds__(256) void k_build_indirection(IndArgs a)
     }
 }
 
+// Range record of every row tile, for the plans that keep a tile's input pixels in LDS: the smallest valid
+// entry of the tile (a byte offset) and the number of pixel rows from there to the largest one.  A tile without
+// valid entries gets {0, 1}.  One wavefront per tile.
+__global__ __launch_bounds__(256) void k_tile_ranges(const int32_t* ind, int4* ranges, int64_t m_tiles, int32_t per_tile,
+                                                     int32_t stride_bytes)
+{
+    const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= m_tiles) return;
+    const int lane = threadIdx.x & 63;
+    const int32_t* src = ind + tile * per_tile;
+    int32_t lo = INT32_MAX, hi = -1;
+    for (int32_t i = lane; i < per_tile; i += 64) {
+        const int32_t e = src[i];
+        if (e >= 0) {
+            lo = e < lo ? e : lo;
+            hi = e > hi ? e : hi;
+        }
+    }
+    for (int d = 32; d >= 1; d >>= 1) {
+        const int32_t lo2 = __shfl_xor(lo, d, 64), hi2 = __shfl_xor(hi, d, 64);
+        lo = lo2 < lo ? lo2 : lo;
+        hi = hi2 > hi ? hi2 : hi;
+    }
+    if (lane == 0) ranges[tile] = hi < 0 ? make_int4(0, 1, 0, 0) : make_int4(lo, (hi - lo) / stride_bytes + 1, 0, 0);
+}
+
 int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_t* ind, hipStream_t s)
 {
     IndArgs a;
@@ -165,6 +195,12 @@ int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_
     const int64_t threads = a.m_padded / 4;
     hipLaunchKernelGGL(k_build_indirection, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, a);
     ICV_HIP_CHECK(hipGetLastError());
+    if (g.patch_rows) {
+        int4* ranges = (int4*)(ind + a.m_padded * g.T);
+        hipLaunchKernelGGL(k_tile_ranges, dim3((unsigned)((g.m_tiles + 3) / 4)), dim3(256), 0, s, ind, ranges,
+                           g.m_tiles, g.MR * g.T, a.stride_bytes);
+        ICV_HIP_CHECK(hipGetLastError());
+    }
     return ICV_OK;
 }
 

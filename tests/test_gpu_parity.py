@@ -150,9 +150,17 @@ def test_small_shapes_match_oracle(s):
 N_PLANS = 15    # plan 1 = vector ALU, 2.. = tensor-core tile variants
 
 
+PATCH_VARIANTS = (0, 1, 3, 6, 7)     # tile variants the pixel-range kernel is instantiated for
+
+
+@pytest.mark.parametrize("staging", [0, 1, 2])
 @pytest.mark.parametrize("plan", range(1, N_PLANS + 1))
 @pytest.mark.parametrize("dtype", ["bf16", "u8i8"])
-def test_every_tile_variant(plan, dtype):
+def test_every_tile_variant(plan, dtype, staging):
+    if staging and plan == 1:
+        pytest.skip("row staging is a property of the tensor-core kernels")
+    variant = plan - 2
+    plan |= staging << 12
     zp = 128 if dtype == "u8i8" else 0
     for s in (ConvShape("v_a", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype=dtype, zero_point=zp, seed=51),
               ConvShape("v_b", 1, 20, 33, 128, 200, 2, 3, SY=1, SX=2, PT=0, PL=1, PB=1, PR=1, dtype=dtype, zero_point=zp, seed=52),
@@ -165,9 +173,81 @@ def test_every_tile_variant(plan, dtype):
         except icv.IcvError as e:
             # a forced variant may decline a stage width it cannot split over its wavefronts -- loudly, not wrongly
             row_bytes = s.C * (1 if dtype == "u8i8" else 2)
-            assert e.status == icv.ICV_ERR_UNSUPPORTED and row_bytes % 128 != 0, (plan, s.name, e)
+            no_patch = staging == 2 and variant not in PATCH_VARIANTS
+            assert e.status == icv.ICV_ERR_UNSUPPORTED and (row_bytes % 128 != 0 or no_patch), (plan, s.name, e)
             continue
+        if staging == 2:
+            assert "patch" in icv.plan_name(buf.p)
         check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+
+
+# ---------------------------------------------------------------- pixel range kept in LDS
+def _patch_shapes():
+    mk = ConvShape
+    return [
+        # several channel chunks per row (256-byte rows), tiles crossing image boundaries, K tail
+        mk("p_chunks", 3, 13, 17, 128, 72, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=71),
+        # stride 2 both ways, 5x5, asymmetric padding
+        mk("p_s2", 2, 31, 29, 64, 64, 5, 5, SY=2, SX=2, PT=2, PL=2, PB=1, PR=1, seed=72),
+        # dilation 2 x 3, different strides
+        mk("p_dil", 2, 24, 40, 64, 130, 3, 3, SY=1, SX=2, DY=2, DX=3, PT=2, PL=3, PB=2, PR=3, seed=73),
+        # no padding at all: the image-to-image step of the pixel range is larger than a row step
+        mk("p_valid", 4, 12, 12, 32, 64, 3, 3, seed=74),
+        # padding larger than the kernel reach: whole tiles of zero-row entries at the borders
+        mk("p_bigpad", 1, 9, 70, 64, 32, 2, 2, PT=3, PL=3, PB=3, PR=3, seed=75),
+        # one short tile only
+        mk("p_tiny", 1, 5, 6, 64, 16, 2, 2, PT=1, PL=1, seed=76),
+        # padded pixel stride (power of two) with fewer channels used
+        mk("p_stride", 2, 14, 14, 32, 48, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=77),
+        # int8, 256-byte rows
+        mk("p_i8", 2, 15, 15, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=78),
+        mk("p_i8_s2", 2, 21, 18, 64, 64, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=79),
+    ]
+
+
+@pytest.mark.parametrize("s", _patch_shapes(), ids=lambda s: s.name)
+@pytest.mark.parametrize("knobs", [0, 2 << 4, 3 << 4, 5 << 4, 1 << 10, (2 << 4) | (1 << 10)],
+                         ids=["auto", "ring2", "ring3", "ring5", "kcb64", "ring2_kcb64"])
+def test_pixel_range_kernel_matches_oracle(s, knobs):
+    plan = (2 << 12) | knobs
+    stride = 64 if s.name == "p_stride" else 0
+    x, w = make_tensors(s)
+    if stride:
+        xp = np.zeros(x.shape[:-1] + (stride,), dtype=x.dtype)
+        xp[..., :s.C] = x
+        xp[..., s.C:] = 0x7fc0                                     # NaN bit patterns in the unused channels
+    else:
+        xp = x
+    p = icv.make_params(s, plan, in_pixel_stride=stride)
+    assert "patch" in icv.plan_name(p), icv.plan_name(p)
+    _say("pixel-range", s.name, icv.plan_name(p), "knobs", knobs)
+    buf = icv.prepare(s, icv.to_device(w), plan=plan, in_pixel_stride=stride)
+    xd = icv.to_device(xp)
+    icv.run(buf, xd)
+    torch.cuda.synchronize()
+    check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+
+
+@pytest.mark.parametrize("s", _patch_shapes()[:6] + [CONFIGS["cfg3c_5x5_asym"].with_(N=2)], ids=lambda s: s.name)
+def test_range_records_match_oracle_entries(s):
+    """Per row tile: smallest valid entry and pixel count up to the largest, from the oracle's entries."""
+    x, w = make_tensors(s)
+    buf = icv.prepare(s, icv.to_device(w), plan=2 << 12)
+    torch.cuda.synchronize()
+    rec = icv.tile_ranges(buf)
+    assert rec is not None
+    mr = icv.indirection_index(buf.p, 0, 1)
+    want = oracle.indirection(s)
+    esz = 1 if s.dtype == "u8i8" else 2
+    cap = icv.tile_span_bound(buf.p, mr)
+    for t in range(rec.shape[0]):
+        v = want[t * mr:(t + 1) * mr]
+        v = v[v >= 0]
+        if v.size:
+            assert rec[t, 0] == int(v.min()) * s.C * esz and rec[t, 1] == int(v.max() - v.min() + 1), t
+        else:
+            assert tuple(rec[t, :2]) == (0, 1), t
+        assert rec[t, 1] <= cap and rec[t, 2] == 0 and rec[t, 3] == 0
 
 
 # ---------------------------------------------------------------- properties of the path
@@ -208,7 +288,8 @@ def test_im2col_gemm_ablation_agrees_with_indirect_path(name):
     # the patch matrix itself: row m, tap t holds the pixel row the indirection entry names
     M, T = buf.M, s.R * s.S
     esz = 1 if s.dtype == "u8i8" else 2
-    kp = icv.im2col_bytes(buf.p) // (len(buf.indirection) // T)       # bytes per patch row (padded for short rows)
+    mr = icv.indirection_index(buf.p, 0, 1)                         # row tile (T > 1 in all these shapes)
+    kp = icv.im2col_bytes(buf.p) // (-(-M // mr) * mr)               # bytes per patch row (padded for short rows)
     rows = ws.cpu().numpy()[:M * kp].reshape(M, kp)
     assert not rows[:, T * s.C * esz:].any()
     rows = rows[:, :T * s.C * esz].reshape(M, T, s.C * esz)

@@ -44,10 +44,16 @@ def test_output_size_and_buffer_sizes(lib, name):
     assert (Hout, Wout) == oracle.out_extent(s)
     M, T = s.N * Hout * Wout, s.R * s.S
     nbytes = icv.indirection_bytes(p)
+    if "patch" in icv.plan_name(p):                         # one 16-byte range record per row tile follows
+        mr = icv.indirection_index(p, 0, 1)
+        nbytes -= 16 * -(-M // mr)
     assert nbytes % (4 * T) == 0 and nbytes >= 4 * M * T
     assert nbytes < 4 * (M + 256) * T                       # padding is less than one row tile
-    # the indirection buffer does not depend on the number of input channels (section 1.1)
-    assert icv.indirection_bytes(icv.make_params(s.with_(C=s.C * 2))) == nbytes or s.dtype == "f32"
+    # the entries do not depend on the number of input channels (section 1.1); with the row staging fixed,
+    # neither does the tile the library picks
+    per_tap = 1 << 12
+    assert (icv.indirection_bytes(icv.make_params(s.with_(C=s.C * 2), plan=per_tap)) ==
+            icv.indirection_bytes(icv.make_params(s, plan=per_tap))) or s.dtype == "f32"
     esz = {"f32": 4, "bf16": 2, "u8i8": 1}[s.dtype]
     assert icv.packed_filter_bytes(p) >= s.K * T * s.C * esz
     assert icv.zero_row_bytes(p) >= s.C * esz and icv.zero_row_bytes(p) % 16 == 0
@@ -95,8 +101,9 @@ def test_invalid_arguments_are_rejected(lib):
     assert _status(lib, s, out_pixel_stride=8) == icv.ICV_ERR_INVALID_ARG           # stride < K
     assert _status(lib, s, R=80, PT=0, PB=0) == icv.ICV_ERR_INVALID_ARG             # kernel larger than input
     assert _status(lib, s, N=1 << 20) == icv.ICV_ERR_INVALID_ARG                    # input of 2 GiB or more
-    assert _status(lib, s, plan=1 << 12) == icv.ICV_ERR_INVALID_ARG
-    assert _status(lib, s, plan=2 | (7 << 4)) == icv.ICV_ERR_INVALID_ARG            # ring deeper than 6
+    assert _status(lib, s, plan=1 << 14) == icv.ICV_ERR_INVALID_ARG
+    assert _status(lib, s, plan=3 << 12) == icv.ICV_ERR_INVALID_ARG                 # no such row staging
+    assert _status(lib, s, plan=2 | (13 << 4)) == icv.ICV_ERR_INVALID_ARG           # ring deeper than 12
     assert _status(lib, s, plan=2 | (1 << 4)) == icv.ICV_ERR_INVALID_ARG            # a ring needs two slots
     assert _status(lib, CONFIGS["cfg4_int8_3x3"], input_zero_point=300) == icv.ICV_ERR_INVALID_ARG
     assert lib.icv_output_size(None, None, None) == icv.ICV_ERR_INVALID_ARG
@@ -128,3 +135,62 @@ def test_plans(lib):
     # odd channel counts fall back to the vector-ALU kernel instead of failing
     odd = ConvShape("odd", 1, 8, 8, 5, 3, 3, 3)
     assert icv.plan_name(icv.make_params(odd)).startswith("generic")
+
+
+def _exact_span(shape, rows):
+    """Largest (max - min + 1) over the valid oracle entries of any window of `rows` consecutive output pixels
+    that starts at a multiple of `rows` (the library's row tiles)."""
+    from oracle import direct_conv as oracle
+    ind = oracle.indirection(shape)                     # [M][T] pixel index or -1
+    M = ind.shape[0]
+    worst = 0
+    for m0 in range(0, M, rows):
+        blk = ind[m0:m0 + rows]
+        v = blk[blk >= 0]
+        if v.size:
+            worst = max(worst, int(v.max() - v.min() + 1))
+    return worst
+
+
+def test_tile_span_bound_covers_every_tile(lib):
+    """The LDS patch is sized by a closed-form bound; it must cover the pixel span of every row tile.  Checked by
+    brute force on the oracle's indirection entries for random shapes and the benchmark shapes."""
+    import numpy as np
+    from paper_1907_02129_amd.workloads import random_small_shape
+    rng = np.random.default_rng(5)
+    tight = 0
+    for i in range(300):
+        shape = random_small_shape(rng)
+        p = icv.make_params(shape)
+        for rows in (1, 2, 7, 32, 128):
+            bound = icv.tile_span_bound(p, rows)
+            exact = _exact_span(shape, rows)
+            assert bound >= exact, (shape, rows, bound, exact)
+            tight += bound == exact
+    assert tight > 0                                    # the bound is attained, not merely huge
+    for name in ("cfg2_3x3_c64", "cfg3a_3x3_s2", "cfg3b_3x3_d2", "cfg3c_5x5_asym", "cfg4_int8_3x3"):
+        shape = CONFIGS[name].with_(N=2)
+        p = icv.make_params(shape)
+        for rows in (128, 256):
+            bound, exact = icv.tile_span_bound(p, rows), _exact_span(shape, rows)
+            assert exact <= bound <= exact + 2 * shape.Win + shape.Hin * shape.Win // 8, (name, rows, bound, exact)
+    assert icv.tile_span_bound(icv.make_params(CONFIGS["cfg2_3x3_c64"]), 0) == -1
+    # the worked numbers: 3x3 stride 1 on 56 x 56 -> 255 steps + 2 rows + 2 pixels + 1
+    assert icv.tile_span_bound(icv.make_params(CONFIGS["cfg2_3x3_c64"]), 256) == 255 + 2 * 56 + 2 + 1
+
+
+def test_range_records_are_counted_in_the_buffer_size(lib):
+    s = CONFIGS["cfg2_3x3_c64"]
+    streamed = icv.make_params(s, plan=1 << 12)
+    patch = icv.make_params(s, plan=2 << 12)
+    assert "patch" in icv.plan_name(patch) and "patch" not in icv.plan_name(streamed)
+    mr = icv.indirection_index(patch, 0, 1)
+    tiles = -(-(s.N * 56 * 56) // mr)
+    assert icv.indirection_bytes(patch) == tiles * mr * 9 * 4 + tiles * 16
+    mr_s = icv.indirection_index(streamed, 0, 1)
+    tiles_s = -(-(s.N * 56 * 56) // mr_s)
+    assert icv.indirection_bytes(streamed) == tiles_s * mr_s * 9 * 4
+    # a single kernel element has nothing to re-use: rows are gathered per element
+    assert "patch" not in icv.plan_name(icv.make_params(CONFIGS["cfg5a_1x1"]))
+    # forcing the pixel-range kernel where it cannot run is an error, not a silent fallback
+    assert _status(lib, CONFIGS["cfg5a_1x1"], plan=2 << 12) == icv.ICV_ERR_UNSUPPORTED
