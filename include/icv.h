@@ -67,7 +67,8 @@ typedef struct icv_conv_params {
                                   bits 0-3 kernel (1 vector ALU, 2.. tile variant), bits 4-7 LDS ring depth (2..12),
                                   bits 8-9 workgroups per CU (1, 2), bits 10-11 stage width (1: 64 B, 2: 128 B),
                                   bits 12-13 row staging (1: rows gathered per kernel element, 2: the tile's
-                                  input pixel range kept in LDS).  All set-up calls and the conv call of one problem must use the same value. */
+                                  input pixel range kept in LDS), bits 14-16 kernel elements per pipeline
+                                  stage of the latter.  All set-up calls and the conv call of one problem must use the same value. */
 } icv_conv_params;
 
 /* Hout, Wout by the formula above.  ICV_ERR_INVALID_ARG when the parameters are not a valid problem. */
@@ -97,7 +98,7 @@ ICV_API int64_t icv_indirection_index(const icv_conv_params* p, int64_t m, int32
 
 /*
  * Upper bound on the number of consecutive input pixels that the valid entries of any `rows` consecutive
- * output pixels span (the entries of neighbouring output pixels overlap, section 3.4's re-use of input rows);
+ * output pixels span (the entries of neighbouring output pixels overlap, the re-use of input rows that section 3 lists as the method's second performance factor);
  * the library sizes its LDS input patch with it.  Host arithmetic only.  Returns -1 on invalid arguments.
  */
 ICV_API int64_t icv_tile_span_bound(const icv_conv_params* p, int32_t rows);

@@ -61,6 +61,16 @@ static const char* kPatchNames[2][14] = {
     {"mfma_i8_128x64_c2x2_patch", "mfma_i8_128x128_c2x2_patch", "", "mfma_i8_256x64_c4x2_patch", "", "",
      "mfma_i8_256x128_c4x2_patch", "mfma_i8_128x128_c4x2_patch", "", "", "", "", "", ""},
 };
+static const char* kGemmNames[2][14] = {
+    {"gemm_bf16_128x64_c2x2_p4", "gemm_bf16_128x128_c2x2_p4", "gemm_bf16_128x64_c4x2_p4", "gemm_bf16_256x64_c4x2_p8",
+     "gemm_bf16_256x128_c2x2_p4", "gemm_bf16_64x64_c2x2_p4", "gemm_bf16_256x128_c4x2_p8", "gemm_bf16_128x128_c4x2_p8",
+     "gemm_bf16_256x128_c4x2_p4", "gemm_bf16_128x128_c2x2_p8", "gemm_bf16_256x128_u4x2", "gemm_bf16_128x128_u4x2",
+     "gemm_bf16_256x64_u4x2", "gemm_bf16_128x64_u4x2"},
+    {"gemm_i8_128x64_c2x2_p4", "gemm_i8_128x128_c2x2_p4", "gemm_i8_128x64_c4x2_p4", "gemm_i8_256x64_c4x2_p8",
+     "gemm_i8_256x128_c2x2_p4", "gemm_i8_64x64_c2x2_p4", "gemm_i8_256x128_c4x2_p8", "gemm_i8_128x128_c4x2_p8",
+     "gemm_i8_256x128_c4x2_p4", "gemm_i8_128x128_c2x2_p8", "gemm_i8_256x128_u4x2", "gemm_i8_128x128_u4x2",
+     "gemm_i8_256x64_u4x2", "gemm_i8_128x64_u4x2"},
+};
 static const char* kMfmaNames[2][14] = {
     {"mfma_bf16_128x64_c2x2_p4", "mfma_bf16_128x128_c2x2_p4", "mfma_bf16_128x64_c4x2_p4", "mfma_bf16_256x64_c4x2_p8",
      "mfma_bf16_256x128_c2x2_p4", "mfma_bf16_64x64_c2x2_p4", "mfma_bf16_256x128_c4x2_p8", "mfma_bf16_128x128_c4x2_p8",
@@ -85,10 +95,11 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     if (p->dtype == ICV_U8I8 && (p->input_zero_point < 0 || p->input_zero_point > 255)) return ICV_ERR_INVALID_ARG;
     // plan: bits 0-3 kernel (0 auto, 1 vector ALU, 2.. tile variant), bits 4-7 ring depth, bits 8-9 workgroups
     // per CU, bits 10-11 stage width (1: 64 bytes, 2: 128 bytes), bits 12-13 row staging (1: rows gathered per
-    // kernel element, 2: the tile's pixel range kept in LDS); 0 in a field leaves the choice to the library
+    // kernel element, 2: the tile's pixel range kept in LDS), bits 14-16 kernel elements per pipeline stage of the
+    // pixel-range kernel; 0 in a field leaves the choice to the library
     const int plan_kernel = p->plan & 15, plan_ring = (p->plan >> 4) & 15, plan_per_cu = (p->plan >> 8) & 3,
-              plan_kcb = (p->plan >> 10) & 3, plan_staging = (p->plan >> 12) & 3;
-    if (p->plan < 0 || p->plan >= (1 << 14) || plan_kernel > kNumTileVariants + 1 || plan_ring == 1 || plan_ring > 12 ||
+              plan_kcb = (p->plan >> 10) & 3, plan_staging = (p->plan >> 12) & 3, plan_group = (p->plan >> 14) & 7;
+    if (p->plan < 0 || p->plan >= (1 << 17) || plan_kernel > kNumTileVariants + 1 || plan_ring == 1 || plan_ring > 12 ||
         plan_per_cu > 2 || plan_kcb > 2 || plan_staging > 2)
         return ICV_ERR_INVALID_ARG;
 
@@ -115,6 +126,8 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     g->out_stride = p->out_pixel_stride ? p->out_pixel_stride : p->K;
     g->patch_rows = 0;
     g->cc_major = 0;
+    g->group = plan_group;
+    g->gemm_on_input = 0;
 
     // ---- plan: which kernel, which tile
     const int64_t row_bytes = (int64_t)p->C * g->elem_bytes;        // bytes of one gathered A row
@@ -202,6 +215,13 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         g->taps_per_stage = 1;
         g->n_stages = g->T * g->stages_per_tap;
         g->name = (patch_rows ? kPatchNames : kMfmaNames)[p->dtype == ICV_U8I8 ? 1 : 0][variant];
+        // Section 3.2, closing paragraph: a 1x1 stride-1 convolution needs no im2col, the plain GEMM primitive has
+        // the edge there and switching between the two primitives by convolution parameters is advised.  Its A matrix is the input tensor; the indirection buffer is built but not read.
+        if (T == 1 && p->SY == 1 && p->SX == 1 && p->PT == 0 && p->PL == 0 && p->PB == 0 && p->PR == 0 &&
+            plan_staging != 1) {
+            g->gemm_on_input = 1;
+            g->name = kGemmNames[p->dtype == ICV_U8I8 ? 1 : 0][variant];
+        }
     } else {
         g->kind = PLAN_GENERIC;
         g->variant = -1;
@@ -316,7 +336,9 @@ static int conv_common(const icv_conv_params* p, const Geometry& g, const void* 
                        const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s)
 {
     if (g.kind == PLAN_MFMA && g.patch_rows && !a_direct) return launch_igemm_patch(p, g, a, packed, ind, out, s);
-    if (g.kind == PLAN_MFMA) return launch_igemm_mfma(p, g, a, packed, ind, zero_row, out, a_direct, s);
+    if (g.kind == PLAN_MFMA)
+        return launch_igemm_mfma(p, g, a, packed, ind, zero_row, out,
+                                 a_direct ? A_DENSE_WORKSPACE : (g.gemm_on_input ? A_DENSE_INPUT : A_GATHERED), s);
     if (g.kind == PLAN_MFMA_LOWC) return launch_igemm_lowc(p, g, a, packed, ind, zero_row, out, a_direct, s);
     return launch_igemm_generic(p, g, a, packed, ind, zero_row, out, a_direct, s);
 }

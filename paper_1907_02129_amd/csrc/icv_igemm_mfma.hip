@@ -53,6 +53,7 @@ struct IgemmArgs {
     int32_t xcd_mode;          // 1: grid is a multiple of 8 and tiles are dealt per XCD
     int32_t cc_major;          // packed filter stage order: 1 = chunk * T + tap, 0 = tap * stages_per_tap + chunk
     int32_t row_bytes;         // C * element size
+    int64_t a_rows;            // rows of the dense matrix that may be read (later rows of a tile re-read the last one)
 };
 
 template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool DIRECT>
@@ -136,14 +137,20 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
         int itap = 0, icc = 0;   // kernel element and channel chunk of stage `is`
         int islot = 0;           // ring slot the next issued stage goes to
         const uint8_t* wstage = nullptr;     // B tile of the stage to prepare, before the per-lane offset
-        const uint8_t* adirect = nullptr;    // DIRECT: this lane's first row of the tile
+        const uint8_t* adirect[A_VEC];       // DIRECT: the rows of the tile this lane copies from (clamped to the matrix)
         auto enter_tile = [&]() {
             if (ik >= tl.count) return;
             const int64_t tile = tl.first + ik * tl.step;
             const int32_t nt = (int32_t)(tile % g.n_tiles);
             const int64_t mt = tile / g.n_tiles;
             wstage = g.w + ((int64_t)nt * n_stages) * (NR * KCB);
-            if constexpr (DIRECT) adirect = g.a + (mt * MR + a_row[0]) * g.row_stride_bytes;
+            if constexpr (DIRECT) {
+#pragma unroll
+                for (int j = 0; j < A_VEC; j++) {
+                    const int64_t row = mt * MR + a_row[j];
+                    adirect[j] = g.a + (row < g.a_rows ? row : g.a_rows - 1) * g.row_stride_bytes;
+                }
+            }
         };
         enter_tile();
 
@@ -159,7 +166,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
                                                 : (int64_t)is * KCB;
 #pragma unroll
                 for (int j = 0; j < A_VEC; j++)
-                    asrc[j] = adirect + (int64_t)(j * RPB) * g.row_stride_bytes + koff + a_lane_off[j];
+                    asrc[j] = adirect[j] + koff + a_lane_off[j];
             } else {
                 const int32_t* ent = (const int32_t*)(lds + ent_base + (int)(ik & 1) * ent_bytes) + itap * MR;
                 int32_t e[A_VEC];
@@ -353,14 +360,20 @@ __global__ __launch_bounds__(64 * WM * WN) void k_igemm_uni(IgemmArgs g)
     int64_t ik = 0;
     int is = 0, itap = 0, icc = 0, islot = 0;
     const uint8_t* wstage = nullptr;
-    const uint8_t* adirect = nullptr;
+    const uint8_t* adirect[A_VEC];
     auto enter_tile = [&]() {
         if (ik >= tl.count) return;
         const int64_t tile = tl.first + ik * tl.step;
         const int32_t nt = (int32_t)(tile % g.n_tiles);
         const int64_t mt = tile / g.n_tiles;
         wstage = g.w + ((int64_t)nt * n_stages) * (NR * KCB);
-        if constexpr (DIRECT) adirect = g.a + (mt * MR + a_row[0]) * g.row_stride_bytes;
+        if constexpr (DIRECT) {
+#pragma unroll
+            for (int j = 0; j < A_VEC; j++) {
+                const int64_t row = mt * MR + a_row[j];
+                adirect[j] = g.a + (row < g.a_rows ? row : g.a_rows - 1) * g.row_stride_bytes;
+            }
+        }
     };
     enter_tile();
     const uint8_t* asrc[A_VEC];
@@ -374,7 +387,7 @@ __global__ __launch_bounds__(64 * WM * WN) void k_igemm_uni(IgemmArgs g)
                                             : (int64_t)is * KCB;
 #pragma unroll
             for (int j = 0; j < A_VEC; j++)
-                asrc[j] = adirect + (int64_t)(j * RPB) * g.row_stride_bytes + koff + a_lane_off[j];
+                asrc[j] = adirect[j] + koff + a_lane_off[j];
         } else {
             const int32_t* ent = (const int32_t*)(lds + ent_base + (int)(ik & 1) * ent_bytes) + itap * MR;
             int32_t e[A_VEC];
@@ -578,8 +591,11 @@ static int launch_dtype(const Geometry& g, const IgemmArgs& a, bool direct, hipS
 }
 
 int launch_igemm_mfma(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
-                      const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s)
+                      const int32_t* ind, const void* zero_row, void* out, int a_mode, hipStream_t s)
 {
+    // A dense A matrix is either the im2col workspace (rows of T*C elements, padded to whole tiles) or, for a
+    // 1x1 stride-1 unpadded convolution, the input tensor itself (M rows of in_pixel_stride elements).
+    const bool a_direct = a_mode != A_GATHERED, on_input = a_mode == A_DENSE_INPUT;
     // the host-side table and the instantiations above must describe the same tiles
     const TileVariant& tv = kTileVariants[g.variant];
     if (tv.MR != g.MR || tv.NR != g.NR) return ICV_ERR_UNSUPPORTED;
@@ -590,7 +606,8 @@ int launch_igemm_mfma(const icv_conv_params* p, const Geometry& g, const void* i
     a.ind = ind;
     a.out = out;
     a.M = g.M;
-    a.row_stride_bytes = a_direct ? (int64_t)g.T * p->C * g.elem_bytes : (int64_t)g.in_stride * g.elem_bytes;
+    a.row_stride_bytes = a_direct && !on_input ? (int64_t)g.T * p->C * g.elem_bytes : (int64_t)g.in_stride * g.elem_bytes;
+    a.a_rows = on_input ? g.M : g.m_tiles * g.MR;
     a.total_tiles = g.m_tiles * g.n_tiles;
     a.K = p->K; a.T = g.T; a.out_stride = g.out_stride;
     a.stages_per_tap = g.stages_per_tap; a.n_stages = g.n_stages;

@@ -1,9 +1,9 @@
 // Tensor-core Indirect GEMM with the gathered rows kept in LDS across kernel elements.
 //
 // Listing 3 reads, for every kernel element, the MR rows its indirection entries name.  For a convolution the
-// R*S entries of neighbouring output pixels name mostly the same input pixels (section 3.4 counts on the cache
-// for that re-use); here the re-use is made explicit.  The valid entries of a tile of MR consecutive output
-// pixels all fall into one short range of consecutive input pixels -- the set-up phase records each tile's first
+// R*S entries of neighbouring output pixels name mostly the same input pixels (the second performance factor
+// section 3 lists: rows contributing to different output pixels are read from the same location); here that
+// re-use is made explicit.  The valid entries of a tile of MR consecutive output pixels all fall into one short range of consecutive input pixels -- the set-up phase records each tile's first
 // byte offset and pixel count next to the entries -- so that range ("patch") is copied to LDS once per tile and
 // channel chunk, and every kernel element then takes its MR rows from the patch by looking its entries up:
 //
@@ -36,7 +36,8 @@ struct PatchArgs {
     int64_t total_tiles;       // m_tiles * n_tiles
     int32_t stride_bytes, stride_shift;   // bytes between input pixels, a power of two
     int32_t K, T, NCC, out_stride, n_tiles;
-    int32_t ring;              // filter-tile slots
+    int32_t ring;              // filter slots in the ring
+    int32_t G;                 // kernel elements per pipeline stage (divides T): one barrier per G filter tiles
     int32_t ent_copies;        // 1 KB pieces of one tile's entries
     int32_t cap_units;         // 1 KB pieces of one patch buffer (the zero row follows them)
     int32_t a_share, e_share;  // copies per producer per stage: next patch, next entries
@@ -65,7 +66,9 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
     const int D = g.ring;
     const int pbytes = (g.cap_units + 1) * 1024;          // patch buffer: cap_units pieces, then the zero row
     const int zoff = g.cap_units * 1024;
-    const int patch_base = D * BS;
+    const int G = g.G;
+    const int slot_bytes = G * BS;                        // one stage: the filter tiles of G kernel elements
+    const int patch_base = D * slot_bytes;
     const int ent_base = patch_base + 2 * pbytes;
     const int ent_bytes = g.ent_copies * 1024;
     const int hdr_base = ent_base + 2 * ent_bytes;        // [parity] int4 copy of the tile's range record
@@ -75,8 +78,65 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const TileList tl = my_tiles(g.total_tiles, g.xcd_mode);
     const int T = g.T, NCC = g.NCC;
-    const int n_st = NCC * T;                             // stages per tile, stage = chunk * T + tap
+    const int TS = T / G;                                 // stages per channel chunk
+    const int n_st = NCC * TS;                            // stages per tile, stage = chunk * TS + tap / G
     const int64_t total_stages = tl.count * n_st;
+
+    const int lrow_in_blk = lane / Q, lchunk = lane % Q;
+    const uint32_t n_tiles = (uint32_t)g.n_tiles;
+    auto m_tile_of = [&](int k) { return (uint32_t)(tl.first + k * tl.step) / n_tiles; };
+    auto n_tile_of = [&](int k) { return (uint32_t)(tl.first + k * tl.step) % n_tiles; };
+    const int count = (int)tl.count;
+    // range record {first byte offset, pixel rows} of my k-th tile, read through the constant address space:
+    // a scalar load, which neither touches the vector-memory counter the copies are tracked with nor makes the
+    // compiler wait on it
+    auto load_range = [&](int k) {
+        int2 r = make_int2(0, 1);
+        if (k < count) {
+            typedef const int32_t __attribute__((address_space(4))) * const_int_ptr;
+            const_int_ptr rec = (const_int_ptr)(uintptr_t)(g.ranges + m_tile_of(k));
+            r = make_int2(rec[0], rec[1]);
+        }
+        return r;
+    };
+    // piece u of a patch: LDS rows u*RPB .. +RPB hold pixels first + row (clamped to the tile's range, so the
+    // read stays inside the tensor), channel chunk cc, piece c of row r taken from source piece c ^ swz(r)
+    auto copy_patch_piece = [&](int u, const uint8_t* src, int nrows, uint32_t dst) {
+        const uint32_t r = (uint32_t)(u * RPB + lrow_in_blk);
+        const uint32_t rc = r < (uint32_t)nrows ? r : (uint32_t)nrows - 1;
+        const uint32_t off = (rc << g.stride_shift) + ((lchunk ^ ((r / P) % Q)) << 4);
+        copy16_global_to_lds(src, off, dst + u * 1024);
+    };
+    // piece u of a tile's entries; piece ent_copies is the tile's range record (16 bytes, one lane)
+    const int ent_chunks = T * MR / 4;
+    auto copy_ent_piece = [&](int u, const int32_t* src, const int4* rec, uint32_t par) {
+        if (u < g.ent_copies) {
+            const int c = u * 64 + lane;
+            if (c < ent_chunks) copy16_global_to_lds(src, (uint32_t)c * 16u, lds_base + ent_base + par * ent_bytes + u * 1024);
+        } else if (u == g.ent_copies) {
+            if (lane == 0) copy16_global_to_lds(rec, 0u, lds_base + hdr_base + par * 16);
+        }
+    };
+
+
+    // ---- start-up, all wavefronts: the first tile's entries, the filter stages the ring runs ahead by, and the first
+    // patch.  Everything but the patch is issued before the tile's range record (a dependent scalar load) is needed.
+    if (count > 0) {
+        constexpr int NW = NC + NP;
+        const uint32_t mt = m_tile_of(0);
+        for (int u = wave; u <= g.ent_copies; u += NW) copy_ent_piece(u, g.ind + (int64_t)mt * T * MR, g.ranges + mt, 0);
+        // stages 0 .. D-2 are contiguous in the packed filter and in the ring (the host keeps D - 1 <= stages per tile)
+        const uint8_t* w0 = g.w + (int64_t)n_tile_of(0) * n_st * slot_bytes;
+        const int b_pieces = (D - 1) * slot_bytes / 1024;
+        for (int u = wave; u < b_pieces; u += NW) {
+            const int row = u * RPB + lrow_in_blk;
+            copy16_global_to_lds(w0, (uint32_t)(row * KCB + ((lchunk ^ ((row / P) % Q)) << 4)), lds_base + u * 1024);
+        }
+        const int2 rng0 = load_range(0);
+        int units = (rng0.y + RPB - 1) / RPB;
+        if (units > g.cap_units) units = g.cap_units;
+        for (int u = wave; u < units; u += NW) copy_patch_piece(u, g.a + rng0.x, rng0.y, lds_base + patch_base);
+    }
 
     if (wave >= NC) {
         // =============================================================== producer
@@ -84,117 +144,99 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
         // wavefront issues an instruction every few cycles only), so everything that can be is precomputed,
         // uniform values stay in scalar registers, and per-lane addresses are 32-bit offsets from uniform bases.
         const int p = wave - NC;
-        const int lrow_in_blk = lane / Q, lchunk = lane % Q;
         uint32_t b_src_off[B_VEC];
 #pragma unroll
         for (int j = 0; j < B_VEC; j++) {
             const int row = (p * B_VEC + j) * RPB + lrow_in_blk;
             b_src_off[j] = row * KCB + ((lchunk ^ ((row / P) % Q)) << 4);
         }
-        const uint32_t n_tiles = (uint32_t)g.n_tiles;
-        auto m_tile_of = [&](int k) { return (uint32_t)(tl.first + k * tl.step) / n_tiles; };
-        auto n_tile_of = [&](int k) { return (uint32_t)(tl.first + k * tl.step) % n_tiles; };
-        const int count = (int)tl.count;
-        // range record {first byte offset, pixel rows} of my k-th tile, read through the constant address space:
-        // a scalar load, which neither touches the vector-memory counter the copies are tracked with nor makes the
-        // compiler wait on it
-        auto load_range = [&](int k) {
-            int2 r = make_int2(0, 1);
-            if (k < count) {
-                typedef const int32_t __attribute__((address_space(4))) * const_int_ptr;
-                const_int_ptr rec = (const_int_ptr)(uintptr_t)(g.ranges + m_tile_of(k));
-                r = make_int2(rec[0], rec[1]);
-            }
-            return r;
-        };
-        // piece u of a patch: LDS rows u*RPB .. +RPB hold pixels first + row (clamped to the tile's range, so the
-        // read stays inside the tensor), channel chunk cc, piece c of row r taken from source piece c ^ swz(r)
-        auto copy_patch_piece = [&](int u, const uint8_t* src, int nrows, uint32_t dst) {
-            const uint32_t r = (uint32_t)(u * RPB + lrow_in_blk);
-            const uint32_t rc = r < (uint32_t)nrows ? r : (uint32_t)nrows - 1;
-            const uint32_t off = (rc << g.stride_shift) + ((lchunk ^ ((r / P) % Q)) << 4);
-            copy16_global_to_lds(src, off, dst + u * 1024);
-        };
-        // piece u of a tile's entries; piece ent_copies is the tile's range record (16 bytes, one lane)
-        const int ent_chunks = T * MR / 4;
-        auto copy_ent_piece = [&](int u, const int32_t* src, const int4* rec, uint32_t par) {
-            if (u < g.ent_copies) {
-                const int c = u * 64 + lane;
-                if (c < ent_chunks) copy16_global_to_lds(src, (uint32_t)c * 16u, lds_base + ent_base + par * ent_bytes + u * 1024);
-            } else if (u == g.ent_copies) {
-                if (lane == 0) copy16_global_to_lds(rec, 0u, lds_base + hdr_base + par * 16);
-            }
-        };
-
-        // filter-tile cursor: the next stage to issue is stage bs of my tile bk, into slot bslot
+        // filter cursor: the next stage to issue is stage bs of my tile bk, into slot bslot; a stage's G filter
+        // tiles are contiguous in the packed filter
         int bk = 0, bs = 0, bslot = 0;
-        const uint8_t* wsrc = g.w + (int64_t)(count > 0 ? n_tile_of(0) : 0) * n_st * BS;
-        auto issue_b = [&]() {
+        const uint8_t* wsrc = g.w + (int64_t)(count > 0 ? n_tile_of(0) : 0) * n_st * slot_bytes;
+        auto issue_b = [&](bool copy) {
             if (bk >= count) return;
-            const uint32_t slot = lds_base + (uint32_t)bslot * BS;
+            if (copy) {
+                uint32_t dst = lds_base + (uint32_t)bslot * slot_bytes + p * B_VEC * 1024;
+                for (int t = 0; t < G; t++) {
 #pragma unroll
-            for (int j = 0; j < B_VEC; j++) copy16_global_to_lds(wsrc, b_src_off[j], slot + (p * B_VEC + j) * 1024);
-            wsrc += BS;
+                    for (int j = 0; j < B_VEC; j++) copy16_global_to_lds(wsrc, b_src_off[j], dst + j * 1024);
+                    wsrc += BS;
+                    dst += BS;
+                }
+            } else {
+                wsrc += slot_bytes;
+            }
             bslot = bslot + 1 == D ? 0 : bslot + 1;
             if (++bs == n_st) {
                 bs = 0;
-                if (++bk < count) wsrc = g.w + (int64_t)n_tile_of(bk) * n_st * BS;
+                if (++bk < count) wsrc = g.w + (int64_t)n_tile_of(bk) * n_st * slot_bytes;
             }
         };
-
-        int2 rng_k = load_range(0), rng_k1 = load_range(1);
-        if (count > 0) {
-            const uint32_t mt = m_tile_of(0);
-            for (int u = p; u <= g.ent_copies; u += NP)
-                copy_ent_piece(u, g.ind + (int64_t)mt * T * MR, g.ranges + mt, 0);
-            int units = (rng_k.y + RPB - 1) / RPB;
-            if (units > g.cap_units) units = g.cap_units;
-            for (int u = p; u < units; u += NP) copy_patch_piece(u, g.a + rng_k.x, rng_k.y, lds_base + patch_base);
-        }
-        for (int q = 0; q < D - 1; q++) issue_b();
+        for (int q = 0; q < D - 1; q++) issue_b(false);     // those stages were copied at start-up
         wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();         // first tile's entries, patch and filter stages are in LDS
 
-        // Shares go out before the stage's filter tile.  Copies retire in order, so "at most (ring-2) * B_VEC copies
-        // outstanding" then implies: the filter tile issued ring-1 stages ago has landed, and so has every share
-        // issued ring-1 or more stages ago -- which is why shares stop ring-1 stages before their data is needed.
-        const int a_last = T - D + 1, e_last = n_st - D + 1;     // last tap / stage that still carries a share
-        int younger = (int)total_stages - 1;                     // stages after the one being handed over
-        for (int k = 0; k < count; k++) {
-            const bool next_tile = k + 1 < count;
-            const uint32_t mt1 = next_tile ? m_tile_of(k + 1) : 0;
-            const int32_t* ent_src = g.ind + (int64_t)mt1 * T * MR;
-            const int4* rec_src = g.ranges + mt1;
-            const uint32_t ent_par = (uint32_t)((k + 1) & 1);
-            int s = 0;
-            for (int cc = 0; cc < NCC; cc++) {
-                // the patch after this one: (k, cc+1) or (k+1, 0); its buffer was last read in the patch before this one
-                const bool same_tile = cc + 1 < NCC;
-                const int2 rng = same_tile ? rng_k : rng_k1;
-                const bool next_patch = same_tile || next_tile;
-                const uint8_t* psrc = g.a + rng.x + (same_tile ? cc + 1 : 0) * KCB;
-                int units = next_patch ? (rng.y + RPB - 1) / RPB : 0;
-                if (units > g.cap_units) units = g.cap_units;
-                const uint32_t pdst = lds_base + patch_base + (uint32_t)((k * NCC + cc + 1) & 1) * pbytes;
-                for (int tap = 0; tap < T; tap++, s++) {
-                    // (towards the end fewer filter tiles follow the one waited for)
-                    wait_all_but_stages<B_VEC>(younger < D - 2 ? younger : D - 2);
-                    --younger;
-                    __builtin_amdgcn_s_barrier();     // hand this stage to the consumers; they are done with the one before
-                    if (tap <= a_last) {
-                        int u = tap * g.a_share * NP + p;
-                        for (int j = 0; j < g.a_share; j++, u += NP)
-                            if (u < units) copy_patch_piece(u, psrc, rng.y, pdst);
+        // Shares go out before the stage's filter tiles.  Copies retire in order, so "at most ALLOWED <= (ring-2) *
+        // G * B_VEC copies outstanding" then implies: the filter tiles issued ring-1 stages ago have landed, and so
+        // has every share issued ring-1 or more stages ago -- which is why shares stop ring-1 stages before their
+        // data is needed.  s_waitcnt takes an immediate, so the loop is instantiated for a few allowances and the
+        // largest one not above the exact value is used (waiting for more than necessary is always safe).
+        const int a_last = TS - D + 1, e_last = n_st - D + 1;     // last stage of a patch / tile that still carries a share
+        auto run = [&](auto allowed_c) {
+            constexpr int ALLOWED = decltype(allowed_c)::value;
+            int younger = (int)total_stages - 1;                  // stages after the one being handed over
+            int2 rng_k = load_range(0), rng_k1 = load_range(1);
+            for (int k = 0; k < count; k++) {
+                const bool next_tile = k + 1 < count;
+                const uint32_t mt1 = next_tile ? m_tile_of(k + 1) : 0;
+                const int32_t* ent_src = g.ind + (int64_t)mt1 * T * MR;
+                const int4* rec_src = g.ranges + mt1;
+                const uint32_t ent_par = (uint32_t)((k + 1) & 1);
+                int s = 0;
+                for (int cc = 0; cc < NCC; cc++) {
+                    // the patch after this one: (k, cc+1) or (k+1, 0); its buffer was last read in the patch before this one
+                    const bool same_tile = cc + 1 < NCC;
+                    const int2 rng = same_tile ? rng_k : rng_k1;
+                    const bool next_patch = same_tile || next_tile;
+                    const uint8_t* psrc = g.a + rng.x + (same_tile ? cc + 1 : 0) * KCB;
+                    int units = next_patch ? (rng.y + RPB - 1) / RPB : 0;
+                    if (units > g.cap_units) units = g.cap_units;
+                    const uint32_t pdst = lds_base + patch_base + (uint32_t)((k * NCC + cc + 1) & 1) * pbytes;
+                    for (int ts = 0; ts < TS; ts++, s++) {
+                        if (younger >= D - 2) wait_vmcnt<ALLOWED>();
+                        else wait_all_but_stages<1>(0);           // the last stages: nothing useful is in flight behind them
+                        --younger;
+                        __builtin_amdgcn_s_barrier();     // hand this stage to the consumers; they are done with the one before
+                        if (ts <= a_last) {
+                            int u = ts * g.a_share * NP + p;
+                            for (int j = 0; j < g.a_share; j++, u += NP)
+                                if (u < units) copy_patch_piece(u, psrc, rng.y, pdst);
+                        }
+                        if (next_tile && s <= e_last) {
+                            int u = s * g.e_share * NP + p;
+                            for (int j = 0; j < g.e_share; j++, u += NP) copy_ent_piece(u, ent_src, rec_src, ent_par);
+                        }
+                        issue_b(true);
                     }
-                    if (next_tile && s <= e_last) {
-                        int u = s * g.e_share * NP + p;
-                        for (int j = 0; j < g.e_share; j++, u += NP) copy_ent_piece(u, ent_src, rec_src, ent_par);
-                    }
-                    issue_b();
                 }
+                rng_k = rng_k1;
+                rng_k1 = load_range(k + 2);
             }
-            rng_k = rng_k1;
-            rng_k1 = load_range(k + 2);
+        };
+        {
+            const int exact = (D - 2) * G * B_VEC;
+            if (exact >= 32) run(std::integral_constant<int, 32>());
+            else if (exact >= 24) run(std::integral_constant<int, 24>());
+            else if (exact >= 16) run(std::integral_constant<int, 16>());
+            else if (exact >= 12) run(std::integral_constant<int, 12>());
+            else if (exact >= 8) run(std::integral_constant<int, 8>());
+            else if (exact >= 6) run(std::integral_constant<int, 6>());
+            else if (exact >= 4) run(std::integral_constant<int, 4>());
+            else if (exact >= 3) run(std::integral_constant<int, 3>());
+            else if (exact >= 2) run(std::integral_constant<int, 2>());
+            else if (exact >= 1) run(std::integral_constant<int, 1>());
+            else run(std::integral_constant<int, 0>());
         }
         wait_vmcnt<0>();
     } else {
@@ -212,6 +254,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
                 *(uint32_t*)(lds + patch_base + (i >> 8) * pbytes + zoff + (i & 255) * 4) = zv;
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
+        wait_vmcnt<0>();                      // this wavefront's share of the start-up copies
         __builtin_amdgcn_s_barrier();         // pairs with the producers' start-up barrier
         int slot = 0;
         for (int64_t k = 0; k < tl.count; k++) {
@@ -224,23 +267,43 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
                     for (int r = 0; r < 16; r++) acc[i][j][r] = 0;
 
             const int32_t* ent = (const int32_t*)(lds + ent_base + (int)(k & 1) * ent_bytes) + wm * MRW + lrow;
+            // The rows of kernel element tap+1 are looked up while the MFMAs of tap run: the entries and the patch
+            // are in LDS for the whole tile, only the filter tile behind the next barrier is not.
             int32_t first = 0;
+            uint32_t abase[MB], aswz[MB];        // LDS row of the patch (or the zero row) per 32-row block, and its swizzle
+            auto locate = [&](const int32_t (&e)[MB], uint32_t pb) {
+#pragma unroll
+                for (int i = 0; i < MB; i++) {
+                    const uint32_t r = (uint32_t)(e[i] - first) >> g.stride_shift;
+                    abase[i] = pb + (e[i] < 0 ? (uint32_t)zoff : r * KCB);
+                    aswz[i] = e[i] < 0 ? 0u : ((r / P) % Q) << 4;
+                }
+            };
             for (int cc = 0; cc < NCC; cc++) {
                 const uint32_t pb = patch_base + (uint32_t)((k * NCC + cc) & 1) * pbytes;
-                for (int tap = 0; tap < T; tap++) {
-                    __builtin_amdgcn_s_barrier();
-                    if (cc == 0 && tap == 0) first = *(const int32_t*)(lds + hdr_base + (int)(k & 1) * 16);
-                    // entry -> LDS row of the patch (or the zero row) and that row's swizzle
-                    uint32_t abase[MB], aswz[MB];
+                for (int tap = 0, t_in_stage = 0; tap < T; tap++) {
+                    if (t_in_stage == 0) __builtin_amdgcn_s_barrier();
+                    if (cc == 0 && tap == 0) {
+                        // first stage of the tile: its entries and range record only became visible with this barrier
+                        first = *(const int32_t*)(lds + hdr_base + (int)(k & 1) * 16);
+                        int32_t e0[MB];
 #pragma unroll
-                    for (int i = 0; i < MB; i++) {
-                        const int32_t e = ent[tap * MR + i * 32];
-                        const uint32_t r = (uint32_t)(e - first) >> g.stride_shift;
-                        abase[i] = pb + (e < 0 ? (uint32_t)zoff : r * KCB);
-                        aswz[i] = e < 0 ? 0u : ((r / P) % Q) << 4;
+                        for (int i = 0; i < MB; i++) e0[i] = ent[i * 32];
+                        locate(e0, pb);
                     }
-                    const uint8_t* S = lds + slot * BS;
-                    slot = slot + 1 == D ? 0 : slot + 1;
+                    // entries of the next kernel element of this tile (the next chunk starts over at element 0)
+                    const bool more = tap + 1 < T || cc + 1 < NCC;
+                    const int ntap = tap + 1 < T ? tap + 1 : 0;
+                    int32_t en[MB];
+                    if (more) {
+#pragma unroll
+                        for (int i = 0; i < MB; i++) en[i] = ent[ntap * MR + i * 32];
+                    }
+                    const uint8_t* S = lds + slot * slot_bytes + t_in_stage * BS;
+                    if (++t_in_stage == G) {
+                        t_in_stage = 0;
+                        slot = slot + 1 == D ? 0 : slot + 1;
+                    }
 #pragma unroll
                     for (int ks = 0; ks < KSTEPS; ks++) {
                         const uint32_t piece = (uint32_t)(2 * ks + lhalf) << 4;
@@ -255,6 +318,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
 #pragma unroll
                             for (int j = 0; j < NB; j++) acc[i][j] = mfma32<I8>(af[i], bf[j], acc[i][j]);
                     }
+                    if (more) locate(en, tap + 1 < T ? pb : patch_base + (uint32_t)((k * NCC + cc + 1) & 1) * pbytes);
                 }
             }
 
@@ -294,6 +358,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
 // ------------------------------------------------------------------ launch
 size_t patch_lds_bytes(int NR, int KCB, int ring, int cap_units, int ent_copies)
 {
+    // `ring` counts filter tiles (slots times kernel elements per slot)
     return (size_t)ring * NR * KCB + (size_t)2 * (cap_units + 1) * 1024 + (size_t)2 * ent_copies * 1024 + 2048;
 }
 
@@ -301,26 +366,41 @@ template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB>
 static int launch_one(const Geometry& g, PatchArgs a, hipStream_t s)
 {
     constexpr int threads = 64 * (WM * WN + NP);
-    constexpr int B_VEC = NR * KCB / 1024 / NP;
     auto kern = k_igemm_patch<I8, MR, NR, WM, WN, NP, KCB>;
-    const int n_st = a.NCC * a.T;
     a.ent_copies = (int32_t)(((size_t)a.T * MR * 4 + 1023) / 1024);
     a.cap_units = (int32_t)(((size_t)g.patch_rows * KCB + 1023) / 1024);
-    // Ring depth.  A copy takes on the order of a microsecond from issue to completion under load, a stage far
-    // less, and a stage's filter tile must be issued ring - 1 stages ahead: as deep as fits (LDS, the 6-bit copy
-    // counter, enough stages left to spread the shares over), at most 8.
-    int ring = g.ring ? g.ring : 8;
-    for (;; --ring) {
-        if (ring < 2) return ICV_ERR_UNSUPPORTED;
-        if (a.T - ring + 2 < 1 || n_st - ring + 2 < 1) continue;
-        a.a_share = (a.cap_units + NP * (a.T - ring + 2) - 1) / (NP * (a.T - ring + 2));
-        a.e_share = (a.ent_copies + 1 + NP * (n_st - ring + 2) - 1) / (NP * (n_st - ring + 2));
-        if ((ring - 2) * B_VEC > 63) continue;
-        if (patch_lds_bytes(NR, KCB, ring, a.cap_units, a.ent_copies) > kLdsPerCu) continue;
-        break;
+    // Kernel elements per stage: a stage should hold enough MFMAs (16 per consumer wavefront) to amortise its
+    // barrier and the producers' bookkeeping; G divides T.
+    constexpr int mfma_per_tap = (MR / WM / 32) * (NR / WN / 32) * (KCB / 32);
+    int G = g.group;
+    if (G == 0) {
+        G = 1;
+        while (G * mfma_per_tap < 16 && G < a.T) ++G;
     }
+    if (G > a.T) G = a.T;
+    // Ring depth.  A copy takes on the order of a microsecond from issue to completion under load, a stage far
+    // less, and a stage's filter tiles must be issued ring - 1 stages ahead: as deep as fits (LDS, enough stages
+    // left to spread the shares over), at most 8, at least 3 unless only fewer kernel elements per stage allow it.
+    int ring = 0;
+    for (; G >= 1; --G) {
+        if (a.T % G) continue;
+        const int TS = a.T / G, n_st = a.NCC * TS;
+        for (ring = g.ring ? g.ring : 8; ring >= 2; --ring) {
+            if (TS - ring + 2 < 1 || n_st - ring + 2 < 1) continue;
+            if (patch_lds_bytes(NR, KCB, ring * G, a.cap_units, a.ent_copies) > kLdsPerCu) continue;
+            break;
+        }
+        if (ring >= 3 || (ring == 2 && (G == 1 || g.group || g.ring == 2))) break;
+    }
+    if (G < 1 || ring < 2) return ICV_ERR_UNSUPPORTED;
+    {
+        const int TS = a.T / G, n_st = a.NCC * TS;
+        a.a_share = (a.cap_units + NP * (TS - ring + 2) - 1) / (NP * (TS - ring + 2));
+        a.e_share = (a.ent_copies + 1 + NP * (n_st - ring + 2) - 1) / (NP * (n_st - ring + 2));
+    }
+    a.G = G;
     a.ring = ring;
-    const size_t lds_bytes = patch_lds_bytes(NR, KCB, ring, a.cap_units, a.ent_copies);
+    const size_t lds_bytes = patch_lds_bytes(NR, KCB, ring * G, a.cap_units, a.ent_copies);
     int per_cu = g.blocks_per_cu ? g.blocks_per_cu : 1;
     if (per_cu == 2 && (lds_bytes > kLdsPerCu / 2 || threads > 512)) per_cu = 1;
 
@@ -386,7 +466,7 @@ int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* 
     a.stride_bytes = (int32_t)stride_bytes; a.stride_shift = shift;
     a.K = p->K; a.T = g.T; a.NCC = g.stages_per_tap; a.out_stride = g.out_stride;
     a.n_tiles = (int32_t)g.n_tiles;
-    a.ring = 0; a.ent_copies = 0; a.cap_units = 0; a.a_share = 0; a.e_share = 0; a.xcd_mode = 0;
+    a.ring = 0; a.G = 1; a.ent_copies = 0; a.cap_units = 0; a.a_share = 0; a.e_share = 0; a.xcd_mode = 0;
     return p->dtype == ICV_U8I8 ? launch_dtype<true>(g, a, s) : launch_dtype<false>(g, a, s);
 }
 

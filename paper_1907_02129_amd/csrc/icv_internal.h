@@ -33,6 +33,8 @@ struct Geometry {
     int64_t m_tiles, n_tiles;
     int32_t ring;            // forced LDS ring depth (0: launcher decides)
     int32_t blocks_per_cu;   // forced co-resident workgroups per CU (0: launcher decides)
+    int32_t gemm_on_input;   // 1: 1x1 stride-1 unpadded convolution run as a plain GEMM on the input tensor
+    int32_t group;           // forced kernel elements per pipeline stage of the pixel-range kernel (0: launcher decides)
     int32_t patch_rows;      // > 0: the tile's input pixel range is kept in LDS, this many pixel rows reserved
     int32_t cc_major;        // 1: stage = chunk * T + tap (channel chunks outermost), 0: stage = tap * chunks + chunk
     const char* name;
@@ -64,8 +66,10 @@ int launch_im2col(const icv_conv_params* p, const Geometry& g, const void* input
 
 // a_direct = false: rows of A come from the indirection buffer (the method);
 // a_direct = true : A is the dense [M][T*C] patch matrix with constant row stride (ablation GEMM).
+// The tensor-core kernel has a third mode: the input tensor itself as the dense matrix (1x1, stride 1, no padding).
+enum AMode : int { A_GATHERED = 0, A_DENSE_WORKSPACE = 1, A_DENSE_INPUT = 2 };
 int launch_igemm_mfma(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
-                      const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s);
+                      const int32_t* ind, const void* zero_row, void* out, int a_mode, hipStream_t s);
 int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                        const int32_t* ind, void* out, hipStream_t s);
 bool patch_variant_supported(int variant);

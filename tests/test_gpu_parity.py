@@ -206,8 +206,10 @@ def _patch_shapes():
 
 
 @pytest.mark.parametrize("s", _patch_shapes(), ids=lambda s: s.name)
-@pytest.mark.parametrize("knobs", [0, 2 << 4, 3 << 4, 5 << 4, 1 << 10, (2 << 4) | (1 << 10)],
-                         ids=["auto", "ring2", "ring3", "ring5", "kcb64", "ring2_kcb64"])
+@pytest.mark.parametrize("knobs", [0, 2 << 4, 3 << 4, 5 << 4, 1 << 10, (2 << 4) | (1 << 10), 1 << 14, (3 << 14) | (1 << 10),
+                                   (5 << 14) | (2 << 4), 2 << 14],
+                         ids=["auto", "ring2", "ring3", "ring5", "kcb64", "ring2_kcb64", "group1", "group3_kcb64",
+                              "group5_ring2", "group2"])
 def test_pixel_range_kernel_matches_oracle(s, knobs):
     plan = (2 << 12) | knobs
     stride = 64 if s.name == "p_stride" else 0
@@ -248,6 +250,37 @@ def test_range_records_match_oracle_entries(s):
         else:
             assert tuple(rec[t, :2]) == (0, 1), t
         assert rec[t, 1] <= cap and rec[t, 2] == 0 and rec[t, 3] == 0
+
+
+# ---------------------------------------------------------------- 1x1 stride-1: plain GEMM on the input tensor
+@pytest.mark.parametrize("s", [
+    ConvShape("g_exact", 2, 16, 16, 64, 64, 1, 1, seed=81),                        # M a multiple of every tile
+    ConvShape("g_ragged", 3, 7, 11, 128, 72, 1, 1, seed=82),                       # M = 231: last tile mostly past M
+    ConvShape("g_one_row", 1, 1, 1, 64, 200, 1, 1, seed=83),
+    ConvShape("g_i8", 2, 9, 13, 256, 96, 1, 1, dtype="u8i8", zero_point=128, seed=84),
+], ids=lambda s: s.name)
+@pytest.mark.parametrize("pixel_stride", [0, 320])
+def test_pointwise_convolution_runs_as_gemm_on_the_input(s, pixel_stride):
+    x, w = make_tensors(s)
+    xp = x
+    if pixel_stride:
+        # the tensor ends right after the last pixel's channels: reading a row past M would leave the allocation
+        flat = np.full(x.shape[0] * x.shape[1] * x.shape[2] * pixel_stride, 0x7f if s.dtype == "u8i8" else 0x7fc0, dtype=x.dtype)
+        v = flat.reshape(-1, pixel_stride)
+        v[:, :s.C] = x.reshape(-1, s.C)
+        xp = flat
+    for plan in (0, 1 << 12):                                   # dispatch to the GEMM, and the gathered path for comparison
+        p = icv.make_params(s, plan, in_pixel_stride=pixel_stride)
+        assert icv.plan_name(p).startswith("gemm_" if plan == 0 else "mfma_"), icv.plan_name(p)
+        _say("pointwise", s.name, icv.plan_name(p), "pixel stride", pixel_stride)
+        buf = icv.prepare(s, icv.to_device(w), plan=plan, in_pixel_stride=pixel_stride)
+        buf.output.fill_(-7)
+        icv.run(buf, icv.to_device(xp))
+        torch.cuda.synchronize()
+        check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+    # anything that needs an indirection buffer keeps using it
+    assert icv.plan_name(icv.make_params(s.with_(SY=2, SX=2))).startswith("mfma_")
+    assert icv.plan_name(icv.make_params(s.with_(PT=1, PB=1))).startswith("mfma_")
 
 
 # ---------------------------------------------------------------- properties of the path

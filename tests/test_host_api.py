@@ -101,7 +101,7 @@ def test_invalid_arguments_are_rejected(lib):
     assert _status(lib, s, out_pixel_stride=8) == icv.ICV_ERR_INVALID_ARG           # stride < K
     assert _status(lib, s, R=80, PT=0, PB=0) == icv.ICV_ERR_INVALID_ARG             # kernel larger than input
     assert _status(lib, s, N=1 << 20) == icv.ICV_ERR_INVALID_ARG                    # input of 2 GiB or more
-    assert _status(lib, s, plan=1 << 14) == icv.ICV_ERR_INVALID_ARG
+    assert _status(lib, s, plan=1 << 17) == icv.ICV_ERR_INVALID_ARG
     assert _status(lib, s, plan=3 << 12) == icv.ICV_ERR_INVALID_ARG                 # no such row staging
     assert _status(lib, s, plan=2 | (13 << 4)) == icv.ICV_ERR_INVALID_ARG           # ring deeper than 12
     assert _status(lib, s, plan=2 | (1 << 4)) == icv.ICV_ERR_INVALID_ARG            # a ring needs two slots
@@ -132,6 +132,9 @@ def test_plans(lib):
     assert icv.plan_name(icv.make_params(CONFIGS["cfg1_tiny_f32"])).startswith("generic")
     assert icv.plan_name(icv.make_params(CONFIGS["cfg2_3x3_c64"])).startswith("mfma_bf16")
     assert icv.plan_name(icv.make_params(CONFIGS["cfg4_int8_3x3"])).startswith("mfma_i8")
+    # 1x1 stride 1 without padding is a plain GEMM on the input tensor (section 3.2's advice to switch primitives)
+    assert icv.plan_name(icv.make_params(CONFIGS["cfg5a_1x1"])).startswith("gemm_bf16")
+    assert icv.plan_name(icv.make_params(CONFIGS["cfg5a_1x1"].with_(SX=2, SY=2))).startswith("mfma_bf16")
     # odd channel counts fall back to the vector-ALU kernel instead of failing
     odd = ConvShape("odd", 1, 8, 8, 5, 3, 3, 3)
     assert icv.plan_name(icv.make_params(odd)).startswith("generic")
