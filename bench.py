@@ -32,8 +32,8 @@ LLC_BYTES = 256 << 20
 # HBM traffic of the dominant kernel per launch, bytes, measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None until measured.
 MEASURED_TRAFFIC = {
-    # profiles/igemm_cfg2_hbm_traffic.md: FETCH 8430.8 KiB x 1.99975 + WRITE 25101.4 KiB x 1.0
-    "cfg2_3x3_c64": int((8430.8 * 1.99975 + 25101.4) * 1024),
+    # profiles/igemm_cfg2_hbm_traffic.md: FETCH 8472.3 KiB x 1.99975 + WRITE 25109.3 KiB x 1.0
+    "cfg2_3x3_c64": int((8472.3 * 1.99975 + 25109.3) * 1024),
 }
 
 
@@ -132,19 +132,30 @@ def sets_for_cold(s, Hout, Wout):
     return min(32, max(2, int(np.ceil(2.5 * LLC_BYTES / per_set))))
 
 
-def cpu_baseline(s, x, w):
-    """The oracle as it stands, timed on this host's cores on the headline workload (one full pass)."""
+def cpu_baseline(s, x, w, min_seconds=1.0, max_passes=20):
+    """The oracle as it stands, timed on this host's cores on the headline workload: whole passes of the full
+    problem until `min_seconds` of wall time (times the cores used: some 10-30 s of CPU work), best pass reported."""
     import oracle
-    t0 = time.perf_counter()
-    if s.dtype == "u8i8":
-        oracle.conv2d_u8i8(s, x, w, s.zero_point)
-    else:
-        oracle.conv2d(s, x, w)
-    dt = time.perf_counter() - t0
+
+    def one_pass():
+        t0 = time.perf_counter()
+        if s.dtype == "u8i8":
+            oracle.conv2d_u8i8(s, x, w, s.zero_point)
+        else:
+            oracle.conv2d(s, x, w)
+        return time.perf_counter() - t0
+
+    times = []
+    while len(times) < max_passes and (not times or sum(times) < min_seconds):
+        times.append(one_pass())
+    dt = min(times)
     Hout, Wout = oracle.out_extent(s)
-    return {"value": flops(s, Hout, Wout) / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "seconds": round(dt, 3),
-            "sample": f"one full pass of {s.name} (fp64 7-loop direct convolution, OpenMP over n,oy)"}
+    cores = oracle.num_threads()
+    return {"value": flops(s, Hout, Wout) / dt / 1e12, "unit": "TFLOP/s", "cores": cores,
+            "kind": "oracle", "seconds": round(dt, 3), "passes": len(times),
+            "cpu_seconds_total": round(sum(times) * cores, 1),
+            "sample": f"{len(times)} full passes of {s.name} (fp64 7-loop direct convolution, OpenMP over n,oy), "
+                      f"fastest pass reported"}
 
 
 def main():

@@ -56,9 +56,11 @@ int64_t tile_span_bound(const icv_conv_params* p, int64_t Hout, int64_t Wout, in
 static const char* kGenericNames[3] = {"generic_f32", "generic_bf16", "generic_u8i8"};
 static const char* kLowcNames[2] = {"mfma_bf16_lowc_64x64", "mfma_i8_lowc_64x64"};
 static const char* kPatchNames[2][14] = {
-    {"mfma_bf16_128x64_c2x2_patch", "mfma_bf16_128x128_c2x2_patch", "", "mfma_bf16_256x64_c4x2_patch", "", "",
+    {"mfma_bf16_128x64_c2x2_patch", "mfma_bf16_128x128_c2x2_patch", "", "mfma_bf16_256x64_c4x2_patch",
+     "mfma_bf16_256x128_c2x2_patch", "",
      "mfma_bf16_256x128_c4x2_patch", "mfma_bf16_128x128_c4x2_patch", "", "", "", "", "", ""},
-    {"mfma_i8_128x64_c2x2_patch", "mfma_i8_128x128_c2x2_patch", "", "mfma_i8_256x64_c4x2_patch", "", "",
+    {"mfma_i8_128x64_c2x2_patch", "mfma_i8_128x128_c2x2_patch", "", "mfma_i8_256x64_c4x2_patch",
+     "mfma_i8_256x128_c2x2_patch", "",
      "mfma_i8_256x128_c4x2_patch", "mfma_i8_128x128_c4x2_patch", "", "", "", "", "", ""},
 };
 static const char* kGemmNames[2][14] = {
@@ -139,37 +141,42 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     int patch_rows = 0, patch_kcb = 0;
     // LDS-resident pixel range: worthwhile when several kernel elements re-read the rows, possible when the pixel
     // stride is a power of two (entry -> LDS row is a shift) and two patch buffers fit beside the other buffers
-    auto try_patch = [&](int v, bool forced) {
+    auto try_patch = [&](int v, bool kcb64_ok) {
         if (plan_staging == 1 || T < 4 || !patch_variant_supported(v)) return false;
         if ((stride_bytes & (stride_bytes - 1)) != 0) return false;
         const TileVariant& tv = kTileVariants[v];
         if ((int64_t)tv.MR * T * 4 > 24 * 1024) return false;
         const int64_t rows = tile_span_bound(p, Hout, Wout, tv.MR);
         const int ent_copies = (int)((tv.MR * T * 4 + 1023) / 1024);
-        // Measured on MI355X: the per-stage synchronisation is only amortised with 128-byte stages, so unless the
-        // plan is forced the pixel-range kernel is taken when two patches of 128-byte rows fit.
         const int kcb_max = (row_bytes % 128 == 0 && plan_kcb != 1) ? 128 : 64;
-        const int kcb_min = forced ? 64 : 128;
-        for (int kcb = kcb_max; kcb >= kcb_min; kcb -= 64) {
+        for (int kcb = kcb_max; kcb >= 64; kcb -= 64) {
             const int64_t cap_units = (rows * kcb + 1023) / 1024;
-            if (cap_units < 4096 && patch_lds_bytes(tv.NR, kcb, 2, (int)cap_units, ent_copies) <= 160 * 1024) {
+            if (cap_units >= 4096) continue;
+            // one workgroup per compute unit with double buffers, or two with single buffers (64-wide tiles)
+            const bool fits_one = patch_lds_bytes(tv.NR, kcb, 2, (int)cap_units, ent_copies, 2) <= 160 * 1024;
+            const bool fits_two = tv.NR == 64 && plan_per_cu != 1 &&
+                                  patch_lds_bytes(tv.NR, kcb, 2, (int)cap_units, ent_copies, 1) <= 80 * 1024;
+            // 64-byte stages only pay off when two workgroups share a compute unit, or when asked for
+            if (fits_two || (fits_one && (kcb == 128 || kcb64_ok))) {
                 variant = v; patch_rows = (int)rows; patch_kcb = kcb;
                 return true;
             }
         }
         return false;
     };
-    // wide filters: 256-row tiles when they still give every compute unit a tile, else 128-row tiles
-    const int wide = ((M + 255) / 256) * ((p->K + 127) / 128) >= 256 ? 6 : 7;
+    // Measured on MI355X.  64-wide filters: 256 x 64 tiles, else 128 x 64, two workgroups per compute unit when the
+    // single-buffer layout fits half the LDS (with one workgroup and 64-byte stages the per-stage work is too small
+    // and gathering per kernel element is as fast).  Wider filters: 256 x 128 tiles
+    // of 64 x 64 wavefront blocks when every compute unit still gets a tile (64-byte stages are fine there, several
+    // kernel elements share a stage), else 128 x 128 tiles with 128-byte stages.
+    const bool big_m = ((M + 255) / 256) * ((p->K + 127) / 128) >= 256;
+    const bool forced = plan_staging == 2;
     if (mfma_ok) {
         if (plan_kernel >= 2) {
             variant = plan_kernel - 2;
-            if (!try_patch(variant, plan_staging == 2) && plan_staging == 2) return ICV_ERR_UNSUPPORTED;
-        } else if (p->K <= 64 ? (try_patch(3, false) || try_patch(0, false))
-                              : (try_patch(wide, false) || try_patch(wide == 6 ? 7 : 1, false))) {
-            // a pixel-range plan fits
-        } else if (plan_staging == 2 && (p->K <= 64 ? (try_patch(3, true) || try_patch(0, true))
-                                                    : (try_patch(wide, true) || try_patch(1, true)))) {
+            if (!try_patch(variant, forced) && forced) return ICV_ERR_UNSUPPORTED;
+        } else if (p->K <= 64 ? (try_patch(3, forced) || try_patch(0, forced))
+                              : ((big_m && try_patch(6, true)) || try_patch(7, forced) || try_patch(1, forced))) {
             // a pixel-range plan fits
         } else if (plan_staging == 2) {
             return ICV_ERR_UNSUPPORTED;

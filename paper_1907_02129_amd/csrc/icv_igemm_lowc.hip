@@ -32,14 +32,17 @@ struct LowcArgs {
     int32_t direct;         // 1: `a` is the dense patch matrix [rows][KP] of the ablation path
 };
 
+// register type of one gathered piece (native vectors: arrays of them are kept in registers)
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 template <int U>
 struct Piece;
 template <>
-struct Piece<8> { using type = uint2; };
+struct Piece<8> { using type = u32x2_t; };
 template <>
-struct Piece<16> { using type = uint4; };
+struct Piece<16> { using type = u32x4_t; };
 template <>
-struct Piece<32> { using type = uint4; };   // moved as two 16-byte halves
+struct Piece<32> { using type = u32x4_t; };   // moved as two 16-byte halves
 
 // One workgroup (4 wavefronts) per 64 x 64 output tile; wavefront w owns the 32 x 32 block (w / 2, w % 2).
 template <bool I8, int U>
@@ -82,33 +85,49 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
     const int ksteps = g.KP / 32;
     out_t* out = (out_t*)g.out;
 
-    for (int64_t mt = blockIdx.x; mt < g.m_tiles; mt += gridDim.x) {
-        __syncthreads();      // previous tile's fragment reads are done (first pass: filter and padding are in)
-        // ---- gather: thread -> (row = tid % 64, taps tid / 64, +4, ...); the 64 entries of a tap are contiguous
-        if (g.direct) {
-            const uint8_t* src = g.a + mt * MR * (int64_t)g.KP;
-            const int vec_per_row = g.KP / 16;
-            for (int v = tid; v < MR * vec_per_row; v += 256) {
-                const int row = v / vec_per_row, c = v - row * vec_per_row;
-                *(uint4*)(ldsA + row * pitch + c * 16) = *(const uint4*)(src + (int64_t)row * g.KP + c * 16);
-            }
-        }
+    // Entries of a batch of kernel elements of row tile mt: thread -> row tid % 64, elements tap0, tap0 + 4, ...
+    // (the 64 entries of an element are contiguous).  A batch is 16 elements, or 8 of the 32-byte rows.
+    constexpr int NB = U == 32 ? 8 : 16;
+    constexpr int NV = U == 32 ? 2 * NB : NB;             // 16-byte (8-byte for U = 8) registers of a batch
+    using piece_t = typename Piece<U>::type;
+    const int n_taps = g.direct ? 0 : g.T;
+    uint8_t* dstrow = ldsA + (tid & 63) * pitch;
+    auto load_entries = [&](int64_t mt, int tap0, int32_t (&e)[NB]) __attribute__((always_inline)) {
         const int32_t* ent = g.ind + mt * ((int64_t)g.T * MR) + (tid & 63);
-        uint8_t* dstrow = ldsA + (tid & 63) * pitch;
-        for (int tap = tid >> 6; tap < (g.direct ? 0 : g.T); tap += 4) {
-            const int32_t e = ent[tap * MR];
-            const uint8_t* src = e < 0 ? g.zero_row : g.a + (uint32_t)e;
+#pragma unroll
+        for (int j = 0; j < NB; j++) {
+            const int tap = tap0 + 4 * j;
+            e[j] = tap < n_taps ? ent[tap * MR] : INT32_MIN;
+        }
+    };
+    // the rows a batch of entries names -> registers (elements past the last one read the zero row and are dropped)
+    auto gather = [&](const int32_t (&e)[NB], piece_t (&v)[NV]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < NB; j++) {
+            const uint8_t* src = e[j] < 0 ? g.zero_row : g.a + (uint32_t)e[j];
             if constexpr (U == 32) {
-                const uint4 lo = *(const uint4*)src, hi = *(const uint4*)(src + 16);
-                *(uint4*)(dstrow + tap * 32) = lo;
-                *(uint4*)(dstrow + tap * 32 + 16) = hi;
+                v[2 * j] = *(const piece_t*)src;
+                v[2 * j + 1] = *(const piece_t*)(src + 16);
             } else {
-                using piece_t = typename Piece<U>::type;
-                *(piece_t*)(dstrow + tap * U) = *(const piece_t*)src;
+                v[j] = *(const piece_t*)src;
             }
         }
-        __syncthreads();
-        // ---- multiply
+    };
+    auto to_lds = [&](int tap0, const piece_t (&v)[NV]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < NB; j++) {
+            const int tap = tap0 + 4 * j;
+            if (tap < n_taps) {
+                if constexpr (U == 32) {
+                    *(piece_t*)(dstrow + tap * 32) = v[2 * j];
+                    *(piece_t*)(dstrow + tap * 32 + 16) = v[2 * j + 1];
+                } else {
+                    *(piece_t*)(dstrow + tap * U) = v[j];
+                }
+            }
+        }
+    };
+    auto multiply_and_store = [&](int64_t mt) __attribute__((always_inline)) {
         acc_t acc;
 #pragma unroll
         for (int r = 0; r < 16; r++) acc[r] = 0;
@@ -125,7 +144,7 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
                                                               __builtin_bit_cast(bf16x8_t, bv), acc, 0, 0, 0);
             }
         }
-        // ---- store: register r of lane l holds row 8*(r/4) + 4*(l>>5) + (r&3), column l&31
+        // register r of lane l holds row 8*(r/4) + 4*(l>>5) + (r&3), column l&31
         const int64_t m_base = mt * MR + wm * 32 + 4 * lhalf;
         const int32_t col = nt * NR + wn * 32 + lrow;
 #pragma unroll
@@ -133,6 +152,55 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
             const int64_t row = m_base + 8 * (r >> 2) + (r & 3);
             if (row < g.M && col < g.K) out[row * g.out_stride + col] = acc[r];
         }
+    };
+
+    const int64_t G = gridDim.x;
+    if (!g.direct && n_taps <= 4 * NB) {
+        // One batch covers the tile (the usual case).  Software pipeline over my row tiles: while tile i is
+        // multiplied and stored, the rows of tile i+1 are already on their way to registers and the entries of
+        // tile i+2 are being read, so neither of the two dependent global loads is waited for in full.
+        int32_t e[NB];
+        piece_t v[NV];
+        int64_t mt = blockIdx.x;
+        if (mt < g.m_tiles) {
+            load_entries(mt, tid >> 6, e);
+            gather(e, v);
+            if (mt + G < g.m_tiles) load_entries(mt + G, tid >> 6, e);
+        }
+        for (; mt < g.m_tiles; mt += G) {
+            __syncthreads();      // previous tile's fragment reads are done (first pass: filter and padding are in)
+            to_lds(tid >> 6, v);
+            __syncthreads();
+            if (mt + G < g.m_tiles) {
+                gather(e, v);
+                if (mt + 2 * G < g.m_tiles) load_entries(mt + 2 * G, tid >> 6, e);
+            }
+            multiply_and_store(mt);
+        }
+        return;
+    }
+
+    for (int64_t mt = blockIdx.x; mt < g.m_tiles; mt += G) {
+        __syncthreads();      // previous tile's fragment reads are done (first pass: filter and padding are in)
+        if (g.direct) {
+            const uint8_t* src = g.a + mt * MR * (int64_t)g.KP;
+            const int vec_per_row = g.KP / 16;
+            for (int v = tid; v < MR * vec_per_row; v += 256) {
+                const int row = v / vec_per_row, c = v - row * vec_per_row;
+                *(uint4*)(ldsA + row * pitch + c * 16) = *(const uint4*)(src + (int64_t)row * g.KP + c * 16);
+            }
+        }
+        // gather, batch by batch: all entries of a batch are in registers before the rows they name are loaded,
+        // and all rows before anything goes to LDS, so the dependent loads of the elements overlap
+        for (int tap0 = tid >> 6; tap0 < n_taps; tap0 += 4 * NB) {
+            int32_t e[NB];
+            piece_t v[NV];
+            load_entries(mt, tap0, e);
+            gather(e, v);
+            to_lds(tap0, v);
+        }
+        __syncthreads();
+        multiply_and_store(mt);
     }
 }
 

@@ -41,6 +41,9 @@ struct PatchArgs {
     int32_t ent_copies;        // 1 KB pieces of one tile's entries
     int32_t cap_units;         // 1 KB pieces of one patch buffer (the zero row follows them)
     int32_t a_share, e_share;  // copies per producer per stage: next patch, next entries
+    int32_t nbuf;              // 2: the next patch and entries load while the current ones are used; 1: one buffer,
+                               //    loaded between patches (for two workgroups per compute unit, which cover
+                               //    each other's load bubbles)
     int32_t xcd_mode;
 };
 
@@ -69,9 +72,11 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
     const int G = g.G;
     const int slot_bytes = G * BS;                        // one stage: the filter tiles of G kernel elements
     const int patch_base = D * slot_bytes;
-    const int ent_base = patch_base + 2 * pbytes;
+    const bool single = g.nbuf == 1;
+    const uint32_t bufmask = single ? 0u : 1u;            // buffer of patch / tile number x: x & bufmask
+    const int ent_base = patch_base + g.nbuf * pbytes;
     const int ent_bytes = g.ent_copies * 1024;
-    const int hdr_base = ent_base + 2 * ent_bytes;        // [parity] int4 copy of the tile's range record
+    const int hdr_base = ent_base + g.nbuf * ent_bytes;   // [buffer] int4 copy of the tile's range record
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -192,7 +197,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
                 const uint32_t mt1 = next_tile ? m_tile_of(k + 1) : 0;
                 const int32_t* ent_src = g.ind + (int64_t)mt1 * T * MR;
                 const int4* rec_src = g.ranges + mt1;
-                const uint32_t ent_par = (uint32_t)((k + 1) & 1);
+                const uint32_t ent_par = (uint32_t)(k + 1) & bufmask;
                 int s = 0;
                 for (int cc = 0; cc < NCC; cc++) {
                     // the patch after this one: (k, cc+1) or (k+1, 0); its buffer was last read in the patch before this one
@@ -202,22 +207,32 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
                     const uint8_t* psrc = g.a + rng.x + (same_tile ? cc + 1 : 0) * KCB;
                     int units = next_patch ? (rng.y + RPB - 1) / RPB : 0;
                     if (units > g.cap_units) units = g.cap_units;
-                    const uint32_t pdst = lds_base + patch_base + (uint32_t)((k * NCC + cc + 1) & 1) * pbytes;
+                    const uint32_t pdst = lds_base + patch_base + ((uint32_t)(k * NCC + cc + 1) & bufmask) * pbytes;
                     for (int ts = 0; ts < TS; ts++, s++) {
-                        if (younger >= D - 2) wait_vmcnt<ALLOWED>();
-                        else wait_all_but_stages<1>(0);           // the last stages: nothing useful is in flight behind them
+                        // one buffer: a patch's first stage also waits for the bulk load issued just before it;
+                        // the last stages: nothing useful is in flight behind them
+                        if (younger >= D - 2 && !(single && ts == 0)) wait_vmcnt<ALLOWED>();
+                        else wait_vmcnt<0>();
                         --younger;
                         __builtin_amdgcn_s_barrier();     // hand this stage to the consumers; they are done with the one before
-                        if (ts <= a_last) {
+                        if (!single && ts <= a_last) {
                             int u = ts * g.a_share * NP + p;
                             for (int j = 0; j < g.a_share; j++, u += NP)
                                 if (u < units) copy_patch_piece(u, psrc, rng.y, pdst);
                         }
-                        if (next_tile && s <= e_last) {
+                        if (!single && next_tile && s <= e_last) {
                             int u = s * g.e_share * NP + p;
                             for (int j = 0; j < g.e_share; j++, u += NP) copy_ent_piece(u, ent_src, rec_src, ent_par);
                         }
                         issue_b(true);
+                    }
+                    if (single) {
+                        // the consumers are done with this patch (and, after a tile's last one, with its entries):
+                        // load the next ones into the same buffers
+                        __builtin_amdgcn_s_barrier();
+                        for (int u = p; u < units; u += NP) copy_patch_piece(u, psrc, rng.y, pdst);
+                        if (!same_tile && next_tile)
+                            for (int u = p; u <= g.ent_copies; u += NP) copy_ent_piece(u, ent_src, rec_src, ent_par);
                     }
                 }
                 rng_k = rng_k1;
@@ -250,7 +265,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
         // the zero row of both patch buffers (bytes that multiply as zero: 0x80 for centred uint8)
         {
             const uint32_t zv = I8 ? 0x80808080u : 0u;
-            for (int i = tid; i < 2 * 256; i += 64 * NC)
+            for (int i = tid; i < g.nbuf * 256; i += 64 * NC)
                 *(uint32_t*)(lds + patch_base + (i >> 8) * pbytes + zoff + (i & 255) * 4) = zv;
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
@@ -266,7 +281,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
 #pragma unroll
                     for (int r = 0; r < 16; r++) acc[i][j][r] = 0;
 
-            const int32_t* ent = (const int32_t*)(lds + ent_base + (int)(k & 1) * ent_bytes) + wm * MRW + lrow;
+            const int32_t* ent = (const int32_t*)(lds + ent_base + (int)((uint32_t)k & bufmask) * ent_bytes) + wm * MRW + lrow;
             // The rows of kernel element tap+1 are looked up while the MFMAs of tap run: the entries and the patch
             // are in LDS for the whole tile, only the filter tile behind the next barrier is not.
             int32_t first = 0;
@@ -280,12 +295,12 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
                 }
             };
             for (int cc = 0; cc < NCC; cc++) {
-                const uint32_t pb = patch_base + (uint32_t)((k * NCC + cc) & 1) * pbytes;
+                const uint32_t pb = patch_base + ((uint32_t)(k * NCC + cc) & bufmask) * pbytes;
                 for (int tap = 0, t_in_stage = 0; tap < T; tap++) {
                     if (t_in_stage == 0) __builtin_amdgcn_s_barrier();
                     if (cc == 0 && tap == 0) {
                         // first stage of the tile: its entries and range record only became visible with this barrier
-                        first = *(const int32_t*)(lds + hdr_base + (int)(k & 1) * 16);
+                        first = *(const int32_t*)(lds + hdr_base + (int)((uint32_t)k & bufmask) * 16);
                         int32_t e0[MB];
 #pragma unroll
                         for (int i = 0; i < MB; i++) e0[i] = ent[i * 32];
@@ -318,8 +333,9 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
 #pragma unroll
                             for (int j = 0; j < NB; j++) acc[i][j] = mfma32<I8>(af[i], bf[j], acc[i][j]);
                     }
-                    if (more) locate(en, tap + 1 < T ? pb : patch_base + (uint32_t)((k * NCC + cc + 1) & 1) * pbytes);
+                    if (more) locate(en, tap + 1 < T ? pb : patch_base + ((uint32_t)(k * NCC + cc + 1) & bufmask) * pbytes);
                 }
+                if (single) __builtin_amdgcn_s_barrier();     // done reading this patch: the producers may refill its buffer
             }
 
             // epilogue: accumulator register r of lane l holds row 8*(r/4) + 4*(l>>5) + (r&3), column l&31
@@ -356,10 +372,10 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
 }
 
 // ------------------------------------------------------------------ launch
-size_t patch_lds_bytes(int NR, int KCB, int ring, int cap_units, int ent_copies)
+size_t patch_lds_bytes(int NR, int KCB, int ring, int cap_units, int ent_copies, int nbuf)
 {
     // `ring` counts filter tiles (slots times kernel elements per slot)
-    return (size_t)ring * NR * KCB + (size_t)2 * (cap_units + 1) * 1024 + (size_t)2 * ent_copies * 1024 + 2048;
+    return (size_t)ring * NR * KCB + (size_t)nbuf * (cap_units + 1) * 1024 + (size_t)nbuf * ent_copies * 1024 + 2048;
 }
 
 template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB>
@@ -374,35 +390,41 @@ static int launch_one(const Geometry& g, PatchArgs a, hipStream_t s)
     constexpr int mfma_per_tap = (MR / WM / 32) * (NR / WN / 32) * (KCB / 32);
     int G = g.group;
     if (G == 0) {
-        G = 1;
-        while (G * mfma_per_tap < 16 && G < a.T) ++G;
+        for (G = 1; G < a.T && (a.T % G || G * mfma_per_tap < 16); ++G) {}
     }
     if (G > a.T) G = a.T;
+    // Two workgroups per compute unit (on request): each gets half the LDS and a single patch / entry buffer, and
+    // covers the other's load bubbles, start-up and epilogue.  Otherwise one workgroup with double buffers.
     // Ring depth.  A copy takes on the order of a microsecond from issue to completion under load, a stage far
     // less, and a stage's filter tiles must be issued ring - 1 stages ahead: as deep as fits (LDS, enough stages
     // left to spread the shares over), at most 8, at least 3 unless only fewer kernel elements per stage allow it.
+    const int G0 = G;
+    int per_cu = g.blocks_per_cu ? g.blocks_per_cu : (NR == 64 ? 2 : 1);
     int ring = 0;
-    for (; G >= 1; --G) {
-        if (a.T % G) continue;
-        const int TS = a.T / G, n_st = a.NCC * TS;
-        for (ring = g.ring ? g.ring : 8; ring >= 2; --ring) {
-            if (TS - ring + 2 < 1 || n_st - ring + 2 < 1) continue;
-            if (patch_lds_bytes(NR, KCB, ring * G, a.cap_units, a.ent_copies) > kLdsPerCu) continue;
-            break;
+    for (; per_cu >= 1; --per_cu) {
+        a.nbuf = per_cu == 2 ? 1 : 2;
+        const size_t budget = kLdsPerCu / per_cu;
+        for (G = G0; G >= 1; --G) {
+            if (a.T % G) continue;
+            const int TS = a.T / G, n_st = a.NCC * TS;
+            for (ring = g.ring ? g.ring : 8; ring >= 2; --ring) {
+                if (n_st - ring + 2 < 1 || (a.nbuf == 2 && TS - ring + 2 < 1)) continue;
+                if (patch_lds_bytes(NR, KCB, ring * G, a.cap_units, a.ent_copies, a.nbuf) > budget) continue;
+                break;
+            }
+            if (ring >= 3 || (ring == 2 && (G == 1 || g.group || g.ring == 2))) break;
         }
-        if (ring >= 3 || (ring == 2 && (G == 1 || g.group || g.ring == 2))) break;
+        if (G >= 1 && ring >= 2) break;
     }
-    if (G < 1 || ring < 2) return ICV_ERR_UNSUPPORTED;
+    if (per_cu < 1) return ICV_ERR_UNSUPPORTED;
     {
         const int TS = a.T / G, n_st = a.NCC * TS;
-        a.a_share = (a.cap_units + NP * (TS - ring + 2) - 1) / (NP * (TS - ring + 2));
-        a.e_share = (a.ent_copies + 1 + NP * (n_st - ring + 2) - 1) / (NP * (n_st - ring + 2));
+        a.a_share = a.nbuf == 2 ? (a.cap_units + NP * (TS - ring + 2) - 1) / (NP * (TS - ring + 2)) : 0;
+        a.e_share = a.nbuf == 2 ? (a.ent_copies + 1 + NP * (n_st - ring + 2) - 1) / (NP * (n_st - ring + 2)) : 0;
     }
     a.G = G;
     a.ring = ring;
-    const size_t lds_bytes = patch_lds_bytes(NR, KCB, ring * G, a.cap_units, a.ent_copies);
-    int per_cu = g.blocks_per_cu ? g.blocks_per_cu : 1;
-    if (per_cu == 2 && (lds_bytes > kLdsPerCu / 2 || threads > 512)) per_cu = 1;
+    const size_t lds_bytes = patch_lds_bytes(NR, KCB, ring * G, a.cap_units, a.ent_copies, a.nbuf);
 
     int64_t grid = (int64_t)device_cu_count() * per_cu;
     if (grid > a.total_tiles) grid = a.total_tiles;
@@ -438,13 +460,14 @@ static int launch_dtype(const Geometry& g, const PatchArgs& a, hipStream_t s)
         case 0: return launch_tile<I8, 128, 64, 2, 2>(g, a, s);
         case 1: return launch_tile<I8, 128, 128, 2, 2>(g, a, s);
         case 3: return launch_tile<I8, 256, 64, 4, 2>(g, a, s);
+        case 4: return launch_tile<I8, 256, 128, 2, 2>(g, a, s);
         case 6: return launch_tile<I8, 256, 128, 4, 2>(g, a, s);
         case 7: return launch_tile<I8, 128, 128, 4, 2>(g, a, s);
         default: return ICV_ERR_UNSUPPORTED;
     }
 }
 
-bool patch_variant_supported(int variant) { return variant == 0 || variant == 1 || variant == 3 || variant == 6 || variant == 7; }
+bool patch_variant_supported(int variant) { return variant == 0 || variant == 1 || variant == 3 || variant == 4 || variant == 6 || variant == 7; }
 
 int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                        const int32_t* ind, void* out, hipStream_t s)
@@ -466,7 +489,7 @@ int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* 
     a.stride_bytes = (int32_t)stride_bytes; a.stride_shift = shift;
     a.K = p->K; a.T = g.T; a.NCC = g.stages_per_tap; a.out_stride = g.out_stride;
     a.n_tiles = (int32_t)g.n_tiles;
-    a.ring = 0; a.G = 1; a.ent_copies = 0; a.cap_units = 0; a.a_share = 0; a.e_share = 0; a.xcd_mode = 0;
+    a.ring = 0; a.G = 1; a.ent_copies = 0; a.cap_units = 0; a.a_share = 0; a.e_share = 0; a.nbuf = 2; a.xcd_mode = 0;
     return p->dtype == ICV_U8I8 ? launch_dtype<true>(g, a, s) : launch_dtype<false>(g, a, s);
 }
 

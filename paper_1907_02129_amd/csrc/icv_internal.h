@@ -73,7 +73,7 @@ int launch_igemm_mfma(const icv_conv_params* p, const Geometry& g, const void* i
 int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                        const int32_t* ind, void* out, hipStream_t s);
 bool patch_variant_supported(int variant);
-size_t patch_lds_bytes(int NR, int KCB, int ring, int cap_units, int ent_copies);
+size_t patch_lds_bytes(int NR, int KCB, int ring, int cap_units, int ent_copies, int nbuf);
 int launch_igemm_lowc(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                       const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s);
 int launch_igemm_generic(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,

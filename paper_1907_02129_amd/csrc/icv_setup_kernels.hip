@@ -159,28 +159,38 @@ __global__ __launch_bounds__(256) void k_build_indirection(IndArgs a)
 
 // Range record of every row tile, for the plans that keep a tile's input pixels in LDS: the smallest valid
 // entry of the tile (a byte offset) and the number of pixel rows from there to the largest one.  A tile without
-// valid entries gets {0, 1}.  One wavefront per tile.
-__global__ __launch_bounds__(256) void k_tile_ranges(const int32_t* ind, int4* ranges, int64_t m_tiles, int32_t per_tile,
-                                                     int32_t stride_bytes)
+// valid entries gets {0, 1}.  One workgroup per tile.
+__global__ __launch_bounds__(256) void k_tile_ranges(const int32_t* ind, int4* ranges, int32_t per_tile, int32_t stride_bytes)
 {
-    const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (tile >= m_tiles) return;
-    const int lane = threadIdx.x & 63;
-    const int32_t* src = ind + tile * per_tile;
+    __shared__ int32_t part[8];
+    const int64_t tile = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int4* src = (const int4*)(ind + tile * per_tile);      // per_tile is a multiple of 32
     int32_t lo = INT32_MAX, hi = -1;
-    for (int32_t i = lane; i < per_tile; i += 64) {
-        const int32_t e = src[i];
-        if (e >= 0) {
-            lo = e < lo ? e : lo;
-            hi = e > hi ? e : hi;
-        }
+    for (int32_t i = threadIdx.x; i < per_tile / 4; i += 256) {
+        const int4 v = src[i];
+        const int32_t e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; j++)
+            if (e[j] >= 0) {
+                lo = e[j] < lo ? e[j] : lo;
+                hi = e[j] > hi ? e[j] : hi;
+            }
     }
     for (int d = 32; d >= 1; d >>= 1) {
         const int32_t lo2 = __shfl_xor(lo, d, 64), hi2 = __shfl_xor(hi, d, 64);
         lo = lo2 < lo ? lo2 : lo;
         hi = hi2 > hi ? hi2 : hi;
     }
-    if (lane == 0) ranges[tile] = hi < 0 ? make_int4(0, 1, 0, 0) : make_int4(lo, (hi - lo) / stride_bytes + 1, 0, 0);
+    if (lane == 0) { part[wave] = lo; part[4 + wave] = hi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; w++) {
+            lo = part[w] < lo ? part[w] : lo;
+            hi = part[4 + w] > hi ? part[4 + w] : hi;
+        }
+        ranges[tile] = hi < 0 ? make_int4(0, 1, 0, 0) : make_int4(lo, (hi - lo) / stride_bytes + 1, 0, 0);
+    }
 }
 
 int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_t* ind, hipStream_t s)
@@ -197,8 +207,8 @@ int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_
     ICV_HIP_CHECK(hipGetLastError());
     if (g.patch_rows) {
         int4* ranges = (int4*)(ind + a.m_padded * g.T);
-        hipLaunchKernelGGL(k_tile_ranges, dim3((unsigned)((g.m_tiles + 3) / 4)), dim3(256), 0, s, ind, ranges,
-                           g.m_tiles, g.MR * g.T, a.stride_bytes);
+        hipLaunchKernelGGL(k_tile_ranges, dim3((unsigned)g.m_tiles), dim3(256), 0, s, ind, ranges, g.MR * g.T,
+                           a.stride_bytes);
         ICV_HIP_CHECK(hipGetLastError());
     }
     return ICV_OK;

@@ -150,7 +150,7 @@ def test_small_shapes_match_oracle(s):
 N_PLANS = 15    # plan 1 = vector ALU, 2.. = tensor-core tile variants
 
 
-PATCH_VARIANTS = (0, 1, 3, 6, 7)     # tile variants the pixel-range kernel is instantiated for
+PATCH_VARIANTS = (0, 1, 3, 4, 6, 7)     # tile variants the pixel-range kernel is instantiated for
 
 
 @pytest.mark.parametrize("staging", [0, 1, 2])
@@ -207,9 +207,9 @@ def _patch_shapes():
 
 @pytest.mark.parametrize("s", _patch_shapes(), ids=lambda s: s.name)
 @pytest.mark.parametrize("knobs", [0, 2 << 4, 3 << 4, 5 << 4, 1 << 10, (2 << 4) | (1 << 10), 1 << 14, (3 << 14) | (1 << 10),
-                                   (5 << 14) | (2 << 4), 2 << 14],
+                                   (5 << 14) | (2 << 4), 2 << 14, 2 << 8, (2 << 8) | (1 << 10) | (2 << 4), (2 << 8) | (2 << 14)],
                          ids=["auto", "ring2", "ring3", "ring5", "kcb64", "ring2_kcb64", "group1", "group3_kcb64",
-                              "group5_ring2", "group2"])
+                              "group5_ring2", "group2", "two_per_cu", "two_per_cu_kcb64_ring2", "two_per_cu_group2"])
 def test_pixel_range_kernel_matches_oracle(s, knobs):
     plan = (2 << 12) | knobs
     stride = 64 if s.name == "p_stride" else 0
