@@ -375,7 +375,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
 size_t patch_lds_bytes(int NR, int KCB, int ring, int cap_units, int ent_copies, int nbuf)
 {
     // `ring` counts filter tiles (slots times kernel elements per slot)
-    return (size_t)ring * NR * KCB + (size_t)nbuf * (cap_units + 1) * 1024 + (size_t)nbuf * ent_copies * 1024 + 2048;
+    return (size_t)ring * NR * KCB + (size_t)nbuf * (cap_units + 1) * 1024 + (size_t)nbuf * ent_copies * 1024 + 1024;
 }
 
 template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB>
