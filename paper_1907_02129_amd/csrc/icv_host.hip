@@ -141,7 +141,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     int patch_rows = 0, patch_kcb = 0;
     // LDS-resident pixel range: worthwhile when several kernel elements re-read the rows, possible when the pixel
     // stride is a power of two (entry -> LDS row is a shift) and two patch buffers fit beside the other buffers
-    auto try_patch = [&](int v, bool kcb64_ok) {
+    auto try_patch = [&](int v) {
         if (plan_staging == 1 || T < 4 || !patch_variant_supported(v)) return false;
         if ((stride_bytes & (stride_bytes - 1)) != 0) return false;
         const TileVariant& tv = kTileVariants[v];
@@ -156,8 +156,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
             const bool fits_one = patch_lds_bytes(tv.NR, kcb, 2, (int)cap_units, ent_copies, 2) <= 160 * 1024;
             const bool fits_two = tv.NR == 64 && plan_per_cu != 1 &&
                                   patch_lds_bytes(tv.NR, kcb, 2, (int)cap_units, ent_copies, 1) <= 80 * 1024;
-            // 64-byte stages only pay off when two workgroups share a compute unit, or when asked for
-            if (fits_two || (fits_one && (kcb == 128 || kcb64_ok))) {
+            if (fits_two || fits_one) {
                 variant = v; patch_rows = (int)rows; patch_kcb = kcb;
                 return true;
             }
@@ -165,18 +164,16 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         return false;
     };
     // Measured on MI355X.  64-wide filters: 256 x 64 tiles, else 128 x 64, two workgroups per compute unit when the
-    // single-buffer layout fits half the LDS (with one workgroup and 64-byte stages the per-stage work is too small
-    // and gathering per kernel element is as fast).  Wider filters: 256 x 128 tiles
-    // of 64 x 64 wavefront blocks when every compute unit still gets a tile (64-byte stages are fine there, several
-    // kernel elements share a stage), else 128 x 128 tiles with 128-byte stages.
+    // single-buffer layout fits half the LDS.  Wider filters: 256 x 128 tiles of 64 x 64 wavefront blocks when every
+    // compute unit still gets a tile, else 128 x 128 tiles.  128-byte stages when the patch fits, else 64-byte ones
+    // (the launcher then puts several kernel elements into a stage).
     const bool big_m = ((M + 255) / 256) * ((p->K + 127) / 128) >= 256;
     const bool forced = plan_staging == 2;
     if (mfma_ok) {
         if (plan_kernel >= 2) {
             variant = plan_kernel - 2;
-            if (!try_patch(variant, forced) && forced) return ICV_ERR_UNSUPPORTED;
-        } else if (p->K <= 64 ? (try_patch(3, forced) || try_patch(0, forced))
-                              : ((big_m && try_patch(6, true)) || try_patch(7, forced) || try_patch(1, forced))) {
+            if (!try_patch(variant) && forced) return ICV_ERR_UNSUPPORTED;
+        } else if (p->K <= 64 ? (try_patch(3) || try_patch(0)) : ((big_m && try_patch(6)) || try_patch(7) || try_patch(1))) {
             // a pixel-range plan fits
         } else if (plan_staging == 2) {
             return ICV_ERR_UNSUPPORTED;

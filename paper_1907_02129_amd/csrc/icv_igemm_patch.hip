@@ -296,9 +296,11 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
             };
             for (int cc = 0; cc < NCC; cc++) {
                 const uint32_t pb = patch_base + ((uint32_t)(k * NCC + cc) & bufmask) * pbytes;
-                for (int tap = 0, t_in_stage = 0; tap < T; tap++) {
-                    if (t_in_stage == 0) __builtin_amdgcn_s_barrier();
-                    if (cc == 0 && tap == 0) {
+                const uint32_t pb_next = patch_base + ((uint32_t)(k * NCC + cc + 1) & bufmask) * pbytes;
+                const int32_t* entp = ent;                 // entries of the kernel element being multiplied
+                for (int ts = 0; ts < TS; ts++) {
+                    __builtin_amdgcn_s_barrier();
+                    if (cc == 0 && ts == 0) {
                         // first stage of the tile: its entries and range record only became visible with this barrier
                         first = *(const int32_t*)(lds + hdr_base + (int)((uint32_t)k & bufmask) * 16);
                         int32_t e0[MB];
@@ -306,34 +308,34 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
                         for (int i = 0; i < MB; i++) e0[i] = ent[i * 32];
                         locate(e0, pb);
                     }
-                    // entries of the next kernel element of this tile (the next chunk starts over at element 0)
-                    const bool more = tap + 1 < T || cc + 1 < NCC;
-                    const int ntap = tap + 1 < T ? tap + 1 : 0;
-                    int32_t en[MB];
-                    if (more) {
+                    const uint8_t* S = lds + slot * slot_bytes;
+                    slot = slot + 1 == D ? 0 : slot + 1;
+                    for (int t = 0; t < G; t++) {
+                        // entries of the next kernel element; after a chunk's last one the next chunk starts over at
+                        // element 0 in the other patch buffer (after the tile's last one the result is not used)
+                        const bool last = ts == TS - 1 && t == G - 1;
+                        const int32_t* entn = last ? ent : entp + MR;
+                        int32_t en[MB];
 #pragma unroll
-                        for (int i = 0; i < MB; i++) en[i] = ent[ntap * MR + i * 32];
+                        for (int i = 0; i < MB; i++) en[i] = entn[i * 32];
+#pragma unroll
+                        for (int ks = 0; ks < KSTEPS; ks++) {
+                            const uint32_t piece = (uint32_t)(2 * ks + lhalf) << 4;
+                            uint4 af[MB], bf[NB];
+#pragma unroll
+                            for (int i = 0; i < MB; i++) af[i] = *(const uint4*)(lds + abase[i] + (piece ^ aswz[i]));
+#pragma unroll
+                            for (int j = 0; j < NB; j++)
+                                bf[j] = *(const uint4*)(S + b_frag_base + j * 32 * KCB + (piece ^ (uint32_t)(bswz << 4)));
+#pragma unroll
+                            for (int i = 0; i < MB; i++)
+#pragma unroll
+                                for (int j = 0; j < NB; j++) acc[i][j] = mfma32<I8>(af[i], bf[j], acc[i][j]);
+                        }
+                        locate(en, last ? pb_next : pb);
+                        entp = entn;
+                        S += BS;
                     }
-                    const uint8_t* S = lds + slot * slot_bytes + t_in_stage * BS;
-                    if (++t_in_stage == G) {
-                        t_in_stage = 0;
-                        slot = slot + 1 == D ? 0 : slot + 1;
-                    }
-#pragma unroll
-                    for (int ks = 0; ks < KSTEPS; ks++) {
-                        const uint32_t piece = (uint32_t)(2 * ks + lhalf) << 4;
-                        uint4 af[MB], bf[NB];
-#pragma unroll
-                        for (int i = 0; i < MB; i++) af[i] = *(const uint4*)(lds + abase[i] + (piece ^ aswz[i]));
-#pragma unroll
-                        for (int j = 0; j < NB; j++)
-                            bf[j] = *(const uint4*)(S + b_frag_base + j * 32 * KCB + (piece ^ (uint32_t)(bswz << 4)));
-#pragma unroll
-                        for (int i = 0; i < MB; i++)
-#pragma unroll
-                            for (int j = 0; j < NB; j++) acc[i][j] = mfma32<I8>(af[i], bf[j], acc[i][j]);
-                    }
-                    if (more) locate(en, tap + 1 < T ? pb : patch_base + ((uint32_t)(k * NCC + cc + 1) & bufmask) * pbytes);
                 }
                 if (single) __builtin_amdgcn_s_barrier();     // done reading this patch: the producers may refill its buffer
             }
@@ -397,7 +399,7 @@ static int launch_one(const Geometry& g, PatchArgs a, hipStream_t s)
     // covers the other's load bubbles, start-up and epilogue.  Otherwise one workgroup with double buffers.
     // Ring depth.  A copy takes on the order of a microsecond from issue to completion under load, a stage far
     // less, and a stage's filter tiles must be issued ring - 1 stages ahead: as deep as fits (LDS, enough stages
-    // left to spread the shares over), at most 8, at least 3 unless only fewer kernel elements per stage allow it.
+    // left to spread the shares over), at most 8; when LDS is short, kernel elements per stage go before depth.
     const int G0 = G;
     int per_cu = g.blocks_per_cu ? g.blocks_per_cu : (NR == 64 ? 2 : 1);
     int ring = 0;
@@ -412,7 +414,7 @@ static int launch_one(const Geometry& g, PatchArgs a, hipStream_t s)
                 if (patch_lds_bytes(NR, KCB, ring * G, a.cap_units, a.ent_copies, a.nbuf) > budget) continue;
                 break;
             }
-            if (ring >= 3 || (ring == 2 && (G == 1 || g.group || g.ring == 2))) break;
+            if (ring >= 2) break;      // measured: more kernel elements per stage beat a deeper ring
         }
         if (G >= 1 && ring >= 2) break;
     }
