@@ -147,6 +147,38 @@ def test_small_shapes_match_oracle(s):
     check_against_oracle(s, buf.output.cpu().numpy(), x, w)
 
 
+def _random_tensor_core_shapes(n=36):
+    """Random shapes the tensor-core plans accept: channel counts that are multiples of 32 (bf16) / 64 (uint8),
+    any kernel size, stride, dilation and (asymmetric) padding, batches whose images end inside row tiles."""
+    rng = np.random.default_rng(2024)
+    out = []
+    while len(out) < n:
+        dtype = "u8i8" if len(out) % 3 == 2 else "bf16"
+        R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        DY, DX = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        SY, SX = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        PT, PL, PB, PR = (int(v) for v in rng.integers(0, 5, size=4))
+        Hin, Win = int(rng.integers(1, 34)), int(rng.integers(1, 40))
+        if Hin + PT + PB < DY * (R - 1) + 1 or Win + PL + PR < DX * (S - 1) + 1:
+            continue
+        C = int(rng.integers(1, 5)) * (64 if dtype == "u8i8" else 32)
+        K = int(rng.integers(1, 160))
+        out.append(ConvShape(f"r{len(out)}_{dtype}_{R}x{S}", int(rng.integers(1, 4)), Hin, Win, C, K, R, S, SY=SY, SX=SX,
+                             DY=DY, DX=DX, PT=PT, PL=PL, PB=PB, PR=PR, dtype=dtype,
+                             zero_point=128 if dtype == "u8i8" else 0, seed=1000 + len(out)))
+    return out
+
+
+@pytest.mark.parametrize("s", _random_tensor_core_shapes(), ids=lambda s: s.name)
+def test_random_tensor_core_shapes_match_oracle(s):
+    name = icv.plan_name(icv.make_params(s))
+    _say("conv", s.name, name, s)
+    assert name.startswith(("mfma_", "gemm_"))
+    x, w = make_tensors(s)
+    buf, xd = run_indirect(s, x, w)
+    check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+
+
 N_PLANS = 15    # plan 1 = vector ALU, 2.. = tensor-core tile variants
 
 
