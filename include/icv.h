@@ -77,8 +77,11 @@ ICV_API int icv_output_size(const icv_conv_params* p, int32_t* Hout, int32_t* Wo
 /*
  * Buffer sizes in bytes (0 when the parameters are invalid).
  *  indirection  : int32 entries, M rounded up to whole row tiles, times R*S (independent of C, section 1.1);
- *                 kernels that keep a tile's input pixels in LDS append one 16-byte record per row tile:
- *                 {smallest valid entry of the tile, pixels from there to the largest one, 0, 0}
+ *                 kernels that keep a tile's input pixels in LDS append one 16-byte record per row tile,
+ *                 {smallest valid entry of the tile, pixels from there to the largest one, 0, 0}, and then the
+ *                 entries once more, in the same order, as uint16 pixel numbers inside their tile's range
+ *                 ((entry - smallest entry) / pixel stride; the zero row is the number after the range's
+ *                 LDS buffer)
  *  packed filter: the [K][R][S][C] filter re-laid as the tiles the GEMM kernel reads, K padded to the tile
  *  zero row     : C elements (section 2.3's explicit zero vector), rounded up to 16 bytes
  *  im2col       : the [M][R*S*C] patch matrix of the ablation path

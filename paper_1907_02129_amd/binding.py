@@ -236,16 +236,20 @@ def run(buf: ConvBuffers, input_dev: torch.Tensor) -> torch.Tensor:
 
 
 def tile_ranges(buf: ConvBuffers):
-    """Range records appended to the buffer by the plans that keep pixel ranges in LDS: (tiles, 4) int32 or None."""
+    """What the pixel-range plans append to the entries: (range records (tiles, 4) int32, row numbers
+    (tiles, T, MR) uint16), or None for other plans."""
     p = buf.p
     T = p.R * p.S
     phys = buf.indirection.cpu().numpy()
-    mr = indirection_index(p, 0, 1) if T > 1 else None
-    if mr is None:
+    if T == 1:
         return None
+    mr = indirection_index(p, 0, 1)
     tiles = -(-buf.M // mr)
-    rest = phys[tiles * mr * T:]
-    return rest.reshape(tiles, 4) if len(rest) == tiles * 4 else None
+    n = tiles * mr * T
+    rest = phys[n:]
+    if len(rest) != tiles * 4 + n // 2:
+        return None
+    return rest[:tiles * 4].reshape(tiles, 4), rest[tiles * 4:].view(np.uint16).reshape(tiles, T, mr)
 
 
 def logical_indirection(buf: ConvBuffers) -> np.ndarray:

@@ -145,9 +145,9 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         if (plan_staging == 1 || T < 4 || !patch_variant_supported(v)) return false;
         if ((stride_bytes & (stride_bytes - 1)) != 0) return false;
         const TileVariant& tv = kTileVariants[v];
-        if ((int64_t)tv.MR * T * 4 > 24 * 1024) return false;
+        if ((int64_t)tv.MR * T * 2 > 24 * 1024) return false;     // two tiles' row numbers (uint16) stay in LDS
         const int64_t rows = tile_span_bound(p, Hout, Wout, tv.MR);
-        const int ent_copies = (int)((tv.MR * T * 4 + 1023) / 1024);
+        const int ent_copies = (int)((tv.MR * T * 2 + 1023) / 1024);
         const int kcb_max = (row_bytes % 128 == 0 && plan_kcb != 1) ? 128 : 64;
         for (int kcb = kcb_max; kcb >= 64; kcb -= 64) {
             const int64_t cap_units = (rows * kcb + 1023) / 1024;
@@ -184,7 +184,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
             else variant = 1;
         }
         // a workgroup keeps two tiles' worth of entries in LDS: 2 * MR*T int32 (plus padding)
-        if ((int64_t)kTileVariants[variant].MR * T * 4 > 24 * 1024) mfma_ok = false;
+        if (!patch_rows && (int64_t)kTileVariants[variant].MR * T * 4 > 24 * 1024) mfma_ok = false;
     }
     // very short rows (first-layer convolutions): the whole reduction of a tile is gathered at once
     const bool lowc_ok = p->dtype != ICV_F32 && plan_kernel == 0 &&
@@ -266,8 +266,9 @@ size_t icv_indirection_bytes(const icv_conv_params* p)
 {
     Geometry g;
     if (make_geometry(p, &g) != ICV_OK) return 0;
-    // entries, then (pixel-range plans) one 16-byte range record per row tile
-    return (size_t)g.m_tiles * g.MR * g.T * sizeof(int32_t) + (g.patch_rows ? (size_t)g.m_tiles * 16 : 0);
+    // entries, then (pixel-range plans) one 16-byte range record per row tile and the entries as 16-bit row numbers
+    const size_t n = (size_t)g.m_tiles * g.MR * g.T;
+    return n * sizeof(int32_t) + (g.patch_rows ? (size_t)g.m_tiles * 16 + n * sizeof(uint16_t) : 0);
 }
 
 size_t icv_packed_filter_bytes(const icv_conv_params* p)

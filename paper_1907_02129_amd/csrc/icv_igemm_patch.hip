@@ -3,11 +3,15 @@
 // Listing 3 reads, for every kernel element, the MR rows its indirection entries name.  For a convolution the
 // R*S entries of neighbouring output pixels name mostly the same input pixels (the second performance factor
 // section 3 lists: rows contributing to different output pixels are read from the same location); here that
-// re-use is made explicit.  The valid entries of a tile of MR consecutive output pixels all fall into one short range of consecutive input pixels -- the set-up phase records each tile's first
-// byte offset and pixel count next to the entries -- so that range ("patch") is copied to LDS once per tile and
-// channel chunk, and every kernel element then takes its MR rows from the patch by looking its entries up:
+// re-use is made explicit.  The valid entries of a tile of MR consecutive output pixels all fall into one short
+// range of consecutive input pixels, so that range ("patch") is copied to LDS once per tile and channel chunk,
+// and every kernel element then takes its MR rows from the patch.  The set-up phase prepares this next to the
+// int32 entries: per tile a range record {first byte offset, pixel count}, and the tile's entries rewritten as
+// 16-bit LDS row numbers,
 //
-//     LDS row of entry e  =  (e - first offset of the tile) / pixel stride      (zero row: one extra LDS row)
+//     row number of entry e  =  (e - first offset of the tile) / pixel stride      (zero row: the row after the patch)
+//
+// which is what the kernel reads: half the bytes of the entries, and no subtraction, shift or select per lookup.
 //
 // The loop nest is Listing 3's with the channel chunks outermost (chunk, kernel element, channels of the chunk);
 // only the filter tile of a stage (NR rows x KCB bytes, contiguous in the packed filter) still streams through a
@@ -29,7 +33,7 @@ namespace icv {
 struct PatchArgs {
     const uint8_t* a;          // input tensor
     const uint8_t* w;          // packed filter [n tile][channel chunk][tap][NR][KCB]
-    const int32_t* ind;        // [m tile][tap][MR]
+    const uint16_t* rows;      // [m tile][tap][MR]: the entries as LDS row numbers of the tile's patch (set-up makes them)
     const int4* ranges;        // per m tile: {first byte offset, pixel rows, 0, 0}
     void* out;
     int64_t M;
@@ -38,7 +42,7 @@ struct PatchArgs {
     int32_t K, T, NCC, out_stride, n_tiles;
     int32_t ring;              // filter slots in the ring
     int32_t G;                 // kernel elements per pipeline stage (divides T): one barrier per G filter tiles
-    int32_t ent_copies;        // 1 KB pieces of one tile's entries
+    int32_t ent_copies;        // 1 KB pieces of one tile's row numbers
     int32_t cap_units;         // 1 KB pieces of one patch buffer (the zero row follows them)
     int32_t a_share, e_share;  // copies per producer per stage: next patch, next entries
     int32_t nbuf;              // 2: the next patch and entries load while the current ones are used; 1: one buffer,
@@ -76,7 +80,6 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
     const uint32_t bufmask = single ? 0u : 1u;            // buffer of patch / tile number x: x & bufmask
     const int ent_base = patch_base + g.nbuf * pbytes;
     const int ent_bytes = g.ent_copies * 1024;
-    const int hdr_base = ent_base + g.nbuf * ent_bytes;   // [buffer] int4 copy of the tile's range record
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -112,14 +115,12 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
         const uint32_t off = (rc << g.stride_shift) + ((lchunk ^ ((r / P) % Q)) << 4);
         copy16_global_to_lds(src, off, dst + u * 1024);
     };
-    // piece u of a tile's entries; piece ent_copies is the tile's range record (16 bytes, one lane)
-    const int ent_chunks = T * MR / 4;
-    auto copy_ent_piece = [&](int u, const int32_t* src, const int4* rec, uint32_t par) {
+    // piece u of a tile's row numbers (T * MR uint16, contiguous)
+    const int ent_chunks = T * MR / 8;
+    auto copy_ent_piece = [&](int u, const uint16_t* src, uint32_t par) {
         if (u < g.ent_copies) {
             const int c = u * 64 + lane;
             if (c < ent_chunks) copy16_global_to_lds(src, (uint32_t)c * 16u, lds_base + ent_base + par * ent_bytes + u * 1024);
-        } else if (u == g.ent_copies) {
-            if (lane == 0) copy16_global_to_lds(rec, 0u, lds_base + hdr_base + par * 16);
         }
     };
 
@@ -129,7 +130,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
     if (count > 0) {
         constexpr int NW = NC + NP;
         const uint32_t mt = m_tile_of(0);
-        for (int u = wave; u <= g.ent_copies; u += NW) copy_ent_piece(u, g.ind + (int64_t)mt * T * MR, g.ranges + mt, 0);
+        for (int u = wave; u < g.ent_copies; u += NW) copy_ent_piece(u, g.rows + (int64_t)mt * T * MR, 0);
         // stages 0 .. D-2 are contiguous in the packed filter and in the ring (the host keeps D - 1 <= stages per tile)
         const uint8_t* w0 = g.w + (int64_t)n_tile_of(0) * n_st * slot_bytes;
         const int b_pieces = (D - 1) * slot_bytes / 1024;
@@ -195,8 +196,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
             for (int k = 0; k < count; k++) {
                 const bool next_tile = k + 1 < count;
                 const uint32_t mt1 = next_tile ? m_tile_of(k + 1) : 0;
-                const int32_t* ent_src = g.ind + (int64_t)mt1 * T * MR;
-                const int4* rec_src = g.ranges + mt1;
+                const uint16_t* ent_src = g.rows + (int64_t)mt1 * T * MR;
                 const uint32_t ent_par = (uint32_t)(k + 1) & bufmask;
                 int s = 0;
                 for (int cc = 0; cc < NCC; cc++) {
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
                         }
                         if (!single && next_tile && s <= e_last) {
                             int u = s * g.e_share * NP + p;
-                            for (int j = 0; j < g.e_share; j++, u += NP) copy_ent_piece(u, ent_src, rec_src, ent_par);
+                            for (int j = 0; j < g.e_share; j++, u += NP) copy_ent_piece(u, ent_src, ent_par);
                         }
                         issue_b(true);
                     }
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
                         __builtin_amdgcn_s_barrier();
                         for (int u = p; u < units; u += NP) copy_patch_piece(u, psrc, rng.y, pdst);
                         if (!same_tile && next_tile)
-                            for (int u = p; u <= g.ent_copies; u += NP) copy_ent_piece(u, ent_src, rec_src, ent_par);
+                            for (int u = p; u < g.ent_copies; u += NP) copy_ent_piece(u, ent_src, ent_par);
                     }
                 }
                 rng_k = rng_k1;
@@ -281,32 +281,29 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
 #pragma unroll
                     for (int r = 0; r < 16; r++) acc[i][j][r] = 0;
 
-            const int32_t* ent = (const int32_t*)(lds + ent_base + (int)((uint32_t)k & bufmask) * ent_bytes) + wm * MRW + lrow;
-            // The rows of kernel element tap+1 are looked up while the MFMAs of tap run: the entries and the patch
-            // are in LDS for the whole tile, only the filter tile behind the next barrier is not.
-            int32_t first = 0;
-            uint32_t abase[MB], aswz[MB];        // LDS row of the patch (or the zero row) per 32-row block, and its swizzle
-            auto locate = [&](const int32_t (&e)[MB], uint32_t pb) {
+            const uint16_t* ent = (const uint16_t*)(lds + ent_base + (int)((uint32_t)k & bufmask) * ent_bytes) + wm * MRW + lrow;
+            // The rows of kernel element tap+1 are looked up while the MFMAs of tap run: the row numbers and the
+            // patch are in LDS for the whole tile, only the filter tile behind the next barrier is not.
+            uint32_t abase[MB], aswz[MB];        // LDS address of the patch row per 32-row block, and the row's swizzle
+            auto locate = [&](const uint32_t (&r)[MB], uint32_t pb) {
 #pragma unroll
                 for (int i = 0; i < MB; i++) {
-                    const uint32_t r = (uint32_t)(e[i] - first) >> g.stride_shift;
-                    abase[i] = pb + (e[i] < 0 ? (uint32_t)zoff : r * KCB);
-                    aswz[i] = e[i] < 0 ? 0u : ((r / P) % Q) << 4;
+                    abase[i] = pb + r[i] * KCB;            // the zero row is simply the row after the patch
+                    aswz[i] = ((r[i] / P) % Q) << 4;
                 }
             };
             for (int cc = 0; cc < NCC; cc++) {
                 const uint32_t pb = patch_base + ((uint32_t)(k * NCC + cc) & bufmask) * pbytes;
                 const uint32_t pb_next = patch_base + ((uint32_t)(k * NCC + cc + 1) & bufmask) * pbytes;
-                const int32_t* entp = ent;                 // entries of the kernel element being multiplied
+                const uint16_t* entp = ent;                // row numbers of the kernel element being multiplied
                 for (int ts = 0; ts < TS; ts++) {
                     __builtin_amdgcn_s_barrier();
                     if (cc == 0 && ts == 0) {
-                        // first stage of the tile: its entries and range record only became visible with this barrier
-                        first = *(const int32_t*)(lds + hdr_base + (int)((uint32_t)k & bufmask) * 16);
-                        int32_t e0[MB];
+                        // first stage of the tile: its row numbers only became visible with this barrier
+                        uint32_t r0[MB];
 #pragma unroll
-                        for (int i = 0; i < MB; i++) e0[i] = ent[i * 32];
-                        locate(e0, pb);
+                        for (int i = 0; i < MB; i++) r0[i] = ent[i * 32];
+                        locate(r0, pb);
                     }
                     const uint8_t* S = lds + slot * slot_bytes;
                     slot = slot + 1 == D ? 0 : slot + 1;
@@ -314,8 +311,8 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
                         // entries of the next kernel element; after a chunk's last one the next chunk starts over at
                         // element 0 in the other patch buffer (after the tile's last one the result is not used)
                         const bool last = ts == TS - 1 && t == G - 1;
-                        const int32_t* entn = last ? ent : entp + MR;
-                        int32_t en[MB];
+                        const uint16_t* entn = last ? ent : entp + MR;
+                        uint32_t en[MB];
 #pragma unroll
                         for (int i = 0; i < MB; i++) en[i] = entn[i * 32];
 #pragma unroll
@@ -377,7 +374,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
 size_t patch_lds_bytes(int NR, int KCB, int ring, int cap_units, int ent_copies, int nbuf)
 {
     // `ring` counts filter tiles (slots times kernel elements per slot)
-    return (size_t)ring * NR * KCB + (size_t)nbuf * (cap_units + 1) * 1024 + (size_t)nbuf * ent_copies * 1024 + 1024;
+    return (size_t)ring * NR * KCB + (size_t)nbuf * (cap_units + 1) * 1024 + (size_t)nbuf * ent_copies * 1024;
 }
 
 template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB>
@@ -385,7 +382,7 @@ static int launch_one(const Geometry& g, PatchArgs a, hipStream_t s)
 {
     constexpr int threads = 64 * (WM * WN + NP);
     auto kern = k_igemm_patch<I8, MR, NR, WM, WN, NP, KCB>;
-    a.ent_copies = (int32_t)(((size_t)a.T * MR * 4 + 1023) / 1024);
+    a.ent_copies = (int32_t)(((size_t)a.T * MR * 2 + 1023) / 1024);
     a.cap_units = (int32_t)(((size_t)g.patch_rows * KCB + 1023) / 1024);
     // Kernel elements per stage: a stage should hold enough MFMAs (16 per consumer wavefront) to amortise its
     // barrier and the producers' bookkeeping; G divides T.
@@ -422,7 +419,7 @@ static int launch_one(const Geometry& g, PatchArgs a, hipStream_t s)
     {
         const int TS = a.T / G, n_st = a.NCC * TS;
         a.a_share = a.nbuf == 2 ? (a.cap_units + NP * (TS - ring + 2) - 1) / (NP * (TS - ring + 2)) : 0;
-        a.e_share = a.nbuf == 2 ? (a.ent_copies + 1 + NP * (n_st - ring + 2) - 1) / (NP * (n_st - ring + 2)) : 0;
+        a.e_share = a.nbuf == 2 ? (a.ent_copies + NP * (n_st - ring + 2) - 1) / (NP * (n_st - ring + 2)) : 0;
     }
     a.G = G;
     a.ring = ring;
@@ -483,8 +480,9 @@ int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* 
     PatchArgs a;
     a.a = (const uint8_t*)input;
     a.w = (const uint8_t*)packed;
-    a.ind = ind;
+    // the buffer: int32 entries, then the tiles' range records, then the entries as 16-bit patch row numbers
     a.ranges = (const int4*)(ind + g.m_tiles * g.MR * (int64_t)g.T);
+    a.rows = (const uint16_t*)(a.ranges + g.m_tiles);
     a.out = out;
     a.M = g.M;
     a.total_tiles = g.m_tiles * g.n_tiles;

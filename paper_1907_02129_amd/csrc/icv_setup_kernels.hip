@@ -193,6 +193,25 @@ __global__ __launch_bounds__(256) void k_tile_ranges(const int32_t* ind, int4* r
     }
 }
 
+// The entries of every row tile as LDS row numbers of the tile's pixel range: (entry - first offset) / pixel
+// stride, or `zero_row_number` (the row after the patch) for the zero row.  Same [tile][tap][row] order.
+__global__ __launch_bounds__(256) void k_patch_rows(const int32_t* ind, const int4* ranges, uint16_t* rows, int32_t per_tile,
+                                                    int32_t stride_bytes, uint32_t zero_row_number)
+{
+    const int64_t tile = blockIdx.x;
+    const int32_t first = ranges[tile].x;
+    const int4* src = (const int4*)(ind + tile * per_tile);      // per_tile is a multiple of 32
+    uint2* dst = (uint2*)(rows + tile * per_tile);
+    for (int32_t i = threadIdx.x; i < per_tile / 4; i += 256) {
+        const int4 v = src[i];
+        const int32_t e[4] = {v.x, v.y, v.z, v.w};
+        uint32_t r[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) r[j] = e[j] < 0 ? zero_row_number : (uint32_t)(e[j] - first) / (uint32_t)stride_bytes;
+        dst[i] = make_uint2(r[0] | (r[1] << 16), r[2] | (r[3] << 16));
+    }
+}
+
 int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_t* ind, hipStream_t s)
 {
     IndArgs a;
@@ -209,6 +228,12 @@ int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_
         int4* ranges = (int4*)(ind + a.m_padded * g.T);
         hipLaunchKernelGGL(k_tile_ranges, dim3((unsigned)g.m_tiles), dim3(256), 0, s, ind, ranges, g.MR * g.T,
                            a.stride_bytes);
+        ICV_HIP_CHECK(hipGetLastError());
+        // the zero row sits after the patch buffer, whose size is whole 1 KB pieces
+        const uint32_t zero_row_number = (uint32_t)((((int64_t)g.patch_rows * g.KCB + 1023) / 1024) * 1024 / g.KCB);
+        if (zero_row_number > 65535) return ICV_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(k_patch_rows, dim3((unsigned)g.m_tiles), dim3(256), 0, s, ind, ranges,
+                           (uint16_t*)(ranges + g.m_tiles), g.MR * g.T, a.stride_bytes, zero_row_number);
         ICV_HIP_CHECK(hipGetLastError());
     }
     return ICV_OK;

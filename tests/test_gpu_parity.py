@@ -268,20 +268,31 @@ def test_range_records_match_oracle_entries(s):
     x, w = make_tensors(s)
     buf = icv.prepare(s, icv.to_device(w), plan=2 << 12)
     torch.cuda.synchronize()
-    rec = icv.tile_ranges(buf)
-    assert rec is not None
+    got = icv.tile_ranges(buf)
+    assert got is not None
+    rec, rows = got
     mr = icv.indirection_index(buf.p, 0, 1)
     want = oracle.indirection(s)
+    M, T = want.shape
     esz = 1 if s.dtype == "u8i8" else 2
     cap = icv.tile_span_bound(buf.p, mr)
     for t in range(rec.shape[0]):
-        v = want[t * mr:(t + 1) * mr]
-        v = v[v >= 0]
+        blk = want[t * mr:(t + 1) * mr]                    # (rows of the tile, T) pixel index or -1
+        v = blk[blk >= 0]
+        first = int(v.min()) if v.size else 0
         if v.size:
-            assert rec[t, 0] == int(v.min()) * s.C * esz and rec[t, 1] == int(v.max() - v.min() + 1), t
+            assert rec[t, 0] == first * s.C * esz and rec[t, 1] == int(v.max()) - first + 1, t
         else:
             assert tuple(rec[t, :2]) == (0, 1), t
         assert rec[t, 1] <= cap and rec[t, 2] == 0 and rec[t, 3] == 0
+        # the entries as row numbers of the tile's range; the zero row (and rows past M) is one number beyond it
+        got_rows = rows[t, :, :blk.shape[0]].T.astype(np.int64)
+        zero = got_rows[blk < 0]
+        assert np.array_equal(got_rows[blk >= 0], blk[blk >= 0] - first)
+        if zero.size:
+            assert zero.min() == zero.max() >= cap
+        if blk.shape[0] < mr:
+            assert np.all(rows[t, :, blk.shape[0]:] >= cap)
 
 
 # ---------------------------------------------------------------- 1x1 stride-1: plain GEMM on the input tensor

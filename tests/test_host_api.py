@@ -46,7 +46,8 @@ def test_output_size_and_buffer_sizes(lib, name):
     nbytes = icv.indirection_bytes(p)
     if "patch" in icv.plan_name(p):                         # one 16-byte range record per row tile follows
         mr = icv.indirection_index(p, 0, 1)
-        nbytes -= 16 * -(-M // mr)
+        tiles = -(-M // mr)
+        nbytes -= 16 * tiles + 2 * tiles * mr * T           # ... and the entries again as uint16 row numbers
     assert nbytes % (4 * T) == 0 and nbytes >= 4 * M * T
     assert nbytes < 4 * (M + 256) * T                       # padding is less than one row tile
     # the entries do not depend on the number of input channels (section 1.1); with the row staging fixed,
@@ -189,7 +190,7 @@ def test_range_records_are_counted_in_the_buffer_size(lib):
     assert "patch" in icv.plan_name(patch) and "patch" not in icv.plan_name(streamed)
     mr = icv.indirection_index(patch, 0, 1)
     tiles = -(-(s.N * 56 * 56) // mr)
-    assert icv.indirection_bytes(patch) == tiles * mr * 9 * 4 + tiles * 16
+    assert icv.indirection_bytes(patch) == tiles * mr * 9 * 4 + tiles * 16 + tiles * mr * 9 * 2
     mr_s = icv.indirection_index(streamed, 0, 1)
     tiles_s = -(-(s.N * 56 * 56) // mr_s)
     assert icv.indirection_bytes(streamed) == tiles_s * mr_s * 9 * 4
