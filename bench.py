@@ -32,8 +32,8 @@ LLC_BYTES = 256 << 20
 # HBM traffic of the dominant kernel per launch, bytes, measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None until measured.
 MEASURED_TRAFFIC = {
-    # profiles/igemm_cfg2_hbm_traffic.md: FETCH 8472.3 KiB x 1.99975 + WRITE 25109.3 KiB x 1.0
-    "cfg2_3x3_c64": int((8472.3 * 1.99975 + 25109.3) * 1024),
+    # profiles/igemm_cfg2_hbm_traffic.md: FETCH 7586.5 KiB x 1.99975 + WRITE 25098.0 KiB x 1.0
+    "cfg2_3x3_c64": int((7586.5 * 1.99975 + 25098.0) * 1024),
 }
 
 
@@ -277,13 +277,20 @@ def main():
             row["indirection_build_ms"] = ts
             row["indirection_GBps"] = ib / (ts * 1e-3) / 1e9
             if sh.dtype != "f32":
-                ta, ti, tg = pr.time_ablation()
+                # the ablation and the per-element-gather variant run with the tile the library picks for them
+                # (plan bit 12: rows gathered per kernel element), not with the pixel-range plan's tile
+                pr_abl = Problem(icv, torch, sh, sets=min(len(pr.bufs), 12), plan=1 << 12)
+                if icv.plan_name(pr_abl.p) != icv.plan_name(pp):
+                    row["per_element_gather_kernel"] = icv.plan_name(pr_abl.p)
+                    row["per_element_gather_ms"] = pr_abl.time_quantiles(repeats=9, inner=10, warmup=3)[0]
+                ta, ti, tg = pr_abl.time_ablation()
                 row["im2col_gemm_ms"] = ta
                 row["im2col_ms"] = ti
                 row["gemm_only_ms"] = tg
                 row["speedup_vs_im2col_gemm"] = ta / m
             shapes[nm] = row
             del pr
+            pr_abl = None
             torch.cuda.empty_cache()
         out["shapes"] = shapes
 
