@@ -182,3 +182,48 @@ void oracle_indirect_gemm_f64(const oracle_shape *p, const int32_t *entries, con
             out[m * p->K + oc] = acc;
         }
 }
+
+/*
+ * Output stage applied to the accumulators of the convolution above (an extension beyond the paper, which only
+ * names a bias tensor among the operands of its benchmark protocol, section 3.1): per output channel oc
+ *
+ *   float  : y = acc + bias[oc];  relu: y = max(y, 0)                      (all in double)
+ *   int32  : y = acc + bias[oc];  relu: y = max(y, 0)
+ *   requantised uint8 (from the int32 result y):
+ *            q = clamp( rint( (float)y * scale ) + out_zero_point, 0, 255 )
+ *            with the product and the rounding (to nearest, ties to even) in IEEE single precision, the rounded
+ *            value limited to +-1e9 before it becomes an integer.
+ *
+ * bias may be NULL (no bias).  `count` elements, channel = index % K.
+ */
+void oracle_epilogue_f64(double *y, int64_t count, int32_t K, const double *bias, int32_t relu)
+{
+    for (int64_t i = 0; i < count; i++) {
+        double v = y[i] + (bias ? bias[i % K] : 0.0);
+        if (relu && v < 0.0) v = 0.0;
+        y[i] = v;
+    }
+}
+
+void oracle_epilogue_i32(int32_t *y, int64_t count, int32_t K, const int32_t *bias, int32_t relu)
+{
+    for (int64_t i = 0; i < count; i++) {
+        int32_t v = y[i] + (bias ? bias[i % K] : 0);
+        if (relu && v < 0) v = 0;
+        y[i] = v;
+    }
+}
+
+void oracle_requantise_u8(const int32_t *y, int64_t count, float scale, int32_t out_zero_point, uint8_t *q)
+{
+    for (int64_t i = 0; i < count; i++) {
+        volatile float prod = (float)y[i] * scale;      /* volatile: one correctly rounded single-precision product */
+        float r = __builtin_rintf(prod);
+        if (r > 1e9f) r = 1e9f;
+        if (r < -1e9f) r = -1e9f;
+        int64_t v = (int64_t)r + out_zero_point;
+        if (v < 0) v = 0;
+        if (v > 255) v = 255;
+        q[i] = (uint8_t)v;
+    }
+}

@@ -31,7 +31,8 @@ def _load():
         lib.oracle_out_extent.restype = ctypes.c_int32
         lib.oracle_out_extent.argtypes = [ctypes.c_int32] * 6
         for fn in (lib.oracle_conv2d_f64, lib.oracle_conv2d_u8i8, lib.oracle_indirection,
-                   lib.oracle_indirect_gemm_f64):
+                   lib.oracle_indirect_gemm_f64, lib.oracle_epilogue_f64, lib.oracle_epilogue_i32,
+                   lib.oracle_requantise_u8):
             fn.restype = None
         _lib = lib
     return _lib
@@ -137,3 +138,30 @@ def indirect_gemm(s, entries: np.ndarray, x, w) -> np.ndarray:
     lib.oracle_indirect_gemm_f64(ctypes.byref(cs), _ptr(entries), _ptr(x64), ctypes.c_int64(x64.shape[3]),
                                  _ptr(zero), _ptr(w64), _ptr(out))
     return out
+
+
+def epilogue(y: np.ndarray, bias=None, relu: bool = False) -> np.ndarray:
+    """Bias add and ReLU on the accumulators of conv2d / conv2d_u8i8 (float64 or int32, last axis = K)."""
+    lib = _load()
+    K = y.shape[-1]
+    out = np.ascontiguousarray(y).copy()
+    if out.dtype == np.int32:
+        b = None if bias is None else np.ascontiguousarray(bias, dtype=np.int32)
+        lib.oracle_epilogue_i32(_ptr(out), ctypes.c_int64(out.size), ctypes.c_int32(K),
+                                _ptr(b) if b is not None else None, ctypes.c_int32(int(relu)))
+    else:
+        assert out.dtype == np.float64
+        b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float64)
+        lib.oracle_epilogue_f64(_ptr(out), ctypes.c_int64(out.size), ctypes.c_int32(K),
+                                _ptr(b) if b is not None else None, ctypes.c_int32(int(relu)))
+    return out
+
+
+def requantise_u8(y: np.ndarray, scale: float, out_zero_point: int) -> np.ndarray:
+    """uint8 codes of an int32 result: clamp(rint(float32(y) * float32(scale)) + zero point, 0, 255)."""
+    lib = _load()
+    y = np.ascontiguousarray(y, dtype=np.int32)
+    q = np.empty(y.shape, dtype=np.uint8)
+    lib.oracle_requantise_u8(_ptr(y), ctypes.c_int64(y.size), ctypes.c_float(scale), ctypes.c_int32(out_zero_point),
+                             _ptr(q))
+    return q

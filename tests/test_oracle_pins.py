@@ -284,3 +284,47 @@ def test_padded_channel_layout_equals_three_channel_problem():
     s3 = s4.with_(C=3)
     got3 = oracle.conv2d(s3, x4, np.ascontiguousarray(w4[..., :3]))    # pixel stride 4, C = 3
     assert np.array_equal(got3, oracle.conv2d(s4, x4, w4))
+
+
+# ---------------------------------------------------------------- output stage (bias, ReLU, requantisation)
+def test_epilogue_bias_and_relu_against_their_definitions():
+    """Integer-valued data: the convolution is exact in double, so bias and ReLU can be checked exactly against
+    plain numpy broadcasting on the unfused result."""
+    rng = np.random.default_rng(11)
+    s = ConvShape("ep", 2, 7, 6, 5, 4, 3, 2, SY=2, SX=1, PT=1, PL=0, PB=1, PR=1, dtype="f32")
+    x = rng.integers(-4, 5, size=(s.N, s.Hin, s.Win, s.C)).astype(np.float32)
+    w = rng.integers(-3, 4, size=(s.K, s.R, s.S, s.C)).astype(np.float32)
+    bias = rng.integers(-20, 21, size=s.K).astype(np.float64)
+    y = oracle.conv2d(s, x, w)
+    assert np.array_equal(oracle.epilogue(y, bias, False), y + bias[None, None, None, :])
+    assert np.array_equal(oracle.epilogue(y, None, True), np.maximum(y, 0.0))
+    assert np.array_equal(oracle.epilogue(y, bias, True), np.maximum(y + bias, 0.0))
+    assert np.array_equal(oracle.epilogue(y), y)                                   # nothing asked: nothing changes
+    # a bias on one channel only moves that channel, by exactly the bias
+    one = np.zeros(s.K); one[2] = 7.0
+    d = oracle.epilogue(y, one) - y
+    assert np.all(d[..., 2] == 7.0) and not d[..., [0, 1, 3]].any()
+    # int32 accumulators
+    yi = rng.integers(-1000, 1000, size=(3, 4, 5, 6)).astype(np.int32)
+    bi = rng.integers(-500, 500, size=6).astype(np.int32)
+    assert np.array_equal(oracle.epilogue(yi, bi, True), np.maximum(yi + bi, 0))
+    assert oracle.epilogue(yi, bi, True).dtype == np.int32
+
+
+def test_requantisation_rounds_to_nearest_even_in_single_precision_and_saturates():
+    # hand cases: scale 0.5 makes every odd accumulator a tie
+    y = np.array([0, 1, 2, 3, 4, 5, -1, -2, -3, 600, -600, 2**31 - 1, -2**31], dtype=np.int32)
+    q = oracle.requantise_u8(y, 0.5, 10)
+    #            0   0.5->0  1  1.5->2  2  2.5->2  -0.5->-0  -1  -1.5->-2  300->sat  -300->sat  huge  -huge
+    assert q.tolist() == [10, 10, 11, 12, 12, 12, 10, 9, 8, 255, 0, 255, 0]
+    # against the same formula written with numpy's float32 arithmetic (rint is ties-to-even)
+    rng = np.random.default_rng(12)
+    y = rng.integers(-40_000_000, 40_000_000, size=20000).astype(np.int32)         # beyond 2^24: the conversion rounds
+    for scale, zp in ((1.7e-5, 128), (3.0517578125e-05, 0), (0.00390625, 255), (1.0, 3)):
+        r = np.rint(y.astype(np.float32) * np.float32(scale))
+        want = np.clip(np.clip(r, -1e9, 1e9).astype(np.int64) + zp, 0, 255).astype(np.uint8)
+        assert np.array_equal(oracle.requantise_u8(y, scale, zp), want)
+    # monotone in the accumulator, and the zero point is the code of accumulator 0
+    ys = np.sort(y)
+    qs = oracle.requantise_u8(ys, 1.7e-5, 128).astype(np.int32)
+    assert np.all(np.diff(qs) >= 0) and oracle.requantise_u8(np.zeros(1, np.int32), 1.7e-5, 128)[0] == 128
