@@ -69,6 +69,21 @@ class Problem:
         self.i = (self.i + 1) % len(self.bufs)
         self.icv.conv2d_nhwc(b.p, x, b.packed, b.indirection, b.zero_row, b.output)
 
+    def enable_fused(self):
+        """Switch step() to the fused output stage: bias + ReLU, bfloat16 (uint8 for the int8 path) output."""
+        icv, torch, s = self.icv, self.torch, self.s
+        quant = s.dtype == "u8i8"
+        self.bias = torch.zeros(s.K, dtype=torch.int32 if quant else torch.float32, device="cuda:0")
+        self.narrow = [torch.empty(b.output.shape, dtype=torch.uint8 if quant else torch.bfloat16, device="cuda:0")
+                       for b in self.bufs]
+        self.ep = icv.make_epilogue(self.bias, True, icv.ICV_OUT_U8 if quant else icv.ICV_OUT_BF16, 1e-4, 128)
+
+        def step():
+            b, x, o = self.bufs[self.i], self.xs[self.i], self.narrow[self.i]
+            self.i = (self.i + 1) % len(self.bufs)
+            icv.conv2d_nhwc_fused(b.p, x, b.packed, b.indirection, b.zero_row, self.ep, o)
+        self.step = step
+
     def time_steps(self, steps, warmup):
         """ms per step, HIP events on the launch stream around `steps` back-to-back launches."""
         torch = self.torch
@@ -272,6 +287,10 @@ def main():
                    "frac_of_peak": f / (m * 1e-3) / 1e12 / PEAK[sh.dtype],
                    "GBps_algorithmic": ab / (m * 1e-3) / 1e9,
                    "frac_of_hbm_peak": ab / (m * 1e-3) / 1e9 / HBM_PEAK_GBS}
+            if sh.dtype != "f32":
+                # the same launch with the fused output stage (bias + ReLU, 2- or 1-byte output elements)
+                pr.enable_fused()
+                row["fused_bias_relu_narrow_out_ms"] = pr.time_quantiles(repeats=9, inner=10, warmup=3)[0]
             ts = pr.time_setup(reps=10)
             ib = pr.bufs[0].M * sh.R * sh.S * 4
             row["indirection_build_ms"] = ts

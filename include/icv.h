@@ -140,6 +140,31 @@ ICV_API int icv_conv2d_nhwc(const icv_conv_params* p, const void* input, const v
                     const void* indirection, const void* zero_row, void* output, void* stream);
 
 /*
+ * The same convolution with an output stage fused into the kernel's epilogue.  Not part of the paper's
+ * algorithm (the paper only lists a bias tensor among the operands of its benchmark, section 3.1); it saves the
+ * extra pass over the output that a separate bias / activation / conversion kernel would cost.  Per output
+ * channel k:   y = acc + bias[k];   relu: y = max(y, 0);   then, by out_type,
+ *   ICV_OUT_ACC : y stored as float (ICV_F32, ICV_BF16) or int32 (ICV_U8I8), as icv_conv2d_nhwc does;
+ *   ICV_OUT_BF16: float paths only; y rounded to bfloat16 (nearest, ties to even), 2 bytes per element;
+ *   ICV_OUT_U8  : ICV_U8I8 only; q = clamp(rint((float)y * out_scale) + out_zero_point, 0, 255), the product and
+ *                 the rounding (ties to even) in single precision, 1 byte per element.
+ * `output` is [N][Hout][Wout] pixels of out_pixel_stride elements of that type.  bias: K floats, or K int32 for
+ * ICV_U8I8, device memory, 4-byte aligned, or NULL.  ICV_ERR_INVALID_ARG for an out_type that does not fit the
+ * dtype, a scale that is not positive and finite, a zero point outside 0..255.
+ */
+typedef enum icv_out_type { ICV_OUT_ACC = 0, ICV_OUT_BF16 = 1, ICV_OUT_U8 = 2 } icv_out_type;
+typedef struct icv_epilogue {
+    const void* bias;
+    int32_t relu;            /* 0 or 1 */
+    int32_t out_type;        /* icv_out_type */
+    float out_scale;         /* ICV_OUT_U8 */
+    int32_t out_zero_point;  /* ICV_OUT_U8 */
+} icv_epilogue;
+ICV_API int icv_conv2d_nhwc_fused(const icv_conv_params* p, const void* input, const void* packed_filter,
+                          const void* indirection, const void* zero_row, const icv_epilogue* epilogue,
+                          void* output, void* stream);
+
+/*
  * Ablation, not the method: the GEMM-based algorithm the paper compares against (section 1, "GEMM-based
  * algorithms"): write the [M][R*S*C] patch matrix (im2col), then a plain constant-stride GEMM with the same
  * tensor-core inner loop.  icv_im2col and icv_gemm_nhwc are its two halves; icv_conv2d_nhwc_im2col runs both.

@@ -27,7 +27,7 @@ DTYPES = {"f32": ICV_F32, "bf16": ICV_BF16, "u8i8": ICV_U8I8}
 EXPORTS = (
     "icv_output_size", "icv_indirection_bytes", "icv_packed_filter_bytes", "icv_zero_row_bytes",
     "icv_im2col_bytes", "icv_indirection_index", "icv_tile_span_bound", "icv_init_zero_row", "icv_pack_filter",
-    "icv_setup_indirection", "icv_conv2d_nhwc", "icv_im2col", "icv_gemm_nhwc", "icv_conv2d_nhwc_im2col",
+    "icv_setup_indirection", "icv_conv2d_nhwc", "icv_conv2d_nhwc_fused", "icv_im2col", "icv_gemm_nhwc", "icv_conv2d_nhwc_im2col",
     "icv_plan_name", "icv_status_string", "icv_last_hip_error",
 )
 
@@ -46,6 +46,13 @@ class icv_conv_params(ctypes.Structure):
         "N", "Hin", "Win", "C", "K", "R", "S", "SY", "SX", "DY", "DX", "PT", "PL", "PB", "PR",
         "in_pixel_stride", "out_pixel_stride", "dtype", "input_zero_point", "plan")]
 
+
+class icv_epilogue(ctypes.Structure):
+    _fields_ = [("bias", ctypes.c_void_p), ("relu", ctypes.c_int32), ("out_type", ctypes.c_int32),
+                ("out_scale", ctypes.c_float), ("out_zero_point", ctypes.c_int32)]
+
+
+ICV_OUT_ACC, ICV_OUT_BF16, ICV_OUT_U8 = 0, 1, 2
 
 _lib = None
 
@@ -73,6 +80,7 @@ def load_library(path: str | None = None):
         "icv_pack_filter": (ctypes.c_int, [P, vp, vp, vp]),
         "icv_setup_indirection": (ctypes.c_int, [P, vp, vp]),
         "icv_conv2d_nhwc": (ctypes.c_int, [P, vp, vp, vp, vp, vp, vp]),
+        "icv_conv2d_nhwc_fused": (ctypes.c_int, [P, vp, vp, vp, vp, ctypes.POINTER(icv_epilogue), vp, vp]),
         "icv_im2col": (ctypes.c_int, [P, vp, vp, vp]),
         "icv_gemm_nhwc": (ctypes.c_int, [P, vp, vp, vp, vp]),
         "icv_conv2d_nhwc_im2col": (ctypes.c_int, [P, vp, vp, vp, vp, vp]),
@@ -173,6 +181,18 @@ def setup_indirection(p, indirection, stream=None):
 def conv2d_nhwc(p, input, packed_filter, indirection, zero_row, output, stream=None):
     _check(load_library().icv_conv2d_nhwc(ctypes.byref(p), _ptr(input), _ptr(packed_filter), _ptr(indirection),
                                           _ptr(zero_row), _ptr(output), _stream(stream)), "icv_conv2d_nhwc")
+
+
+def conv2d_nhwc_fused(p, input, packed_filter, indirection, zero_row, epilogue, output, stream=None):
+    _check(load_library().icv_conv2d_nhwc_fused(ctypes.byref(p), _ptr(input), _ptr(packed_filter), _ptr(indirection),
+                                                _ptr(zero_row), ctypes.byref(epilogue), _ptr(output),
+                                                _stream(stream)), "icv_conv2d_nhwc_fused")
+
+
+def make_epilogue(bias=None, relu=False, out_type=ICV_OUT_ACC, out_scale=1.0, out_zero_point=0) -> icv_epilogue:
+    """icv_epilogue; `bias` is a device tensor (float32, or int32 for u8i8) that the caller keeps alive."""
+    return icv_epilogue(bias.data_ptr() if bias is not None else None, int(relu), out_type, out_scale,
+                        out_zero_point)
 
 
 def im2col(p, input, ws, stream=None):

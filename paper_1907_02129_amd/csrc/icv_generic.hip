@@ -18,6 +18,7 @@ struct GenericArgs {
     void* out;
     int64_t M;
     int32_t K, T, C, in_stride, out_stride, zero_point, a_direct;
+    EpilogueArgs ep;
 };
 
 __device__ inline float to_float(float v) { return v; }
@@ -50,7 +51,7 @@ __global__ __launch_bounds__(256) void k_igemm_generic(GenericArgs g)
             }
         }
     }
-    ((TAcc*)g.out)[m * g.out_stride + oc] = acc;
+    emit_output(g.out, m * g.out_stride + oc, acc + output_bias<TAcc>(g.ep, oc, g.K), g.ep);
 }
 
 int launch_igemm_generic(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
@@ -62,6 +63,7 @@ int launch_igemm_generic(const icv_conv_params* p, const Geometry& g, const void
     a.in_stride = g.in_stride; a.out_stride = g.out_stride;
     a.zero_point = p->dtype == ICV_U8I8 ? p->input_zero_point : 0;
     a.a_direct = a_direct ? 1 : 0;
+    a.ep = g.ep;
     const int64_t gx = (g.M + 3) / 4;
     if (gx > 0x7fffffffll || g.n_tiles > 65535) return ICV_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)gx, (unsigned)g.n_tiles);

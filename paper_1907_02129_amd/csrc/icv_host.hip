@@ -130,6 +130,8 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     g->cc_major = 0;
     g->group = plan_group;
     g->gemm_on_input = 0;
+    g->ep.bias = nullptr; g->ep.scale = 1.0f; g->ep.relu = 0; g->ep.out_kind = ICV_OUT_ACC; g->ep.out_zero_point = 0;
+    g->ep_plain = true;
 
     // ---- plan: which kernel, which tile
     const int64_t row_bytes = (int64_t)p->C * g->elem_bytes;        // bytes of one gathered A row
@@ -358,6 +360,34 @@ int icv_conv2d_nhwc(const icv_conv_params* p, const void* input, const void* pac
     if (!aligned16(input) || !aligned16(packed_filter) || !aligned16(indirection) || !aligned16(zero_row) ||
         !aligned16(output))
         return ICV_ERR_INVALID_ARG;
+    return conv_common(p, g, input, packed_filter, (const int32_t*)indirection, zero_row, output, false,
+                       (hipStream_t)stream);
+}
+
+int icv_conv2d_nhwc_fused(const icv_conv_params* p, const void* input, const void* packed_filter,
+                          const void* indirection, const void* zero_row, const icv_epilogue* ep, void* output,
+                          void* stream)
+{
+    Geometry g;
+    const int st = make_geometry(p, &g);
+    if (st != ICV_OK) return st;
+    if (!input || !packed_filter || !indirection || !zero_row || !output || !ep) return ICV_ERR_INVALID_ARG;
+    if (!aligned16(input) || !aligned16(packed_filter) || !aligned16(indirection) || !aligned16(zero_row) ||
+        !aligned16(output))
+        return ICV_ERR_INVALID_ARG;
+    if (ep->relu != 0 && ep->relu != 1) return ICV_ERR_INVALID_ARG;
+    if (ep->bias && ((uintptr_t)ep->bias & 3u)) return ICV_ERR_INVALID_ARG;
+    const bool quantised = p->dtype == ICV_U8I8;
+    if (ep->out_type != ICV_OUT_ACC && ep->out_type != (quantised ? ICV_OUT_U8 : ICV_OUT_BF16)) return ICV_ERR_INVALID_ARG;
+    if (ep->out_type == ICV_OUT_U8 &&
+        (!(ep->out_scale > 0.0f) || !(ep->out_scale < 3.0e38f) || ep->out_zero_point < 0 || ep->out_zero_point > 255))
+        return ICV_ERR_INVALID_ARG;
+    g.ep.bias = ep->bias;
+    g.ep.scale = ep->out_scale;
+    g.ep.relu = ep->relu;
+    g.ep.out_kind = ep->out_type;
+    g.ep.out_zero_point = ep->out_zero_point;
+    g.ep_plain = !ep->bias && !ep->relu && ep->out_type == ICV_OUT_ACC;
     return conv_common(p, g, input, packed_filter, (const int32_t*)indirection, zero_row, output, false,
                        (hipStream_t)stream);
 }

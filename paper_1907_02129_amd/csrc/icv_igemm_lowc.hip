@@ -10,15 +10,9 @@
 //
 // LDS rows are padded by 16 bytes (odd number of 16-byte units per row) instead of swizzled: ds_write_b64
 // from the gather and ds_read_b128 for the fragments are then both spread over the banks.
-#include <type_traits>
-#include "icv_internal.h"
+#include "icv_mfma_common.h"
 
 namespace icv {
-
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
-typedef int i32x4_t __attribute__((ext_vector_type(4)));
-typedef int i32x16_t __attribute__((ext_vector_type(16)));
 
 struct LowcArgs {
     const uint8_t* a;
@@ -30,6 +24,7 @@ struct LowcArgs {
     int32_t K, T, out_stride, n_tiles;
     int32_t KP;             // padded reduction bytes per row, multiple of 32
     int32_t direct;         // 1: `a` is the dense patch matrix [rows][KP] of the ablation path
+    EpilogueArgs ep;
 };
 
 // register type of one gathered piece (native vectors: arrays of them are kept in registers)
@@ -45,7 +40,7 @@ template <>
 struct Piece<32> { using type = u32x4_t; };   // moved as two 16-byte halves
 
 // One workgroup (4 wavefronts) per 64 x 64 output tile; wavefront w owns the 32 x 32 block (w / 2, w % 2).
-template <bool I8, int U>
+template <bool I8, int U, bool FUSED>
 __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
 {
     constexpr int MR = 64, NR = 64;
@@ -57,6 +52,7 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
     uint8_t* ldsA = lds + NR * pitch;       // [MR][pitch]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const EpilogueArgs ep = g.ep;
     const int nt = blockIdx.y;
 
     // ---- filter slice of this column tile -> LDS, once
@@ -83,7 +79,6 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
     const uint8_t* a_frag = ldsA + (wm * 32 + lrow) * pitch + lhalf * 16;
     const uint8_t* b_frag = ldsB + (wn * 32 + lrow) * pitch + lhalf * 16;
     const int ksteps = g.KP / 32;
-    out_t* out = (out_t*)g.out;
 
     // Entries of a batch of kernel elements of row tile mt: thread -> row tid % 64, elements tap0, tap0 + 4, ...
     // (the 64 entries of an element are contiguous).  A batch is 16 elements, or 8 of the 32-byte rows.
@@ -128,7 +123,8 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
         }
     };
     auto multiply_and_store = [&](int64_t mt) __attribute__((always_inline)) {
-        acc_t acc;
+        acc_t block[1][1];                   // one 32 x 32 block per wavefront
+        acc_t& acc = block[0][0];
 #pragma unroll
         for (int r = 0; r < 16; r++) acc[r] = 0;
         for (int ks = 0; ks < ksteps; ks++) {
@@ -147,11 +143,8 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
         // register r of lane l holds row 8*(r/4) + 4*(l>>5) + (r&3), column l&31
         const int64_t m_base = mt * MR + wm * 32 + 4 * lhalf;
         const int32_t col = nt * NR + wn * 32 + lrow;
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-            const int64_t row = m_base + 8 * (r >> 2) + (r & 3);
-            if (row < g.M && col < g.K) out[row * g.out_stride + col] = acc[r];
-        }
+        const bool whole = (mt + 1) * MR <= g.M && (nt + 1) * NR <= g.K;
+        store_tile<FUSED, I8, 1, 1>(g.out, block, g.M, g.K, g.out_stride, m_base, col, whole, ep);
     };
 
     const int64_t G = gridDim.x;
@@ -217,6 +210,7 @@ int launch_igemm_lowc(const icv_conv_params* p, const Geometry& g, const void* i
     a.K = p->K; a.T = g.T; a.out_stride = g.out_stride; a.n_tiles = (int32_t)g.n_tiles;
     a.KP = g.KCB;
     a.direct = a_direct ? 1 : 0;
+    a.ep = g.ep;
     const size_t lds_bytes = (size_t)128 * (a.KP + 16);
     if (lds_bytes > 80 * 1024 || g.n_tiles > 65535) return ICV_ERR_UNSUPPORTED;
     int cus = 256, dev = 0;
@@ -232,9 +226,10 @@ int launch_igemm_lowc(const icv_conv_params* p, const Geometry& g, const void* i
     const bool i8 = p->dtype == ICV_U8I8;
 #define ICV_LOWC_LAUNCH(I8, U)                                                                                  \
     do {                                                                                                        \
-        auto kern = k_igemm_lowc<I8, U>;                                                                        \
+        auto kern = g.ep_plain ? k_igemm_lowc<I8, U, false> : k_igemm_lowc<I8, U, true>;                        \
         if (lds_bytes > 64 * 1024) {                                                                            \
-            static bool raised = false;                                                                         \
+            static bool raised_both[2] = {false, false};     /* one flag per instantiation */                  \
+            bool& raised = raised_both[g.ep_plain ? 0 : 1];                                                     \
             if (!raised) {                                                                                      \
                 ICV_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                                   160 * 1024));                                                 \

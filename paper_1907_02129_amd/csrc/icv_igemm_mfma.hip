@@ -54,9 +54,10 @@ struct IgemmArgs {
     int32_t cc_major;          // packed filter stage order: 1 = chunk * T + tap, 0 = tap * stages_per_tap + chunk
     int32_t row_bytes;         // C * element size
     int64_t a_rows;            // rows of the dense matrix that may be read (later rows of a tile re-read the last one)
+    EpilogueArgs ep;           // output stage (read by the FUSED instantiations only)
 };
 
-template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool DIRECT>
+template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool DIRECT, bool FUSED>
 __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
 {
     constexpr int NC = WM * WN;              // consumer wavefronts; NP producer wavefronts follow them
@@ -226,7 +227,6 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
         const uint32_t a_frag_base = (wm * MRW + lrow) * KCB;
         const uint32_t b_frag_base = MR * KCB + (wn * NRW + lrow) * KCB;
         using out_t = typename std::conditional<I8, int32_t, float>::type;
-        out_t* out = (out_t*)g.out;
 
         __builtin_amdgcn_s_barrier();         // pairs with the producers' start-up barrier
         int slot = 0;
@@ -264,29 +264,8 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
             const int64_t mt = tile / g.n_tiles;
             const int64_t m_base = mt * MR + wm * MRW + 4 * lhalf;
             const int32_t n_base = nt * NR + wn * NRW + lrow;
-            const bool full = (mt + 1) * MR <= g.M && (nt + 1) * NR <= g.K;     // no row or column tail
-            if (full) {
-                out_t* o = out + m_base * g.out_stride + n_base;
-#pragma unroll
-                for (int i = 0; i < MB; i++)
-#pragma unroll
-                    for (int j = 0; j < NB; j++)
-#pragma unroll
-                        for (int r = 0; r < 16; r++)
-                            __builtin_nontemporal_store(acc[i][j][r], &o[(int64_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * g.out_stride + j * 32]);
-            } else {
-#pragma unroll
-                for (int i = 0; i < MB; i++)
-#pragma unroll
-                    for (int j = 0; j < NB; j++) {
-                        const int32_t col = n_base + j * 32;
-#pragma unroll
-                        for (int r = 0; r < 16; r++) {
-                            const int64_t row = m_base + i * 32 + 8 * (r >> 2) + (r & 3);
-                            if (row < g.M && col < g.K) out[row * g.out_stride + col] = acc[i][j][r];
-                        }
-                    }
-            }
+            const bool whole = (mt + 1) * MR <= g.M && (nt + 1) * NR <= g.K;     // no row or column tail
+            store_tile<FUSED, I8, MB, NB>(g.out, acc, g.M, g.K, g.out_stride, m_base, n_base, whole, g.ep);
         }
     }
 }
@@ -297,7 +276,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
 // wavefronts per SIMD cover each other's LDS and issue latencies.  The ring, the entry prefetch, the tile list
 // and the per-stage barrier are those of the split kernel above.  Output stores share the vmcnt counter with
 // the copies here: after a tile's epilogue the next waits also drain those stores (safe, merely conservative).
-template <bool I8, int MR, int NR, int WM, int WN, int KCB, bool DIRECT>
+template <bool I8, int MR, int NR, int WM, int WN, int KCB, bool DIRECT, bool FUSED>
 __global__ __launch_bounds__(64 * WM * WN) void k_igemm_uni(IgemmArgs g)
 {
     constexpr int NW = WM * WN;              // wavefronts; all copy and all multiply
@@ -428,7 +407,6 @@ __global__ __launch_bounds__(64 * WM * WN) void k_igemm_uni(IgemmArgs g)
     const int swz = (lrow / P) % Q;
     const uint32_t a_frag_base = (wm * MRW + lrow) * KCB;
     const uint32_t b_frag_base = MR * KCB + (wn * NRW + lrow) * KCB;
-    out_t* out = (out_t*)g.out;
 
     fetch_entries(0);
     fetch_entries(1);
@@ -476,41 +454,20 @@ __global__ __launch_bounds__(64 * WM * WN) void k_igemm_uni(IgemmArgs g)
         const int64_t mt = tile / g.n_tiles;
         const int64_t m_base = mt * MR + wm * MRW + 4 * lhalf;
         const int32_t n_base = nt * NR + wn * NRW + lrow;
-        const bool full = (mt + 1) * MR <= g.M && (nt + 1) * NR <= g.K;
-        if (full) {
-            out_t* o = out + m_base * g.out_stride + n_base;
-#pragma unroll
-            for (int i = 0; i < MB; i++)
-#pragma unroll
-                for (int j = 0; j < NB; j++)
-#pragma unroll
-                    for (int r = 0; r < 16; r++)
-                        __builtin_nontemporal_store(acc[i][j][r], &o[(int64_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * g.out_stride + j * 32]);
-        } else {
-#pragma unroll
-            for (int i = 0; i < MB; i++)
-#pragma unroll
-                for (int j = 0; j < NB; j++) {
-                    const int32_t col = n_base + j * 32;
-#pragma unroll
-                    for (int r = 0; r < 16; r++) {
-                        const int64_t row = m_base + i * 32 + 8 * (r >> 2) + (r & 3);
-                        if (row < g.M && col < g.K) out[row * g.out_stride + col] = acc[i][j][r];
-                    }
-                }
-        }
+        const bool whole = (mt + 1) * MR <= g.M && (nt + 1) * NR <= g.K;     // no row or column tail
+        store_tile<FUSED, I8, MB, NB>(g.out, acc, g.M, g.K, g.out_stride, m_base, n_base, whole, g.ep);
     }
     wait_vmcnt<0>();
 }
 
 // ------------------------------------------------------------------ launch
-template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool DIRECT>
+template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool DIRECT, bool FUSED>
 static int launch_one(const Geometry& g, IgemmArgs a, hipStream_t s)
 {
     constexpr int threads = 64 * (WM * WN + NP);
     void (*kern)(IgemmArgs);
-    if constexpr (NP == 0) kern = k_igemm_uni<I8, MR, NR, WM, WN, KCB, DIRECT>;
-    else kern = k_igemm_mfma<I8, MR, NR, WM, WN, NP, KCB, DIRECT>;
+    if constexpr (NP == 0) kern = k_igemm_uni<I8, MR, NR, WM, WN, KCB, DIRECT, FUSED>;
+    else kern = k_igemm_mfma<I8, MR, NR, WM, WN, NP, KCB, DIRECT, FUSED>;
     constexpr size_t slot = (size_t)(MR + NR) * KCB;
     a.ent_copies = DIRECT ? 0 : (int32_t)(((size_t)g.T * MR * 4 + 1023) / 1024);
     const size_t ent = (size_t)2 * a.ent_copies * 1024;
@@ -551,20 +508,28 @@ static int launch_one(const Geometry& g, IgemmArgs a, hipStream_t s)
     return ICV_OK;
 }
 
+// picks the DIRECT (dense A) and FUSED (output stage) instantiation
+template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB>
+static int launch_pick(const Geometry& g, const IgemmArgs& a, bool direct, hipStream_t s)
+{
+    if (direct)
+        return g.ep_plain ? launch_one<I8, MR, NR, WM, WN, NP, KCB, true, false>(g, a, s)
+                          : launch_one<I8, MR, NR, WM, WN, NP, KCB, true, true>(g, a, s);
+    return g.ep_plain ? launch_one<I8, MR, NR, WM, WN, NP, KCB, false, false>(g, a, s)
+                      : launch_one<I8, MR, NR, WM, WN, NP, KCB, false, true>(g, a, s);
+}
+
 template <bool I8, int MR, int NR, int WM, int WN, int NP>
 static int launch_tile(const Geometry& g, const IgemmArgs& a, bool direct, hipStream_t s)
 {
     if (g.KCB == 128) {
-        return direct ? launch_one<I8, MR, NR, WM, WN, NP, 128, true>(g, a, s)
-                      : launch_one<I8, MR, NR, WM, WN, NP, 128, false>(g, a, s);
+        return launch_pick<I8, MR, NR, WM, WN, NP, 128>(g, a, direct, s);
     }
     if constexpr (NR * 64 / 1024 >= (NP == 0 ? WM * WN : NP)) {      // a 64-byte stage of the B tile must still split over the copying wavefronts
-        return direct ? launch_one<I8, MR, NR, WM, WN, NP, 64, true>(g, a, s)
-                      : launch_one<I8, MR, NR, WM, WN, NP, 64, false>(g, a, s);
+        return launch_pick<I8, MR, NR, WM, WN, NP, 64>(g, a, direct, s);
     } else {
         if constexpr (NP == 0) return ICV_ERR_UNSUPPORTED;
-        else return direct ? launch_one<I8, MR, NR, WM, WN, 4, 64, true>(g, a, s)
-                           : launch_one<I8, MR, NR, WM, WN, 4, 64, false>(g, a, s);
+        else return launch_pick<I8, MR, NR, WM, WN, 4, 64>(g, a, direct, s);
     }
 }
 
@@ -614,6 +579,7 @@ int launch_igemm_mfma(const icv_conv_params* p, const Geometry& g, const void* i
     a.n_tiles = (int32_t)g.n_tiles;
     a.ring = 0; a.ent_copies = 0; a.xcd_mode = 0;
     a.cc_major = g.cc_major; a.row_bytes = p->C * g.elem_bytes;
+    a.ep = g.ep;
     return p->dtype == ICV_U8I8 ? launch_dtype<true>(g, a, a_direct, s) : launch_dtype<false>(g, a, a_direct, s);
 }
 

@@ -49,9 +49,10 @@ struct PatchArgs {
                                //    loaded between patches (for two workgroups per compute unit, which cover
                                //    each other's load bubbles)
     int32_t xcd_mode;
+    EpilogueArgs ep;           // output stage (read by the FUSED instantiations only)
 };
 
-template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB>
+template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool FUSED>
 __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g)
 {
     constexpr int NC = WM * WN;
@@ -260,7 +261,6 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
         const int lrow = lane & 31, lhalf = lane >> 5;
         const int bswz = (lrow / P) % Q;
         const uint32_t b_frag_base = (wn * NRW + lrow) * KCB;
-        out_t* out = (out_t*)g.out;
 
         // the zero row of both patch buffers (bytes that multiply as zero: 0x80 for centred uint8)
         {
@@ -343,29 +343,8 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
             const int64_t mt = tile / g.n_tiles;
             const int64_t m_base = mt * MR + wm * MRW + 4 * lhalf;
             const int32_t n_base = nt * NR + wn * NRW + lrow;
-            const bool full = (mt + 1) * MR <= g.M && (nt + 1) * NR <= g.K;
-            if (full) {
-                out_t* o = out + m_base * g.out_stride + n_base;
-#pragma unroll
-                for (int i = 0; i < MB; i++)
-#pragma unroll
-                    for (int j = 0; j < NB; j++)
-#pragma unroll
-                        for (int r = 0; r < 16; r++)
-                            __builtin_nontemporal_store(acc[i][j][r], &o[(int64_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * g.out_stride + j * 32]);
-            } else {
-#pragma unroll
-                for (int i = 0; i < MB; i++)
-#pragma unroll
-                    for (int j = 0; j < NB; j++) {
-                        const int32_t col = n_base + j * 32;
-#pragma unroll
-                        for (int r = 0; r < 16; r++) {
-                            const int64_t row = m_base + i * 32 + 8 * (r >> 2) + (r & 3);
-                            if (row < g.M && col < g.K) out[row * g.out_stride + col] = acc[i][j][r];
-                        }
-                    }
-            }
+            const bool whole = (mt + 1) * MR <= g.M && (nt + 1) * NR <= g.K;     // no row or column tail
+            store_tile<FUSED, I8, MB, NB>(g.out, acc, g.M, g.K, g.out_stride, m_base, n_base, whole, g.ep);
         }
     }
 }
@@ -377,11 +356,11 @@ size_t patch_lds_bytes(int NR, int KCB, int ring, int cap_units, int ent_copies,
     return (size_t)ring * NR * KCB + (size_t)nbuf * (cap_units + 1) * 1024 + (size_t)nbuf * ent_copies * 1024;
 }
 
-template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB>
+template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool FUSED>
 static int launch_one(const Geometry& g, PatchArgs a, hipStream_t s)
 {
     constexpr int threads = 64 * (WM * WN + NP);
-    auto kern = k_igemm_patch<I8, MR, NR, WM, WN, NP, KCB>;
+    auto kern = k_igemm_patch<I8, MR, NR, WM, WN, NP, KCB, FUSED>;
     a.ent_copies = (int32_t)(((size_t)a.T * MR * 2 + 1023) / 1024);
     a.cap_units = (int32_t)(((size_t)g.patch_rows * KCB + 1023) / 1024);
     // Kernel elements per stage: a stage should hold enough MFMAs (16 per consumer wavefront) to amortise its
@@ -448,8 +427,11 @@ static int launch_one(const Geometry& g, PatchArgs a, hipStream_t s)
 template <bool I8, int MR, int NR, int WM, int WN>
 static int launch_tile(const Geometry& g, const PatchArgs& a, hipStream_t s)
 {
-    if (g.KCB == 128) return launch_one<I8, MR, NR, WM, WN, 4, 128>(g, a, s);
-    return launch_one<I8, MR, NR, WM, WN, 4, 64>(g, a, s);
+    if (g.KCB == 128)
+        return g.ep_plain ? launch_one<I8, MR, NR, WM, WN, 4, 128, false>(g, a, s)
+                          : launch_one<I8, MR, NR, WM, WN, 4, 128, true>(g, a, s);
+    return g.ep_plain ? launch_one<I8, MR, NR, WM, WN, 4, 64, false>(g, a, s)
+                      : launch_one<I8, MR, NR, WM, WN, 4, 64, true>(g, a, s);
 }
 
 template <bool I8>
@@ -489,6 +471,7 @@ int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* 
     a.stride_bytes = (int32_t)stride_bytes; a.stride_shift = shift;
     a.K = p->K; a.T = g.T; a.NCC = g.stages_per_tap; a.out_stride = g.out_stride;
     a.n_tiles = (int32_t)g.n_tiles;
+    a.ep = g.ep;
     a.ring = 0; a.G = 1; a.ent_copies = 0; a.cap_units = 0; a.a_share = 0; a.e_share = 0; a.nbuf = 2; a.xcd_mode = 0;
     return p->dtype == ICV_U8I8 ? launch_dtype<true>(g, a, s) : launch_dtype<false>(g, a, s);
 }

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 #include "icv.h"
 
 namespace icv {
@@ -13,6 +14,47 @@ enum PlanKind : int32_t {
     PLAN_MFMA = 2,      // tensor-core indirect GEMM, C a multiple of the k-granule
     PLAN_MFMA_LOWC = 3  // tensor-core indirect GEMM for pixel rows of 8, 16 or 32 bytes (first-layer convolutions)
 };
+
+// Output stage of icv_conv2d_nhwc_fused, as the kernels see it (icv_epilogue with the bias pointer typed by use).
+struct EpilogueArgs {
+    const void* bias;          // K floats (float paths) or K int32 (u8i8); null: none
+    float scale;               // requantisation scale (uint8 output)
+    int32_t relu;              // 0 / 1
+    int32_t out_kind;          // ICV_OUT_ACC / ICV_OUT_BF16 / ICV_OUT_U8
+    int32_t out_zero_point;
+};
+
+// One output element through the output stage; `v` already includes the channel's bias (the caller reads it once
+// per column, see output_bias).  `idx` counts elements of the output type.  All branches are uniform.
+__device__ inline void emit_output(void* out, int64_t idx, float v, const EpilogueArgs& e)
+{
+    v = fmaxf(v, e.relu ? 0.0f : -__builtin_inff());
+    if (e.out_kind == ICV_OUT_BF16) ((__bf16*)out)[idx] = (__bf16)v;     // hardware conversion: nearest, ties to even
+    else ((float*)out)[idx] = v;
+}
+
+__device__ inline void emit_output(void* out, int64_t idx, int32_t v, const EpilogueArgs& e)
+{
+    const int32_t lo = e.relu ? 0 : INT32_MIN;
+    v = v > lo ? v : lo;
+    if (e.out_kind == ICV_OUT_U8) {
+        // clamp(rint((float)v * scale) + zero point, 0, 255); single-precision product, ties to even
+        float r = rintf(__fmul_rn((float)v, e.scale));
+        r = fminf(fmaxf(r, -1e9f), 1e9f);
+        int32_t q = (int32_t)r + e.out_zero_point;
+        q = q < 0 ? 0 : (q > 255 ? 255 : q);
+        ((uint8_t*)out)[idx] = (uint8_t)q;
+    } else {
+        ((int32_t*)out)[idx] = v;
+    }
+}
+
+// bias of output channel `col` in the accumulator's type (0 without a bias or past the last channel)
+template <typename T>
+__device__ inline T output_bias(const EpilogueArgs& e, int32_t col, int32_t K)
+{
+    return e.bias && col < K ? ((const T*)e.bias)[col] : (T)0;
+}
 
 // Geometry derived once per call from icv_conv_params (host side).
 struct Geometry {
@@ -38,6 +80,8 @@ struct Geometry {
     int32_t patch_rows;      // > 0: the tile's input pixel range is kept in LDS, this many pixel rows reserved
     int32_t cc_major;        // 1: stage = chunk * T + tap (channel chunks outermost), 0: stage = tap * chunks + chunk
     const char* name;
+    EpilogueArgs ep;         // output stage of this call (plain: no bias, no ReLU, accumulator type)
+    bool ep_plain;
 };
 
 // Upper bound on the number of consecutive input pixels spanned by the valid indirection entries of any

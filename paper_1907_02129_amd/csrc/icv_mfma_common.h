@@ -78,6 +78,81 @@ __device__ inline void wait_all_but_stages(int stages)
     }
 }
 
+// Epilogue of the tensor-core kernels: a wavefront's MB x NB accumulator blocks -> output[row][col].  Register r
+// of lane l of a block holds row 8*(r/4) + 4*(l>>5) + (r&3), column l&31; m_base / n_base are this lane's row
+// and column of register 0 of block (0, 0).
+//   FUSED = false: raw accumulators.  Whole tiles take unguarded non-temporal stores (the output is written once
+//                  and not read again by this kernel), tail tiles guarded ones.
+//   FUSED = true : the output stage of icv_conv2d_nhwc_fused (bias, ReLU, narrow output types).  A separate
+//                  instantiation: its per-element work would otherwise raise the plain kernel's register use
+//                  enough to lose the second co-resident workgroup.
+template <bool FUSED, int KIND, int MB, int NB, typename ACC, typename OUT_ACC>
+__device__ inline void store_tile_as(void* outp, const ACC (&acc)[MB][NB], int64_t M, int32_t K, int64_t out_stride,
+                                     int64_t m_base, int32_t n_base, bool whole, const EpilogueArgs& ep)
+{
+    using store_t = typename std::conditional<KIND == ICV_OUT_BF16, __bf16,
+                    typename std::conditional<KIND == ICV_OUT_U8, uint8_t, OUT_ACC>::type>::type;
+    store_t* out = (store_t*)outp;
+    const float scale = ep.scale;
+    const int32_t zero_point = ep.out_zero_point;
+    auto convert = [=](OUT_ACC v) -> store_t {
+        if constexpr (KIND == ICV_OUT_BF16) {
+            return (__bf16)v;                                  // hardware conversion: nearest, ties to even
+        } else if constexpr (KIND == ICV_OUT_U8) {
+            float f = rintf(__fmul_rn((float)v, scale));       // single-precision product, ties to even
+            f = fminf(fmaxf(f, -1e9f), 1e9f);
+            int32_t q = (int32_t)f + zero_point;
+            return (uint8_t)(q < 0 ? 0 : (q > 255 ? 255 : q));
+        } else {
+            return v;
+        }
+    };
+    OUT_ACC lo;
+    if constexpr (std::is_integral<OUT_ACC>::value) lo = FUSED && ep.relu ? 0 : INT32_MIN;
+    else lo = FUSED && ep.relu ? 0.0f : -__builtin_inff();
+#pragma unroll
+    for (int i = 0; i < MB; i++)
+#pragma unroll
+        for (int j = 0; j < NB; j++) {
+            const int32_t col = n_base + j * 32;
+            OUT_ACC bias = 0;
+            if constexpr (FUSED) bias = output_bias<OUT_ACC>(ep, col, K);
+            if (whole) {
+                store_t* o = out + (m_base + i * 32) * out_stride + col;
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    OUT_ACC v = (OUT_ACC)acc[i][j][r];
+                    if constexpr (FUSED) { v += bias; v = v > lo ? v : lo; }
+                    __builtin_nontemporal_store(convert(v), &o[(int64_t)(8 * (r >> 2) + (r & 3)) * out_stride]);
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const int64_t row = m_base + i * 32 + 8 * (r >> 2) + (r & 3);
+                    OUT_ACC v = (OUT_ACC)acc[i][j][r];
+                    if constexpr (FUSED) { v += bias; v = v > lo ? v : lo; }
+                    if (row < M && col < K) out[row * out_stride + col] = convert(v);
+                }
+            }
+        }
+}
+
+template <bool FUSED, bool I8, int MB, int NB, typename ACC>
+__device__ inline void store_tile(void* out, const ACC (&acc)[MB][NB], int64_t M, int32_t K, int64_t out_stride,
+                                  int64_t m_base, int32_t n_base, bool whole, const EpilogueArgs& ep)
+{
+    using out_acc_t = typename std::conditional<I8, int32_t, float>::type;
+    if constexpr (!FUSED) {
+        store_tile_as<false, ICV_OUT_ACC, MB, NB, ACC, out_acc_t>(out, acc, M, K, out_stride, m_base, n_base, whole, ep);
+    } else if constexpr (I8) {
+        if (ep.out_kind == ICV_OUT_U8) store_tile_as<true, ICV_OUT_U8, MB, NB, ACC, out_acc_t>(out, acc, M, K, out_stride, m_base, n_base, whole, ep);
+        else store_tile_as<true, ICV_OUT_ACC, MB, NB, ACC, out_acc_t>(out, acc, M, K, out_stride, m_base, n_base, whole, ep);
+    } else {
+        if (ep.out_kind == ICV_OUT_BF16) store_tile_as<true, ICV_OUT_BF16, MB, NB, ACC, out_acc_t>(out, acc, M, K, out_stride, m_base, n_base, whole, ep);
+        else store_tile_as<true, ICV_OUT_ACC, MB, NB, ACC, out_acc_t>(out, acc, M, K, out_stride, m_base, n_base, whole, ep);
+    }
+}
+
 // Tile list of a persistent workgroup.  Workgroups are dealt round-robin to the 8 XCDs (block b runs on
 // XCD b % 8).  In XCD mode XCD x owns the contiguous tile range [first, first + count) and its G/8 workgroups
 // take tiles first + i, first + i + G/8, ... ; otherwise block b takes b, b + G, ...

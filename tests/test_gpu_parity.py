@@ -326,6 +326,104 @@ def test_pointwise_convolution_runs_as_gemm_on_the_input(s, pixel_stride):
     assert icv.plan_name(icv.make_params(s.with_(PT=1, PB=1))).startswith("mfma_")
 
 
+# ---------------------------------------------------------------- fused output stage
+def _bf16_bits_to_f64(a: np.ndarray) -> np.ndarray:
+    return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+FUSED_SHAPES = [
+    CONFIGS["cfg1_tiny_f32"],                                                                     # vector-ALU kernel
+    ConvShape("f_patch", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=91),               # pixel-range kernel
+    ConvShape("f_gather", 2, 13, 17, 96, 40, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, seed=92),  # per-element gather
+    ConvShape("f_gemm", 3, 7, 11, 128, 72, 1, 1, seed=93),                                        # GEMM on the input
+    ConvShape("f_lowc", 2, 30, 26, 4, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=94),     # short rows
+    ConvShape("f_i8_patch", 2, 15, 15, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=95),
+    ConvShape("f_i8_lowc", 2, 11, 23, 8, 33, 5, 5, PT=2, PL=2, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=96),
+    ConvShape("f_i8_alu", 1, 9, 9, 64, 16, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=7, seed=97),
+]
+
+
+@pytest.mark.parametrize("s", FUSED_SHAPES, ids=lambda s: s.name)
+@pytest.mark.parametrize("relu", [False, True], ids=["linear", "relu"])
+@pytest.mark.parametrize("narrow", [False, True], ids=["acc_type", "narrow_out"])
+def test_fused_output_stage_matches_oracle(s, relu, narrow):
+    x, w = make_tensors(s)
+    rng = np.random.default_rng(s.seed + 500)
+    quant = s.dtype == "u8i8"
+    buf = icv.prepare(s, icv.to_device(w))
+    _say("fused", s.name, icv.plan_name(buf.p), "relu" if relu else "", "narrow" if narrow else "")
+    xd = icv.to_device(x)
+    if quant:
+        acc = oracle.conv2d_u8i8(s, x, w, s.zero_point, centred=True)
+        bias = rng.integers(-5000, 5000, size=s.K).astype(np.int32)
+        want = oracle.epilogue(acc, bias, relu)
+        scale, zp = float(np.float32(200.0 / np.abs(want).max())), 77
+        bias_dev = icv.to_device(bias)
+        ep = icv.make_epilogue(bias_dev, relu, icv.ICV_OUT_U8 if narrow else icv.ICV_OUT_ACC, scale, zp)
+        out = torch.full(want.shape, 201 if narrow else -7, dtype=torch.uint8 if narrow else torch.int32, device="cuda:0")
+        icv.conv2d_nhwc_fused(buf.p, xd, buf.packed, buf.indirection, buf.zero_row, ep, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        want = oracle.requantise_u8(want, scale, zp) if narrow else want
+        assert np.array_equal(got, want), f"{(got != want).sum()} of {want.size} differ"      # integer work: bit-exact
+        if narrow:
+            assert got.min() == (zp if relu else 0) and got.max() == 255                         # the codes use the range, both clamps
+        return
+    acc, mag = oracle.conv2d_abs(s, x, w)
+    bias = (rng.standard_normal(s.K) * np.abs(acc).max() * 0.3).astype(np.float32)
+    want = oracle.epilogue(acc, bias.astype(np.float64), relu)
+    if narrow and s.dtype == "f32":
+        narrow = False                    # bf16 output is offered for the float paths; exercise it on the fp32 kernel too
+        out_type = icv.ICV_OUT_BF16
+    else:
+        out_type = icv.ICV_OUT_BF16 if narrow else icv.ICV_OUT_ACC
+    bias_dev = icv.to_device(bias)
+    ep = icv.make_epilogue(bias_dev, relu, out_type)
+    out = torch.full(want.shape, 9.0, dtype=torch.bfloat16 if out_type == icv.ICV_OUT_BF16 else torch.float32, device="cuda:0")
+    icv.conv2d_nhwc_fused(buf.p, xd, buf.packed, buf.indirection, buf.zero_row, ep, out)
+    torch.cuda.synchronize()
+    if out_type == icv.ICV_OUT_BF16:
+        got = _bf16_bits_to_f64(out.view(torch.int16).cpu().numpy().view(np.uint16))
+    else:
+        got = out.cpu().numpy().astype(np.float64)
+    err = np.abs(got - want)
+    # a bfloat16 output carries 8 significant bits whatever the inputs were: the bf16 bar applies to it
+    assert err.max() / np.abs(want).max() <= (TOL["bf16"] if out_type == icv.ICV_OUT_BF16 else TOL[s.dtype])
+    # accumulation in fp32 (any order), the bias add, and for bf16 output one rounding to 8 significant bits
+    n_terms = s.R * s.S * s.C + 1
+    bound = 2.0 * n_terms * 2.0 ** -24 * (mag + np.abs(bias)[None, None, None, :]) + 1e-30
+    if out_type == icv.ICV_OUT_BF16:
+        bound = bound + 2.0 ** -8 * np.abs(want)
+    assert (err / bound).max() <= 1.0
+    if relu:
+        assert got.min() == 0.0 and (got == 0).mean() > 0.05
+
+
+def test_fused_with_nothing_to_fuse_equals_the_plain_call_and_rejects_bad_stages():
+    s = ConvShape("f_same", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=98)
+    x, w = make_tensors(s)
+    buf, xd = run_indirect(s, x, w)
+    plain = buf.output.clone()
+    buf.output.fill_(-7)
+    icv.conv2d_nhwc_fused(buf.p, xd, buf.packed, buf.indirection, buf.zero_row, icv.make_epilogue(), buf.output)
+    torch.cuda.synchronize()
+    assert torch.equal(plain, buf.output)
+    for bad in (icv.make_epilogue(out_type=icv.ICV_OUT_U8, out_scale=0.1),          # uint8 codes of a float path
+                icv.make_epilogue(out_type=7), icv.make_epilogue(relu=2)):
+        with pytest.raises(icv.IcvError) as e:
+            icv.conv2d_nhwc_fused(buf.p, xd, buf.packed, buf.indirection, buf.zero_row, bad, buf.output)
+        assert e.value.status == icv.ICV_ERR_INVALID_ARG
+    q = CONFIGS["cfg4_int8_3x3"].with_(N=1)
+    xq, wq = make_tensors(q)
+    bq, xqd = run_indirect(q, xq, wq)
+    for bad in (icv.make_epilogue(out_type=icv.ICV_OUT_BF16), icv.make_epilogue(out_type=icv.ICV_OUT_U8, out_scale=0.0),
+                icv.make_epilogue(out_type=icv.ICV_OUT_U8, out_scale=float("nan")),
+                icv.make_epilogue(out_type=icv.ICV_OUT_U8, out_scale=0.1, out_zero_point=256)):
+        with pytest.raises(icv.IcvError) as e:
+            icv.conv2d_nhwc_fused(bq.p, xqd, bq.packed, bq.indirection, bq.zero_row, bad, bq.output)
+        assert e.value.status == icv.ICV_ERR_INVALID_ARG
+
+
 # ---------------------------------------------------------------- properties of the path
 def test_output_pixel_stride_and_untouched_gaps():
     s = ConvShape("ostride", 2, 10, 12, 64, 40, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=61)

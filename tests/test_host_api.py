@@ -121,6 +121,14 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
     assert lib.icv_init_zero_row(ctypes.byref(p), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
     assert lib.icv_im2col(ctypes.byref(p), vp(0), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
     assert lib.icv_gemm_nhwc(ctypes.byref(p), vp(0), vp(0), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
+    ep = icv.make_epilogue()
+    a = vp(0x1000)
+    assert lib.icv_conv2d_nhwc_fused(ctypes.byref(p), a, a, a, a, None, a, vp(0)) == icv.ICV_ERR_INVALID_ARG
+    assert lib.icv_conv2d_nhwc_fused(ctypes.byref(p), a, a, a, a, ctypes.byref(ep), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
+    for bad in (icv.make_epilogue(out_type=icv.ICV_OUT_U8, out_scale=1.0), icv.make_epilogue(out_type=3),
+                icv.make_epilogue(relu=-1)):
+        # rejected by the host checks, before anything is launched on the (made-up) pointers
+        assert lib.icv_conv2d_nhwc_fused(ctypes.byref(p), a, a, a, a, ctypes.byref(bad), a, vp(0)) == icv.ICV_ERR_INVALID_ARG
 
 
 def test_status_strings(lib):
