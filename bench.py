@@ -166,7 +166,12 @@ def cpu_baseline(s, x, w, min_seconds=1.0, max_passes=20):
     dt = min(times)
     Hout, Wout = oracle.out_extent(s)
     cores = oracle.num_threads()
+    # one more pass on a single thread, the setting of the paper's own measurements (section 3.1)
+    oracle.set_num_threads(1)
+    dt1 = one_pass()
+    oracle.set_num_threads(cores)
     return {"value": flops(s, Hout, Wout) / dt / 1e12, "unit": "TFLOP/s", "cores": cores,
+            "single_thread": {"value": flops(s, Hout, Wout) / dt1 / 1e12, "seconds": round(dt1, 3)},
             "kind": "oracle", "seconds": round(dt, 3), "passes": len(times),
             "cpu_seconds_total": round(sum(times) * cores, 1),
             "sample": f"{len(times)} full passes of {s.name} (fp64 7-loop direct convolution, OpenMP over n,oy), "

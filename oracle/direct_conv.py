@@ -58,6 +58,14 @@ def num_threads() -> int:
     return len(os.sched_getaffinity(0))
 
 
+def set_num_threads(n: int) -> None:
+    """Fix the number of OpenMP threads of the following calls (the paper's protocol is single-threaded)."""
+    lib = _load()
+    fn = lib.omp_set_num_threads          # from the OpenMP runtime the oracle is linked against
+    fn.restype, fn.argtypes = None, [ctypes.c_int]
+    fn(int(n))
+
+
 def out_extent(s):
     """(Hout, Wout) by the floor formula stated in direct_conv.c."""
     lib = _load()
