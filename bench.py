@@ -312,6 +312,16 @@ def main():
                 row["im2col_ms"] = ti
                 row["gemm_only_ms"] = tg
                 row["speedup_vs_im2col_gemm"] = ta / m
+            if sh.N > 1 and not icv.plan_name(pp).startswith("gemm_"):
+                # batch-independent indirection buffer (plan bit 17): one image's entries serve the whole batch
+                pr_img = Problem(icv, torch, sh, sets=min(len(pr.bufs), 12), plan=1 << 17)
+                row["per_image_buffer"] = {
+                    "kernel": icv.plan_name(pr_img.p),
+                    "ms": pr_img.time_quantiles(repeats=9, inner=10, warmup=3)[0],
+                    "indirection_build_ms": pr_img.time_setup(reps=10),
+                    "indirection_bytes": icv.indirection_bytes(pr_img.p),
+                    "whole_batch_indirection_bytes": icv.indirection_bytes(pp)}
+                pr_img = None
             shapes[nm] = row
             del pr
             pr_abl = None

@@ -68,7 +68,15 @@ typedef struct icv_conv_params {
                                   bits 8-9 workgroups per CU (1, 2), bits 10-11 stage width (1: 64 B, 2: 128 B),
                                   bits 12-13 row staging (1: rows gathered per kernel element, 2: the tile's
                                   input pixel range kept in LDS), bits 14-16 kernel elements per pipeline
-                                  stage of the latter.  All set-up calls and the conv call of one problem must use the same value. */
+                                  stage of the latter.  All set-up calls and the conv call of one problem must use the same value.
+                                  Bit 17 (an option, not a tuning knob): batch-independent indirection buffer.  The
+                                  buffer then holds the entries of ONE image, offsets relative to that image's first
+                                  pixel, and row tiles never straddle two images; the kernels add n * Hin*Win*pixel
+                                  stride for image n.  Section 2.3 lists a change of batch size among the events that
+                                  force the buffer to be (partly) rebuilt; with this bit none is needed: a buffer
+                                  built with any N serves every N, and N plays no part in the choice of the tile
+                                  (the packed filter and zero row do not depend on N either).  The price is a
+                                  partial last tile per image instead of one per batch. */
 } icv_conv_params;
 
 /* Hout, Wout by the formula above.  ICV_ERR_INVALID_ARG when the parameters are not a valid problem. */
@@ -76,7 +84,8 @@ ICV_API int icv_output_size(const icv_conv_params* p, int32_t* Hout, int32_t* Wo
 
 /*
  * Buffer sizes in bytes (0 when the parameters are invalid).
- *  indirection  : int32 entries, M rounded up to whole row tiles, times R*S (independent of C, section 1.1);
+ *  indirection  : int32 entries, M rounded up to whole row tiles, times R*S (independent of C, section 1.1;
+ *                 with plan bit 17, M is Hout*Wout, one image's output pixels, whatever N is);
  *                 kernels that keep a tile's input pixels in LDS append one 16-byte record per row tile,
  *                 {smallest valid entry of the tile, pixels from there to the largest one, 0, 0}, and then the
  *                 entries once more, in the same order, as uint16 pixel numbers inside their tile's range
@@ -95,7 +104,8 @@ ICV_API size_t icv_im2col_bytes(const icv_conv_params* p);
  * Where the entry of output pixel m = (n*Hout + oy)*Wout + ox and kernel element tap = ky*S + kx sits in
  * the indirection buffer (index in int32 units).  The physical order is [row tile][tap][row in tile], the
  * order in which Listing 3 consumes pointers (*ppa++: all rows of the tile for one tap, then the next tap).
- * Rows past M in the last tile name the zero row.  Returns -1 on invalid arguments.
+ * Rows past M in the last tile name the zero row.  Returns -1 on invalid arguments.  With plan bit 17 the buffer
+ * describes one image: m = oy*Wout + ox < Hout*Wout.
  */
 ICV_API int64_t icv_indirection_index(const icv_conv_params* p, int64_t m, int32_t tap);
 
@@ -121,7 +131,8 @@ ICV_API int icv_pack_filter(const icv_conv_params* p, const void* filter_krsc, v
  * base, ((n*Hin + iy)*Win + ix) * in_pixel_stride * sizeof(element), or INT32_MIN for "the zero row": the
  * paper's row pointer minus the tensor's base pointer.  Storing offsets keeps the buffer valid when the
  * input or zero-row pointers change (the paper's fourth invalidation rule then never applies); it must be
- * rebuilt only when the shape, stride, dilation, padding, pixel stride, element type or batch size change.
+ * rebuilt only when the shape, stride, dilation, padding, pixel stride, element type or batch size change
+ * (with plan bit 17 not even for the batch size: N is not read).
  * The input tensor must be smaller than 2 GiB (ICV_ERR_INVALID_ARG otherwise).
  *   indirection: icv_indirection_bytes() device.
  */

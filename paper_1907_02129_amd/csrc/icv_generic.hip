@@ -18,6 +18,7 @@ struct GenericArgs {
     void* out;
     int64_t M;
     int32_t K, T, C, in_stride, out_stride, zero_point, a_direct;
+    int64_t img_rows, image_bytes;
     EpilogueArgs ep;
 };
 
@@ -32,7 +33,11 @@ __global__ __launch_bounds__(256) void k_igemm_generic(GenericArgs g)
     if (m >= g.M || oc >= g.K) return;
     const TIn* in = (const TIn*)g.a;
     const TW* w = (const TW*)g.w + (int64_t)oc * g.T * g.C;
-    const int32_t* ent = g.a_direct ? nullptr : g.ind + (m >> 6) * ((int64_t)g.T * 64) + (m & 63);
+    // batch-independent buffer: the entries are those of pixel m % img_rows, the rows they name lie in batch
+    // element m / img_rows (img_rows = M and image_bytes = 0 otherwise)
+    const int64_t img = m / g.img_rows, mi = m - img * g.img_rows;
+    const int32_t* ent = g.a_direct ? nullptr : g.ind + (mi >> 6) * ((int64_t)g.T * 64) + (mi & 63);
+    const uint8_t* a_img = (const uint8_t*)in + img * g.image_bytes;
     TAcc acc = 0;
     for (int32_t t = 0; t < g.T; t++) {
         const TIn* row;
@@ -40,7 +45,7 @@ __global__ __launch_bounds__(256) void k_igemm_generic(GenericArgs g)
             row = in + (m * g.T + t) * (int64_t)g.C;
         } else {
             const int32_t e = ent[(int64_t)t * 64];
-            row = e < 0 ? (const TIn*)g.zero_row : (const TIn*)((const uint8_t*)in + e);   // byte offset entry
+            row = e < 0 ? (const TIn*)g.zero_row : (const TIn*)(a_img + e);   // byte offset entry
         }
         const TW* wr = w + (int64_t)t * g.C;
         for (int32_t c = 0; c < g.C; c++) {
@@ -63,6 +68,8 @@ int launch_igemm_generic(const icv_conv_params* p, const Geometry& g, const void
     a.in_stride = g.in_stride; a.out_stride = g.out_stride;
     a.zero_point = p->dtype == ICV_U8I8 ? p->input_zero_point : 0;
     a.a_direct = a_direct ? 1 : 0;
+    a.img_rows = a_direct ? g.M : g.img_rows;
+    a.image_bytes = a_direct ? 0 : g.image_bytes;
     a.ep = g.ep;
     const int64_t gx = (g.M + 3) / 4;
     if (gx > 0x7fffffffll || g.n_tiles > 65535) return ICV_ERR_UNSUPPORTED;

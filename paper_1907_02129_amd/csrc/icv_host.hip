@@ -98,10 +98,11 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     // plan: bits 0-3 kernel (0 auto, 1 vector ALU, 2.. tile variant), bits 4-7 ring depth, bits 8-9 workgroups
     // per CU, bits 10-11 stage width (1: 64 bytes, 2: 128 bytes), bits 12-13 row staging (1: rows gathered per
     // kernel element, 2: the tile's pixel range kept in LDS), bits 14-16 kernel elements per pipeline stage of the
-    // pixel-range kernel; 0 in a field leaves the choice to the library
+    // pixel-range kernel, bit 17 batch-independent indirection buffer; 0 in a field leaves the choice to the library
     const int plan_kernel = p->plan & 15, plan_ring = (p->plan >> 4) & 15, plan_per_cu = (p->plan >> 8) & 3,
               plan_kcb = (p->plan >> 10) & 3, plan_staging = (p->plan >> 12) & 3, plan_group = (p->plan >> 14) & 7;
-    if (p->plan < 0 || p->plan >= (1 << 17) || plan_kernel > kNumTileVariants + 1 || plan_ring == 1 || plan_ring > 12 ||
+    const int plan_per_image = (p->plan >> 17) & 1;
+    if (p->plan < 0 || p->plan >= (1 << 18) || plan_kernel > kNumTileVariants + 1 || plan_ring == 1 || plan_ring > 12 ||
         plan_per_cu > 2 || plan_kcb > 2 || plan_staging > 2)
         return ICV_ERR_INVALID_ARG;
 
@@ -169,7 +170,9 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     // single-buffer layout fits half the LDS.  Wider filters: 256 x 128 tiles of 64 x 64 wavefront blocks when every
     // compute unit still gets a tile, else 128 x 128 tiles.  128-byte stages when the patch fits, else 64-byte ones
     // (the launcher then puts several kernel elements into a stage).
-    const bool big_m = ((M + 255) / 256) * ((p->K + 127) / 128) >= 256;
+    // A batch-independent buffer must have the same layout for every N, so its tile is chosen as for one image.
+    const int64_t m_choice = plan_per_image ? Hout * Wout : M;
+    const bool big_m = ((m_choice + 255) / 256) * ((p->K + 127) / 128) >= 256;
     const bool forced = plan_staging == 2;
     if (mfma_ok) {
         if (plan_kernel >= 2) {
@@ -241,12 +244,26 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         g->n_stages = g->T;
         g->name = kGenericNames[p->dtype];
     }
-    g->m_tiles = (M + g->MR - 1) / g->MR;
+    // the GEMM on the input tensor reads no entries, so it keeps the plain tiling
+    g->per_image = plan_per_image && !g->gemm_on_input ? 1 : 0;
+    g->img_rows = g->per_image ? Hout * Wout : M;
+    g->img_tiles = (g->img_rows + g->MR - 1) / g->MR;
+    g->image_bytes = g->per_image ? (int64_t)p->Hin * p->Win * stride_bytes : 0;
+    g->m_tiles = g->per_image ? g->img_tiles * p->N : g->img_tiles;
     g->n_tiles = (p->K + g->NR - 1) / g->NR;
     return ICV_OK;
 }
 
 static bool aligned16(const void* ptr) { return ((uintptr_t)ptr & 15u) == 0; }
+
+// The ablation path has no indirection buffer: it always tiles the whole batch.
+static int make_ablation_geometry(const icv_conv_params* p, Geometry* g)
+{
+    if (!p) return ICV_ERR_INVALID_ARG;
+    icv_conv_params q = *p;
+    q.plan &= ~(1 << 17);
+    return make_geometry(&q, g);
+}
 
 }  // namespace icv
 
@@ -269,8 +286,8 @@ size_t icv_indirection_bytes(const icv_conv_params* p)
     Geometry g;
     if (make_geometry(p, &g) != ICV_OK) return 0;
     // entries, then (pixel-range plans) one 16-byte range record per row tile and the entries as 16-bit row numbers
-    const size_t n = (size_t)g.m_tiles * g.MR * g.T;
-    return n * sizeof(int32_t) + (g.patch_rows ? (size_t)g.m_tiles * 16 + n * sizeof(uint16_t) : 0);
+    const size_t n = (size_t)g.img_tiles * g.MR * g.T;
+    return n * sizeof(int32_t) + (g.patch_rows ? (size_t)g.img_tiles * 16 + n * sizeof(uint16_t) : 0);
 }
 
 size_t icv_packed_filter_bytes(const icv_conv_params* p)
@@ -291,7 +308,7 @@ size_t icv_zero_row_bytes(const icv_conv_params* p)
 size_t icv_im2col_bytes(const icv_conv_params* p)
 {
     Geometry g;
-    if (make_geometry(p, &g) != ICV_OK) return 0;
+    if (make_ablation_geometry(p, &g) != ICV_OK) return 0;
     // rows padded to whole tiles so the GEMM kernel may read (and discard) the rows past M
     if (g.kind == PLAN_MFMA_LOWC) return (size_t)g.m_tiles * g.MR * g.KCB;
     return (size_t)g.m_tiles * g.MR * g.T * p->C * g.elem_bytes;
@@ -301,7 +318,7 @@ int64_t icv_indirection_index(const icv_conv_params* p, int64_t m, int32_t tap)
 {
     Geometry g;
     if (make_geometry(p, &g) != ICV_OK) return -1;
-    if (m < 0 || m >= g.m_tiles * g.MR || tap < 0 || tap >= g.T) return -1;
+    if (m < 0 || m >= g.img_tiles * g.MR || tap < 0 || tap >= g.T) return -1;
     return (m / g.MR) * ((int64_t)g.T * g.MR) + (int64_t)tap * g.MR + m % g.MR;
 }
 
@@ -395,7 +412,7 @@ int icv_conv2d_nhwc_fused(const icv_conv_params* p, const void* input, const voi
 int icv_im2col(const icv_conv_params* p, const void* input, void* im2col_ws, void* stream)
 {
     Geometry g;
-    const int st = make_geometry(p, &g);
+    const int st = make_ablation_geometry(p, &g);
     if (st != ICV_OK) return st;
     if (!input || !im2col_ws || !aligned16(input) || !aligned16(im2col_ws)) return ICV_ERR_INVALID_ARG;
     return launch_im2col(p, g, input, im2col_ws, (hipStream_t)stream);
@@ -405,7 +422,7 @@ int icv_gemm_nhwc(const icv_conv_params* p, const void* im2col_ws, const void* p
                   void* stream)
 {
     Geometry g;
-    const int st = make_geometry(p, &g);
+    const int st = make_ablation_geometry(p, &g);
     if (st != ICV_OK) return st;
     if (!im2col_ws || !packed_filter || !output) return ICV_ERR_INVALID_ARG;
     if (!aligned16(im2col_ws) || !aligned16(packed_filter) || !aligned16(output)) return ICV_ERR_INVALID_ARG;

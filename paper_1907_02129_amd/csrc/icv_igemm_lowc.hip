@@ -21,6 +21,8 @@ struct LowcArgs {
     const int32_t* ind;     // [m tile][tap][64], byte offsets, negative = zero row
     void* out;
     int64_t M, m_tiles;
+    int64_t image_bytes;    // batch-independent buffer: bytes between batch elements of the input (else 0)
+    uint32_t img_tiles, img_rows;  // row tiles and output pixels per image (one image = the whole batch otherwise)
     int32_t K, T, out_stride, n_tiles;
     int32_t KP;             // padded reduction bytes per row, multiple of 32
     int32_t direct;         // 1: `a` is the dense patch matrix [rows][KP] of the ablation path
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
     const int n_taps = g.direct ? 0 : g.T;
     uint8_t* dstrow = ldsA + (tid & 63) * pitch;
     auto load_entries = [&](int64_t mt, int tap0, int32_t (&e)[NB]) __attribute__((always_inline)) {
-        const int32_t* ent = g.ind + mt * ((int64_t)g.T * MR) + (tid & 63);
+        const int32_t* ent = g.ind + ((uint32_t)mt % g.img_tiles) * ((int64_t)g.T * MR) + (tid & 63);      // tile of the buffer
 #pragma unroll
         for (int j = 0; j < NB; j++) {
             const int tap = tap0 + 4 * j;
@@ -96,10 +98,11 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
         }
     };
     // the rows a batch of entries names -> registers (elements past the last one read the zero row and are dropped)
-    auto gather = [&](const int32_t (&e)[NB], piece_t (&v)[NV]) __attribute__((always_inline)) {
+    auto gather = [&](int64_t mt, const int32_t (&e)[NB], piece_t (&v)[NV]) __attribute__((always_inline)) {
+        const uint8_t* a_img = g.a + ((uint32_t)mt / g.img_tiles) * g.image_bytes;     // the batch element of this tile
 #pragma unroll
         for (int j = 0; j < NB; j++) {
-            const uint8_t* src = e[j] < 0 ? g.zero_row : g.a + (uint32_t)e[j];
+            const uint8_t* src = e[j] < 0 ? g.zero_row : a_img + (uint32_t)e[j];
             if constexpr (U == 32) {
                 v[2 * j] = *(const piece_t*)src;
                 v[2 * j + 1] = *(const piece_t*)(src + 16);
@@ -141,10 +144,12 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
             }
         }
         // register r of lane l holds row 8*(r/4) + 4*(l>>5) + (r&3), column l&31
-        const int64_t m_base = mt * MR + wm * 32 + 4 * lhalf;
+        const uint32_t img = (uint32_t)mt / g.img_tiles, t_img = (uint32_t)mt - img * g.img_tiles;      // batch element, row tile in it
+        const int64_t img_row0 = (int64_t)img * g.img_rows;
+        const int64_t m_base = img_row0 + (int64_t)t_img * MR + wm * 32 + 4 * lhalf;
         const int32_t col = nt * NR + wn * 32 + lrow;
-        const bool whole = (mt + 1) * MR <= g.M && (nt + 1) * NR <= g.K;
-        store_tile<FUSED, I8, 1, 1>(g.out, block, g.M, g.K, g.out_stride, m_base, col, whole, ep);
+        const bool whole = (t_img + 1) * MR <= g.img_rows && (nt + 1) * NR <= g.K;
+        store_tile<FUSED, I8, 1, 1>(g.out, block, img_row0 + g.img_rows, g.K, g.out_stride, m_base, col, whole, ep);
     };
 
     const int64_t G = gridDim.x;
@@ -157,7 +162,7 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
         int64_t mt = blockIdx.x;
         if (mt < g.m_tiles) {
             load_entries(mt, tid >> 6, e);
-            gather(e, v);
+            gather(mt, e, v);
             if (mt + G < g.m_tiles) load_entries(mt + G, tid >> 6, e);
         }
         for (; mt < g.m_tiles; mt += G) {
@@ -165,7 +170,7 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
             to_lds(tid >> 6, v);
             __syncthreads();
             if (mt + G < g.m_tiles) {
-                gather(e, v);
+                gather(mt + G, e, v);
                 if (mt + 2 * G < g.m_tiles) load_entries(mt + 2 * G, tid >> 6, e);
             }
             multiply_and_store(mt);
@@ -189,7 +194,7 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
             int32_t e[NB];
             piece_t v[NV];
             load_entries(mt, tap0, e);
-            gather(e, v);
+            gather(mt, e, v);
             to_lds(tap0, v);
         }
         __syncthreads();
@@ -207,6 +212,9 @@ int launch_igemm_lowc(const icv_conv_params* p, const Geometry& g, const void* i
     a.ind = ind;
     a.out = out;
     a.M = g.M; a.m_tiles = g.m_tiles;
+    a.image_bytes = a_direct ? 0 : g.image_bytes;
+    a.img_tiles = (uint32_t)(a_direct ? g.m_tiles : g.img_tiles);
+    a.img_rows = (uint32_t)(a_direct ? g.M : g.img_rows);
     a.K = p->K; a.T = g.T; a.out_stride = g.out_stride; a.n_tiles = (int32_t)g.n_tiles;
     a.KP = g.KCB;
     a.direct = a_direct ? 1 : 0;

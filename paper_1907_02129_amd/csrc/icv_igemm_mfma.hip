@@ -54,6 +54,8 @@ struct IgemmArgs {
     int32_t cc_major;          // packed filter stage order: 1 = chunk * T + tap, 0 = tap * stages_per_tap + chunk
     int32_t row_bytes;         // C * element size
     int64_t a_rows;            // rows of the dense matrix that may be read (later rows of a tile re-read the last one)
+    int64_t image_bytes;       // batch-independent buffer: bytes between batch elements of the input (else 0)
+    uint32_t img_tiles, img_rows;  // row tiles and output pixels per image (one image = the whole batch otherwise)
     EpilogueArgs ep;           // output stage (read by the FUSED instantiations only)
 };
 
@@ -117,7 +119,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
         auto fetch_entries = [&](int64_t k) {
             if constexpr (!DIRECT) {
                 if (k >= tl.count) return;
-                const int64_t mt = (tl.first + k * tl.step) / g.n_tiles;
+                const int64_t mt = (uint32_t)((tl.first + k * tl.step) / g.n_tiles) % g.img_tiles;      // tile of the buffer
                 const int32_t* src = g.ind + mt * ((int64_t)g.T * MR);
                 const uint32_t dst = lds_base + ent_base + (uint32_t)(k & 1) * ent_bytes;
                 const int n_chunks = g.T * MR / 4;
@@ -139,11 +141,13 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
         int islot = 0;           // ring slot the next issued stage goes to
         const uint8_t* wstage = nullptr;     // B tile of the stage to prepare, before the per-lane offset
         const uint8_t* adirect[A_VEC];       // DIRECT: the rows of the tile this lane copies from (clamped to the matrix)
+        const uint8_t* a_img = g.a;          // the batch element the tile's entries refer to
         auto enter_tile = [&]() {
             if (ik >= tl.count) return;
             const int64_t tile = tl.first + ik * tl.step;
             const int32_t nt = (int32_t)(tile % g.n_tiles);
             const int64_t mt = tile / g.n_tiles;
+            a_img = g.a + ((uint32_t)mt / g.img_tiles) * g.image_bytes;
             wstage = g.w + ((int64_t)nt * n_stages) * (NR * KCB);
             if constexpr (DIRECT) {
 #pragma unroll
@@ -174,7 +178,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
 #pragma unroll
                 for (int j = 0; j < A_VEC; j++) e[j] = ent[a_row[j]];     // all LDS reads first
                 const uint8_t* zsrc = g.zero_row + icc * KCB;
-                const uint8_t* abase = g.a + icc * KCB;
+                const uint8_t* abase = a_img + icc * KCB;
 #pragma unroll
                 for (int j = 0; j < A_VEC; j++) {
                     // entry = byte offset of the pixel row from the input base; negative = the zero row
@@ -262,10 +266,12 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
             const int64_t tile = tl.first + k * tl.step;
             const int32_t nt = (int32_t)(tile % g.n_tiles);
             const int64_t mt = tile / g.n_tiles;
-            const int64_t m_base = mt * MR + wm * MRW + 4 * lhalf;
+            const uint32_t img = (uint32_t)mt / g.img_tiles, t_img = (uint32_t)mt - img * g.img_tiles;      // batch element, row tile in it
+            const int64_t img_row0 = (int64_t)img * g.img_rows;
+            const int64_t m_base = img_row0 + (int64_t)t_img * MR + wm * MRW + 4 * lhalf;
             const int32_t n_base = nt * NR + wn * NRW + lrow;
-            const bool whole = (mt + 1) * MR <= g.M && (nt + 1) * NR <= g.K;     // no row or column tail
-            store_tile<FUSED, I8, MB, NB>(g.out, acc, g.M, g.K, g.out_stride, m_base, n_base, whole, g.ep);
+            const bool whole = (t_img + 1) * MR <= g.img_rows && (nt + 1) * NR <= g.K;     // no row or column tail
+            store_tile<FUSED, I8, MB, NB>(g.out, acc, img_row0 + g.img_rows, g.K, g.out_stride, m_base, n_base, whole, g.ep);
         }
     }
 }
@@ -326,7 +332,7 @@ __global__ __launch_bounds__(64 * WM * WN) void k_igemm_uni(IgemmArgs g)
     auto fetch_entries = [&](int64_t k) {
         if constexpr (!DIRECT) {
             if (k >= tl.count) return;
-            const int64_t mt = (tl.first + k * tl.step) / g.n_tiles;
+            const int64_t mt = (uint32_t)((tl.first + k * tl.step) / g.n_tiles) % g.img_tiles;          // tile of the buffer
             const int32_t* src = g.ind + mt * ((int64_t)g.T * MR);
             const uint32_t dst = lds_base + ent_base + (uint32_t)(k & 1) * ent_bytes;
             const int n_chunks = g.T * MR / 4;
@@ -340,11 +346,13 @@ __global__ __launch_bounds__(64 * WM * WN) void k_igemm_uni(IgemmArgs g)
     int is = 0, itap = 0, icc = 0, islot = 0;
     const uint8_t* wstage = nullptr;
     const uint8_t* adirect[A_VEC];
+    const uint8_t* a_img = g.a;
     auto enter_tile = [&]() {
         if (ik >= tl.count) return;
         const int64_t tile = tl.first + ik * tl.step;
         const int32_t nt = (int32_t)(tile % g.n_tiles);
         const int64_t mt = tile / g.n_tiles;
+        a_img = g.a + ((uint32_t)mt / g.img_tiles) * g.image_bytes;
         wstage = g.w + ((int64_t)nt * n_stages) * (NR * KCB);
         if constexpr (DIRECT) {
 #pragma unroll
@@ -373,7 +381,7 @@ __global__ __launch_bounds__(64 * WM * WN) void k_igemm_uni(IgemmArgs g)
 #pragma unroll
             for (int j = 0; j < A_VEC; j++) e[j] = ent[a_row[j]];
             const uint8_t* zsrc = g.zero_row + icc * KCB;
-            const uint8_t* abase = g.a + icc * KCB;
+            const uint8_t* abase = a_img + icc * KCB;
 #pragma unroll
             for (int j = 0; j < A_VEC; j++) {
                 const uint32_t off = (uint32_t)(e[j] + a_lane_off[j]);
@@ -452,10 +460,12 @@ __global__ __launch_bounds__(64 * WM * WN) void k_igemm_uni(IgemmArgs g)
         const int64_t tile = tl.first + k * tl.step;
         const int32_t nt = (int32_t)(tile % g.n_tiles);
         const int64_t mt = tile / g.n_tiles;
-        const int64_t m_base = mt * MR + wm * MRW + 4 * lhalf;
+        const uint32_t img = (uint32_t)mt / g.img_tiles, t_img = (uint32_t)mt - img * g.img_tiles;
+        const int64_t img_row0 = (int64_t)img * g.img_rows;
+        const int64_t m_base = img_row0 + (int64_t)t_img * MR + wm * MRW + 4 * lhalf;
         const int32_t n_base = nt * NR + wn * NRW + lrow;
-        const bool whole = (mt + 1) * MR <= g.M && (nt + 1) * NR <= g.K;     // no row or column tail
-        store_tile<FUSED, I8, MB, NB>(g.out, acc, g.M, g.K, g.out_stride, m_base, n_base, whole, g.ep);
+        const bool whole = (t_img + 1) * MR <= g.img_rows && (nt + 1) * NR <= g.K;     // no row or column tail
+        store_tile<FUSED, I8, MB, NB>(g.out, acc, img_row0 + g.img_rows, g.K, g.out_stride, m_base, n_base, whole, g.ep);
     }
     wait_vmcnt<0>();
 }
@@ -573,6 +583,9 @@ int launch_igemm_mfma(const icv_conv_params* p, const Geometry& g, const void* i
     a.M = g.M;
     a.row_stride_bytes = a_direct && !on_input ? (int64_t)g.T * p->C * g.elem_bytes : (int64_t)g.in_stride * g.elem_bytes;
     a.a_rows = on_input ? g.M : g.m_tiles * g.MR;
+    a.image_bytes = a_direct ? 0 : g.image_bytes;
+    a.img_tiles = (uint32_t)(a_direct ? g.m_tiles : g.img_tiles);
+    a.img_rows = (uint32_t)(a_direct ? g.M : g.img_rows);
     a.total_tiles = g.m_tiles * g.n_tiles;
     a.K = p->K; a.T = g.T; a.out_stride = g.out_stride;
     a.stages_per_tap = g.stages_per_tap; a.n_stages = g.n_stages;

@@ -38,6 +38,8 @@ struct PatchArgs {
     void* out;
     int64_t M;
     int64_t total_tiles;       // m_tiles * n_tiles
+    int64_t image_bytes;       // batch-independent buffer: bytes between batch elements of the input (else 0)
+    uint32_t img_tiles, img_rows;   // row tiles and output pixels per image (one image = the whole batch otherwise)
     int32_t stride_bytes, stride_shift;   // bytes between input pixels, a power of two
     int32_t K, T, NCC, out_stride, n_tiles;
     int32_t ring;              // filter slots in the ring
@@ -93,7 +95,9 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
 
     const int lrow_in_blk = lane / Q, lchunk = lane % Q;
     const uint32_t n_tiles = (uint32_t)g.n_tiles;
-    auto m_tile_of = [&](int k) { return (uint32_t)(tl.first + k * tl.step) / n_tiles; };
+    auto m_tile_of = [&](int k) { return (uint32_t)(tl.first + k * tl.step) / n_tiles; };     // global row tile
+    auto buf_tile_of = [&](int k) { return m_tile_of(k) % g.img_tiles; };                      // ... in the buffer
+    auto image_of = [&](int k) { return m_tile_of(k) / g.img_tiles; };                         // batch element
     auto n_tile_of = [&](int k) { return (uint32_t)(tl.first + k * tl.step) % n_tiles; };
     const int count = (int)tl.count;
     // range record {first byte offset, pixel rows} of my k-th tile, read through the constant address space:
@@ -103,7 +107,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
         int2 r = make_int2(0, 1);
         if (k < count) {
             typedef const int32_t __attribute__((address_space(4))) * const_int_ptr;
-            const_int_ptr rec = (const_int_ptr)(uintptr_t)(g.ranges + m_tile_of(k));
+            const_int_ptr rec = (const_int_ptr)(uintptr_t)(g.ranges + buf_tile_of(k));
             r = make_int2(rec[0], rec[1]);
         }
         return r;
@@ -130,7 +134,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
     // patch.  Everything but the patch is issued before the tile's range record (a dependent scalar load) is needed.
     if (count > 0) {
         constexpr int NW = NC + NP;
-        const uint32_t mt = m_tile_of(0);
+        const uint32_t mt = buf_tile_of(0);
         for (int u = wave; u < g.ent_copies; u += NW) copy_ent_piece(u, g.rows + (int64_t)mt * T * MR, 0);
         // stages 0 .. D-2 are contiguous in the packed filter and in the ring (the host keeps D - 1 <= stages per tile)
         const uint8_t* w0 = g.w + (int64_t)n_tile_of(0) * n_st * slot_bytes;
@@ -142,7 +146,8 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
         const int2 rng0 = load_range(0);
         int units = (rng0.y + RPB - 1) / RPB;
         if (units > g.cap_units) units = g.cap_units;
-        for (int u = wave; u < units; u += NW) copy_patch_piece(u, g.a + rng0.x, rng0.y, lds_base + patch_base);
+        for (int u = wave; u < units; u += NW)
+            copy_patch_piece(u, g.a + (int64_t)image_of(0) * g.image_bytes + rng0.x, rng0.y, lds_base + patch_base);
     }
 
     if (wave >= NC) {
@@ -196,7 +201,9 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
             int2 rng_k = load_range(0), rng_k1 = load_range(1);
             for (int k = 0; k < count; k++) {
                 const bool next_tile = k + 1 < count;
-                const uint32_t mt1 = next_tile ? m_tile_of(k + 1) : 0;
+                const uint32_t mt1 = next_tile ? buf_tile_of(k + 1) : 0;
+                const uint8_t* a_k = g.a + (int64_t)image_of(k) * g.image_bytes;                        // this tile's image
+                const uint8_t* a_k1 = g.a + (int64_t)(next_tile ? image_of(k + 1) : 0) * g.image_bytes;  // the next tile's
                 const uint16_t* ent_src = g.rows + (int64_t)mt1 * T * MR;
                 const uint32_t ent_par = (uint32_t)(k + 1) & bufmask;
                 int s = 0;
@@ -205,7 +212,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
                     const bool same_tile = cc + 1 < NCC;
                     const int2 rng = same_tile ? rng_k : rng_k1;
                     const bool next_patch = same_tile || next_tile;
-                    const uint8_t* psrc = g.a + rng.x + (same_tile ? cc + 1 : 0) * KCB;
+                    const uint8_t* psrc = (same_tile ? a_k : a_k1) + rng.x + (same_tile ? cc + 1 : 0) * KCB;
                     int units = next_patch ? (rng.y + RPB - 1) / RPB : 0;
                     if (units > g.cap_units) units = g.cap_units;
                     const uint32_t pdst = lds_base + patch_base + ((uint32_t)(k * NCC + cc + 1) & bufmask) * pbytes;
@@ -340,11 +347,13 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
             // epilogue: accumulator register r of lane l holds row 8*(r/4) + 4*(l>>5) + (r&3), column l&31
             const int64_t tile = tl.first + k * tl.step;
             const int32_t nt = (int32_t)(tile % g.n_tiles);
-            const int64_t mt = tile / g.n_tiles;
-            const int64_t m_base = mt * MR + wm * MRW + 4 * lhalf;
+            const uint32_t mt = (uint32_t)(tile / g.n_tiles);
+            const uint32_t img = mt / g.img_tiles, t_img = mt - img * g.img_tiles;     // batch element, row tile in it
+            const int64_t img_row0 = (int64_t)img * g.img_rows;
+            const int64_t m_base = img_row0 + (int64_t)t_img * MR + wm * MRW + 4 * lhalf;
             const int32_t n_base = nt * NR + wn * NRW + lrow;
-            const bool whole = (mt + 1) * MR <= g.M && (nt + 1) * NR <= g.K;     // no row or column tail
-            store_tile<FUSED, I8, MB, NB>(g.out, acc, g.M, g.K, g.out_stride, m_base, n_base, whole, g.ep);
+            const bool whole = (t_img + 1) * MR <= g.img_rows && (nt + 1) * NR <= g.K;     // no row or column tail
+            store_tile<FUSED, I8, MB, NB>(g.out, acc, img_row0 + g.img_rows, g.K, g.out_stride, m_base, n_base, whole, g.ep);
         }
     }
 }
@@ -463,8 +472,11 @@ int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* 
     a.a = (const uint8_t*)input;
     a.w = (const uint8_t*)packed;
     // the buffer: int32 entries, then the tiles' range records, then the entries as 16-bit patch row numbers
-    a.ranges = (const int4*)(ind + g.m_tiles * g.MR * (int64_t)g.T);
-    a.rows = (const uint16_t*)(a.ranges + g.m_tiles);
+    a.ranges = (const int4*)(ind + g.img_tiles * g.MR * (int64_t)g.T);
+    a.rows = (const uint16_t*)(a.ranges + g.img_tiles);
+    a.image_bytes = g.image_bytes;
+    a.img_tiles = (uint32_t)g.img_tiles;
+    a.img_rows = (uint32_t)g.img_rows;
     a.out = out;
     a.M = g.M;
     a.total_tiles = g.m_tiles * g.n_tiles;

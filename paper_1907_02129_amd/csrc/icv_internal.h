@@ -72,7 +72,12 @@ struct Geometry {
     int32_t stages_per_tap;  // C*elem_bytes / KCB (MFMA)        | 1
     int32_t taps_per_stage;  // 1                                | KCB / 8 (LOWC)
     int32_t n_stages;        // pipeline stages in the reduction
-    int64_t m_tiles, n_tiles;
+    int64_t m_tiles, n_tiles; // row tiles the kernels walk, column tiles
+    // Row tiles never straddle an "image" of img_rows output pixels: with a batch-independent indirection buffer an
+    // image is one batch element (img_rows = Hout*Wout, the buffer describes img_tiles tiles and the kernels add
+    // batch index * image_bytes to what the entries name), otherwise the whole batch is a single image of M rows.
+    int32_t per_image;
+    int64_t img_tiles, img_rows, image_bytes;
     int32_t ring;            // forced LDS ring depth (0: launcher decides)
     int32_t blocks_per_cu;   // forced co-resident workgroups per CU (0: launcher decides)
     int32_t gemm_on_input;   // 1: 1x1 stride-1 unpadded convolution run as a plain GEMM on the input tensor

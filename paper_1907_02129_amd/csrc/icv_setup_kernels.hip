@@ -216,7 +216,8 @@ int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_
 {
     IndArgs a;
     a.ind = ind;
-    a.M = g.M; a.m_padded = g.m_tiles * g.MR;
+    // a batch-independent buffer holds the entries of one image (batch index 0); img_rows = M otherwise
+    a.M = g.img_rows; a.m_padded = g.img_tiles * g.MR;
     a.Hin = p->Hin; a.Win = p->Win; a.Hout = g.Hout; a.Wout = g.Wout;
     a.R = p->R; a.S = p->S; a.SY = p->SY; a.SX = p->SX; a.DY = p->DY; a.DX = p->DX;
     a.PT = p->PT; a.PL = p->PL; a.MR = g.MR; a.T = g.T;
@@ -226,14 +227,14 @@ int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_
     ICV_HIP_CHECK(hipGetLastError());
     if (g.patch_rows) {
         int4* ranges = (int4*)(ind + a.m_padded * g.T);
-        hipLaunchKernelGGL(k_tile_ranges, dim3((unsigned)g.m_tiles), dim3(256), 0, s, ind, ranges, g.MR * g.T,
+        hipLaunchKernelGGL(k_tile_ranges, dim3((unsigned)g.img_tiles), dim3(256), 0, s, ind, ranges, g.MR * g.T,
                            a.stride_bytes);
         ICV_HIP_CHECK(hipGetLastError());
         // the zero row sits after the patch buffer, whose size is whole 1 KB pieces
         const uint32_t zero_row_number = (uint32_t)((((int64_t)g.patch_rows * g.KCB + 1023) / 1024) * 1024 / g.KCB);
         if (zero_row_number > 65535) return ICV_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL(k_patch_rows, dim3((unsigned)g.m_tiles), dim3(256), 0, s, ind, ranges,
-                           (uint16_t*)(ranges + g.m_tiles), g.MR * g.T, a.stride_bytes, zero_row_number);
+        hipLaunchKernelGGL(k_patch_rows, dim3((unsigned)g.img_tiles), dim3(256), 0, s, ind, ranges,
+                           (uint16_t*)(ranges + g.img_tiles), g.MR * g.T, a.stride_bytes, zero_row_number);
         ICV_HIP_CHECK(hipGetLastError());
     }
     return ICV_OK;

@@ -326,6 +326,51 @@ def test_pointwise_convolution_runs_as_gemm_on_the_input(s, pixel_stride):
     assert icv.plan_name(icv.make_params(s.with_(PT=1, PB=1))).startswith("mfma_")
 
 
+# ---------------------------------------------------------------- batch-independent indirection buffer
+PER_IMAGE = 1 << 17
+
+PER_IMAGE_SHAPES = [
+    CONFIGS["cfg1_tiny_f32"].with_(N=3),                                                            # vector ALU
+    ConvShape("b_patch", 3, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=101),                # 437 pixels per image
+    ConvShape("b_patch_chunks", 2, 13, 17, 128, 72, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=102),
+    ConvShape("b_gather", 4, 13, 17, 96, 40, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, seed=103),   # rows per element
+    ConvShape("b_gather_1x1_s2", 3, 15, 15, 64, 64, 1, 1, SY=2, SX=2, seed=104),
+    ConvShape("b_lowc", 3, 30, 26, 4, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=105),
+    ConvShape("b_i8", 3, 15, 15, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=106),
+    ConvShape("b_tiny_images", 9, 3, 3, 64, 32, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=107),            # 9 pixels per image
+    CONFIGS["cfg3c_5x5_asym"].with_(N=2),                                                           # 12321 = 48 * 256 + 33
+]
+
+
+@pytest.mark.parametrize("s", PER_IMAGE_SHAPES, ids=lambda s: s.name)
+def test_batch_independent_buffer_matches_oracle(s):
+    x, w = make_tensors(s)
+    _say("per-image", s.name, icv.plan_name(icv.make_params(s, plan=PER_IMAGE)))
+    buf, xd = run_indirect(s, x, w, plan=PER_IMAGE)
+    check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+    # the buffer is that of one image: entry by entry the oracle's entries of batch element 0
+    one = s.with_(N=1)
+    got, pad = icv.logical_indirection(icv.prepare(one, icv.to_device(w), plan=PER_IMAGE))
+    assert np.array_equal(got, oracle.indirection(one)) and np.all(pad == -1)
+    assert icv.indirection_bytes(buf.p) == icv.indirection_bytes(icv.make_params(one, plan=PER_IMAGE))
+
+
+def test_batch_independent_buffer_serves_any_batch_size():
+    """Built once, used for batches of 1, 2 and 5 images without touching it (section 2.3: a batch-size increase
+    only needs the entries of the new images; here there are none to add)."""
+    base = ConvShape("b_grow", 1, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=111)
+    big = base.with_(N=5)
+    x, w = make_tensors(big)
+    built = icv.prepare(base, icv.to_device(w), plan=PER_IMAGE)
+    for n in (1, 2, 5):
+        s = base.with_(N=n)
+        xs = np.ascontiguousarray(x[:n])
+        other = icv.prepare(s, icv.to_device(w), plan=PER_IMAGE)       # output, packed filter for this batch size
+        icv.conv2d_nhwc(other.p, icv.to_device(xs), other.packed, built.indirection, other.zero_row, other.output)
+        torch.cuda.synchronize()
+        check_against_oracle(s, other.output.cpu().numpy(), xs, w)
+
+
 # ---------------------------------------------------------------- fused output stage
 def _bf16_bits_to_f64(a: np.ndarray) -> np.ndarray:
     return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)

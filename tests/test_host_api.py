@@ -102,7 +102,7 @@ def test_invalid_arguments_are_rejected(lib):
     assert _status(lib, s, out_pixel_stride=8) == icv.ICV_ERR_INVALID_ARG           # stride < K
     assert _status(lib, s, R=80, PT=0, PB=0) == icv.ICV_ERR_INVALID_ARG             # kernel larger than input
     assert _status(lib, s, N=1 << 20) == icv.ICV_ERR_INVALID_ARG                    # input of 2 GiB or more
-    assert _status(lib, s, plan=1 << 17) == icv.ICV_ERR_INVALID_ARG
+    assert _status(lib, s, plan=1 << 18) == icv.ICV_ERR_INVALID_ARG
     assert _status(lib, s, plan=3 << 12) == icv.ICV_ERR_INVALID_ARG                 # no such row staging
     assert _status(lib, s, plan=2 | (13 << 4)) == icv.ICV_ERR_INVALID_ARG           # ring deeper than 12
     assert _status(lib, s, plan=2 | (1 << 4)) == icv.ICV_ERR_INVALID_ARG            # a ring needs two slots
@@ -206,3 +206,26 @@ def test_range_records_are_counted_in_the_buffer_size(lib):
     assert "patch" not in icv.plan_name(icv.make_params(CONFIGS["cfg5a_1x1"]))
     # forcing the pixel-range kernel where it cannot run is an error, not a silent fallback
     assert _status(lib, CONFIGS["cfg5a_1x1"], plan=2 << 12) == icv.ICV_ERR_UNSUPPORTED
+
+
+def test_batch_independent_indirection_buffer_sizes(lib):
+    """Plan bit 17: the buffer describes one image, so its size does not depend on N (section 2.3 re-initialises
+    the buffer when the batch grows; with one image per buffer there is nothing to re-initialise)."""
+    PER_IMAGE = 1 << 17
+    for name in ("cfg2_3x3_c64", "cfg3c_5x5_asym", "cfg5b_7x7_s2", "cfg1_tiny_f32"):
+        s = CONFIGS[name]
+        one = icv.indirection_bytes(icv.make_params(s.with_(N=1), plan=PER_IMAGE))
+        assert one > 0
+        for n in (2, 7, s.N):
+            assert icv.indirection_bytes(icv.make_params(s.with_(N=n), plan=PER_IMAGE)) == one
+        # and it is the size of the whole-batch buffer of a single image
+        assert one == icv.indirection_bytes(icv.make_params(s.with_(N=1)))
+        assert icv.indirection_bytes(icv.make_params(s)) > one or s.N == 1
+        # the index function addresses pixels of one image only
+        p = icv.make_params(s, plan=PER_IMAGE)
+        Hout, Wout = icv.output_size(p)
+        assert icv.indirection_index(p, Hout * Wout - 1, 0) >= 0
+        assert icv.indirection_index(p, s.N * Hout * Wout - 1, 0) == -1 or s.N == 1
+    # a 1x1 stride-1 convolution reads no entries at all; the option changes nothing for it
+    g = CONFIGS["cfg5a_1x1"]
+    assert icv.plan_name(icv.make_params(g, plan=PER_IMAGE)).startswith("gemm_")
