@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the Indirect Convolution hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--no-shapes]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--no-shapes] [--sweep N]
 
 A step is one icv_conv2d_nhwc call (the Indirect GEMM, epilogue included) on the headline workload
 (ResNet-style 3x3 bf16 convolution, N=32, 56x56, C=K=64).  As in the paper's protocol (section 3.1,
@@ -118,33 +118,128 @@ class Problem:
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
 
-    def time_ablation(self, steps=20, warmup=3):
-        """im2col + GEMM through the same MFMA core: (total ms, im2col ms, gemm ms)."""
-        torch, icv, b, x = self.torch, self.icv, self.bufs[0], self.xs[0]
-        ws = torch.empty(icv.im2col_bytes(b.p), dtype=torch.uint8, device="cuda:0")
-        out = torch.empty_like(b.output)
+    def time_ablation(self, steps=20, warmup=3, graph_steps=0):
+        """im2col + GEMM through the same MFMA core: (total ms, im2col ms, gemm ms), rotating over as many
+        workspace / output sets as the indirect path rotates buffer sets (the same cache regime).  With
+        graph_steps, that many calls are replayed from a HIP graph instead of being issued one by one."""
+        torch, icv = self.torch, self.icv
+        n = len(self.bufs)
+        wss = [torch.empty(icv.im2col_bytes(self.p), dtype=torch.uint8, device="cuda:0") for _ in range(n)]
+        outs = [torch.empty_like(b.output) for b in self.bufs]
 
         def timed(fn):
-            for _ in range(warmup):
-                fn()
+            if graph_steps:
+                state = {"i": 0}
+
+                def step():
+                    fn(state["i"] % n)
+                    state["i"] += 1
+                return graph_time(torch, step, graph_steps)
+            for i in range(warmup):
+                fn(i % n)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            for _ in range(steps):
-                fn()
+            for i in range(steps):
+                fn(i % n)
             e1.record()
             torch.cuda.synchronize()
             return e0.elapsed_time(e1) / steps
 
-        t_all = timed(lambda: icv.conv2d_nhwc_im2col(b.p, x, b.packed, ws, out))
-        t_i2c = timed(lambda: icv.im2col(b.p, x, ws))
-        t_gemm = timed(lambda: icv.gemm_nhwc(b.p, ws, b.packed, out))
+        bufs, xs = self.bufs, self.xs
+        t_all = timed(lambda i: icv.conv2d_nhwc_im2col(bufs[i].p, xs[i], bufs[i].packed, wss[i], outs[i]))
+        t_i2c = timed(lambda i: icv.im2col(bufs[i].p, xs[i], wss[i]))
+        t_gemm = timed(lambda i: icv.gemm_nhwc(bufs[i].p, wss[i], bufs[i].packed, outs[i]))
         return t_all, t_i2c, t_gemm
 
 
 def sets_for_cold(s, Hout, Wout):
     per_set = algorithmic_bytes(s, Hout, Wout)
     return min(32, max(2, int(np.ceil(2.5 * LLC_BYTES / per_set))))
+
+
+def graph_time(torch, step, per_replay, reps=9):
+    """Median ms per step of `per_replay` steps captured into one HIP graph and replayed `reps` times: what the GPU
+    needs for the launches, without the host's per-call cost (some 8 us through ctypes, more than the small layers'
+    kernels take)."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(3):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(per_replay):
+            step()
+    g.replay()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) / per_replay)
+    return float(np.median(ts))
+
+
+def layer_sweep(icv, torch, N):
+    """The distinct convolutions of ResNet-18 and SqueezeNet 1.0 (the paper's section 3.1, "Models", Table 2) with
+    synthetic data at batch N: the Indirect Convolution, the im2col + GEMM algorithm and its GEMM part alone, as in
+    the paper's figures 3 and 4, and the geometric means by layer type of its Tables 3 and 4 (performance of the
+    Indirect GEMM primitive relative to the GEMM primitive).  Medians of 9 replays of a HIP graph of launches
+    that rotate over the buffer sets (cold where the sets exceed the last-level cache)."""
+    from paper_1907_02129_amd.workloads import resnet18_layers, squeezenet10_layers, layer_type
+    layers, ratios = {}, {}
+    for model, fn in (("resnet18", resnet18_layers), ("squeezenet10", squeezenet10_layers)):
+        for sh in fn(N):
+            pp = icv.make_params(sh)
+            ho, wo = icv.output_size(pp)
+            nsets = min(sets_for_cold(sh, ho, wo), 12)
+            pr = Problem(icv, torch, sh, sets=nsets)
+            per_replay = 2 * nsets if nsets >= 5 else 12
+            t_default = graph_time(torch, pr.step, per_replay)
+            f = flops(sh, ho, wo, sh.c_logical or None)
+            kind = layer_type(sh)
+            row = {"type": kind, "M": sh.N * ho * wo, "C": sh.c_logical or sh.C, "K": sh.K,
+                   "kernel": icv.plan_name(pp), "ms": t_default, "TFLOPs": f / (t_default * 1e-3) / 1e12}
+            # the Indirect GEMM primitive proper (rows gathered through the buffer) where the default is another
+            # form of it; the ablation runs with the tile the library picks for a plain GEMM
+            pr_g = Problem(icv, torch, sh, sets=nsets, plan=1 << 12)
+            t_gather = t_default
+            if icv.plan_name(pr_g.p) != icv.plan_name(pp):
+                t_gather = graph_time(torch, pr_g.step, per_replay)
+                row["per_element_gather_ms"] = t_gather
+            ta, ti, tg = pr_g.time_ablation(graph_steps=per_replay)
+            row["gemm_only_ms"] = tg
+            if kind == "1x1 stride-1":
+                # no im2col in the GEMM-based algorithm here (the patch matrix is the input tensor): the paper's
+                # comparison is GEMM primitive against Indirect GEMM primitive
+                t_gemm_based = t_default if row["kernel"].startswith("gemm_") else tg
+                t_indirect = t_gather
+                cls = "1x1 stride-1"
+            else:
+                row["im2col_gemm_ms"] = ta
+                t_gemm_based, t_indirect = ta, t_default
+                cls = "1x1 stride-2" if kind == "1x1 stride-2" else "non-1x1"
+            row["indirect_vs_gemm_based"] = t_gemm_based / t_indirect
+            row["indirect_vs_gemm_primitive"] = (t_gemm_based if cls == "1x1 stride-1" else tg) / t_indirect
+            layers[sh.name] = row
+            ratios.setdefault((model, cls), []).append((row["indirect_vs_gemm_primitive"],
+                                                        row["indirect_vs_gemm_based"]))
+            pr = pr_g = None
+            torch.cuda.empty_cache()
+    geo = {}
+    for (model, cls), rs in ratios.items():
+        a = np.array(rs)
+        g = np.exp(np.log(a).mean(axis=0))
+        geo.setdefault(model, {})[cls] = {"layers": len(rs),
+                                          "indirect_gemm_vs_gemm_primitive_pct": (float(g[0]) - 1) * 100,
+                                          "indirect_vs_gemm_based_algorithm_pct": (float(g[1]) - 1) * 100}
+    return {"N": N, "layers": layers, "geomean_by_type": geo}
 
 
 def cpu_baseline(s, x, w, min_seconds=1.0, max_passes=20):
@@ -185,6 +280,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-shapes", action="store_true", help="skip the per-shape table and the ablation")
+    ap.add_argument("--sweep", type=int, default=0, metavar="N",
+                    help="add the ResNet-18 / SqueezeNet 1.0 layer sweep at batch N (section 3.1, Table 2)")
     ap.add_argument("--workload", default=None, help="time another shape as the headline (tuning)")
     ap.add_argument("--plan", type=int, default=0)
     ap.add_argument("--traffic-probe", action="store_true",
@@ -327,6 +424,9 @@ def main():
             pr_abl = None
             torch.cuda.empty_cache()
         out["shapes"] = shapes
+
+    if args.sweep > 0:
+        out["layer_sweep"] = layer_sweep(icv, torch, args.sweep)
 
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(s, prob.x_host, prob.w_host)

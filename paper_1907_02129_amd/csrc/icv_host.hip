@@ -57,10 +57,10 @@ static const char* kGenericNames[3] = {"generic_f32", "generic_bf16", "generic_u
 static const char* kLowcNames[2] = {"mfma_bf16_lowc_64x64", "mfma_i8_lowc_64x64"};
 static const char* kPatchNames[2][14] = {
     {"mfma_bf16_128x64_c2x2_patch", "mfma_bf16_128x128_c2x2_patch", "", "mfma_bf16_256x64_c4x2_patch",
-     "mfma_bf16_256x128_c2x2_patch", "",
+     "mfma_bf16_256x128_c2x2_patch", "mfma_bf16_64x64_c2x2_patch",
      "mfma_bf16_256x128_c4x2_patch", "mfma_bf16_128x128_c4x2_patch", "", "", "", "", "", ""},
     {"mfma_i8_128x64_c2x2_patch", "mfma_i8_128x128_c2x2_patch", "", "mfma_i8_256x64_c4x2_patch",
-     "mfma_i8_256x128_c2x2_patch", "",
+     "mfma_i8_256x128_c2x2_patch", "mfma_i8_64x64_c2x2_patch",
      "mfma_i8_256x128_c4x2_patch", "mfma_i8_128x128_c4x2_patch", "", "", "", "", "", ""},
 };
 static const char* kGemmNames[2][14] = {
@@ -166,27 +166,54 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         }
         return false;
     };
-    // Measured on MI355X.  64-wide filters: 256 x 64 tiles, else 128 x 64, two workgroups per compute unit when the
-    // single-buffer layout fits half the LDS.  Wider filters: 256 x 128 tiles of 64 x 64 wavefront blocks when every
-    // compute unit still gets a tile, else 128 x 128 tiles.  128-byte stages when the patch fits, else 64-byte ones
-    // (the launcher then puts several kernel elements into a stage).
-    // A batch-independent buffer must have the same layout for every N, so its tile is chosen as for one image.
-    const int64_t m_choice = plan_per_image ? Hout * Wout : M;
-    const bool big_m = ((m_choice + 255) / 256) * ((p->K + 127) / 128) >= 256;
+    // Measured on MI355X.  64-wide filters: 256 x 64 tiles, two workgroups per compute unit when the single-buffer
+    // layout fits half the LDS.  Wider filters: 256 x 128 tiles of 64 x 64 wavefront blocks when every compute unit
+    // still gets a tile, else 128 x 128 tiles.  A grid that leaves compute units idle costs more than a smaller
+    // tile's lower efficiency (one 128 x 128 tile keeps a compute unit busy as long as two 128 x 64 tiles keep two),
+    // so the tile is halved until the grid fills the chip: 128 x 64, then 64 x 64.  128-byte stages when the patch
+    // fits, else 64-byte ones (the launcher then puts several kernel elements into a stage).
+    // A batch-independent buffer must have the same layout for every N, so its tile is chosen as for a batch
+    // that fills the chip.
+    const int64_t kCus = 256;
+    auto tiles_of = [&](int64_t mr, int64_t nr) { return ((M + mr - 1) / mr) * ((p->K + nr - 1) / nr); };
+    // candidates from the largest tile down; the first whose grid fills the chip is the preferred one
+    int order[5], n_order = 0;
+    if (p->K <= 64) {
+        order[n_order++] = 3;                                                        // 256 x 64
+    } else {
+        if (!plan_per_image && tiles_of(256, 128) >= kCus) order[n_order++] = 6;     // 256 x 128
+        order[n_order++] = 7;                                                        // 128 x 128, 64 x 64 blocks
+        order[n_order++] = 1;                                                        // 128 x 128, 32 x 64 blocks
+    }
+    order[n_order++] = 0;                                                            // 128 x 64
+    order[n_order++] = 5;                                                            // 64 x 64
+    int first = 0;
+    if (!plan_per_image) {
+        auto fills = [&](int v) {
+            const TileVariant& tv = kTileVariants[v];
+            // 128 x 128 tiles run one workgroup per compute unit and want one and a half rounds before their higher
+            // efficiency pays (measured); 64-wide ones run two side by side
+            return tiles_of(tv.MR, tv.NR) * 2 >= (tv.MR == 128 && tv.NR == 128 ? 3 * kCus : 2 * kCus);
+        };
+        while (first < n_order - 1 && !fills(order[first])) ++first;
+    }
     const bool forced = plan_staging == 2;
     if (mfma_ok) {
         if (plan_kernel >= 2) {
             variant = plan_kernel - 2;
             if (!try_patch(variant) && forced) return ICV_ERR_UNSUPPORTED;
-        } else if (p->K <= 64 ? (try_patch(3) || try_patch(0)) : ((big_m && try_patch(6)) || try_patch(7) || try_patch(1))) {
-            // a pixel-range plan fits
-        } else if (plan_staging == 2) {
-            return ICV_ERR_UNSUPPORTED;
         } else {
-            // measured on MI355X: a 64-wide filter is served best by 256-row tiles with 8 + 8 wavefronts (when a
-            // tile's entries still fit their LDS budget), wider filters by 128 x 128 tiles
-            if (p->K <= 64) variant = (int64_t)256 * T * 4 <= 24 * 1024 ? 3 : 0;
-            else variant = 1;
+            // the pixel-range kernel with the preferred tile, else with the next smaller one that fits its LDS
+            int i = first;
+            while (i < n_order && !try_patch(order[i])) ++i;
+            if (i == n_order) {
+                if (plan_staging == 2) return ICV_ERR_UNSUPPORTED;
+                // rows gathered per kernel element: 128 x 128 in the 32 x 64 split (measured), 256-row tiles only
+                // when a tile's entries fit their LDS budget
+                variant = order[first];
+                if (variant == 6 || variant == 7) variant = 1;
+                if (variant == 3 && (int64_t)256 * T * 4 > 24 * 1024) variant = 0;
+            }
         }
         // a workgroup keeps two tiles' worth of entries in LDS: 2 * MR*T int32 (plus padding)
         if (!patch_rows && (int64_t)kTileVariants[variant].MR * T * 4 > 24 * 1024) mfma_ok = false;

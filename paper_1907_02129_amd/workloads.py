@@ -71,6 +71,69 @@ CONFIGS = {
                               PT=3, PL=3, PB=3, PR=3, seed=7, c_logical=3),
 }
 
+
+
+def _stored_channels(C: int) -> int:
+    """Channels as they are kept in memory for the 16-bit tensor-core kernels: 3 -> 4 (an 8-byte pixel); counts that
+    are neither a multiple of 32 nor 4, 8 or 16 are rounded up to a multiple of 32 (64-byte rows).  The padding
+    channels of input and filter hold zeros."""
+    if C == 3:
+        return 4
+    if C % 32 == 0 or C in (4, 8, 16):
+        return C
+    return -(-C // 32) * 32
+
+
+def _layer(model, tag, N, hw, C, K, k, stride, pad, seed, dtype="bf16"):
+    Cs = _stored_channels(C)
+    return ConvShape(f"{model}.{tag}", N, hw, hw, Cs, K, k, k, SY=stride, SX=stride, PT=pad, PL=pad, PB=pad, PR=pad,
+                     dtype=dtype, zero_point=128 if dtype == "u8i8" else 0, seed=seed,
+                     c_logical=C if Cs != C else 0)
+
+
+def layer_type(s: ConvShape) -> str:
+    """The row of the paper's Table 2 a shape belongs to, e.g. "3x3 stride-1"."""
+    return f"{s.R}x{s.S} stride-{s.SY}"
+
+
+def resnet18_layers(N: int = 32):
+    """The distinct convolutions of ResNet-18 on 224 x 224 images, from the published architecture (a 7x7 stride-2
+    stem to 112 x 112, a stride-2 pooling to 56 x 56, then four stages of 3x3 convolutions with 64, 128, 256, 512
+    channels at 56, 28, 14, 7 pixels; each later stage opens with a stride-2 3x3 convolution and a stride-2 1x1
+    projection on the shortcut).  Identical parameter sets appear once, as in the paper's Table 2."""
+    out = [_layer("resnet18", "conv1", N, 224, 3, 64, 7, 2, 3, 1000)]
+    hw, c = 56, 64
+    out.append(_layer("resnet18", "stage1.3x3", N, hw, c, c, 3, 1, 1, 1001))
+    for i, k in enumerate((128, 256, 512)):
+        out.append(_layer("resnet18", f"stage{i + 2}.3x3s2", N, hw, c, k, 3, 2, 1, 1010 + 3 * i))
+        out.append(_layer("resnet18", f"stage{i + 2}.1x1s2", N, hw, c, k, 1, 2, 0, 1011 + 3 * i))
+        hw, c = hw // 2, k
+        out.append(_layer("resnet18", f"stage{i + 2}.3x3", N, hw, c, c, 3, 1, 1, 1012 + 3 * i))
+    return out
+
+
+def squeezenet10_layers(N: int = 32):
+    """The distinct convolutions of SqueezeNet 1.0 on 224 x 224 images, from the published architecture: an unpadded
+    7x7 stride-2 stem with 96 filters (109 x 109), eight fire modules (a 1x1 squeeze, then a 1x1 and a padded 3x3
+    expand side by side) with 3x3 stride-2 ceiling-mode poolings after the stem, fire4 and fire8 (54, 27, 13
+    pixels), and a 1x1 classifier convolution with 1000 filters.  Identical parameter sets appear once."""
+    out = [_layer("squeezenet", "conv1", N, 224, 3, 96, 7, 2, 0, 2000)]
+    # (module, pixels, input channels, squeeze filters, expand filters per branch)
+    fires = [(2, 54, 96, 16, 64), (3, 54, 128, 16, 64), (4, 54, 128, 32, 128), (5, 27, 256, 32, 128),
+             (6, 27, 256, 48, 192), (7, 27, 384, 48, 192), (8, 27, 384, 64, 256), (9, 13, 512, 64, 256)]
+    seen = set()
+    for m, hw, cin, sq, ex in fires:
+        for tag, c, k, r in ((f"fire{m}.squeeze", cin, sq, 1), (f"fire{m}.expand1x1", sq, ex, 1),
+                             (f"fire{m}.expand3x3", sq, ex, 3)):
+            key = (hw, c, k, r)
+            if key in seen:
+                continue
+            seen.add(key)
+            out.append(_layer("squeezenet", tag, N, hw, c, k, r, 1, r // 2, 2000 + 10 * m + r))
+    out.append(_layer("squeezenet", "conv10", N, 13, 512, 1000, 1, 1, 0, 2100))
+    return out
+
+
 # The configuration the headline metric is quoted on.
 HEADLINE = "cfg2_3x3_c64"
 

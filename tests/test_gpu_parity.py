@@ -182,7 +182,7 @@ def test_random_tensor_core_shapes_match_oracle(s):
 N_PLANS = 15    # plan 1 = vector ALU, 2.. = tensor-core tile variants
 
 
-PATCH_VARIANTS = (0, 1, 3, 4, 6, 7)     # tile variants the pixel-range kernel is instantiated for
+PATCH_VARIANTS = (0, 1, 3, 4, 5, 6, 7)     # tile variants the pixel-range kernel is instantiated for
 
 
 @pytest.mark.parametrize("staging", [0, 1, 2])
@@ -242,8 +242,10 @@ def _patch_shapes():
                                    (5 << 14) | (2 << 4), 2 << 14, 2 << 8, (2 << 8) | (1 << 10) | (2 << 4), (2 << 8) | (2 << 14)],
                          ids=["auto", "ring2", "ring3", "ring5", "kcb64", "ring2_kcb64", "group1", "group3_kcb64",
                               "group5_ring2", "group2", "two_per_cu", "two_per_cu_kcb64_ring2", "two_per_cu_group2"])
-def test_pixel_range_kernel_matches_oracle(s, knobs):
-    plan = (2 << 12) | knobs
+@pytest.mark.parametrize("tile", [0, 2, 5, 9], ids=["tile_auto", "128x64", "256x64", "128x128"])
+def test_pixel_range_kernel_matches_oracle(s, knobs, tile):
+    # small shapes get the smallest tile when the library chooses; the larger ones are forced (plan bits 0-3)
+    plan = (2 << 12) | knobs | tile
     stride = 64 if s.name == "p_stride" else 0
     x, w = make_tensors(s)
     if stride:
@@ -253,8 +255,11 @@ def test_pixel_range_kernel_matches_oracle(s, knobs):
     else:
         xp = x
     p = icv.make_params(s, plan, in_pixel_stride=stride)
-    assert "patch" in icv.plan_name(p), icv.plan_name(p)
-    _say("pixel-range", s.name, icv.plan_name(p), "knobs", knobs)
+    name = icv.plan_name(p)
+    if tile and not name:
+        pytest.skip("this tile's pixel range (or row numbers) does not fit LDS for the shape")
+    assert "patch" in name, name
+    _say("pixel-range", s.name, name, "knobs", knobs)
     buf = icv.prepare(s, icv.to_device(w), plan=plan, in_pixel_stride=stride)
     xd = icv.to_device(xp)
     icv.run(buf, xd)
@@ -369,6 +374,23 @@ def test_batch_independent_buffer_serves_any_batch_size():
         icv.conv2d_nhwc(other.p, icv.to_device(xs), other.packed, built.indirection, other.zero_row, other.output)
         torch.cuda.synchronize()
         check_against_oracle(s, other.output.cpu().numpy(), xs, w)
+
+
+# ---------------------------------------------------------------- the paper's model layers
+from paper_1907_02129_amd.workloads import resnet18_layers, squeezenet10_layers
+
+MODEL_LAYERS = resnet18_layers(2) + squeezenet10_layers(2)
+
+
+@pytest.mark.parametrize("s", MODEL_LAYERS, ids=lambda s: s.name)
+def test_model_layers_match_oracle(s):
+    """Every distinct convolution of ResNet-18 and SqueezeNet 1.0 (section 3.1, Table 2) at batch 2, with the plan
+    the library picks and with the batch-independent buffer."""
+    x, w = make_tensors(s)
+    for plan in (0, PER_IMAGE):
+        _say("layer", s.name, icv.plan_name(icv.make_params(s, plan=plan)))
+        buf, xd = run_indirect(s, x, w, plan=plan)
+        check_against_oracle(s, buf.output.cpu().numpy(), x, w)
 
 
 # ---------------------------------------------------------------- fused output stage

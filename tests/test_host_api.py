@@ -218,8 +218,8 @@ def test_batch_independent_indirection_buffer_sizes(lib):
         assert one > 0
         for n in (2, 7, s.N):
             assert icv.indirection_bytes(icv.make_params(s.with_(N=n), plan=PER_IMAGE)) == one
-        # and it is the size of the whole-batch buffer of a single image
-        assert one == icv.indirection_bytes(icv.make_params(s.with_(N=1)))
+        # the kernel and tile do not depend on N either (the buffer's layout follows the tile)
+        assert len({icv.plan_name(icv.make_params(s.with_(N=n), plan=PER_IMAGE)) for n in (1, 2, 7, s.N)}) == 1
         assert icv.indirection_bytes(icv.make_params(s)) > one or s.N == 1
         # the index function addresses pixels of one image only
         p = icv.make_params(s, plan=PER_IMAGE)
@@ -229,3 +229,35 @@ def test_batch_independent_indirection_buffer_sizes(lib):
     # a 1x1 stride-1 convolution reads no entries at all; the option changes nothing for it
     g = CONFIGS["cfg5a_1x1"]
     assert icv.plan_name(icv.make_params(g, plan=PER_IMAGE)).startswith("gemm_")
+
+
+def test_model_layer_lists_match_the_papers_table_2():
+    """The layer sweep's shapes are written from the published architectures; their distinct operators, counted by
+    type, must be what the paper's Table 2 prints (fixture), which a missing, duplicated or mistyped layer breaks."""
+    import os
+    from collections import Counter
+    from paper_1907_02129_amd.workloads import resnet18_layers, squeezenet10_layers, layer_type
+    want = {"resnet18": Counter(), "squeezenet": Counter()}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "table2_layer_types.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            kind, a, b = line.strip().split(",")
+            if int(a):
+                want["resnet18"][kind] = int(a)
+            if int(b):
+                want["squeezenet"][kind] = int(b)
+    for model, fn in (("resnet18", resnet18_layers), ("squeezenet", squeezenet10_layers)):
+        layers = fn(2)
+        assert Counter(layer_type(s) for s in layers) == want[model]
+        # distinct parameter sets, distinct names, every shape valid for the library
+        keys = {(s.Hin, s.c_logical or s.C, s.K, s.R, s.SY, s.PT) for s in layers}
+        assert len(keys) == len(layers) == len({s.name for s in layers})
+        for s in layers:
+            p = icv.make_params(s)
+            assert icv.output_size(p)[0] > 0 and icv.indirection_bytes(p) > 0
+            assert s.R == s.S and s.SY == s.SX and (s.c_logical or s.C) <= s.C
+    # the 3x3 convolutions keep the image size (padding 1); the stems halve it
+    first = resnet18_layers(1)[0]
+    assert icv.output_size(icv.make_params(first)) == (112, 112)
+    assert icv.output_size(icv.make_params(squeezenet10_layers(1)[0])) == (109, 109)
