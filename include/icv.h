@@ -86,10 +86,11 @@ ICV_API int icv_output_size(const icv_conv_params* p, int32_t* Hout, int32_t* Wo
  * Buffer sizes in bytes (0 when the parameters are invalid).
  *  indirection  : int32 entries, M rounded up to whole row tiles, times R*S (independent of C, section 1.1;
  *                 with plan bit 17, M is Hout*Wout, one image's output pixels, whatever N is);
- *                 kernels that keep a tile's input pixels in LDS append one 16-byte record per row tile,
+ *                 kernels that keep a tile's input pixels in LDS, and the kernel for very short pixel rows
+ *                 (which reads the entries in this compact form), append one 16-byte record per row tile,
  *                 {smallest valid entry of the tile, pixels from there to the largest one, 0, 0}, and then the
  *                 entries once more, in the same order, as uint16 pixel numbers inside their tile's range
- *                 ((entry - smallest entry) / pixel stride; the zero row is the number after the range's
+ *                 ((entry - smallest entry) / pixel stride; the zero row is 65535 for short pixel rows, else the number after the range's
  *                 LDS buffer)
  *  packed filter: the [K][R][S][C] filter re-laid as the tiles the GEMM kernel reads, K padded to the tile
  *  zero row     : C elements (section 2.3's explicit zero vector), rounded up to 16 bytes

@@ -261,15 +261,16 @@ def tile_ranges(buf: ConvBuffers):
     p = buf.p
     T = p.R * p.S
     phys = buf.indirection.cpu().numpy()
-    if T == 1:
-        return None
-    mr = indirection_index(p, 0, 1)
-    tiles = -(-buf.M // mr)
-    n = tiles * mr * T
-    rest = phys[n:]
-    if len(rest) != tiles * 4 + n // 2:
-        return None
-    return rest[:tiles * 4].reshape(tiles, 4), rest[tiles * 4:].view(np.uint16).reshape(tiles, T, mr)
+    # the index function shows the tile height where there are several kernel elements; with one the order is the
+    # identity for every height, and the height is the one that explains the buffer's size
+    heights = (indirection_index(p, 0, 1),) if T > 1 else (64, 128, 256)
+    for mr in heights:
+        tiles = -(-buf.M // mr)
+        n = tiles * mr * T
+        rest = phys[n:]
+        if len(rest) == tiles * 4 + n // 2:
+            return rest[:tiles * 4].reshape(tiles, 4), rest[tiles * 4:].view(np.uint16).reshape(tiles, T, mr)
+    return None
 
 
 def logical_indirection(buf: ConvBuffers) -> np.ndarray:
@@ -280,7 +281,11 @@ def logical_indirection(buf: ConvBuffers) -> np.ndarray:
     phys = buf.indirection.cpu().numpy()
     # the layout is [tile][tap][MR] (range records may follow); recover MR from the index function
     # (with a single kernel element the order is the identity and no records follow)
-    mr = indirection_index(p, 0, 1) if T > 1 else len(phys)
+    if T > 1:
+        mr = indirection_index(p, 0, 1)
+    else:
+        compact = tile_ranges(buf)
+        mr = compact[1].size if compact is not None else len(phys)
     tiles = -(-buf.M // mr)
     phys = phys[:tiles * mr * T]
     assert indirection_index(p, mr, 0) in (-1, mr * T) and indirection_index(p, 1, 0) == 1

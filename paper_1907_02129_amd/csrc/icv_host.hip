@@ -128,6 +128,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     g->in_stride = p->in_pixel_stride ? p->in_pixel_stride : p->C;
     g->out_stride = p->out_pixel_stride ? p->out_pixel_stride : p->K;
     g->patch_rows = 0;
+    g->zero_row_number = 0;
     g->cc_major = 0;
     g->group = plan_group;
     g->gemm_on_input = 0;
@@ -234,6 +235,13 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         g->taps_per_stage = g->T;
         g->n_stages = 1;
         g->name = kLowcNames[p->dtype == ICV_U8I8 ? 1 : 0];
+        // compact entries (16-bit pixel numbers inside the tile's range) when every tile's range is short enough;
+        // plan "rows gathered per kernel element" keeps the int32 offsets, for comparison
+        const int64_t span = tile_span_bound(p, Hout, Wout, 64);
+        if (plan_staging != 1 && span < 65535) {
+            g->patch_rows = (int32_t)span;
+            g->zero_row_number = 65535u;
+        }
     } else if (mfma_ok) {
         const TileVariant& tv = kTileVariants[variant];
         g->kind = PLAN_MFMA;
@@ -244,6 +252,8 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         if (plan_kcb == 1) g->KCB = 64;
         if (patch_rows) g->KCB = patch_kcb;
         g->patch_rows = patch_rows;
+        // the zero row sits after the patch buffer, whose size is whole 1 KB pieces
+        g->zero_row_number = patch_rows ? (uint32_t)((((int64_t)patch_rows * g->KCB + 1023) / 1024) * 1024 / g->KCB) : 0u;
         g->cc_major = patch_rows ? 1 : 0;
         g->ring = plan_ring;
         g->blocks_per_cu = plan_per_cu;

@@ -5,8 +5,14 @@
 // (kernel elements outside, channels inside) are flattened: the reduction index is k = tap*C + c, the whole
 // reduction of a tile (R*S*C elements, zero-padded to a multiple of the 32-byte k-step) is gathered into LDS at
 // once, one U-byte load per (output pixel, kernel element) through the indirection buffer, and the tile is then
-// multiplied in one sweep of MFMAs.  The packed filter slice of the workgroup's column tile stays in LDS for
-// all the row tiles the (persistent) workgroup walks, because it is as large as the gathered A tile.
+// multiplied in one sweep of MFMAs.  The packed filter slice of the workgroup's columns stays in LDS for
+// all the row tiles the (persistent) workgroup walks, because it is no larger than the gathered A tile.  A
+// workgroup takes as many 32-column blocks as fit its LDS budget (all of K for the usual first layers), so the
+// rows, whose gather is the expensive part, are fetched once and not once per column tile.
+//
+// The entries are read in their compact form when the set-up phase wrote one: per row tile a range record with
+// the smallest valid byte offset, and per entry a 16-bit pixel number relative to it (0xFFFF = zero row), half
+// the bytes of the int32 offsets; with so few channels the entries are the larger part of what a tile reads.
 //
 // LDS rows are padded by 16 bytes (odd number of 16-byte units per row) instead of swizzled: ds_write_b64
 // from the gather and ds_read_b128 for the fragments are then both spread over the banks.
@@ -19,12 +25,17 @@ struct LowcArgs {
     const uint8_t* zero_row;
     const uint8_t* w;       // packed filter [n tile][64][KP]
     const int32_t* ind;     // [m tile][tap][64], byte offsets, negative = zero row
+    const int4* ranges;     // compact form: per row tile {smallest valid byte offset, ...}, or null
+    const uint16_t* rows;   // compact form: [m tile][tap][64] pixel numbers from that offset on, 0xFFFF = zero row
     void* out;
     int64_t M, m_tiles;
     int64_t image_bytes;    // batch-independent buffer: bytes between batch elements of the input (else 0)
     uint32_t img_tiles, img_rows;  // row tiles and output pixels per image (one image = the whole batch otherwise)
     int32_t K, T, out_stride, n_tiles;
     int32_t KP;             // padded reduction bytes per row, multiple of 32
+    int32_t stride_bytes;   // bytes between input pixels
+    int32_t col_blocks;     // 32-column blocks per workgroup (blockIdx.y selects the group)
+    int32_t k_rows;         // rows of the packed filter (K padded to 64)
     int32_t direct;         // 1: `a` is the dense patch matrix [rows][KP] of the ablation path
     EpilogueArgs ep;
 };
@@ -41,27 +52,31 @@ struct Piece<16> { using type = u32x4_t; };
 template <>
 struct Piece<32> { using type = u32x4_t; };   // moved as two 16-byte halves
 
-// One workgroup (4 wavefronts) per 64 x 64 output tile; wavefront w owns the 32 x 32 block (w / 2, w % 2).
+// One workgroup (4 wavefronts) per tile of 64 rows x (32 * col_blocks) columns; its 32 x 32 blocks are dealt out
+// to the wavefronts in turn.
 template <bool I8, int U, bool FUSED>
 __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
 {
-    constexpr int MR = 64, NR = 64;
+    constexpr int MR = 64;
     using acc_t = typename std::conditional<I8, i32x16_t, f32x16_t>::type;
     using out_t = typename std::conditional<I8, int32_t, float>::type;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int pitch = g.KP + 16;
-    uint8_t* ldsB = lds;                    // [NR][pitch]
-    uint8_t* ldsA = lds + NR * pitch;       // [MR][pitch]
+    const int col0 = blockIdx.y * g.col_blocks * 32;                       // first column of this workgroup
+    int n_cols = g.k_rows - col0;                                          // packed filter rows from there on
+    if (n_cols > g.col_blocks * 32) n_cols = g.col_blocks * 32;
+    const int n_blocks = 2 * (n_cols / 32);                                // 32 x 32 blocks of the tile
+    uint8_t* ldsB = lds;                                // [32 * col_blocks][pitch]
+    uint8_t* ldsA = lds + g.col_blocks * 32 * pitch;    // [MR][pitch]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const EpilogueArgs ep = g.ep;
-    const int nt = blockIdx.y;
 
-    // ---- filter slice of this column tile -> LDS, once
+    // ---- filter slice of this workgroup's columns -> LDS, once
     {
-        const uint8_t* src = g.w + (int64_t)nt * NR * g.KP;
+        const uint8_t* src = g.w + (int64_t)col0 * g.KP;
         const int vec_per_row = g.KP / 16;
-        for (int v = tid; v < NR * vec_per_row; v += 256) {
+        for (int v = tid; v < n_cols * vec_per_row; v += 256) {
             const int row = v / vec_per_row, c = v - row * vec_per_row;
             *(uint4*)(ldsB + row * pitch + c * 16) = *(const uint4*)(src + (int64_t)row * g.KP + c * 16);
         }
@@ -76,11 +91,9 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
         }
     }
 
-    const int wm = wave >> 1, wn = wave & 1;
     const int lrow = lane & 31, lhalf = lane >> 5;
-    const uint8_t* a_frag = ldsA + (wm * 32 + lrow) * pitch + lhalf * 16;
-    const uint8_t* b_frag = ldsB + (wn * 32 + lrow) * pitch + lhalf * 16;
     const int ksteps = g.KP / 32;
+    const bool compact = g.rows != nullptr;
 
     // Entries of a batch of kernel elements of row tile mt: thread -> row tid % 64, elements tap0, tap0 + 4, ...
     // (the 64 entries of an element are contiguous).  A batch is 16 elements, or 8 of the 32-byte rows.
@@ -89,12 +102,25 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
     using piece_t = typename Piece<U>::type;
     const int n_taps = g.direct ? 0 : g.T;
     uint8_t* dstrow = ldsA + (tid & 63) * pitch;
+    // (compact form: turned into byte offsets here, with the tile's first offset from its range record)
     auto load_entries = [&](int64_t mt, int tap0, int32_t (&e)[NB]) __attribute__((always_inline)) {
-        const int32_t* ent = g.ind + ((uint32_t)mt % g.img_tiles) * ((int64_t)g.T * MR) + (tid & 63);      // tile of the buffer
+        const uint32_t bt = (uint32_t)mt % g.img_tiles;                                                     // tile of the buffer
+        if (compact) {
+            const uint16_t* ent = g.rows + bt * ((int64_t)g.T * MR) + (tid & 63);
+            const int32_t first = g.ranges[bt].x;
 #pragma unroll
-        for (int j = 0; j < NB; j++) {
-            const int tap = tap0 + 4 * j;
-            e[j] = tap < n_taps ? ent[tap * MR] : INT32_MIN;
+            for (int j = 0; j < NB; j++) {
+                const int tap = tap0 + 4 * j;
+                const uint32_t r = tap < n_taps ? ent[tap * MR] : 0xFFFFu;
+                e[j] = r == 0xFFFFu ? INT32_MIN : first + (int32_t)(r * (uint32_t)g.stride_bytes);
+            }
+        } else {
+            const int32_t* ent = g.ind + bt * ((int64_t)g.T * MR) + (tid & 63);
+#pragma unroll
+            for (int j = 0; j < NB; j++) {
+                const int tap = tap0 + 4 * j;
+                e[j] = tap < n_taps ? ent[tap * MR] : INT32_MIN;
+            }
         }
     };
     // the rows a batch of entries names -> registers (elements past the last one read the zero row and are dropped)
@@ -126,30 +152,37 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
         }
     };
     auto multiply_and_store = [&](int64_t mt) __attribute__((always_inline)) {
-        acc_t block[1][1];                   // one 32 x 32 block per wavefront
-        acc_t& acc = block[0][0];
-#pragma unroll
-        for (int r = 0; r < 16; r++) acc[r] = 0;
-        for (int ks = 0; ks < ksteps; ks++) {
-            const uint4 av = *(const uint4*)(a_frag + ks * 32);
-            const uint4 bv = *(const uint4*)(b_frag + ks * 32);
-            if constexpr (I8) {
-                i32x4_t ai = {(int)(av.x ^ 0x80808080u), (int)(av.y ^ 0x80808080u), (int)(av.z ^ 0x80808080u),
-                              (int)(av.w ^ 0x80808080u)};
-                i32x4_t bi = {(int)bv.x, (int)bv.y, (int)bv.z, (int)bv.w};
-                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(ai, bi, acc, 0, 0, 0);
-            } else {
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av),
-                                                              __builtin_bit_cast(bf16x8_t, bv), acc, 0, 0, 0);
-            }
-        }
-        // register r of lane l holds row 8*(r/4) + 4*(l>>5) + (r&3), column l&31
         const uint32_t img = (uint32_t)mt / g.img_tiles, t_img = (uint32_t)mt - img * g.img_tiles;      // batch element, row tile in it
         const int64_t img_row0 = (int64_t)img * g.img_rows;
-        const int64_t m_base = img_row0 + (int64_t)t_img * MR + wm * 32 + 4 * lhalf;
-        const int32_t col = nt * NR + wn * 32 + lrow;
-        const bool whole = (t_img + 1) * MR <= g.img_rows && (nt + 1) * NR <= g.K;
-        store_tile<FUSED, I8, 1, 1>(g.out, block, img_row0 + g.img_rows, g.K, g.out_stride, m_base, col, whole, ep);
+        const bool whole_rows = (t_img + 1) * MR <= g.img_rows;
+        // 32 x 32 block b of the tile: rows 32 * (b & 1), columns 32 * (b >> 1)
+        for (int b = wave; b < n_blocks; b += 4) {
+            const int rb = b & 1, cb = b >> 1;
+            const uint8_t* a_frag = ldsA + (rb * 32 + lrow) * pitch + lhalf * 16;
+            const uint8_t* b_frag = ldsB + (cb * 32 + lrow) * pitch + lhalf * 16;
+            acc_t block[1][1];
+            acc_t& acc = block[0][0];
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[r] = 0;
+            for (int ks = 0; ks < ksteps; ks++) {
+                const uint4 av = *(const uint4*)(a_frag + ks * 32);
+                const uint4 bv = *(const uint4*)(b_frag + ks * 32);
+                if constexpr (I8) {
+                    i32x4_t ai = {(int)(av.x ^ 0x80808080u), (int)(av.y ^ 0x80808080u), (int)(av.z ^ 0x80808080u),
+                                  (int)(av.w ^ 0x80808080u)};
+                    i32x4_t bi = {(int)bv.x, (int)bv.y, (int)bv.z, (int)bv.w};
+                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(ai, bi, acc, 0, 0, 0);
+                } else {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av),
+                                                                  __builtin_bit_cast(bf16x8_t, bv), acc, 0, 0, 0);
+                }
+            }
+            // register r of lane l holds row 8*(r/4) + 4*(l>>5) + (r&3), column l&31
+            const int64_t m_base = img_row0 + (int64_t)t_img * MR + rb * 32 + 4 * lhalf;
+            const int32_t col = col0 + cb * 32 + lrow;
+            const bool whole = whole_rows && col0 + (cb + 1) * 32 <= g.K;
+            store_tile<FUSED, I8, 1, 1>(g.out, block, img_row0 + g.img_rows, g.K, g.out_stride, m_base, col, whole, ep);
+        }
     };
 
     const int64_t G = gridDim.x;
@@ -219,17 +252,34 @@ int launch_igemm_lowc(const icv_conv_params* p, const Geometry& g, const void* i
     a.KP = g.KCB;
     a.direct = a_direct ? 1 : 0;
     a.ep = g.ep;
-    const size_t lds_bytes = (size_t)128 * (a.KP + 16);
-    if (lds_bytes > 80 * 1024 || g.n_tiles > 65535) return ICV_ERR_UNSUPPORTED;
+    a.stride_bytes = g.in_stride * g.elem_bytes;
+    // the compact entries (range records, then 16-bit pixel numbers) follow the int32 entries in the buffer
+    a.ranges = nullptr; a.rows = nullptr;
+    if (!a_direct && g.patch_rows) {
+        a.ranges = (const int4*)(ind + g.img_tiles * g.MR * (int64_t)g.T);
+        a.rows = (const uint16_t*)(a.ranges + g.img_tiles);
+    }
+    // 32-column blocks per workgroup: as many as fit beside the 64 gathered rows in half a compute unit's LDS
+    // (two workgroups per compute unit), spread evenly over the groups
+    a.k_rows = (int32_t)g.n_tiles * 64;
+    const int pitch = a.KP + 16;
+    const int kb_total = (p->K + 31) / 32;
+    int cb_max = (80 * 1024 / pitch - 64) / 32;
+    if (cb_max < 1) return ICV_ERR_UNSUPPORTED;
+    if (cb_max > kb_total) cb_max = kb_total;
+    const int groups = (kb_total + cb_max - 1) / cb_max;
+    a.col_blocks = (kb_total + groups - 1) / groups;
+    if (groups > 65535) return ICV_ERR_UNSUPPORTED;
+    const size_t lds_bytes = (size_t)(64 + 32 * a.col_blocks) * pitch;
     int cus = 256, dev = 0;
     if (hipGetDevice(&dev) == hipSuccess) {
         int n = 0;
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
     }
-    int64_t gx = (int64_t)cus * 2 / g.n_tiles;      // two workgroups per CU, shared among the column tiles
+    int64_t gx = (int64_t)cus * 2 / groups;      // two workgroups per CU, shared among the column groups
     if (gx < 1) gx = 1;
     if (gx > g.m_tiles) gx = g.m_tiles;
-    const dim3 grid((unsigned)gx, (unsigned)g.n_tiles);
+    const dim3 grid((unsigned)gx, (unsigned)groups);
     const int unit = p->C * g.elem_bytes;
     const bool i8 = p->dtype == ICV_U8I8;
 #define ICV_LOWC_LAUNCH(I8, U)                                                                                  \

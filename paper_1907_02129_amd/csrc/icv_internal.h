@@ -83,6 +83,8 @@ struct Geometry {
     int32_t gemm_on_input;   // 1: 1x1 stride-1 unpadded convolution run as a plain GEMM on the input tensor
     int32_t group;           // forced kernel elements per pipeline stage of the pixel-range kernel (0: launcher decides)
     int32_t patch_rows;      // > 0: the tile's input pixel range is kept in LDS, this many pixel rows reserved
+                             // (short-row plan: > 0 when the buffer also holds the compact 16-bit entries)
+    uint32_t zero_row_number;   // what the 16-bit entries hold for the zero row
     int32_t cc_major;        // 1: stage = chunk * T + tap (channel chunks outermost), 0: stage = tap * chunks + chunk
     const char* name;
     EpilogueArgs ep;         // output stage of this call (plain: no bias, no ReLU, accumulator type)

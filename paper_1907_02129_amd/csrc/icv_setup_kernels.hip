@@ -230,9 +230,8 @@ int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_
         hipLaunchKernelGGL(k_tile_ranges, dim3((unsigned)g.img_tiles), dim3(256), 0, s, ind, ranges, g.MR * g.T,
                            a.stride_bytes);
         ICV_HIP_CHECK(hipGetLastError());
-        // the zero row sits after the patch buffer, whose size is whole 1 KB pieces
-        const uint32_t zero_row_number = (uint32_t)((((int64_t)g.patch_rows * g.KCB + 1023) / 1024) * 1024 / g.KCB);
-        if (zero_row_number > 65535) return ICV_ERR_UNSUPPORTED;
+        const uint32_t zero_row_number = g.zero_row_number;
+        if (zero_row_number > 65535 || zero_row_number < (uint32_t)g.patch_rows) return ICV_ERR_UNSUPPORTED;
         hipLaunchKernelGGL(k_patch_rows, dim3((unsigned)g.img_tiles), dim3(256), 0, s, ind, ranges,
                            (uint16_t*)(ranges + g.img_tiles), g.MR * g.T, a.stride_bytes, zero_row_number);
         ICV_HIP_CHECK(hipGetLastError());

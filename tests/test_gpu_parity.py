@@ -131,6 +131,12 @@ def _small_shapes():
     out.append(ConvShape("s_bf16_c16_5x5", 1, 21, 9, 16, 64, 5, 5, SY=1, SX=2, PT=2, PL=2, PB=2, PR=2, seed=36))
     out.append(ConvShape("s_i8_c8_5x5", 2, 11, 23, 8, 33, 5, 5, PT=2, PL=2, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=37))
     out.append(ConvShape("s_i8_c32_3x3", 1, 16, 16, 32, 64, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=38))
+    # ... with more filters than one workgroup keeps in LDS (several column groups, the last one narrower), and a
+    # filter count that leaves a whole 32-column block of the 64-padded packed filter unused
+    out.append(ConvShape("s_bf16_c4_7x7_k200", 2, 20, 18, 4, 200, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=39))
+    out.append(ConvShape("s_i8_c8_5x5_k300", 1, 11, 23, 8, 300, 5, 5, PT=2, PL=2, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=40))
+    out.append(ConvShape("s_bf16_c16_3x3_k96", 2, 13, 9, 16, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=45))
+    out.append(ConvShape("s_bf16_c16_1x1_k33", 2, 13, 9, 16, 33, 1, 1, seed=46))
     # vector-ALU fallback: odd channel counts, fp32, other zero points
     out.append(ConvShape("s_f32_odd", 2, 9, 10, 5, 7, 3, 3, SY=2, SX=1, PT=1, PL=2, PB=0, PR=1, dtype="f32", dist="uniform", seed=41))
     out.append(ConvShape("s_bf16_c3", 1, 12, 12, 3, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=42))
@@ -145,6 +151,12 @@ def test_small_shapes_match_oracle(s):
     x, w = make_tensors(s)
     buf, xd = run_indirect(s, x, w)
     check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+    if "lowc" in icv.plan_name(buf.p):
+        # the short-row kernel reads compact 16-bit entries by default; plan bit 12 keeps it on the int32 offsets
+        assert icv.tile_ranges(buf) is not None
+        buf32, _ = run_indirect(s, x, w, plan=1 << 12)
+        assert icv.tile_ranges(buf32) is None and icv.plan_name(buf32.p) == icv.plan_name(buf.p)
+        assert torch.equal(buf32.output, buf.output)
 
 
 def _random_tensor_core_shapes(n=36):
@@ -267,7 +279,11 @@ def test_pixel_range_kernel_matches_oracle(s, knobs, tile):
     check_against_oracle(s, buf.output.cpu().numpy(), x, w)
 
 
-@pytest.mark.parametrize("s", _patch_shapes()[:6] + [CONFIGS["cfg3c_5x5_asym"].with_(N=2)], ids=lambda s: s.name)
+@pytest.mark.parametrize("s", _patch_shapes()[:6] + [CONFIGS["cfg3c_5x5_asym"].with_(N=2),
+                                                     # the short-row kernel reads the same compact form
+                                                     ConvShape("p_lowc", 2, 30, 26, 4, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=80),
+                                                     ConvShape("p_lowc16", 3, 9, 11, 16, 40, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=81)],
+                         ids=lambda s: s.name)
 def test_range_records_match_oracle_entries(s):
     """Per row tile: smallest valid entry and pixel count up to the largest, from the oracle's entries."""
     x, w = make_tensors(s)
