@@ -238,7 +238,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         // compact entries (16-bit pixel numbers inside the tile's range) when every tile's range is short enough;
         // plan "rows gathered per kernel element" keeps the int32 offsets, for comparison
         const int64_t span = tile_span_bound(p, Hout, Wout, 64);
-        if (plan_staging != 1 && span < 65535) {
+        if (plan_staging != 1 && span < 65535 && stride_bytes < (1 << 24)) {
             g->patch_rows = (int32_t)span;
             g->zero_row_number = 65535u;
         }

@@ -54,6 +54,9 @@ struct Piece<32> { using type = u32x4_t; };   // moved as two 16-byte halves
 
 // One workgroup (4 wavefronts) per tile of 64 rows x (32 * col_blocks) columns; its 32 x 32 blocks are dealt out
 // to the wavefronts in turn.
+constexpr int kMaxColBlocks = 8;                              // 32-column blocks of a workgroup (256 columns)
+constexpr int kMaxBlocksPerWave = 2 * kMaxColBlocks / 4;      // its 32 x 32 blocks, dealt to four wavefronts
+
 template <bool I8, int U, bool FUSED>
 __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
 {
@@ -69,7 +72,7 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
     uint8_t* ldsB = lds;                                // [32 * col_blocks][pitch]
     uint8_t* ldsA = lds + g.col_blocks * 32 * pitch;    // [MR][pitch]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const EpilogueArgs ep = g.ep;
 
     // ---- filter slice of this workgroup's columns -> LDS, once
@@ -94,6 +97,7 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
     const int lrow = lane & 31, lhalf = lane >> 5;
     const int ksteps = g.KP / 32;
     const bool compact = g.rows != nullptr;
+    const bool per_image = g.image_bytes != 0;          // else one "image" is the whole batch: no divisions per tile
 
     // Entries of a batch of kernel elements of row tile mt: thread -> row tid % 64, elements tap0, tap0 + 4, ...
     // (the 64 entries of an element are contiguous).  A batch is 16 elements, or 8 of the 32-byte rows.
@@ -152,11 +156,17 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
         }
     };
     auto multiply_and_store = [&](int64_t mt) __attribute__((always_inline)) {
-        const uint32_t img = (uint32_t)mt / g.img_tiles, t_img = (uint32_t)mt - img * g.img_tiles;      // batch element, row tile in it
+        const uint32_t img = per_image ? (uint32_t)mt / g.img_tiles : 0u;                               // batch element
+        const uint32_t t_img = (uint32_t)mt - img * g.img_tiles;                                        // row tile in it
         const int64_t img_row0 = (int64_t)img * g.img_rows;
         const bool whole_rows = (t_img + 1) * MR <= g.img_rows;
-        // 32 x 32 block b of the tile: rows 32 * (b & 1), columns 32 * (b >> 1)
-        for (int b = wave; b < n_blocks; b += 4) {
+        // 32 x 32 block b of the tile: rows 32 * (b & 1), columns 32 * (b >> 1).  Written without a loop over the
+        // blocks on purpose: before a loop that stores, the compiler waits for every outstanding load, which would
+        // expose the latency of the rows of the next tiles that are in flight at this point.
+#pragma unroll
+        for (int u = 0; u < kMaxBlocksPerWave; u++) {
+            const int b = wave + 4 * u;
+            if (b >= n_blocks) break;
             const int rb = b & 1, cb = b >> 1;
             const uint8_t* a_frag = ldsA + (rb * 32 + lrow) * pitch + lhalf * 16;
             const uint8_t* b_frag = ldsB + (cb * 32 + lrow) * pitch + lhalf * 16;
@@ -177,36 +187,93 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
                                                                   __builtin_bit_cast(bf16x8_t, bv), acc, 0, 0, 0);
                 }
             }
-            // register r of lane l holds row 8*(r/4) + 4*(l>>5) + (r&3), column l&31
             const int64_t m_base = img_row0 + (int64_t)t_img * MR + rb * 32 + 4 * lhalf;
             const int32_t col = col0 + cb * 32 + lrow;
+            // register r of lane l holds row 8*(r/4) + 4*(l>>5) + (r&3), column l&31
             const bool whole = whole_rows && col0 + (cb + 1) * 32 <= g.K;
             store_tile<FUSED, I8, 1, 1>(g.out, block, img_row0 + g.img_rows, g.K, g.out_stride, m_base, col, whole, ep);
         }
     };
 
     const int64_t G = gridDim.x;
-    if (!g.direct && n_taps <= 4 * NB) {
-        // One batch covers the tile (the usual case).  Software pipeline over my row tiles: while tile i is
-        // multiplied and stored, the rows of tile i+1 are already on their way to registers and the entries of
-        // tile i+2 are being read, so neither of the two dependent global loads is waited for in full.
-        int32_t e[NB];
-        piece_t v[NV];
+    if (!g.direct && compact && n_taps <= 4 * NB) {
+        // One batch of compact entries covers the tile (the usual case).  The kernel is bound by instruction issue
+        // and by the latency of its two dependent global loads (entries, then the rows they name), so this path
+        // keeps both short and deep: the wavefront's kernel elements tap0, tap0 + 4, ... are wavefront-uniform
+        // (scalar branches and addresses), a row is loaded from base + 32-bit offset whether its entry is valid or
+        // not and replaced by the zero pattern afterwards (what the zero row holds: zeros, or the zero point 128
+        // for uint8), and a workgroup has the rows of two tiles and the entries of a third in flight while a fourth
+        // is multiplied and stored.  Two register sets take turns (loop unrolled by two).
+        const int tap0 = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const int nb = (n_taps - tap0 + 3) / 4;                    // kernel elements of this wavefront, <= NB
+        const uint32_t stride = (uint32_t)g.stride_bytes;
+        const uint32_t zfill = I8 ? 0x80808080u : 0u;
+        // entries (16-bit) and the byte offset they count from
+        auto load_rows16 = [&](int64_t mt, uint32_t (&r)[NB], int32_t& first) __attribute__((always_inline)) {
+            const uint32_t bt = per_image ? (uint32_t)mt % g.img_tiles : (uint32_t)mt;                   // tile of the buffer
+            const uint16_t* ent = g.rows + bt * ((int64_t)g.T * MR) + tap0 * MR + (tid & 63);
+            first = g.ranges[bt].x;
+#pragma unroll
+            for (int j = 0; j < NB; j++)
+                if (j < nb) r[j] = ent[4 * j * MR];
+        };
+        auto gather16 = [&](int64_t mt, const uint32_t (&r)[NB], int32_t first, piece_t (&v)[NV], uint32_t& zmask)
+                            __attribute__((always_inline)) {
+            const uint8_t* base = g.a + (per_image ? (uint32_t)mt / g.img_tiles : 0u) * g.image_bytes + first;   // wavefront-uniform
+            zmask = 0;
+#pragma unroll
+            for (int j = 0; j < NB; j++)
+                if (j < nb) {
+                    const bool z = r[j] == 0xFFFFu;
+                    zmask |= (z ? 1u : 0u) << j;
+                    const uint32_t off = z ? 0u : __umul24(r[j], stride);      // offset 0 is the tile's first valid pixel
+                    if constexpr (U == 32) {
+                        v[2 * j] = *(const piece_t*)(base + off);
+                        v[2 * j + 1] = *(const piece_t*)(base + off + 16);
+                    } else {
+                        v[j] = *(const piece_t*)(base + off);
+                    }
+                }
+        };
+        auto to_lds16 = [&](const piece_t (&v)[NV], uint32_t zmask) __attribute__((always_inline)) {
+#pragma unroll
+            for (int j = 0; j < NB; j++)
+                if (j < nb) {
+                    const bool z = (zmask >> j) & 1u;
+                    uint8_t* d = dstrow + (tap0 + 4 * j) * U;
+                    if constexpr (U == 32) {
+                        *(piece_t*)d = z ? (piece_t)zfill : v[2 * j];
+                        *(piece_t*)(d + 16) = z ? (piece_t)zfill : v[2 * j + 1];
+                    } else {
+                        *(piece_t*)d = z ? (piece_t)zfill : v[j];
+                    }
+                }
+        };
+        piece_t va[NV], vb[NV];
+        uint32_t r[NB];
+        uint32_t za = 0, zb = 0;
+        int32_t first = 0;
+        const int64_t m_tiles = g.m_tiles;
         int64_t mt = blockIdx.x;
-        if (mt < g.m_tiles) {
-            load_entries(mt, tid >> 6, e);
-            gather(mt, e, v);
-            if (mt + G < g.m_tiles) load_entries(mt + G, tid >> 6, e);
-        }
-        for (; mt < g.m_tiles; mt += G) {
+        if (mt < m_tiles) { load_rows16(mt, r, first); gather16(mt, r, first, va, za); }
+        if (mt + G < m_tiles) { load_rows16(mt + G, r, first); gather16(mt + G, r, first, vb, zb); }
+        if (mt + 2 * G < m_tiles) load_rows16(mt + 2 * G, r, first);
+        // v holds the rows of tile t and is refilled with those of tile t + 2G, whose entries are in r; the entries
+        // of tile t + 3G follow them.  (The compiler waits for every load in flight wherever it waits for one, at
+        // the top of a step; what it waits for there was requested at least one whole step earlier.)
+        auto step = [&](int64_t t, piece_t (&v)[NV], uint32_t& zmask) __attribute__((always_inline)) {
             __syncthreads();      // previous tile's fragment reads are done (first pass: filter and padding are in)
-            to_lds(tid >> 6, v);
+            to_lds16(v, zmask);
             __syncthreads();
-            if (mt + G < g.m_tiles) {
-                gather(mt + G, e, v);
-                if (mt + 2 * G < g.m_tiles) load_entries(mt + 2 * G, tid >> 6, e);
+            if (t + 2 * G < m_tiles) {
+                gather16(t + 2 * G, r, first, v, zmask);
+                if (t + 3 * G < m_tiles) load_rows16(t + 3 * G, r, first);
             }
-            multiply_and_store(mt);
+            multiply_and_store(t);
+        };
+        for (; mt < m_tiles; mt += 2 * G) {
+            step(mt, va, za);
+            if (mt + G < m_tiles) step(mt + G, vb, zb);
         }
         return;
     }
@@ -266,6 +333,7 @@ int launch_igemm_lowc(const icv_conv_params* p, const Geometry& g, const void* i
     const int kb_total = (p->K + 31) / 32;
     int cb_max = (80 * 1024 / pitch - 64) / 32;
     if (cb_max < 1) return ICV_ERR_UNSUPPORTED;
+    if (cb_max > kMaxColBlocks) cb_max = kMaxColBlocks;
     if (cb_max > kb_total) cb_max = kb_total;
     const int groups = (kb_total + cb_max - 1) / cb_max;
     a.col_blocks = (kb_total + groups - 1) / groups;
