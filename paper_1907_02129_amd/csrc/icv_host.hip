@@ -11,7 +11,7 @@ void set_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
 const TileVariant kTileVariants[] = {
     {128, 64, 2, 2, "128x64_c2x2_p4"},
     {128, 128, 2, 2, "128x128_c2x2_p4"},
-    {128, 64, 4, 2, "128x64_c4x2_p4"},
+    {256, 64, 4, 1, "256x64_c4x1_p4"},
     {256, 64, 4, 2, "256x64_c4x2_p8"},
     {256, 128, 2, 2, "256x128_c2x2_p4"},
     {64, 64, 2, 2, "64x64_c2x2_p4"},
@@ -56,29 +56,29 @@ int64_t tile_span_bound(const icv_conv_params* p, int64_t Hout, int64_t Wout, in
 static const char* kGenericNames[3] = {"generic_f32", "generic_bf16", "generic_u8i8"};
 static const char* kLowcNames[2] = {"mfma_bf16_lowc_64x64", "mfma_i8_lowc_64x64"};
 static const char* kPatchNames[2][14] = {
-    {"mfma_bf16_128x64_c2x2_patch", "mfma_bf16_128x128_c2x2_patch", "", "mfma_bf16_256x64_c4x2_patch",
+    {"mfma_bf16_128x64_c2x2_patch", "mfma_bf16_128x128_c2x2_patch", "mfma_bf16_256x64_c4x1_patch", "mfma_bf16_256x64_c4x2_patch",
      "mfma_bf16_256x128_c2x2_patch", "mfma_bf16_64x64_c2x2_patch",
      "mfma_bf16_256x128_c4x2_patch", "mfma_bf16_128x128_c4x2_patch", "", "", "", "", "", ""},
-    {"mfma_i8_128x64_c2x2_patch", "mfma_i8_128x128_c2x2_patch", "", "mfma_i8_256x64_c4x2_patch",
+    {"mfma_i8_128x64_c2x2_patch", "mfma_i8_128x128_c2x2_patch", "mfma_i8_256x64_c4x1_patch", "mfma_i8_256x64_c4x2_patch",
      "mfma_i8_256x128_c2x2_patch", "mfma_i8_64x64_c2x2_patch",
      "mfma_i8_256x128_c4x2_patch", "mfma_i8_128x128_c4x2_patch", "", "", "", "", "", ""},
 };
 static const char* kGemmNames[2][14] = {
-    {"gemm_bf16_128x64_c2x2_p4", "gemm_bf16_128x128_c2x2_p4", "gemm_bf16_128x64_c4x2_p4", "gemm_bf16_256x64_c4x2_p8",
+    {"gemm_bf16_128x64_c2x2_p4", "gemm_bf16_128x128_c2x2_p4", "gemm_bf16_256x64_c4x1_p4", "gemm_bf16_256x64_c4x2_p8",
      "gemm_bf16_256x128_c2x2_p4", "gemm_bf16_64x64_c2x2_p4", "gemm_bf16_256x128_c4x2_p8", "gemm_bf16_128x128_c4x2_p8",
      "gemm_bf16_256x128_c4x2_p4", "gemm_bf16_128x128_c2x2_p8", "gemm_bf16_256x128_u4x2", "gemm_bf16_128x128_u4x2",
      "gemm_bf16_256x64_u4x2", "gemm_bf16_128x64_u4x2"},
-    {"gemm_i8_128x64_c2x2_p4", "gemm_i8_128x128_c2x2_p4", "gemm_i8_128x64_c4x2_p4", "gemm_i8_256x64_c4x2_p8",
+    {"gemm_i8_128x64_c2x2_p4", "gemm_i8_128x128_c2x2_p4", "gemm_i8_256x64_c4x1_p4", "gemm_i8_256x64_c4x2_p8",
      "gemm_i8_256x128_c2x2_p4", "gemm_i8_64x64_c2x2_p4", "gemm_i8_256x128_c4x2_p8", "gemm_i8_128x128_c4x2_p8",
      "gemm_i8_256x128_c4x2_p4", "gemm_i8_128x128_c2x2_p8", "gemm_i8_256x128_u4x2", "gemm_i8_128x128_u4x2",
      "gemm_i8_256x64_u4x2", "gemm_i8_128x64_u4x2"},
 };
 static const char* kMfmaNames[2][14] = {
-    {"mfma_bf16_128x64_c2x2_p4", "mfma_bf16_128x128_c2x2_p4", "mfma_bf16_128x64_c4x2_p4", "mfma_bf16_256x64_c4x2_p8",
+    {"mfma_bf16_128x64_c2x2_p4", "mfma_bf16_128x128_c2x2_p4", "mfma_bf16_256x64_c4x1_p4", "mfma_bf16_256x64_c4x2_p8",
      "mfma_bf16_256x128_c2x2_p4", "mfma_bf16_64x64_c2x2_p4", "mfma_bf16_256x128_c4x2_p8", "mfma_bf16_128x128_c4x2_p8",
      "mfma_bf16_256x128_c4x2_p4", "mfma_bf16_128x128_c2x2_p8", "mfma_bf16_256x128_u4x2", "mfma_bf16_128x128_u4x2",
      "mfma_bf16_256x64_u4x2", "mfma_bf16_128x64_u4x2"},
-    {"mfma_i8_128x64_c2x2_p4", "mfma_i8_128x128_c2x2_p4", "mfma_i8_128x64_c4x2_p4", "mfma_i8_256x64_c4x2_p8",
+    {"mfma_i8_128x64_c2x2_p4", "mfma_i8_128x128_c2x2_p4", "mfma_i8_256x64_c4x1_p4", "mfma_i8_256x64_c4x2_p8",
      "mfma_i8_256x128_c2x2_p4", "mfma_i8_64x64_c2x2_p4", "mfma_i8_256x128_c4x2_p8", "mfma_i8_128x128_c4x2_p8",
      "mfma_i8_256x128_c4x2_p4", "mfma_i8_128x128_c2x2_p8", "mfma_i8_256x128_u4x2", "mfma_i8_128x128_u4x2",
      "mfma_i8_256x64_u4x2", "mfma_i8_128x64_u4x2"},
@@ -167,7 +167,8 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         }
         return false;
     };
-    // Measured on MI355X.  64-wide filters: 256 x 64 tiles, two workgroups per compute unit when the single-buffer
+    // Measured on MI355X.  64-wide filters: 256 x 64 tiles (four consumer wavefronts with 64 x 64 blocks: one LDS
+    // fragment read per MFMA instead of three per two), two workgroups per compute unit when the single-buffer
     // layout fits half the LDS.  Wider filters: 256 x 128 tiles of 64 x 64 wavefront blocks when every compute unit
     // still gets a tile, else 128 x 128 tiles.  A grid that leaves compute units idle costs more than a smaller
     // tile's lower efficiency (one 128 x 128 tile keeps a compute unit busy as long as two 128 x 64 tiles keep two),
@@ -180,7 +181,8 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     // candidates from the largest tile down; the first whose grid fills the chip is the preferred one
     int order[5], n_order = 0;
     if (p->K <= 64) {
-        order[n_order++] = 3;                                                        // 256 x 64
+        order[n_order++] = 2;                                                        // 256 x 64, 64 x 64 blocks
+        order[n_order++] = 3;                                                        // 256 x 64, 64 x 32 blocks
     } else {
         if (!plan_per_image && tiles_of(256, 128) >= kCus) order[n_order++] = 6;     // 256 x 128
         order[n_order++] = 7;                                                        // 128 x 128, 64 x 64 blocks
@@ -213,6 +215,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
                 // when a tile's entries fit their LDS budget
                 variant = order[first];
                 if (variant == 6 || variant == 7) variant = 1;
+                if (variant == 2) variant = 3;                      // eight producer wavefronts feed the gather better
                 if (variant == 3 && (int64_t)256 * T * 4 > 24 * 1024) variant = 0;
             }
         }

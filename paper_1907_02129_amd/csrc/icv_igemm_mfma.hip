@@ -549,7 +549,7 @@ static int launch_dtype(const Geometry& g, const IgemmArgs& a, bool direct, hipS
     switch (g.variant) {
         case 0: return launch_tile<I8, 128, 64, 2, 2, 4>(g, a, direct, s);
         case 1: return launch_tile<I8, 128, 128, 2, 2, 4>(g, a, direct, s);
-        case 2: return launch_tile<I8, 128, 64, 4, 2, 4>(g, a, direct, s);
+        case 2: return launch_tile<I8, 256, 64, 4, 1, 4>(g, a, direct, s);
         case 3: return launch_tile<I8, 256, 64, 4, 2, 8>(g, a, direct, s);
         case 4: return launch_tile<I8, 256, 128, 2, 2, 4>(g, a, direct, s);
         case 5: return launch_tile<I8, 64, 64, 2, 2, 4>(g, a, direct, s);

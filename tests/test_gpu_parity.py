@@ -194,7 +194,7 @@ def test_random_tensor_core_shapes_match_oracle(s):
 N_PLANS = 15    # plan 1 = vector ALU, 2.. = tensor-core tile variants
 
 
-PATCH_VARIANTS = (0, 1, 3, 4, 5, 6, 7)     # tile variants the pixel-range kernel is instantiated for
+PATCH_VARIANTS = (0, 1, 2, 3, 4, 5, 6, 7)     # tile variants the pixel-range kernel is instantiated for
 
 
 @pytest.mark.parametrize("staging", [0, 1, 2])
