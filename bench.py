@@ -32,8 +32,8 @@ LLC_BYTES = 256 << 20
 # HBM traffic of the dominant kernel per launch, bytes, measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None until measured.
 MEASURED_TRAFFIC = {
-    # profiles/igemm_cfg2_hbm_traffic.md: FETCH 7586.5 KiB x 1.99975 + WRITE 25098.0 KiB x 1.0
-    "cfg2_3x3_c64": int((7586.5 * 1.99975 + 25098.0) * 1024),
+    # profiles/igemm_cfg2_hbm_traffic.md: FETCH 7631.2 KiB x 1.99975 + WRITE 25139.0 KiB x 1.0
+    "cfg2_3x3_c64": int((7631.2 * 1.99975 + 25139.0) * 1024),
 }
 
 

@@ -145,7 +145,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     int patch_rows = 0, patch_kcb = 0;
     // LDS-resident pixel range: worthwhile when several kernel elements re-read the rows, possible when the pixel
     // stride is a power of two (entry -> LDS row is a shift) and two patch buffers fit beside the other buffers
-    auto try_patch = [&](int v) {
+    auto try_patch = [&](int v, bool need_two = false) {
         if (plan_staging == 1 || T < 4 || !patch_variant_supported(v)) return false;
         if ((stride_bytes & (stride_bytes - 1)) != 0) return false;
         const TileVariant& tv = kTileVariants[v];
@@ -156,9 +156,10 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         for (int kcb = kcb_max; kcb >= 64; kcb -= 64) {
             const int64_t cap_units = (rows * kcb + 1023) / 1024;
             if (cap_units >= 4096) continue;
-            // one workgroup per compute unit with double buffers, or two with single buffers (64-wide tiles)
-            const bool fits_one = patch_lds_bytes(tv.NR, kcb, 2, (int)cap_units, ent_copies, 2) <= 160 * 1024;
-            const bool fits_two = tv.NR == 64 && plan_per_cu != 1 &&
+            // one workgroup per compute unit with double buffers, or two with single buffers (64-wide tiles and
+            // the tiles with four consumer wavefronts)
+            const bool fits_one = !need_two && patch_lds_bytes(tv.NR, kcb, 2, (int)cap_units, ent_copies, 2) <= 160 * 1024;
+            const bool fits_two = (tv.NR == 64 || tv.WM * tv.WN == 4) && plan_per_cu != 1 &&
                                   patch_lds_bytes(tv.NR, kcb, 2, (int)cap_units, ent_copies, 1) <= 80 * 1024;
             if (fits_two || fits_one) {
                 variant = v; patch_rows = (int)rows; patch_kcb = kcb;
@@ -207,8 +208,10 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
             if (!try_patch(variant) && forced) return ICV_ERR_UNSUPPORTED;
         } else {
             // the pixel-range kernel with the preferred tile, else with the next smaller one that fits its LDS
+            // (128 x 128: four consumer wavefronts with 64 x 64 blocks when two such workgroups share a compute
+            // unit, else eight with 32 x 64 blocks -- measured)
             int i = first;
-            while (i < n_order && !try_patch(order[i])) ++i;
+            while (i < n_order && !(order[i] == 7 && try_patch(1, true)) && !try_patch(order[i])) ++i;
             if (i == n_order) {
                 if (plan_staging == 2) return ICV_ERR_UNSUPPORTED;
                 // rows gathered per kernel element: 128 x 128 in the 32 x 64 split (measured), 256-row tiles only

@@ -386,7 +386,7 @@ static int launch_one(const Geometry& g, PatchArgs a, hipStream_t s)
     // less, and a stage's filter tiles must be issued ring - 1 stages ahead: as deep as fits (LDS, enough stages
     // left to spread the shares over), at most 8; when LDS is short, kernel elements per stage go before depth.
     const int G0 = G;
-    int per_cu = g.blocks_per_cu ? g.blocks_per_cu : (NR == 64 ? 2 : 1);
+    int per_cu = g.blocks_per_cu ? g.blocks_per_cu : (NR == 64 || WM * WN == 4 ? 2 : 1);
     int ring = 0;
     for (; per_cu >= 1; --per_cu) {
         a.nbuf = per_cu == 2 ? 1 : 2;
