@@ -409,6 +409,39 @@ def test_model_layers_match_oracle(s):
         check_against_oracle(s, buf.output.cpu().numpy(), x, w)
 
 
+# ---------------------------------------------------------------- launches captured into a HIP graph
+@pytest.mark.parametrize("s", [
+    ConvShape("h_patch", 3, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=121),
+    ConvShape("h_gather", 2, 13, 17, 96, 40, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, seed=122),
+    ConvShape("h_lowc", 2, 30, 26, 4, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=123),
+    ConvShape("h_gemm", 2, 21, 13, 256, 64, 1, 1, seed=124),
+    ConvShape("h_i8", 2, 15, 15, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=125),
+], ids=lambda s: s.name)
+def test_graph_replays_match_eager(s):
+    """The conv call is kernel launches only (no allocation, no memset, no synchronisation), so it can be captured;
+    every replay, with eager work and synchronisations in between, must give the eager result bit for bit."""
+    x, w = make_tensors(s)
+    buf, xd = run_indirect(s, x, w)                 # eager result (also does the one-time function set-up)
+    check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+    eager = buf.output.clone()
+    _say("graph", s.name, icv.plan_name(buf.p))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        icv.run(buf, xd)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        icv.run(buf, xd)
+    for rep in range(3):
+        buf.output.fill_(-7)                        # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(buf.output, eager), (s.name, rep)
+
+
 # ---------------------------------------------------------------- fused output stage
 def _bf16_bits_to_f64(a: np.ndarray) -> np.ndarray:
     return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
