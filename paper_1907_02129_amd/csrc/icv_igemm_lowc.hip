@@ -52,13 +52,17 @@ struct Piece<16> { using type = u32x4_t; };
 template <>
 struct Piece<32> { using type = u32x4_t; };   // moved as two 16-byte halves
 
-// One workgroup (4 wavefronts) per tile of 64 rows x (32 * col_blocks) columns; its 32 x 32 blocks are dealt out
-// to the wavefronts in turn.
+// A team of 4 wavefronts per tile of 64 rows x (32 * col_blocks) columns; its 32 x 32 blocks are dealt out to the
+// wavefronts in turn.  A workgroup is TEAMS such teams that share the filter slice in LDS and each own a gathered
+// tile: per tile a wavefront runs a chain of dependent steps (entries -> rows -> LDS -> fragments -> MFMA -> stores)
+// that nothing overlaps but other wavefronts, and the filter slice is half the LDS a lone team needs, so sharing it
+// is what lets 16 instead of 8 wavefronts work on a compute unit.  All teams pass the same barriers (there is one
+// kind of barrier), so they walk their tiles in lock step.
 constexpr int kMaxColBlocks = 8;                              // 32-column blocks of a workgroup (256 columns)
 constexpr int kMaxBlocksPerWave = 2 * kMaxColBlocks / 4;      // its 32 x 32 blocks, dealt to four wavefronts
 
-template <bool I8, int U, bool FUSED>
-__global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
+template <bool I8, int U, bool FUSED, int TEAMS>
+__global__ __launch_bounds__(256 * TEAMS) void k_igemm_lowc(LowcArgs g)
 {
     constexpr int MR = 64;
     using acc_t = typename std::conditional<I8, i32x16_t, f32x16_t>::type;
@@ -69,17 +73,17 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
     int n_cols = g.k_rows - col0;                                          // packed filter rows from there on
     if (n_cols > g.col_blocks * 32) n_cols = g.col_blocks * 32;
     const int n_blocks = 2 * (n_cols / 32);                                // 32 x 32 blocks of the tile
-    uint8_t* ldsB = lds;                                // [32 * col_blocks][pitch]
-    uint8_t* ldsA = lds + g.col_blocks * 32 * pitch;    // [MR][pitch]
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int team = TEAMS == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8);
+    const int tid = threadIdx.x & 255, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in the team
+    uint8_t* ldsB = lds;                                                    // [32 * col_blocks][pitch], shared
+    uint8_t* ldsA = lds + (g.col_blocks * 32 + team * MR) * pitch;          // [MR][pitch], the team's own
     const EpilogueArgs ep = g.ep;
 
     // ---- filter slice of this workgroup's columns -> LDS, once
     {
         const uint8_t* src = g.w + (int64_t)col0 * g.KP;
         const int vec_per_row = g.KP / 16;
-        for (int v = tid; v < n_cols * vec_per_row; v += 256) {
+        for (int v = threadIdx.x; v < n_cols * vec_per_row; v += 256 * TEAMS) {
             const int row = v / vec_per_row, c = v - row * vec_per_row;
             *(uint4*)(ldsB + row * pitch + c * 16) = *(const uint4*)(src + (int64_t)row * g.KP + c * 16);
         }
@@ -199,11 +203,9 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
     if (!g.direct && compact && n_taps <= 4 * NB) {
         // One batch of compact entries covers the tile (the usual case).  The kernel is bound by instruction issue
         // and by the latency of its two dependent global loads (entries, then the rows they name), so this path
-        // keeps both short and deep: the wavefront's kernel elements tap0, tap0 + 4, ... are wavefront-uniform
-        // (scalar branches and addresses), a row is loaded from base + 32-bit offset whether its entry is valid or
-        // not and replaced by the zero pattern afterwards (what the zero row holds: zeros, or the zero point 128
-        // for uint8), and a workgroup has the rows of two tiles and the entries of a third in flight while a fourth
-        // is multiplied and stored.  Two register sets take turns (loop unrolled by two).
+        // keeps both short: the wavefront's kernel elements tap0, tap0 + 4, ... are wavefront-uniform (scalar
+        // branches and addresses), a row is loaded from base + 32-bit offset whether its entry is valid or not and
+        // replaced by the zero pattern afterwards (what the zero row holds: zeros, or the zero point 128 for uint8).
         const int tap0 = __builtin_amdgcn_readfirstlane(tid >> 6);
         const int nb = (n_taps - tap0 + 3) / 4;                    // kernel elements of this wavefront, <= NB
         const uint32_t stride = (uint32_t)g.stride_bytes;
@@ -249,34 +251,38 @@ __global__ __launch_bounds__(256) void k_igemm_lowc(LowcArgs g)
                     }
                 }
         };
-        piece_t va[NV], vb[NV];
+        piece_t v[NV];
         uint32_t r[NB];
-        uint32_t za = 0, zb = 0;
+        uint32_t zmask = 0;
         int32_t first = 0;
         const int64_t m_tiles = g.m_tiles;
-        int64_t mt = blockIdx.x;
-        if (mt < m_tiles) { load_rows16(mt, r, first); gather16(mt, r, first, va, za); }
-        if (mt + G < m_tiles) { load_rows16(mt + G, r, first); gather16(mt + G, r, first, vb, zb); }
-        if (mt + 2 * G < m_tiles) load_rows16(mt + 2 * G, r, first);
-        // v holds the rows of tile t and is refilled with those of tile t + 2G, whose entries are in r; the entries
-        // of tile t + 3G follow them.  (The compiler waits for every load in flight wherever it waits for one, at
-        // the top of a step; what it waits for there was requested at least one whole step earlier.)
-        auto step = [&](int64_t t, piece_t (&v)[NV], uint32_t& zmask) __attribute__((always_inline)) {
+        // team q of workgroup b takes tiles b * TEAMS + q + k * Gt; every team runs the steps of the team with the most
+        // tiles (team 0), idle in those it has no tile for, so that all meet at the barriers
+        const int64_t Gt = G * TEAMS;
+        const int64_t t0 = (int64_t)blockIdx.x * TEAMS;
+        const int64_t steps = t0 < m_tiles ? (m_tiles - t0 + Gt - 1) / Gt : 0;
+        int64_t t = t0 + team;
+        if (t < m_tiles) {
+            load_rows16(t, r, first);
+            gather16(t, r, first, v, zmask);
+            if (t + Gt < m_tiles) load_rows16(t + Gt, r, first);
+        }
+        // v holds the rows of tile t; while t is multiplied and stored, the rows of tile t + Gt are on their way to
+        // registers and the entries of tile t + 2 Gt are being read
+        for (int64_t k = 0; k < steps; k++, t += Gt) {
+            const bool live = t < m_tiles;
             __syncthreads();      // previous tile's fragment reads are done (first pass: filter and padding are in)
-            to_lds16(v, zmask);
+            if (live) to_lds16(v, zmask);
             __syncthreads();
-            if (t + 2 * G < m_tiles) {
-                gather16(t + 2 * G, r, first, v, zmask);
-                if (t + 3 * G < m_tiles) load_rows16(t + 3 * G, r, first);
+            if (t + Gt < m_tiles) {
+                gather16(t + Gt, r, first, v, zmask);
+                if (t + 2 * Gt < m_tiles) load_rows16(t + 2 * Gt, r, first);
             }
-            multiply_and_store(t);
-        };
-        for (; mt < m_tiles; mt += 2 * G) {
-            step(mt, va, za);
-            if (mt + G < m_tiles) step(mt + G, vb, zb);
+            if (live) multiply_and_store(t);
         }
         return;
     }
+    if constexpr (TEAMS > 1) return;      // the paths below are single-team (their loops end at different times)
 
     for (int64_t mt = blockIdx.x; mt < g.m_tiles; mt += G) {
         __syncthreads();      // previous tile's fragment reads are done (first pass: filter and padding are in)
@@ -338,37 +344,51 @@ int launch_igemm_lowc(const icv_conv_params* p, const Geometry& g, const void* i
     const int groups = (kb_total + cb_max - 1) / cb_max;
     a.col_blocks = (kb_total + groups - 1) / groups;
     if (groups > 65535) return ICV_ERR_UNSUPPORTED;
-    const size_t lds_bytes = (size_t)(64 + 32 * a.col_blocks) * pitch;
-    int cus = 256, dev = 0;
-    if (hipGetDevice(&dev) == hipSuccess) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
-    }
-    int64_t gx = (int64_t)cus * 2 / groups;      // two workgroups per CU, shared among the column groups
-    if (gx < 1) gx = 1;
-    if (gx > g.m_tiles) gx = g.m_tiles;
-    const dim3 grid((unsigned)gx, (unsigned)groups);
     const int unit = p->C * g.elem_bytes;
     const bool i8 = p->dtype == ICV_U8I8;
-#define ICV_LOWC_LAUNCH(I8, U)                                                                                  \
+    // Teams per workgroup: the path that gathers a whole tile from compact entries in one batch runs several teams
+    // on one filter slice (four for the 8-byte rows, two for the wider ones, whose batches need twice the
+    // registers), one workgroup per compute unit; every other path runs single teams, two workgroups per compute unit.
+    const size_t b_bytes = (size_t)32 * a.col_blocks * pitch, a_bytes = (size_t)64 * pitch;
+    const int batch_taps = unit == 32 ? 32 : 64;
+    int teams = 1;
+    if (!a_direct && a.rows && g.T <= batch_taps) {
+        const int fit = (int)((kLdsPerCu - b_bytes) / a_bytes);
+        const int want = unit == 8 ? 4 : 2;
+        teams = fit >= want ? want : (fit >= 2 ? 2 : 1);
+    }
+    const size_t lds_bytes = b_bytes + teams * a_bytes;
+    const int cus = device_cu_count();
+    int64_t gx = (int64_t)cus * (teams > 1 ? 1 : 2) / groups;      // workgroups, shared among the column groups
+    if (gx < 1) gx = 1;
+    if (gx * teams > g.m_tiles) gx = (g.m_tiles + teams - 1) / teams;
+    const dim3 grid((unsigned)gx, (unsigned)groups);
+#define ICV_LOWC_LAUNCH_T(I8, U, TEAMS)                                                                         \
     do {                                                                                                        \
-        auto kern = g.ep_plain ? k_igemm_lowc<I8, U, false> : k_igemm_lowc<I8, U, true>;                        \
+        auto kern = g.ep_plain ? k_igemm_lowc<I8, U, false, TEAMS> : k_igemm_lowc<I8, U, true, TEAMS>;          \
         if (lds_bytes > 64 * 1024) {                                                                            \
             static bool raised_both[2] = {false, false};     /* one flag per instantiation */                  \
             bool& raised = raised_both[g.ep_plain ? 0 : 1];                                                     \
             if (!raised) {                                                                                      \
                 ICV_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                                  160 * 1024));                                                 \
+                                                  (int)kLdsPerCu));                                             \
                 raised = true;                                                                                  \
             }                                                                                                   \
         }                                                                                                       \
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds_bytes, s, a);                                             \
+        hipLaunchKernelGGL(kern, grid, dim3(256 * TEAMS), lds_bytes, s, a);                                     \
+    } while (0)
+#define ICV_LOWC_LAUNCH(I8, U)                                                                                  \
+    do {                                                                                                        \
+        if (teams == 4) ICV_LOWC_LAUNCH_T(I8, U, 4);                                                            \
+        else if (teams == 2) ICV_LOWC_LAUNCH_T(I8, U, 2);                                                       \
+        else ICV_LOWC_LAUNCH_T(I8, U, 1);                                                                       \
     } while (0)
     if (unit == 8) { if (i8) ICV_LOWC_LAUNCH(true, 8); else ICV_LOWC_LAUNCH(false, 8); }
     else if (unit == 16) { if (i8) ICV_LOWC_LAUNCH(true, 16); else ICV_LOWC_LAUNCH(false, 16); }
     else if (unit == 32) { if (i8) ICV_LOWC_LAUNCH(true, 32); else ICV_LOWC_LAUNCH(false, 32); }
     else return ICV_ERR_UNSUPPORTED;
 #undef ICV_LOWC_LAUNCH
+#undef ICV_LOWC_LAUNCH_T
     ICV_HIP_CHECK(hipGetLastError());
     return ICV_OK;
 }
