@@ -95,10 +95,16 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
 
     const int lrow_in_blk = lane / Q, lchunk = lane % Q;
     const uint32_t n_tiles = (uint32_t)g.n_tiles;
-    auto m_tile_of = [&](int k) { return (uint32_t)(tl.first + k * tl.step) / n_tiles; };     // global row tile
-    auto buf_tile_of = [&](int k) { return m_tile_of(k) % g.img_tiles; };                      // ... in the buffer
-    auto image_of = [&](int k) { return m_tile_of(k) / g.img_tiles; };                         // batch element
-    auto n_tile_of = [&](int k) { return (uint32_t)(tl.first + k * tl.step) % n_tiles; };
+    // (the common cases -- one column tile, a whole-batch buffer -- skip the integer divisions: each is a few
+    // dozen scalar instructions on the start-up path)
+    const bool one_col = n_tiles == 1, per_image = g.image_bytes != 0;
+    auto m_tile_of = [&](int k) {                                                               // global row tile
+        const uint32_t t = (uint32_t)(tl.first + k * tl.step);
+        return one_col ? t : t / n_tiles;
+    };
+    auto buf_tile_of = [&](int k) { return per_image ? m_tile_of(k) % g.img_tiles : m_tile_of(k); };    // ... in the buffer
+    auto image_of = [&](int k) { return per_image ? m_tile_of(k) / g.img_tiles : 0u; };                  // batch element
+    auto n_tile_of = [&](int k) { return one_col ? 0u : (uint32_t)(tl.first + k * tl.step) % n_tiles; };
     const int count = (int)tl.count;
     // range record {first byte offset, pixel rows} of my k-th tile, read through the constant address space:
     // a scalar load, which neither touches the vector-memory counter the copies are tracked with nor makes the
