@@ -145,7 +145,9 @@ ICV_API int icv_setup_indirection(const icv_conv_params* p, void* indirection, v
  *   input        : [N][Hin][Win] pixels of in_pixel_stride elements (first C used)
  *   packed_filter: from icv_pack_filter with the same params
  *   indirection  : from icv_setup_indirection with the same params
- *   zero_row     : from icv_init_zero_row
+ *   zero_row     : from icv_init_zero_row.  Its contents must be what that call wrote: the kernels that stage rows
+ *                  in LDS keep a copy of that constant row there (zeros, or the zero point) instead of fetching
+ *                  this buffer for every padding entry; the other kernels read it as Listing 3 does
  *   output       : [N][Hout][Wout] pixels of out_pixel_stride elements (first K written), float or int32
  */
 ICV_API int icv_conv2d_nhwc(const icv_conv_params* p, const void* input, const void* packed_filter,
