@@ -186,8 +186,8 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         order[n_order++] = 3;                                                        // 256 x 64, 64 x 32 blocks
     } else {
         if (!plan_per_image && tiles_of(256, 128) >= kCus) order[n_order++] = 6;     // 256 x 128
-        order[n_order++] = 7;                                                        // 128 x 128, 64 x 64 blocks
-        order[n_order++] = 1;                                                        // 128 x 128, 32 x 64 blocks
+        order[n_order++] = 7;                                                        // 128 x 128, 32 x 64 blocks
+        order[n_order++] = 1;                                                        // 128 x 128, 64 x 64 blocks
     }
     order[n_order++] = 0;                                                            // 128 x 64
     order[n_order++] = 5;                                                            // 64 x 64
@@ -214,7 +214,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
             while (i < n_order && !(order[i] == 7 && try_patch(1, true)) && !try_patch(order[i])) ++i;
             if (i == n_order) {
                 if (plan_staging == 2) return ICV_ERR_UNSUPPORTED;
-                // rows gathered per kernel element: 128 x 128 in the 32 x 64 split (measured), 256-row tiles only
+                // rows gathered per kernel element: 128 x 128 as 2 x 2 wavefronts (measured), 256-row tiles only
                 // when a tile's entries fit their LDS budget
                 variant = order[first];
                 if (variant == 6 || variant == 7) variant = 1;
