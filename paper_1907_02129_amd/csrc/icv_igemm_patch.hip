@@ -419,11 +419,16 @@ static int launch_one(const Geometry& g, PatchArgs a, hipStream_t s)
     a.ring = ring;
     const size_t lds_bytes = patch_lds_bytes(NR, KCB, ring * G, a.cap_units, a.ent_copies, a.nbuf);
 
-    int64_t grid = (int64_t)device_cu_count() * per_cu;
-    if (grid > a.total_tiles) grid = a.total_tiles;
+    // One workgroup per tile when the tiles fit the chip's slots, else as many as there are slots.  The XCD-aware
+    // tile order needs a multiple of 8 workgroups: rounded UP to it when every tile can have its own workgroup (the
+    // surplus ones find no tile and leave) -- rounding down would give a few workgroups a second tile and double
+    // the kernel's duration.
+    const int64_t slots = (int64_t)device_cu_count() * per_cu;
+    int64_t grid = slots < a.total_tiles ? slots : a.total_tiles;
     a.xcd_mode = 0;
-    if (grid >= 8 && a.total_tiles >= 8) {
-        grid -= grid % 8;
+    if (slots >= 8 && a.total_tiles >= 8) {
+        const int64_t up = (a.total_tiles + 7) / 8 * 8, down = slots - slots % 8;
+        grid = up < down ? up : down;
         a.xcd_mode = 1;
     }
     if (lds_bytes > 64 * 1024) {
