@@ -382,7 +382,7 @@ def main():
             pp = icv.make_params(sh)
             ho, wo = icv.output_size(pp)
             pr = Problem(icv, torch, sh, sets=min(sets_for_cold(sh, ho, wo), 12))
-            m, a, b = pr.time_quantiles(repeats=15, inner=10, warmup=3)
+            m, a, b = pr.time_quantiles(repeats=15, inner=40, warmup=3)
             f = flops(sh, ho, wo, getattr(sh, "c_logical", 0) or None)
             ab = algorithmic_bytes(sh, ho, wo)
             row = {"kernel": icv.plan_name(pp), "ms": m, "q20": a, "q80": b, "TFLOPs": f / (m * 1e-3) / 1e12,
@@ -392,7 +392,7 @@ def main():
             if sh.dtype != "f32":
                 # the same launch with the fused output stage (bias + ReLU, 2- or 1-byte output elements)
                 pr.enable_fused()
-                row["fused_bias_relu_narrow_out_ms"] = pr.time_quantiles(repeats=9, inner=10, warmup=3)[0]
+                row["fused_bias_relu_narrow_out_ms"] = pr.time_quantiles(repeats=9, inner=40, warmup=3)[0]
             ts = pr.time_setup(reps=10)
             ib = pr.bufs[0].M * sh.R * sh.S * 4
             row["indirection_build_ms"] = ts
@@ -403,7 +403,7 @@ def main():
                 pr_abl = Problem(icv, torch, sh, sets=min(len(pr.bufs), 12), plan=1 << 12)
                 if icv.plan_name(pr_abl.p) != icv.plan_name(pp):
                     row["per_element_gather_kernel"] = icv.plan_name(pr_abl.p)
-                    row["per_element_gather_ms"] = pr_abl.time_quantiles(repeats=9, inner=10, warmup=3)[0]
+                    row["per_element_gather_ms"] = pr_abl.time_quantiles(repeats=9, inner=40, warmup=3)[0]
                 ta, ti, tg = pr_abl.time_ablation()
                 row["im2col_gemm_ms"] = ta
                 row["im2col_ms"] = ti
@@ -414,7 +414,7 @@ def main():
                 pr_img = Problem(icv, torch, sh, sets=min(len(pr.bufs), 12), plan=1 << 17)
                 row["per_image_buffer"] = {
                     "kernel": icv.plan_name(pr_img.p),
-                    "ms": pr_img.time_quantiles(repeats=9, inner=10, warmup=3)[0],
+                    "ms": pr_img.time_quantiles(repeats=9, inner=40, warmup=3)[0],
                     "indirection_build_ms": pr_img.time_setup(reps=10),
                     "indirection_bytes": icv.indirection_bytes(pr_img.p),
                     "whole_batch_indirection_bytes": icv.indirection_bytes(pp)}
