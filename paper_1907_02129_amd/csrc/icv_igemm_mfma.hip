@@ -592,6 +592,7 @@ int launch_igemm_mfma(const icv_conv_params* p, const Geometry& g, const void* i
     a.img_tiles = (uint32_t)(a_direct ? g.m_tiles : g.img_tiles);
     a.img_rows = (uint32_t)(a_direct ? g.M : g.img_rows);
     a.total_tiles = g.m_tiles * g.n_tiles;
+    if (a.total_tiles >= (1ll << 31)) return ICV_ERR_UNSUPPORTED;      // the kernels count tiles in 32 bits
     a.K = p->K; a.T = g.T; a.out_stride = g.out_stride;
     a.stages_per_tap = g.stages_per_tap; a.n_stages = g.n_stages;
     a.n_tiles = (int32_t)g.n_tiles;

@@ -44,6 +44,7 @@ struct PatchArgs {
     int32_t K, T, NCC, out_stride, n_tiles;
     int32_t ring;              // filter slots in the ring
     int32_t G;                 // kernel elements per pipeline stage (divides T): one barrier per G filter tiles
+    int32_t TS;                // T / G: stages per channel chunk (from the host, a division less at start-up)
     int32_t ent_copies;        // 1 KB pieces of one tile's row numbers
     int32_t cap_units;         // 1 KB pieces of one patch buffer (the zero row follows them)
     int32_t a_share, e_share;  // copies per producer per stage: next patch, next entries
@@ -89,7 +90,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const TileList tl = my_tiles(g.total_tiles, g.xcd_mode);
     const int T = g.T, NCC = g.NCC;
-    const int TS = T / G;                                 // stages per channel chunk
+    const int TS = g.TS;                                  // stages per channel chunk
     const int n_st = NCC * TS;                            // stages per tile, stage = chunk * TS + tap / G
     const int64_t total_stages = tl.count * n_st;
 
@@ -416,6 +417,7 @@ static int launch_one(const Geometry& g, PatchArgs a, hipStream_t s)
         a.e_share = a.nbuf == 2 ? (a.ent_copies + NP * (n_st - ring + 2) - 1) / (NP * (n_st - ring + 2)) : 0;
     }
     a.G = G;
+    a.TS = a.T / G;
     a.ring = ring;
     const size_t lds_bytes = patch_lds_bytes(NR, KCB, ring * G, a.cap_units, a.ent_copies, a.nbuf);
 
@@ -493,6 +495,7 @@ int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* 
     a.out = out;
     a.M = g.M;
     a.total_tiles = g.m_tiles * g.n_tiles;
+    if (a.total_tiles >= (1ll << 31)) return ICV_ERR_UNSUPPORTED;      // the kernels count tiles in 32 bits
     a.stride_bytes = (int32_t)stride_bytes; a.stride_shift = shift;
     a.K = p->K; a.T = g.T; a.NCC = g.stages_per_tap; a.out_stride = g.out_stride;
     a.n_tiles = (int32_t)g.n_tiles;

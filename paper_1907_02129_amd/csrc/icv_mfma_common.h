@@ -160,22 +160,25 @@ struct TileList {
     int64_t first, step, count;   // tiles first + k*step for k < count
 };
 
-__device__ inline TileList my_tiles(int64_t total, int xcd_mode)
+__device__ inline TileList my_tiles(int64_t total64, int xcd_mode)
 {
-    const int64_t b = blockIdx.x, G = gridDim.x;
+    // 32-bit arithmetic (the host keeps the tile count below 2^31): this runs before a workgroup's first load is
+    // issued, and a 64-bit division is a few hundred instructions there
+    const uint32_t total = (uint32_t)total64, b = blockIdx.x, G = gridDim.x;
     TileList t;
     if (xcd_mode) {
-        const int64_t chunk = total >> 3, rem = total & 7, x = b & 7;
-        const int64_t start = x * chunk + (x < rem ? x : rem);
-        const int64_t len = chunk + (x < rem ? 1 : 0);
-        const int64_t i = b >> 3;
-        t.step = G >> 3;
+        const uint32_t chunk = total >> 3, rem = total & 7, x = b & 7;
+        const uint32_t start = x * chunk + (x < rem ? x : rem);
+        const uint32_t len = chunk + (x < rem ? 1 : 0);
+        const uint32_t i = b >> 3, step = G >> 3;
+        t.step = step;
         t.first = start + i;
-        t.count = i < len ? (len - i + t.step - 1) / t.step : 0;
+        // one tile per workgroup is the common case (the grid is sized for it): no division then
+        t.count = i >= len ? 0 : (i + step >= len ? 1 : (len - i + step - 1) / step);
     } else {
         t.step = G;
         t.first = b;
-        t.count = b < total ? (total - b + G - 1) / G : 0;
+        t.count = b >= total ? 0 : (b + G >= total ? 1 : (total - b + G - 1) / G);
     }
     return t;
 }
