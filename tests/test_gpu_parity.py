@@ -409,6 +409,46 @@ def test_model_layers_match_oracle(s):
         check_against_oracle(s, buf.output.cpu().numpy(), x, w)
 
 
+# ---------------------------------------------------------------- grids with workgroups that find no tile
+@pytest.mark.parametrize("plan", [0, 1 << 12, 2, 4, 7, (1 << 12) | 7], ids=["auto", "gathered", "128x64", "256x64_c4x1", "64x64", "64x64_gathered"])
+@pytest.mark.parametrize("tiles64", [9, 13, 23])
+def test_tile_counts_that_are_not_a_multiple_of_eight(plan, tiles64):
+    """The XCD-aware tile order launches a multiple of 8 workgroups; with 9, 13 or 23 tiles of 64 rows (fewer of the
+    larger tiles) some workgroups own no tile and must leave without touching anything."""
+    rows = 64 * tiles64 - 17                                   # ragged last tile
+    for s in (ConvShape("z_3x3", 1, 1, rows, 64, 64, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=131),
+              ConvShape("z_1x1", 1, 1, rows, 64, 96, 1, 1, seed=132),
+              ConvShape("z_1x1_s2", 1, 2, 2 * rows, 64, 32, 1, 1, SY=2, SX=2, seed=133)):
+        name = icv.plan_name(icv.make_params(s, plan=plan))
+        if not name:
+            continue
+        _say("tiles", s.name, name)
+        x, w = make_tensors(s)
+        buf, xd = run_indirect(s, x, w, plan=plan)
+        check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+
+
+def test_batch_independent_buffer_with_fused_output_and_pixel_strides():
+    s = ConvShape("bf_combo", 3, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=134)
+    x, w = make_tensors(s)
+    rng = np.random.default_rng(5)
+    bias = rng.standard_normal(s.K).astype(np.float32)
+    xs = np.zeros(x.shape[:-1] + (128,), dtype=x.dtype)
+    xs[..., :s.C] = x
+    xs[..., s.C:] = 0x7fc0                                      # NaN bit patterns in the unused channels
+    buf = icv.prepare(s, icv.to_device(w), plan=PER_IMAGE, in_pixel_stride=128, out_pixel_stride=100)
+    out = torch.full((s.N, buf.Hout, buf.Wout, 100), -7, dtype=torch.bfloat16, device="cuda:0")
+    bias_dev = torch.from_numpy(bias).cuda()
+    ep = icv.make_epilogue(bias_dev, True, icv.ICV_OUT_BF16)
+    icv.conv2d_nhwc_fused(buf.p, icv.to_device(xs), buf.packed, buf.indirection, buf.zero_row, ep, out)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    want = oracle.epilogue(oracle.conv2d(s, x, w), bias.astype(np.float64), relu=True)
+    assert np.all(got[..., s.K:] == -7)                         # the pixel stride's padding is not written
+    err = np.abs(got[..., :s.K] - want).max() / np.abs(want).max()
+    assert err <= TOL["bf16"], err
+
+
 # ---------------------------------------------------------------- launches captured into a HIP graph
 @pytest.mark.parametrize("s", [
     ConvShape("h_patch", 3, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=121),
