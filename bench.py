@@ -342,7 +342,7 @@ def main():
     ms_warm = warm.time_steps(args.steps, args.warmup)
     med, q20, q80 = prob.time_quantiles()
     t_setup = prob.time_setup()
-    ind_bytes = prob.bufs[0].M * s.R * s.S * 4
+    ind_bytes = icv.indirection_bytes(prob.p)      # everything the build writes: entries, range records, 16-bit form
 
     abytes = algorithmic_bytes(s, Hout, Wout)
     hbm_time = abytes / (HBM_PEAK_GBS * 1e9)
@@ -394,7 +394,7 @@ def main():
                 pr.enable_fused()
                 row["fused_bias_relu_narrow_out_ms"] = pr.time_quantiles(repeats=9, inner=40, warmup=3)[0]
             ts = pr.time_setup(reps=10)
-            ib = pr.bufs[0].M * sh.R * sh.S * 4
+            ib = icv.indirection_bytes(pp)          # everything the build writes: entries, range records, 16-bit form
             row["indirection_build_ms"] = ts
             row["indirection_GBps"] = ib / (ts * 1e-3) / 1e9
             if sh.dtype != "f32":

@@ -114,8 +114,15 @@ struct IndArgs {
     int64_t M, m_padded;
     int32_t Hin, Win, Hout, Wout, R, S, SY, SX, DY, DX, PT, PL, MR, T;
     int32_t stride_bytes;   // bytes between input pixels
+    // compact form (plans that read it): range records, 16-bit entries, what those hold for the zero row, and
+    // log2 of the pixel stride in bytes (-1: not a power of two)
+    int4* ranges;
+    uint16_t* rows16;
+    uint32_t zero_row_number;
+    int32_t stride_shift;
 };
 
+template <bool COMPACT>
 __global__ __launch_bounds__(256) void k_build_indirection(IndArgs a)
 {
     const int64_t m0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
@@ -141,74 +148,62 @@ __global__ __launch_bounds__(256) void k_build_indirection(IndArgs a)
     const int32_t r = (int32_t)(m0 - tile * a.MR);
     int4* dst = (int4*)(a.ind + tile * ((int64_t)a.T * a.MR) + r);
     const int32_t mr4 = a.MR / 4;
+    auto entries = [&](int32_t ky, int32_t kx, int32_t (&e)[4]) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const int32_t iy = oy[j] * a.SY + ky * a.DY - a.PT;
+            const int32_t ix = ox[j] * a.SX + kx * a.DX - a.PL;
+            const bool in = live[j] && (uint32_t)iy < (uint32_t)a.Hin && (uint32_t)ix < (uint32_t)a.Win;
+            e[j] = in ? ((n[j] * a.Hin + iy) * a.Win + ix) * a.stride_bytes : INT32_MIN;
+        }
+    };
+    int32_t lo = INT32_MAX, hi = -1;          // smallest / largest valid entry of my rows
     for (int32_t ky = 0; ky < a.R; ky++) {
         for (int32_t kx = 0; kx < a.S; kx++) {
             int32_t e[4];
-#pragma unroll
-            for (int j = 0; j < 4; j++) {
-                const int32_t iy = oy[j] * a.SY + ky * a.DY - a.PT;
-                const int32_t ix = ox[j] * a.SX + kx * a.DX - a.PL;
-                const bool in = live[j] && (uint32_t)iy < (uint32_t)a.Hin && (uint32_t)ix < (uint32_t)a.Win;
-                e[j] = in ? ((n[j] * a.Hin + iy) * a.Win + ix) * a.stride_bytes : INT32_MIN;
-            }
+            entries(ky, kx, e);
             *dst = make_int4(e[0], e[1], e[2], e[3]);
             dst += mr4;
-        }
-    }
-}
-
-// Range record of every row tile, for the plans that keep a tile's input pixels in LDS: the smallest valid
-// entry of the tile (a byte offset) and the number of pixel rows from there to the largest one.  A tile without
-// valid entries gets {0, 1}.  One workgroup per tile.
-__global__ __launch_bounds__(256) void k_tile_ranges(const int32_t* ind, int4* ranges, int32_t per_tile, int32_t stride_bytes)
-{
-    __shared__ int32_t part[8];
-    const int64_t tile = blockIdx.x;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int4* src = (const int4*)(ind + tile * per_tile);      // per_tile is a multiple of 32
-    int32_t lo = INT32_MAX, hi = -1;
-    for (int32_t i = threadIdx.x; i < per_tile / 4; i += 256) {
-        const int4 v = src[i];
-        const int32_t e[4] = {v.x, v.y, v.z, v.w};
+            if constexpr (COMPACT) {
 #pragma unroll
-        for (int j = 0; j < 4; j++)
-            if (e[j] >= 0) {
-                lo = e[j] < lo ? e[j] : lo;
-                hi = e[j] > hi ? e[j] : hi;
+                for (int j = 0; j < 4; j++)
+                    if (e[j] >= 0) { lo = e[j] < lo ? e[j] : lo; hi = e[j] > hi ? e[j] : hi; }
             }
-    }
-    for (int d = 32; d >= 1; d >>= 1) {
-        const int32_t lo2 = __shfl_xor(lo, d, 64), hi2 = __shfl_xor(hi, d, 64);
-        lo = lo2 < lo ? lo2 : lo;
-        hi = hi2 > hi ? hi2 : hi;
-    }
-    if (lane == 0) { part[wave] = lo; part[4 + wave] = hi; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        for (int w = 1; w < 4; w++) {
-            lo = part[w] < lo ? part[w] : lo;
-            hi = part[4 + w] > hi ? part[4 + w] : hi;
         }
-        ranges[tile] = hi < 0 ? make_int4(0, 1, 0, 0) : make_int4(lo, (hi - lo) / stride_bytes + 1, 0, 0);
     }
-}
-
-// The entries of every row tile as LDS row numbers of the tile's pixel range: (entry - first offset) / pixel
-// stride, or `zero_row_number` (the row after the patch) for the zero row.  Same [tile][tap][row] order.
-__global__ __launch_bounds__(256) void k_patch_rows(const int32_t* ind, const int4* ranges, uint16_t* rows, int32_t per_tile,
-                                                    int32_t stride_bytes, uint32_t zero_row_number)
-{
-    const int64_t tile = blockIdx.x;
-    const int32_t first = ranges[tile].x;
-    const int4* src = (const int4*)(ind + tile * per_tile);      // per_tile is a multiple of 32
-    uint2* dst = (uint2*)(rows + tile * per_tile);
-    for (int32_t i = threadIdx.x; i < per_tile / 4; i += 256) {
-        const int4 v = src[i];
-        const int32_t e[4] = {v.x, v.y, v.z, v.w};
-        uint32_t r[4];
+    if constexpr (COMPACT) {
+        // The compact form of the same entries, in the same kernel (the entries are recomputed, which is cheaper
+        // than reading them back): the tile's range record -- its smallest valid entry and the number of pixels
+        // from there to the largest one, {0, 1} without any -- and every entry as a 16-bit pixel number inside that
+        // range, `zero_row_number` for the zero row.  The MR / 4 threads of a tile are neighbouring lanes of one
+        // wavefront (MR / 4 is 16, 32 or 64), so the tile's minimum and maximum are a few lane exchanges.
+        for (int d = mr4 >> 1; d >= 1; d >>= 1) {
+            const int32_t lo2 = __shfl_xor(lo, d, 64), hi2 = __shfl_xor(hi, d, 64);
+            lo = lo2 < lo ? lo2 : lo;
+            hi = hi2 > hi ? hi2 : hi;
+        }
+        const int32_t first = hi < 0 ? 0 : lo;
+        if (r == 0) {
+            const uint32_t span = hi < 0 ? 0u : (uint32_t)(hi - lo);
+            const uint32_t pixels = (a.stride_shift >= 0 ? span >> a.stride_shift : span / (uint32_t)a.stride_bytes) + 1;
+            a.ranges[tile] = make_int4(first, (int32_t)pixels, 0, 0);
+        }
+        uint2* dst16 = (uint2*)(a.rows16 + tile * ((int64_t)a.T * a.MR) + r);
+        for (int32_t ky = 0; ky < a.R; ky++) {
+            for (int32_t kx = 0; kx < a.S; kx++) {
+                int32_t e[4];
+                entries(ky, kx, e);
+                uint32_t q[4];
 #pragma unroll
-        for (int j = 0; j < 4; j++) r[j] = e[j] < 0 ? zero_row_number : (uint32_t)(e[j] - first) / (uint32_t)stride_bytes;
-        dst[i] = make_uint2(r[0] | (r[1] << 16), r[2] | (r[3] << 16));
+                for (int j = 0; j < 4; j++) {
+                    const uint32_t off = (uint32_t)(e[j] - first);
+                    q[j] = e[j] < 0 ? a.zero_row_number
+                                    : (a.stride_shift >= 0 ? off >> a.stride_shift : off / (uint32_t)a.stride_bytes);
+                }
+                *dst16 = make_uint2(q[0] | (q[1] << 16), q[2] | (q[3] << 16));
+                dst16 += mr4;
+            }
+        }
     }
 }
 
@@ -223,19 +218,22 @@ int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_
     a.PT = p->PT; a.PL = p->PL; a.MR = g.MR; a.T = g.T;
     a.stride_bytes = g.in_stride * g.elem_bytes;
     const int64_t threads = a.m_padded / 4;
-    hipLaunchKernelGGL(k_build_indirection, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, a);
-    ICV_HIP_CHECK(hipGetLastError());
+    const dim3 grid((unsigned)((threads + 255) / 256));
+    a.ranges = nullptr; a.rows16 = nullptr; a.zero_row_number = 0; a.stride_shift = -1;
     if (g.patch_rows) {
-        int4* ranges = (int4*)(ind + a.m_padded * g.T);
-        hipLaunchKernelGGL(k_tile_ranges, dim3((unsigned)g.img_tiles), dim3(256), 0, s, ind, ranges, g.MR * g.T,
-                           a.stride_bytes);
-        ICV_HIP_CHECK(hipGetLastError());
-        const uint32_t zero_row_number = g.zero_row_number;
-        if (zero_row_number > 65535 || zero_row_number < (uint32_t)g.patch_rows) return ICV_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL(k_patch_rows, dim3((unsigned)g.img_tiles), dim3(256), 0, s, ind, ranges,
-                           (uint16_t*)(ranges + g.img_tiles), g.MR * g.T, a.stride_bytes, zero_row_number);
-        ICV_HIP_CHECK(hipGetLastError());
+        // the range records and the 16-bit entries follow the int32 entries in the buffer
+        if (g.zero_row_number > 65535 || g.zero_row_number < (uint32_t)g.patch_rows) return ICV_ERR_UNSUPPORTED;
+        if (g.MR != 64 && g.MR != 128 && g.MR != 256) return ICV_ERR_UNSUPPORTED;     // a tile's threads share a wavefront
+        a.ranges = (int4*)(ind + a.m_padded * g.T);
+        a.rows16 = (uint16_t*)(a.ranges + g.img_tiles);
+        a.zero_row_number = g.zero_row_number;
+        for (int sh = 0; sh < 31; sh++)
+            if ((1 << sh) == a.stride_bytes) a.stride_shift = sh;
+        hipLaunchKernelGGL(k_build_indirection<true>, grid, dim3(256), 0, s, a);
+    } else {
+        hipLaunchKernelGGL(k_build_indirection<false>, grid, dim3(256), 0, s, a);
     }
+    ICV_HIP_CHECK(hipGetLastError());
     return ICV_OK;
 }
 
