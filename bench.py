@@ -106,17 +106,15 @@ class Problem:
         return float(np.median(ts)), float(np.quantile(ts, 0.2)), float(np.quantile(ts, 0.8))
 
     def time_setup(self, reps=20):
-        torch, b = self.torch, self.bufs[0]
-        self.icv.setup_indirection(b.p, b.indirection)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(reps):
-            bb = self.bufs[i % len(self.bufs)]
+        """ms per indirection build, replayed from a HIP graph over the buffer sets (the build is a single short
+        kernel: issued call by call it would measure the host's launch rate)."""
+        state = {"i": 0}
+
+        def step():
+            bb = self.bufs[state["i"] % len(self.bufs)]
+            state["i"] += 1
             self.icv.setup_indirection(bb.p, bb.indirection)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
+        return graph_time(self.torch, step, max(reps, 2 * len(self.bufs)))
 
     def time_ablation(self, steps=20, warmup=3, graph_steps=0):
         """im2col + GEMM through the same MFMA core: (total ms, im2col ms, gemm ms), rotating over as many
