@@ -106,9 +106,8 @@ int launch_pack_filter(const icv_conv_params* p, const Geometry& g, const void* 
 // Entry (m, tap): iy = oy*SY + ky*DY - PT, ix = ox*SX + kx*DX - PL (Listing 1's index arithmetic);
 // inside the input -> byte offset of pixel (n*Hin + iy)*Win + ix from the input base, else INT32_MIN (the
 // zero row).  Physical order [m tile][tap][MR].
-// One thread owns four consecutive rows m0..m0+3 (MR is a multiple of 4, so they share a tile) and walks
-// all taps, writing one int4 per tap: consecutive threads write consecutive 16-byte pieces of a
-// (tile, tap) run of MR*4 bytes.  The two integer divisions per thread are amortised over 4*T entries.
+// A thread owns four consecutive rows m0..m0+3 of a tile and some of the taps, writing one int4 per tap:
+// neighbouring threads write neighbouring 16-byte pieces of a (tile, tap) run of MR*4 bytes.
 struct IndArgs {
     int32_t* ind;
     int64_t M, m_padded;
@@ -125,8 +124,14 @@ struct IndArgs {
 template <bool COMPACT>
 __global__ __launch_bounds__(256) void k_build_indirection(IndArgs a)
 {
-    const int64_t m0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-    if (m0 >= a.m_padded) return;
+    // One workgroup per row tile.  Thread -> (four consecutive rows of the tile, group of kernel elements): the
+    // MR / 4 row quads times 256 / (MR / 4) element groups; a thread walks the elements tg, tg + groups, ...
+    __shared__ int32_t part[8];
+    const int64_t tile = blockIdx.x;
+    const int32_t mr4 = a.MR / 4;
+    const int32_t quad = threadIdx.x % mr4, tg = threadIdx.x / mr4, groups = 256 / mr4;
+    const int32_t r = 4 * quad;
+    const int64_t m0 = tile * a.MR + r;
     // decompose the four rows
     int32_t n[4], oy[4], ox[4];
     bool live[4];
@@ -144,11 +149,8 @@ __global__ __launch_bounds__(256) void k_build_indirection(IndArgs a)
             if (++x == a.Wout) { x = 0; if (++y == a.Hout) { y = 0; ++b; } }
         }
     }
-    const int64_t tile = m0 / a.MR;
-    const int32_t r = (int32_t)(m0 - tile * a.MR);
-    int4* dst = (int4*)(a.ind + tile * ((int64_t)a.T * a.MR) + r);
-    const int32_t mr4 = a.MR / 4;
-    auto entries = [&](int32_t ky, int32_t kx, int32_t (&e)[4]) {
+    auto entries = [&](int32_t tap, int32_t (&e)[4]) {
+        const int32_t ky = tap / a.S, kx = tap - ky * a.S;
 #pragma unroll
         for (int j = 0; j < 4; j++) {
             const int32_t iy = oy[j] * a.SY + ky * a.DY - a.PT;
@@ -157,52 +159,54 @@ __global__ __launch_bounds__(256) void k_build_indirection(IndArgs a)
             e[j] = in ? ((n[j] * a.Hin + iy) * a.Win + ix) * a.stride_bytes : INT32_MIN;
         }
     };
-    int32_t lo = INT32_MAX, hi = -1;          // smallest / largest valid entry of my rows
-    for (int32_t ky = 0; ky < a.R; ky++) {
-        for (int32_t kx = 0; kx < a.S; kx++) {
-            int32_t e[4];
-            entries(ky, kx, e);
-            *dst = make_int4(e[0], e[1], e[2], e[3]);
-            dst += mr4;
-            if constexpr (COMPACT) {
+    int4* dst = (int4*)(a.ind + tile * ((int64_t)a.T * a.MR) + r);
+    int32_t lo = INT32_MAX, hi = -1;          // smallest / largest valid entry seen by this thread
+    for (int32_t tap = tg; tap < a.T; tap += groups) {
+        int32_t e[4];
+        entries(tap, e);
+        dst[(int64_t)tap * mr4] = make_int4(e[0], e[1], e[2], e[3]);
+        if constexpr (COMPACT) {
 #pragma unroll
-                for (int j = 0; j < 4; j++)
-                    if (e[j] >= 0) { lo = e[j] < lo ? e[j] : lo; hi = e[j] > hi ? e[j] : hi; }
-            }
+            for (int j = 0; j < 4; j++)
+                if (e[j] >= 0) { lo = e[j] < lo ? e[j] : lo; hi = e[j] > hi ? e[j] : hi; }
         }
     }
     if constexpr (COMPACT) {
         // The compact form of the same entries, in the same kernel (the entries are recomputed, which is cheaper
         // than reading them back): the tile's range record -- its smallest valid entry and the number of pixels
         // from there to the largest one, {0, 1} without any -- and every entry as a 16-bit pixel number inside that
-        // range, `zero_row_number` for the zero row.  The MR / 4 threads of a tile are neighbouring lanes of one
-        // wavefront (MR / 4 is 16, 32 or 64), so the tile's minimum and maximum are a few lane exchanges.
-        for (int d = mr4 >> 1; d >= 1; d >>= 1) {
+        // range, `zero_row_number` for the zero row.
+        for (int d = 32; d >= 1; d >>= 1) {
             const int32_t lo2 = __shfl_xor(lo, d, 64), hi2 = __shfl_xor(hi, d, 64);
             lo = lo2 < lo ? lo2 : lo;
             hi = hi2 > hi ? hi2 : hi;
         }
+        const int wave = threadIdx.x >> 6;
+        if ((threadIdx.x & 63) == 0) { part[wave] = lo; part[4 + wave] = hi; }
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < 4; w++) {
+            lo = part[w] < lo ? part[w] : lo;
+            hi = part[4 + w] > hi ? part[4 + w] : hi;
+        }
         const int32_t first = hi < 0 ? 0 : lo;
-        if (r == 0) {
+        if (threadIdx.x == 0) {
             const uint32_t span = hi < 0 ? 0u : (uint32_t)(hi - lo);
             const uint32_t pixels = (a.stride_shift >= 0 ? span >> a.stride_shift : span / (uint32_t)a.stride_bytes) + 1;
             a.ranges[tile] = make_int4(first, (int32_t)pixels, 0, 0);
         }
         uint2* dst16 = (uint2*)(a.rows16 + tile * ((int64_t)a.T * a.MR) + r);
-        for (int32_t ky = 0; ky < a.R; ky++) {
-            for (int32_t kx = 0; kx < a.S; kx++) {
-                int32_t e[4];
-                entries(ky, kx, e);
-                uint32_t q[4];
+        for (int32_t tap = tg; tap < a.T; tap += groups) {
+            int32_t e[4];
+            entries(tap, e);
+            uint32_t q[4];
 #pragma unroll
-                for (int j = 0; j < 4; j++) {
-                    const uint32_t off = (uint32_t)(e[j] - first);
-                    q[j] = e[j] < 0 ? a.zero_row_number
-                                    : (a.stride_shift >= 0 ? off >> a.stride_shift : off / (uint32_t)a.stride_bytes);
-                }
-                *dst16 = make_uint2(q[0] | (q[1] << 16), q[2] | (q[3] << 16));
-                dst16 += mr4;
+            for (int j = 0; j < 4; j++) {
+                const uint32_t off = (uint32_t)(e[j] - first);
+                q[j] = e[j] < 0 ? a.zero_row_number
+                                : (a.stride_shift >= 0 ? off >> a.stride_shift : off / (uint32_t)a.stride_bytes);
             }
+            dst16[(int64_t)tap * mr4] = make_uint2(q[0] | (q[1] << 16), q[2] | (q[3] << 16));
         }
     }
 }
@@ -217,13 +221,13 @@ int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_
     a.R = p->R; a.S = p->S; a.SY = p->SY; a.SX = p->SX; a.DY = p->DY; a.DX = p->DX;
     a.PT = p->PT; a.PL = p->PL; a.MR = g.MR; a.T = g.T;
     a.stride_bytes = g.in_stride * g.elem_bytes;
-    const int64_t threads = a.m_padded / 4;
-    const dim3 grid((unsigned)((threads + 255) / 256));
+    if (g.MR != 64 && g.MR != 128 && g.MR != 256) return ICV_ERR_UNSUPPORTED;         // MR / 4 must divide 256
+    if (g.img_tiles > 0x7fffffffll) return ICV_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)g.img_tiles);
     a.ranges = nullptr; a.rows16 = nullptr; a.zero_row_number = 0; a.stride_shift = -1;
     if (g.patch_rows) {
         // the range records and the 16-bit entries follow the int32 entries in the buffer
         if (g.zero_row_number > 65535 || g.zero_row_number < (uint32_t)g.patch_rows) return ICV_ERR_UNSUPPORTED;
-        if (g.MR != 64 && g.MR != 128 && g.MR != 256) return ICV_ERR_UNSUPPORTED;     // a tile's threads share a wavefront
         a.ranges = (int4*)(ind + a.m_padded * g.T);
         a.rows16 = (uint16_t*)(a.ranges + g.img_tiles);
         a.zero_row_number = g.zero_row_number;
