@@ -387,8 +387,9 @@ static int launch_one(const Geometry& g, PatchArgs a, hipStream_t s)
         for (G = 1; G < a.T && (a.T % G || G * mfma_per_tap < 16); ++G) {}
     }
     if (G > a.T) G = a.T;
-    // Two workgroups per compute unit (on request): each gets half the LDS and a single patch / entry buffer, and
-    // covers the other's load bubbles, start-up and epilogue.  Otherwise one workgroup with double buffers.
+    // Two workgroups per compute unit (64-wide tiles and tiles with four consumer wavefronts, when they fit; or on
+    // request): each gets half the LDS and a single patch / entry buffer, and covers the other's load bubbles,
+    // start-up and epilogue.  Otherwise one workgroup with double buffers.
     // Ring depth.  A copy takes on the order of a microsecond from issue to completion under load, a stage far
     // less, and a stage's filter tiles must be issued ring - 1 stages ahead: as deep as fits (LDS, enough stages
     // left to spread the shares over), at most 8; when LDS is short, kernel elements per stage go before depth.
