@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void k_igemm_generic(GenericArgs g)
 int launch_igemm_generic(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                          const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s)
 {
-    GenericArgs a;
+    GenericArgs a{};      // every field starts at zero; the ones this call uses are set below
     a.a = input; a.w = packed; a.ind = ind; a.zero_row = zero_row; a.out = out;
     a.M = g.M; a.K = p->K; a.T = g.T; a.C = p->C;
     a.in_stride = g.in_stride; a.out_stride = g.out_stride;

@@ -311,7 +311,7 @@ __global__ __launch_bounds__(256 * TEAMS) void k_igemm_lowc(LowcArgs g)
 int launch_igemm_lowc(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                       const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s)
 {
-    LowcArgs a;
+    LowcArgs a{};      // every field starts at zero; the ones this call uses are set below
     a.a = (const uint8_t*)input;
     a.zero_row = (const uint8_t*)zero_row;
     a.w = (const uint8_t*)packed;

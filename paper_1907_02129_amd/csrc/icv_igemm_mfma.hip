@@ -579,7 +579,7 @@ int launch_igemm_mfma(const icv_conv_params* p, const Geometry& g, const void* i
     // the host-side table and the instantiations above must describe the same tiles
     const TileVariant& tv = kTileVariants[g.variant];
     if (tv.MR != g.MR || tv.NR != g.NR) return ICV_ERR_UNSUPPORTED;
-    IgemmArgs a;
+    IgemmArgs a{};      // every field starts at zero; the ones this call uses are set below
     a.a = (const uint8_t*)input;
     a.zero_row = (const uint8_t*)zero_row;
     a.w = (const uint8_t*)packed;

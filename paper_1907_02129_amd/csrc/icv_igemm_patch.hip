@@ -484,7 +484,7 @@ int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* 
     int shift = 0;
     while ((1ll << shift) < stride_bytes) ++shift;
     if ((1ll << shift) != stride_bytes) return ICV_ERR_UNSUPPORTED;
-    PatchArgs a;
+    PatchArgs a{};      // every field starts at zero; the ones this call uses are set below
     a.a = (const uint8_t*)input;
     a.w = (const uint8_t*)packed;
     // the buffer: int32 entries, then the tiles' range records, then the entries as 16-bit patch row numbers

@@ -85,7 +85,7 @@ int launch_pack_filter(const icv_conv_params* p, const Geometry& g, const void* 
         return ICV_OK;
     }
     if (g.kind == PLAN_MFMA) {
-        PackArgs a;
+        PackArgs a{};      // every field starts at zero; the ones this call uses are set below
         a.src = (const uint8_t*)filt;
         a.dst = (uint8_t*)packed;
         a.K = p->K; a.T = g.T; a.CB = (int32_t)CB;
@@ -213,7 +213,7 @@ __global__ __launch_bounds__(256) void k_build_indirection(IndArgs a)
 
 int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_t* ind, hipStream_t s)
 {
-    IndArgs a;
+    IndArgs a{};      // every field starts at zero; the ones this call uses are set below
     a.ind = ind;
     // a batch-independent buffer holds the entries of one image (batch index 0); img_rows = M otherwise
     a.M = g.img_rows; a.m_padded = g.img_tiles * g.MR;
@@ -313,7 +313,7 @@ __global__ __launch_bounds__(256) void k_im2col_lowc(Im2colArgs a, int KP)
 
 int launch_im2col(const icv_conv_params* p, const Geometry& g, const void* input, void* ws, hipStream_t s)
 {
-    Im2colArgs a;
+    Im2colArgs a{};      // every field starts at zero; the ones this call uses are set below
     a.in = (const uint8_t*)input;
     a.ws = (uint8_t*)ws;
     a.M = g.M; a.m_padded = g.m_tiles * g.MR;
