@@ -261,3 +261,35 @@ def test_model_layer_lists_match_the_papers_table_2():
     first = resnet18_layers(1)[0]
     assert icv.output_size(icv.make_params(first)) == (112, 112)
     assert icv.output_size(icv.make_params(squeezenet10_layers(1)[0])) == (109, 109)
+
+
+def test_random_plans_and_shapes_never_confuse_the_host_logic(lib):
+    """Every (shape, plan) pair is either refused as a whole or gets a kernel name and consistent buffer sizes;
+    the tile the sizes are computed for is the one the index function reports."""
+    import numpy as np
+    from paper_1907_02129_amd.workloads import random_small_shape
+    rng = np.random.default_rng(99)
+    seen = set()
+    for i in range(400):
+        dtype = ("f32", "bf16", "u8i8")[i % 3]
+        s = random_small_shape(rng, dtype, c_mult=(1, 32, 64)[i % 3] if i % 2 else 4, max_hw=40, max_ck=4)
+        s = s.with_(N=int(rng.integers(1, 40)))
+        plan = int(rng.integers(0, 1 << 18))
+        p = icv.make_params(s, plan=plan)
+        name = icv.plan_name(p)
+        sizes = (icv.indirection_bytes(p), icv.packed_filter_bytes(p), icv.zero_row_bytes(p))
+        if not name:
+            assert sizes == (0, 0, 0), (s, plan, sizes)
+            continue
+        seen.add(name.split("_")[0])
+        Hout, Wout = icv.output_size(p)
+        T = s.R * s.S
+        rows = Hout * Wout * (1 if (plan >> 17) & 1 and not name.startswith("gemm_") else s.N)
+        assert all(v > 0 for v in sizes)
+        assert sizes[0] >= 4 * rows * T and sizes[0] % 4 == 0
+        assert icv.indirection_index(p, 0, 0) == 0
+        assert icv.indirection_index(p, rows - 1, T - 1) >= 0
+        if T > 1:
+            mr = icv.indirection_index(p, 0, 1)
+            assert mr in (64, 128, 256) and sizes[0] >= 4 * (-(-rows // mr) * mr) * T
+    assert {"generic", "mfma"} <= seen
