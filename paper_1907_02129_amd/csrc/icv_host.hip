@@ -185,7 +185,10 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         order[n_order++] = 2;                                                        // 256 x 64, 64 x 64 blocks
         order[n_order++] = 3;                                                        // 256 x 64, 64 x 32 blocks
     } else {
-        if (!plan_per_image && tiles_of(256, 128) >= kCus) order[n_order++] = 6;     // 256 x 128
+        // 256 x 128 when every compute unit gets one -- but not when some get a second one and others none
+        // (between one and two rounds): 128 x 128 tiles then spread the same work more evenly (measured)
+        const int64_t t6 = tiles_of(256, 128);
+        if (!plan_per_image && t6 >= kCus && !(t6 > kCus && t6 <= 2 * kCus)) order[n_order++] = 6;     // 256 x 128
         order[n_order++] = 7;                                                        // 128 x 128, 32 x 64 blocks
         order[n_order++] = 1;                                                        // 128 x 128, 64 x 64 blocks
     }
