@@ -449,6 +449,28 @@ def test_batch_independent_buffer_with_fused_output_and_pixel_strides():
     assert err <= TOL["bf16"], err
 
 
+# ---------------------------------------------------------------- one zero row for several operators
+def test_one_zero_row_shared_by_operators_of_different_width():
+    """Section 2.3: the explicit zero vector need not be contiguous with the input and can be shared between
+    convolution operators.  One zero row, sized for the widest operator, serves three of them (the kernels that
+    gather rows per kernel element and the vector-ALU kernel fetch it for every padding entry)."""
+    shapes = [ConvShape("zr_c128", 2, 11, 13, 128, 48, 3, 3, PT=2, PL=2, PB=2, PR=2, seed=141),
+              ConvShape("zr_c64", 1, 9, 17, 64, 72, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, seed=142),
+              ConvShape("zr_c32", 3, 7, 7, 32, 40, 5, 5, PT=2, PL=2, PB=2, PR=2, seed=143)]
+    widest = max(shapes, key=lambda s: s.C)
+    zero_row = torch.empty(icv.zero_row_bytes(icv.make_params(widest)), dtype=torch.uint8, device="cuda:0")
+    icv.init_zero_row(icv.make_params(widest), zero_row)
+    for plan in (1 << 12, 1):                                  # gathered tensor-core kernel, vector-ALU kernel
+        for s in shapes:
+            x, w = make_tensors(s)
+            buf = icv.prepare(s, icv.to_device(w), plan=plan)
+            _say("shared zero row", s.name, icv.plan_name(buf.p))
+            buf.zero_row.fill_(0x7f)                           # the operator's own zero row is not the one used
+            icv.conv2d_nhwc(buf.p, icv.to_device(x), buf.packed, buf.indirection, zero_row, buf.output)
+            torch.cuda.synchronize()
+            check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+
+
 # ---------------------------------------------------------------- launches captured into a HIP graph
 @pytest.mark.parametrize("s", [
     ConvShape("h_patch", 3, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=121),
