@@ -194,6 +194,7 @@ def layer_sweep(icv, torch, N):
     layers, ratios = {}, {}
     for model, fn in (("resnet18", resnet18_layers), ("squeezenet10", squeezenet10_layers)):
         for sh in fn(N):
+            sh = icv.stored_for_tensor_cores(sh)       # 3 -> 4 and 48 -> 64 channels, zeros in the padding
             pp = icv.make_params(sh)
             ho, wo = icv.output_size(pp)
             nsets = min(sets_for_cold(sh, ho, wo), 12)

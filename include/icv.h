@@ -59,7 +59,7 @@ typedef struct icv_conv_params {
     int32_t N, Hin, Win, C, K, R, S;
     int32_t SY, SX, DY, DX;
     int32_t PT, PL, PB, PR;    /* implicit zero padding: top, left, bottom, right */
-    int32_t in_pixel_stride;   /* elements between input pixels;  0 means C ("rows can optionally be strided") */
+    int32_t in_pixel_stride;   /* elements between input pixels;  0 means C (section 2.3: input rows may be strided) */
     int32_t out_pixel_stride;  /* elements between output pixels; 0 means K (ldc of Listing 3)                 */
     int32_t dtype;             /* icv_dtype */
     int32_t input_zero_point;  /* ICV_U8I8 only: the value the zero row holds, 0..255 */
@@ -102,13 +102,44 @@ ICV_API size_t icv_zero_row_bytes(const icv_conv_params* p);
 ICV_API size_t icv_im2col_bytes(const icv_conv_params* p);
 
 /*
- * Where the entry of output pixel m = (n*Hout + oy)*Wout + ox and kernel element tap = ky*S + kx sits in
- * the indirection buffer (index in int32 units).  The physical order is [row tile][tap][row in tile], the
- * order in which Listing 3 consumes pointers (*ppa++: all rows of the tile for one tap, then the next tap).
- * Rows past M in the last tile name the zero row.  Returns -1 on invalid arguments.  With plan bit 17 the buffer
- * describes one image: m = oy*Wout + ox < Hout*Wout.
+ * Where the entry of output pixel m = (n*Hout + oy)*Wout + ox and kernel element tap = ky*S + kx sits among the
+ * entries of the indirection buffer (index in entries, see icv_get_indirection_layout).  The physical order is
+ * [row tile][tap][row in tile], the order in which Listing 3 consumes pointers (*ppa++: all rows of the tile for one
+ * tap, then the next tap).  Rows past M in the last tile name the zero row.  Returns -1 on invalid arguments.  With
+ * plan bit 17 the buffer describes one image: m = oy*Wout + ox < Hout*Wout.
  */
 ICV_API int64_t icv_indirection_index(const icv_conv_params* p, int64_t m, int32_t tap);
+
+/*
+ * How icv_setup_indirection lays the buffer out for this problem (section 2.3 fixes what an entry means, not how
+ * it is stored).  All offsets are bytes from the start of the buffer.
+ *   entry_bytes 4: entries are int32 byte offsets of the pixel row from the input base, INT32_MIN = the zero row.
+ *   entry_bytes 2: entries are uint16 pixel numbers counted from their row tile's base, `zero_code` = the zero row;
+ *                  every row tile has a 16-byte record {int32 base byte offset, int32 pixels from the base to the
+ *                  tile's largest valid entry (0: not recorded), int32 base pixel index (0: not recorded), 0}, and
+ *                  entry e names the pixel row at byte offset  base byte offset + e * pixel stride in bytes.
+ * `entries_at` / `entry_bytes` describe the form the convolution kernel of this plan reads; plans that keep the
+ * int32 form beside a 2-byte form report where it starts in `int32_entries_at` (-1: not built).
+ */
+typedef struct icv_indirection_layout {
+    int32_t tile_rows;         /* output pixels per row tile */
+    int32_t entry_bytes;       /* 4 or 2 */
+    int32_t zero_code;         /* 2-byte entries: the value that names the zero row */
+    int32_t record_bytes;      /* 16 when the tiles have records, else 0 */
+    int64_t tiles;             /* row tiles the buffer describes */
+    int64_t entries_at;
+    int64_t records_at;        /* -1 without records */
+    int64_t int32_entries_at;  /* -1 when the int32 form is not built */
+} icv_indirection_layout;
+ICV_API int icv_get_indirection_layout(const icv_conv_params* p, icv_indirection_layout* layout);
+
+/*
+ * Closed-form bounds (host arithmetic) on the input pixels that the valid entries of output pixels m0..m1 name:
+ * *first is not above any of them, *last not below (pixel indices (n*Hin + iy)*Win + ix of the whole tensor).  Both
+ * are non-decreasing in m0 and m1, which is what lets a kernel keep a sliding window of input pixels while it walks
+ * the output pixels in order.  last - first + 1 <= icv_tile_span_bound(p, m1 - m0 + 1).
+ */
+ICV_API int icv_row_pixel_range(const icv_conv_params* p, int64_t m0, int64_t m1, int64_t* first, int64_t* last);
 
 /*
  * Upper bound on the number of consecutive input pixels that the valid entries of any `rows` consecutive

@@ -5,8 +5,8 @@
  * tests, the smoke check and the benchmark's cpu_baseline leg may call it;
  * the product path never does, and this file shares no code with it.
  *
- * What it computes is the direct convolution of the paper's Listing 1
- * ("Implementation of Direct Convolution Algorithm as 7 nested loops"):
+ * What it computes is the direct convolution of the paper's Listing 1, seven
+ * nested loops:
  *
  *   out[n][oy][ox][oc] = sum over ky<R, kx<S, ic<C of
  *                        in[n][iy][ix][ic] * filt[oc][ky][kx][ic]

@@ -26,7 +26,8 @@ DTYPES = {"f32": ICV_F32, "bf16": ICV_BF16, "u8i8": ICV_U8I8}
 # every symbol include/icv.h declares
 EXPORTS = (
     "icv_output_size", "icv_indirection_bytes", "icv_packed_filter_bytes", "icv_zero_row_bytes",
-    "icv_im2col_bytes", "icv_indirection_index", "icv_tile_span_bound", "icv_init_zero_row", "icv_pack_filter",
+    "icv_im2col_bytes", "icv_indirection_index", "icv_get_indirection_layout", "icv_row_pixel_range",
+    "icv_tile_span_bound", "icv_init_zero_row", "icv_pack_filter",
     "icv_setup_indirection", "icv_conv2d_nhwc", "icv_conv2d_nhwc_fused", "icv_im2col", "icv_gemm_nhwc", "icv_conv2d_nhwc_im2col",
     "icv_plan_name", "icv_status_string", "icv_last_hip_error",
 )
@@ -52,6 +53,12 @@ class icv_epilogue(ctypes.Structure):
                 ("out_scale", ctypes.c_float), ("out_zero_point", ctypes.c_int32)]
 
 
+class icv_indirection_layout(ctypes.Structure):
+    _fields_ = [("tile_rows", ctypes.c_int32), ("entry_bytes", ctypes.c_int32), ("zero_code", ctypes.c_int32),
+                ("record_bytes", ctypes.c_int32), ("tiles", ctypes.c_int64), ("entries_at", ctypes.c_int64),
+                ("records_at", ctypes.c_int64), ("int32_entries_at", ctypes.c_int64)]
+
+
 ICV_OUT_ACC, ICV_OUT_BF16, ICV_OUT_U8 = 0, 1, 2
 
 _lib = None
@@ -75,6 +82,9 @@ def load_library(path: str | None = None):
         "icv_zero_row_bytes": (ctypes.c_size_t, [P]),
         "icv_im2col_bytes": (ctypes.c_size_t, [P]),
         "icv_indirection_index": (ctypes.c_int64, [P, ctypes.c_int64, ctypes.c_int32]),
+        "icv_get_indirection_layout": (ctypes.c_int, [P, ctypes.POINTER(icv_indirection_layout)]),
+        "icv_row_pixel_range": (ctypes.c_int, [P, ctypes.c_int64, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64),
+                                               ctypes.POINTER(ctypes.c_int64)]),
         "icv_tile_span_bound": (ctypes.c_int64, [P, ctypes.c_int32]),
         "icv_init_zero_row": (ctypes.c_int, [P, vp, vp]),
         "icv_pack_filter": (ctypes.c_int, [P, vp, vp, vp]),
@@ -158,6 +168,19 @@ def im2col_bytes(p) -> int:
 
 def indirection_index(p, m: int, tap: int) -> int:
     return load_library().icv_indirection_index(ctypes.byref(p), m, tap)
+
+
+def get_indirection_layout(p) -> icv_indirection_layout:
+    L = icv_indirection_layout()
+    _check(load_library().icv_get_indirection_layout(ctypes.byref(p), ctypes.byref(L)), "icv_get_indirection_layout")
+    return L
+
+
+def row_pixel_range(p, m0: int, m1: int):
+    a, b = ctypes.c_int64(), ctypes.c_int64()
+    _check(load_library().icv_row_pixel_range(ctypes.byref(p), m0, m1, ctypes.byref(a), ctypes.byref(b)),
+           "icv_row_pixel_range")
+    return a.value, b.value
 
 
 def tile_span_bound(p, rows: int) -> int:
@@ -255,43 +278,19 @@ def run(buf: ConvBuffers, input_dev: torch.Tensor) -> torch.Tensor:
     return buf.output
 
 
-def tile_ranges(buf: ConvBuffers):
-    """What the pixel-range plans append to the entries: (range records (tiles, 4) int32, row numbers
-    (tiles, T, MR) uint16), or None for other plans."""
-    p = buf.p
-    T = p.R * p.S
-    phys = buf.indirection.cpu().numpy()
-    # the index function shows the tile height where there are several kernel elements; with one the order is the
-    # identity for every height, and the height is the one that explains the buffer's size
-    heights = (indirection_index(p, 0, 1),) if T > 1 else (64, 128, 256)
-    for mr in heights:
-        tiles = -(-buf.M // mr)
-        n = tiles * mr * T
-        rest = phys[n:]
-        if len(rest) == tiles * 4 + n // 2:
-            return rest[:tiles * 4].reshape(tiles, 4), rest[tiles * 4:].view(np.uint16).reshape(tiles, T, mr)
-    return None
-
-
-def logical_indirection(buf: ConvBuffers) -> np.ndarray:
-    """The buffer re-ordered to [M][R*S] through icv_indirection_index, with the byte offsets turned back
-    into pixel indices (-1 = zero row); host side, for tests.  Returns (rows < M, tile-padding rows)."""
-    p = buf.p
-    T = p.R * p.S
-    phys = buf.indirection.cpu().numpy()
-    # the layout is [tile][tap][MR] (range records may follow); recover MR from the index function
-    # (with a single kernel element the order is the identity and no records follow)
-    if T > 1:
-        mr = indirection_index(p, 0, 1)
+def stored_for_tensor_cores(shape):
+    """The shape as its tensors would be kept in memory for the 16-bit / 8-bit tensor-core kernels: 3 channels are
+    stored as 4 (an 8-byte pixel); counts that are neither 4, 8, 16 nor a multiple of 32 are rounded up to a
+    multiple of 32 (64-byte rows).  The padding channels of input and filter hold zeros and `c_logical` keeps the
+    real count (FLOPs are counted on it).  Shapes that need no padding are returned as they are; the unpadded shape
+    is always valid too and runs on the vector-ALU kernel."""
+    C = shape.C
+    if C == 3:
+        Cs = 4
+    elif C % 32 == 0 or C in (4, 8, 16):
+        Cs = C
     else:
-        compact = tile_ranges(buf)
-        mr = compact[1].size if compact is not None else len(phys)
-    tiles = -(-buf.M // mr)
-    phys = phys[:tiles * mr * T]
-    assert indirection_index(p, mr, 0) in (-1, mr * T) and indirection_index(p, 1, 0) == 1
-    logical = phys.reshape(tiles, T, mr).transpose(0, 2, 1).reshape(tiles * mr, T)
-    stride_bytes = (p.in_pixel_stride or p.C) * {ICV_F32: 4, ICV_BF16: 2, ICV_U8I8: 1}[p.dtype]
-    assert np.all((logical >= 0) | (logical == np.iinfo(np.int32).min))
-    assert np.all(logical[logical >= 0] % stride_bytes == 0)
-    logical = np.where(logical < 0, -1, logical // stride_bytes).astype(np.int32)
-    return logical[:buf.M], logical[buf.M:]
+        Cs = -(-C // 32) * 32
+    if Cs == C or shape.dtype == "f32":
+        return shape
+    return shape.with_(C=Cs, c_logical=C)

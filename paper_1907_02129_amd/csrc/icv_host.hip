@@ -1,5 +1,6 @@
 // Host side of libicv.so: argument validation, geometry / plan selection and the C entry points.
 #include "icv_internal.h"
+#include "icv_pixel_range.h"
 
 namespace icv {
 
@@ -50,11 +51,26 @@ int64_t tile_span_bound(const icv_conv_params* p, int64_t Hout, int64_t Wout, in
         if (niw > rows - 1) niw = rows - 1;
     }
     const int64_t walk = SX * (rows - 1) + nrw * (arw > SX ? arw - SX : 0) + niw * (aiw > SX ? aiw - SX : 0);
-    return walk + (int64_t)(p->R - 1) * p->DY * Win + (int64_t)(p->S - 1) * p->DX + 1;
+    // The closed-form window ends of icv_pixel_range.h are clamped into the image, which can move them away from the
+    // unclipped positions when the padding exceeds the kernel's reach: the lower end by at most `lo`, the upper by `hi`.
+    const int64_t x0max = (Wout - 1) * SX - p->PL, x1min = (int64_t)(p->S - 1) * p->DX - p->PL;
+    int64_t lo = x0max - (Win - 1), hi = -x1min;
+    const int64_t below = ((Hout - 1) * SY - p->PT) * Win + x0max - Hin * Win + 1;
+    const int64_t above = ((int64_t)p->PT - (int64_t)(p->R - 1) * p->DY) * Win - x1min;
+    lo = lo > below ? lo : below;
+    hi = hi > above ? hi : above;
+    return walk + (int64_t)(p->R - 1) * p->DY * Win + (int64_t)(p->S - 1) * p->DX + 1 + (lo > 0 ? lo : 0) + (hi > 0 ? hi : 0);
 }
 
 static const char* kGenericNames[3] = {"generic_f32", "generic_bf16", "generic_u8i8"};
 static const char* kLowcNames[2] = {"mfma_bf16_lowc_64x64", "mfma_i8_lowc_64x64"};
+// filter in registers: [dtype][column blocks per workgroup 1, 2, 4][row blocks per wavefront and pass 1, 2]
+static const char* kFregNames[2][3][2] = {
+    {{"mfma_bf16_freg_w1m1", "mfma_bf16_freg_w1m2"}, {"mfma_bf16_freg_w2m1", "mfma_bf16_freg_w2m2"},
+     {"mfma_bf16_freg_w4m1", "mfma_bf16_freg_w4m2"}},
+    {{"mfma_i8_freg_w1m1", "mfma_i8_freg_w1m2"}, {"mfma_i8_freg_w2m1", "mfma_i8_freg_w2m2"},
+     {"mfma_i8_freg_w4m1", "mfma_i8_freg_w4m2"}},
+};
 static const char* kPatchNames[2][14] = {
     {"mfma_bf16_128x64_c2x2_patch", "mfma_bf16_128x128_c2x2_patch", "mfma_bf16_256x64_c4x1_patch", "mfma_bf16_256x64_c4x2_patch",
      "mfma_bf16_256x128_c2x2_patch", "mfma_bf16_64x64_c2x2_patch",
@@ -84,6 +100,8 @@ static const char* kMfmaNames[2][14] = {
      "mfma_i8_256x64_u4x2", "mfma_i8_128x64_u4x2"},
 };
 
+static const int64_t kCusHost = 256;      // compute units the plan is chosen for (the launchers ask the device)
+
 int make_geometry(const icv_conv_params* p, Geometry* g)
 {
     if (!p || !g) return ICV_ERR_INVALID_ARG;
@@ -103,7 +121,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
               plan_kcb = (p->plan >> 10) & 3, plan_staging = (p->plan >> 12) & 3, plan_group = (p->plan >> 14) & 7;
     const int plan_per_image = (p->plan >> 17) & 1;
     if (p->plan < 0 || p->plan >= (1 << 18) || plan_kernel > kNumTileVariants + 1 || plan_ring == 1 || plan_ring > 12 ||
-        plan_per_cu > 2 || plan_kcb > 2 || plan_staging > 2)
+        plan_per_cu > 2 || plan_kcb > 2)
         return ICV_ERR_INVALID_ARG;
 
     const int64_t Hout = out_extent(p->Hin, p->PT, p->PB, p->DY, p->R, p->SY);
@@ -228,11 +246,48 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         // a workgroup keeps two tiles' worth of entries in LDS: 2 * MR*T int32 (plus padding)
         if (!patch_rows && (int64_t)kTileVariants[variant].MR * T * 4 > 24 * 1024) mfma_ok = false;
     }
+    // Filter in registers, input window in an LDS ring (plan staging 3 forces it): kernel sizes and row widths the
+    // kernel is instantiated for, a whole-batch buffer, a window of two passes that fits LDS, 16-bit pixel numbers
+    // per 32-row block, and -- unless forced -- at least one full pass per workgroup.
+    int freg_wn = 0, freg_mb = 0, freg_ring = 0;
+    if (p->dtype != ICV_F32 && !(p->dtype == ICV_U8I8 && p->input_zero_point != 128) && plan_kernel == 0 &&
+        (plan_staging == 0 || plan_staging == 3) && !plan_per_image && row_bytes % 32 == 0 && stride_bytes % 16 == 0 &&
+        freg_shape_supported((int)T, (int)(row_bytes / 32)) && tile_span_bound(p, Hout, Wout, 32) < 65535) {
+        const int wn = p->K <= 32 ? 1 : (p->K <= 64 ? 2 : 4);
+        const int64_t n_blocks = (M + 31) / 32, n_cg = (p->K + 32 * wn - 1) / (32 * wn);
+        const int64_t ranges = kCusHost / n_cg > 0 ? kCusHost / n_cg : 1;
+        for (int mb = 2; mb >= 1 && !freg_mb; --mb) {
+            const int pbk = (4 / wn) * mb;
+            const int64_t need = tile_span_bound(p, Hout, Wout, 2 * pbk * 32) + 16;     // + what a 1 KB copy overshoots
+            int64_t ring = 64;
+            while (ring < need) ring *= 2;
+            if (ring > (1 << 20) || freg_lds_bytes((int)T, (int)(row_bytes / 32), pbk, (int)ring) > 160 * 1024) continue;
+            if (plan_staging != 3 && n_blocks < ranges * pbk) continue;
+            freg_wn = wn; freg_mb = mb; freg_ring = (int)ring;
+        }
+        if (!freg_mb && plan_staging == 3) return ICV_ERR_UNSUPPORTED;
+    } else if (plan_staging == 3) {
+        return ICV_ERR_UNSUPPORTED;
+    }
     // very short rows (first-layer convolutions): the whole reduction of a tile is gathered at once
     const bool lowc_ok = p->dtype != ICV_F32 && plan_kernel == 0 &&
                          (row_bytes == 8 || row_bytes == 16 || row_bytes == 32) && stride_bytes % row_bytes == 0 &&
                          T * row_bytes <= 608 && !(p->dtype == ICV_U8I8 && p->input_zero_point != 128);
-    if (lowc_ok) {
+    g->freg_wn = freg_wn; g->freg_mb = freg_mb; g->freg_ring = freg_ring;
+    if (freg_mb) {
+        g->kind = PLAN_MFMA_FREG;
+        g->variant = -1;
+        g->MR = 32;
+        g->NR = 32 * freg_wn;
+        g->KCB = (int32_t)row_bytes;
+        g->ring = 0;
+        g->blocks_per_cu = 0;
+        g->stages_per_tap = 1;
+        g->taps_per_stage = 1;
+        g->n_stages = g->T;
+        g->zero_row_number = 0xFFFFu;
+        g->name = kFregNames[p->dtype == ICV_U8I8 ? 1 : 0][freg_wn == 4 ? 2 : freg_wn - 1][freg_mb - 1];
+    } else if (lowc_ok) {
         g->kind = PLAN_MFMA_LOWC;
         g->variant = -1;
         g->MR = 64;
@@ -302,13 +357,22 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
 
 static bool aligned16(const void* ptr) { return ((uintptr_t)ptr & 15u) == 0; }
 
-// The ablation path has no indirection buffer: it always tiles the whole batch.
+// The ablation path has no indirection buffer, so it tiles the whole batch as one image.  The tile, stage width and
+// stage order stay those of the problem's own plan (batch-independent buffer or not), because the packed filter the
+// caller passes was laid out by icv_pack_filter for exactly that plan.
 static int make_ablation_geometry(const icv_conv_params* p, Geometry* g)
 {
-    if (!p) return ICV_ERR_INVALID_ARG;
-    icv_conv_params q = *p;
-    q.plan &= ~(1 << 17);
-    return make_geometry(&q, g);
+    const int st = make_geometry(p, g);
+    if (st != ICV_OK) return st;
+    // the packed filter of the filter-in-registers plan is laid out for that kernel alone; the ablation takes a plan
+    // whose filter the plain GEMM kernels read (plan staging 1 or 2)
+    if (g->kind == PLAN_MFMA_FREG) return ICV_ERR_UNSUPPORTED;
+    g->per_image = 0;
+    g->img_rows = g->M;
+    g->img_tiles = (g->M + g->MR - 1) / g->MR;
+    g->m_tiles = g->img_tiles;
+    g->image_bytes = 0;
+    return ICV_OK;
 }
 
 }  // namespace icv
@@ -331,8 +395,10 @@ size_t icv_indirection_bytes(const icv_conv_params* p)
 {
     Geometry g;
     if (make_geometry(p, &g) != ICV_OK) return 0;
-    // entries, then (pixel-range plans) one 16-byte range record per row tile and the entries as 16-bit row numbers
     const size_t n = (size_t)g.img_tiles * g.MR * g.T;
+    // block form: a 16-byte record per block, then 16-bit entries
+    if (g.kind == PLAN_MFMA_FREG) return (size_t)g.img_tiles * 16 + n * sizeof(uint16_t);
+    // entries, then (pixel-range plans) one 16-byte range record per row tile and the entries as 16-bit row numbers
     return n * sizeof(int32_t) + (g.patch_rows ? (size_t)g.img_tiles * 16 + n * sizeof(uint16_t) : 0);
 }
 
@@ -368,6 +434,40 @@ int64_t icv_indirection_index(const icv_conv_params* p, int64_t m, int32_t tap)
     return (m / g.MR) * ((int64_t)g.T * g.MR) + (int64_t)tap * g.MR + m % g.MR;
 }
 
+int icv_get_indirection_layout(const icv_conv_params* p, icv_indirection_layout* L)
+{
+    Geometry g;
+    const int st = make_geometry(p, &g);
+    if (st != ICV_OK) return st;
+    if (!L) return ICV_ERR_INVALID_ARG;
+    const int64_t n = g.img_tiles * g.MR * (int64_t)g.T;
+    L->tile_rows = g.MR;
+    L->tiles = g.img_tiles;
+    if (g.kind == PLAN_MFMA_FREG) {
+        L->entry_bytes = 2; L->zero_code = 0xFFFF; L->record_bytes = 16;
+        L->records_at = 0; L->entries_at = g.img_tiles * 16; L->int32_entries_at = -1;
+    } else if (g.patch_rows) {
+        L->entry_bytes = 2; L->zero_code = (int32_t)g.zero_row_number; L->record_bytes = 16;
+        L->int32_entries_at = 0; L->records_at = n * 4; L->entries_at = n * 4 + g.img_tiles * 16;
+    } else {
+        L->entry_bytes = 4; L->zero_code = 0; L->record_bytes = 0;
+        L->int32_entries_at = 0; L->records_at = -1; L->entries_at = 0;
+    }
+    return ICV_OK;
+}
+
+int icv_row_pixel_range(const icv_conv_params* p, int64_t m0, int64_t m1, int64_t* first, int64_t* last)
+{
+    Geometry g;
+    const int st = make_geometry(p, &g);
+    if (st != ICV_OK) return st;
+    if (m0 < 0 || m1 < m0 || m1 >= g.M || !first || !last) return ICV_ERR_INVALID_ARG;
+    const RangeGeom q{p->Hin, p->Win, g.Hout, g.Wout, p->SY, p->SX, p->DY, p->DX, p->PT, p->PL, p->R, p->S};
+    *first = lowest_pixel_from(q, decompose(q, (uint32_t)m0));
+    *last = highest_pixel_upto(q, decompose(q, (uint32_t)m1));
+    return ICV_OK;
+}
+
 int64_t icv_tile_span_bound(const icv_conv_params* p, int32_t rows)
 {
     Geometry g;
@@ -389,7 +489,7 @@ int icv_pack_filter(const icv_conv_params* p, const void* filter_krsc, void* pac
     Geometry g;
     const int st = make_geometry(p, &g);
     if (st != ICV_OK) return st;
-    if (!filter_krsc || !packed || !aligned16(packed)) return ICV_ERR_INVALID_ARG;
+    if (!filter_krsc || !packed || !aligned16(packed) || !aligned16(filter_krsc)) return ICV_ERR_INVALID_ARG;
     return launch_pack_filter(p, g, filter_krsc, packed, (hipStream_t)stream);
 }
 
@@ -405,6 +505,7 @@ int icv_setup_indirection(const icv_conv_params* p, void* indirection, void* str
 static int conv_common(const icv_conv_params* p, const Geometry& g, const void* a, const void* packed,
                        const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s)
 {
+    if (g.kind == PLAN_MFMA_FREG) return a_direct ? ICV_ERR_UNSUPPORTED : launch_igemm_freg(p, g, a, packed, ind, out, s);
     if (g.kind == PLAN_MFMA && g.patch_rows && !a_direct) return launch_igemm_patch(p, g, a, packed, ind, out, s);
     if (g.kind == PLAN_MFMA)
         return launch_igemm_mfma(p, g, a, packed, ind, zero_row, out,

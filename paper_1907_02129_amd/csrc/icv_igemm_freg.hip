@@ -1,0 +1,335 @@
+// Tensor-core Indirect GEMM with the filter held in registers and the input streamed through an LDS ring.
+//
+// Listing 3's loop nest (row block, kernel element, channels) is kept; what is chosen for gfx950 is where the two
+// operands live while a workgroup walks its share of the output:
+//
+//  * B, the filter.  A wavefront owns one block of 32 output channels and keeps that block's whole filter --
+//    R*S*C elements per channel, already in the operand layout of v_mfma_*_32x32x* -- in its registers for the
+//    lifetime of the kernel: T*KS fragments of four registers (T = R*S kernel elements, KS 32-byte steps per pixel
+//    row; 288 registers for a 3x3 kernel on 256-byte rows).  A compute unit's register file is three times its LDS;
+//    with one wavefront per SIMD the filter of a convolution layer fits there, is loaded once, and costs no LDS
+//    space, no LDS bandwidth and no synchronisation afterwards (section 3.1: the filter never changes, so it can be
+//    repacked once into whatever layout the kernel reads best).
+//  * A, the rows the indirection entries name.  The workgroup walks a contiguous range of output pixels, 32-row
+//    blocks grouped into passes.  The valid entries of consecutive output pixels name a window of consecutive input
+//    pixels that only moves forward (icv_pixel_range.h), so that window is kept in LDS as a ring of pixel rows: each
+//    input pixel is fetched from memory once per workgroup and then read by all R*S kernel elements of all the
+//    output pixels it contributes to (the re-use that section 3 lists as the method's second performance factor,
+//    organised explicitly).  The indirection buffer holds, per row block, a base pixel and per (row, kernel element) a
+//    16-bit pixel number counted from it (0xFFFF: the zero row, section 2.3); the kernel turns an entry into a ring
+//    row with one add and one mask.  Padding entries read a row of zeros kept after the ring.
+//
+// Four wavefronts, one per SIMD, WN column blocks x WM row groups; a pass is WM*MB row blocks.  All four take part in
+// copying the window of the NEXT pass (global -> LDS without a register stop) at the start of a pass, multiply the
+// current pass out of LDS, wait for their own copies, store the pass's outputs, and meet at the only barrier of the
+// pass.  The stores are not waited for until the end of the following pass, and the copies have a whole pass to
+// land, so loads, MFMAs and stores of neighbouring passes overlap inside one workgroup.
+//
+// uint8 activations: every A fragment is XORed with 0x80 (x -> x - 128 as a signed byte); the zero row holds 0x80.
+#include "icv_mfma_common.h"
+#include "icv_pixel_range.h"
+
+namespace icv {
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+struct FregArgs {
+    const uint8_t* a;          // input tensor
+    const uint8_t* w;          // packed filter [column block][fragment][lane][16 bytes]
+    const int4* rec;           // per row block: {base byte offset, 0, base pixel, 0}
+    const uint16_t* ent;       // [row block][kernel element][32]: pixel number from the block's base, 0xFFFF = zero row
+    void* out;
+    RangeGeom q;
+    int64_t M;
+    int32_t K, out_stride;
+    int32_t stride_bytes;      // bytes between input pixels
+    int32_t last_pixel;        // N*Hin*Win - 1
+    uint32_t n_blocks;         // row blocks of 32 output pixels
+    uint32_t ent_bytes;        // bytes of the entries (copies are clamped to them)
+    int32_t n_cg;              // column groups of WN column blocks
+    int32_t n_ranges;          // row ranges: workgroups per column group
+    int32_t xcd_mode;          // 1: XCD x (workgroups x, x + 8, ...) owns a contiguous run of row ranges, all column groups
+    int32_t ring_rows;         // pixel rows of the ring, a power of two and a multiple of 64
+    EpilogueArgs ep;
+};
+
+template <bool I8>
+__device__ inline typename Acc<I8>::type mfma_frag(const u32x4_t& a, const u32x4_t& b, typename Acc<I8>::type c)
+{
+    if constexpr (I8) {
+        const u32x4_t ax = a ^ 0x80808080u;
+        return __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4_t, ax), __builtin_bit_cast(i32x4_t, b), c, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+}
+
+constexpr int freg_slot_bytes(int T, int PBK) { return 1024 + (PBK * T * 64 + 1023) / 1024 * 1024; }
+
+template <bool I8, int T, int KS, int WN, int MB, bool FUSED>
+__global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
+{
+    constexpr int WM = 4 / WN;
+    constexpr int PBK = WM * MB;             // row blocks per pass
+    constexpr int NF = T * KS;               // filter fragments per column block
+    constexpr int PP = KS * 2 + 1;           // 16-byte pieces per ring row: the pixel's KS*32 bytes and one of padding,
+    constexpr int PITCH = PP * 16;           //   which spreads the fragment reads of 16 consecutive rows over all banks
+    constexpr int SLOT = freg_slot_bytes(T, PBK);     // one pass's block records (1 KB) and entries
+    constexpr int ECOP = (SLOT - 1024) / 1024;
+    using acc_t = typename Acc<I8>::type;
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
+    const uint32_t ring_rows = (uint32_t)g.ring_rows, ring_mask = ring_rows - 1;
+    const uint32_t ring_chunks = ring_rows * PP;                  // 16-byte pieces of the ring, a multiple of 64
+    const uint32_t zero_off = ring_chunks * 16;                   // the zero row
+    const uint32_t slot_off = (zero_off + PITCH + 1023) / 1024 * 1024;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lrow = lane & 31, lhalf = lane >> 5;
+
+    // ---- this workgroup's column group and row range
+    uint32_t cg, range;
+    {
+        const uint32_t b = blockIdx.x, n_cg = (uint32_t)g.n_cg;
+        if (g.xcd_mode) {
+            const uint32_t x = b & 7, i = b >> 3, per_xcd = gridDim.x >> 3;
+            cg = i % n_cg;
+            range = x * (per_xcd / n_cg) + i / n_cg;
+        } else {
+            cg = b % n_cg;
+            range = b / n_cg;
+        }
+    }
+    if (range >= (uint32_t)g.n_ranges) return;                    // the whole workgroup, before any barrier
+    const uint32_t rb_lo = (uint32_t)((uint64_t)range * g.n_blocks / (uint32_t)g.n_ranges);
+    const uint32_t rb_hi = (uint32_t)((uint64_t)(range + 1) * g.n_blocks / (uint32_t)g.n_ranges);
+    const int n_pass = (int)((rb_hi - rb_lo + PBK - 1) / PBK);
+    const uint32_t M = (uint32_t)g.M;
+    const int32_t origin = lowest_pixel_from(g.q, decompose(g.q, rb_lo * 32u));       // pixel of ring row 0
+
+    // copies that must have been issued before pass k is multiplied: everything up to the highest pixel its rows name
+    auto copies_upto_pass = [&](int k) -> uint32_t {
+        uint32_t blk_end = rb_lo + (uint32_t)(k + 1) * PBK;
+        if (blk_end > rb_hi) blk_end = rb_hi;
+        uint32_t m_end = blk_end * 32u;
+        if (m_end > M) m_end = M;
+        const int32_t top = highest_pixel_upto(g.q, decompose(g.q, m_end - 1u));
+        const uint32_t pixels = top >= origin ? (uint32_t)(top - origin) + 1u : 1u;
+        return (pixels * PP + 63u) / 64u;
+    };
+    // copy u: ring pieces 64u .. 64u + 63 (one wavefront-wide 1 KB copy); lane -> (pixel, piece of its row)
+    auto copy_ring = [&](uint32_t u) {
+        const uint32_t gch = u * 64u + (uint32_t)lane;
+        const uint32_t ps = gch / PP;
+        uint32_t piece = gch - ps * PP;
+        if (piece > PP - 2) piece = PP - 2;                       // the padding piece repeats the last one
+        uint32_t pix = (uint32_t)origin + ps;
+        if (pix > (uint32_t)g.last_pixel) pix = (uint32_t)g.last_pixel;      // never read past the tensor
+        const uint32_t dst = (uint32_t)__builtin_amdgcn_readfirstlane((int)(lds_base + ((u * 64u) % ring_chunks) * 16u));
+        copy16_global_to_lds(g.a, pix * (uint32_t)g.stride_bytes + piece * 16u, dst);
+    };
+    // my share of everything pass k needs beyond what earlier passes brought in
+    auto issue_pass = [&](int k, uint32_t from, uint32_t upto) {
+        const uint32_t slot = (uint32_t)__builtin_amdgcn_readfirstlane((int)(lds_base + slot_off + (uint32_t)(k & 1) * SLOT));
+        const uint32_t blk0 = rb_lo + (uint32_t)k * PBK;
+        if (wave == 0) {
+            uint32_t blk = blk0 + (uint32_t)lane;
+            if (blk > g.n_blocks - 1) blk = g.n_blocks - 1;
+            if (lane < PBK) copy16_global_to_lds(g.rec, blk * 16u, slot);
+        }
+        for (int e = 0; e < ECOP; e++)
+            if (((e + 1) & 3) == wave) {
+                uint32_t off = blk0 * (uint32_t)(T * 64) + (uint32_t)e * 1024u + (uint32_t)lane * 16u;
+                if (off > g.ent_bytes - 16u) off = g.ent_bytes - 16u;
+                copy16_global_to_lds(g.ent, off, slot + 1024u + (uint32_t)e * 1024u);
+            }
+        for (uint32_t u = from + ((uint32_t)wave - from) % 4u; u < upto; u += 4u) copy_ring(u);
+    };
+
+    // ---- start-up: the first pass's window, this wavefront's filter block, the zero row
+    uint32_t issued = copies_upto_pass(0);
+    issue_pass(0, 0u, issued);
+    const int c = wave % WN, h = wave / WN;
+    u32x4_t B[NF];
+    {
+        const u32x4_t* wp = (const u32x4_t*)(g.w + ((size_t)(cg * WN + c) * NF) * 1024) + lane;
+#pragma unroll
+        for (int f = 0; f < NF; f++) B[f] = wp[f * 64];
+    }
+    for (int i = tid; i < PITCH / 4; i += 256) *(uint32_t*)(lds + zero_off + i * 4) = I8 ? 0x80808080u : 0u;
+    // the filter registers are final from here on: the compiler must not keep a wait for these loads inside the loop
+#pragma unroll
+    for (int f = 0; f < NF; f++) asm volatile("" : : "v"(B[f]));
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    const int32_t col = (int32_t)(cg * WN + c) * 32 + lrow;
+    for (int k = 0; k < n_pass; k++) {
+        // the next pass's window: its copies land while this pass is multiplied (their ring rows and entry slot were
+        // last read in the pass before this one, which every wavefront has left)
+        if (k + 1 < n_pass) {
+            const uint32_t upto = copies_upto_pass(k + 1);
+            issue_pass(k + 1, issued, upto);
+            issued = upto > issued ? upto : issued;
+        }
+
+        const uint8_t* slot = lds + slot_off + (k & 1) * SLOT;
+        const uint16_t* ent = (const uint16_t*)(slot + 1024) + (h * MB) * (T * 32) + lrow;
+        int32_t delta[MB];
+#pragma unroll
+        for (int i = 0; i < MB; i++) delta[i] = *(const int32_t*)(slot + (h * MB + i) * 16 + 8) - origin;
+
+        acc_t acc[MB][1];
+#pragma unroll
+        for (int i = 0; i < MB; i++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[i][0][r] = 0;
+
+        // The reduction as one unrolled sequence of NF steps (kernel element tap = step / KS, 32-byte piece step % KS
+        // of its rows).  The wavefront is alone on its SIMD, so the latencies are hidden by software pipelining: a
+        // step's row numbers are read LA steps ahead, turned into LDS addresses LA - PF steps later, the A fragments
+        // are read PF steps ahead, and only then come the step's MFMAs.  The scheduling barriers keep the compiler
+        // from folding that order back into load-wait-multiply.
+        constexpr int PF = 2, LA = 4;
+        uint32_t e16[T][MB], addr[T][MB];                      // few of them are live at any time
+        u32x4_t af[PF + 1][MB];
+        auto read_rows = [&](int tap) {
+#pragma unroll
+            for (int i = 0; i < MB; i++) e16[tap][i] = ent[(i * T + tap) * 32];
+        };
+        auto locate = [&](int tap) {
+#pragma unroll
+            for (int i = 0; i < MB; i++) {
+                const uint32_t row = (e16[tap][i] + (uint32_t)delta[i]) & ring_mask;
+                addr[tap][i] = (e16[tap][i] == 0xFFFFu ? zero_off : row * PITCH) + (uint32_t)lhalf * 16u;
+            }
+        };
+        auto read_frags = [&](int st) {
+#pragma unroll
+            for (int i = 0; i < MB; i++) af[st % (PF + 1)][i] = *(const u32x4_t*)(lds + addr[st / KS][i] + (st % KS) * 32);
+        };
+#pragma unroll
+        for (int tap = 0; tap * KS < LA && tap < T; tap++) read_rows(tap);
+#pragma unroll
+        for (int tap = 0; tap * KS < LA && tap < T; tap++) locate(tap);
+#pragma unroll
+        for (int st = 0; st < PF && st < NF; st++) read_frags(st);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int st = 0; st < NF; st++) {
+            if ((st + LA) % KS == 0 && (st + LA) / KS < T) read_rows((st + LA) / KS);
+            if ((st + PF) % KS == 0 && (st + PF) / KS < T && (st + PF) >= LA) locate((st + PF) / KS);
+            if (st + PF < NF) read_frags(st + PF);
+#pragma unroll
+            for (int i = 0; i < MB; i++) acc[i][0] = mfma_frag<I8>(af[st % (PF + 1)][i], B[st], acc[i][0]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        // my copies for the next pass (issued a pass ago) and the stores of the pass before this one
+        wait_vmcnt<0>();
+        const uint32_t blk = rb_lo + (uint32_t)k * PBK + (uint32_t)(h * MB);
+        if (blk < rb_hi) {
+            uint32_t m_end = rb_hi * 32u;
+            if (m_end > M) m_end = M;
+            const int64_t m_base = (int64_t)blk * 32 + 4 * lhalf;
+            const bool whole = (blk + MB) * 32u <= m_end && (int32_t)(cg * WN + c + 1) * 32 <= g.K;
+            store_tile<FUSED, I8, MB, 1>(g.out, acc, (int64_t)m_end, g.K, g.out_stride, m_base, col, whole, g.ep);
+        }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    }
+}
+
+// ------------------------------------------------------------------ launch
+size_t freg_lds_bytes(int T, int KS, int PBK, int ring_rows)
+{
+    const size_t pitch = (size_t)(KS * 2 + 1) * 16;
+    const size_t zero_off = (size_t)ring_rows * pitch;
+    const size_t slot_off = (zero_off + pitch + 1023) / 1024 * 1024;
+    return slot_off + 2 * (size_t)freg_slot_bytes(T, PBK);
+}
+
+template <bool I8, int T, int KS, int WN, int MB, bool FUSED>
+static int launch_one(const FregArgs& a, int64_t grid, size_t lds_bytes, hipStream_t s)
+{
+    auto kern = k_igemm_freg<I8, T, KS, WN, MB, FUSED>;
+    if (lds_bytes > 64 * 1024) {
+        static bool raised[kMaxDevices] = {};      // one array per instantiation of this function template
+        const int st = allow_full_lds((const void*)kern, raised);
+        if (st != ICV_OK) return st;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds_bytes, s, a);
+    ICV_HIP_CHECK(hipGetLastError());
+    return ICV_OK;
+}
+
+template <bool I8, int T, int KS>
+static int launch_shape(const Geometry& g, const FregArgs& a, int64_t grid, size_t lds, hipStream_t s)
+{
+#define ICV_FREG_CASE(WN_, MB_)                                                                  \
+    if (g.freg_wn == WN_ && g.freg_mb == MB_)                                                    \
+        return g.ep_plain ? launch_one<I8, T, KS, WN_, MB_, false>(a, grid, lds, s)              \
+                          : launch_one<I8, T, KS, WN_, MB_, true>(a, grid, lds, s);
+    ICV_FREG_CASE(4, 2)
+    ICV_FREG_CASE(4, 1)
+    ICV_FREG_CASE(2, 2)
+    ICV_FREG_CASE(2, 1)
+    ICV_FREG_CASE(1, 2)
+    ICV_FREG_CASE(1, 1)
+#undef ICV_FREG_CASE
+    return ICV_ERR_UNSUPPORTED;
+}
+
+bool freg_shape_supported(int T, int KS) { return (T == 9 && (KS == 2 || KS == 4 || KS == 8)) || (T == 25 && KS == 2); }
+
+int launch_igemm_freg(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
+                      const int32_t* ind, void* out, hipStream_t s)
+{
+    if (g.kind != PLAN_MFMA_FREG || g.MR != 32) return ICV_ERR_UNSUPPORTED;
+    const int KS = g.KCB / 32, T = g.T;
+    if (!freg_shape_supported(T, KS)) return ICV_ERR_UNSUPPORTED;
+    FregArgs a{};      // every field starts at zero; the ones this call uses are set below
+    a.a = (const uint8_t*)input;
+    a.w = (const uint8_t*)packed;
+    a.rec = (const int4*)ind;
+    a.ent = (const uint16_t*)(a.rec + g.img_tiles);
+    a.out = out;
+    a.q = RangeGeom{p->Hin, p->Win, g.Hout, g.Wout, p->SY, p->SX, p->DY, p->DX, p->PT, p->PL, p->R, p->S};
+    a.M = g.M;
+    a.K = p->K; a.out_stride = g.out_stride;
+    a.stride_bytes = g.in_stride * g.elem_bytes;
+    a.last_pixel = (int32_t)((int64_t)p->N * p->Hin * p->Win - 1);
+    a.n_blocks = (uint32_t)g.img_tiles;
+    a.ent_bytes = (uint32_t)((size_t)g.img_tiles * T * 64);
+    a.ring_rows = g.freg_ring;
+    a.ep = g.ep;
+    const int WN = g.freg_wn, PBK = (4 / WN) * g.freg_mb;
+    a.n_cg = (int32_t)g.n_tiles;
+    // One workgroup per compute unit; the column groups share them.  A row range is at least one block.
+    const int cus = device_cu_count();
+    int64_t ranges = cus / a.n_cg;
+    if (ranges < 1) ranges = 1;
+    if (ranges > (int64_t)a.n_blocks) ranges = a.n_blocks;
+    int64_t grid = ranges * a.n_cg;
+    a.xcd_mode = 0;
+    if (ranges % 8 == 0) a.xcd_mode = 1;          // grid / 8 workgroups per XCD, a whole number of row ranges each
+    a.n_ranges = (int32_t)ranges;
+    const size_t lds = freg_lds_bytes(T, KS, PBK, a.ring_rows);
+    if (lds > kLdsPerCu || (a.ring_rows & (a.ring_rows - 1)) || a.ring_rows < 64) return ICV_ERR_UNSUPPORTED;
+    const bool i8 = p->dtype == ICV_U8I8;
+#define ICV_FREG_SHAPE(T_, KS_)                                                                   \
+    if (T == T_ && KS == KS_)                                                                     \
+        return i8 ? launch_shape<true, T_, KS_>(g, a, grid, lds, s) : launch_shape<false, T_, KS_>(g, a, grid, lds, s);
+    ICV_FREG_SHAPE(9, 8)
+    ICV_FREG_SHAPE(9, 4)
+    ICV_FREG_SHAPE(9, 2)
+    ICV_FREG_SHAPE(25, 2)
+#undef ICV_FREG_SHAPE
+    return ICV_ERR_UNSUPPORTED;
+}
+
+}  // namespace icv

@@ -367,13 +367,9 @@ int launch_igemm_lowc(const icv_conv_params* p, const Geometry& g, const void* i
     do {                                                                                                        \
         auto kern = g.ep_plain ? k_igemm_lowc<I8, U, false, TEAMS> : k_igemm_lowc<I8, U, true, TEAMS>;          \
         if (lds_bytes > 64 * 1024) {                                                                            \
-            static bool raised_both[2] = {false, false};     /* one flag per instantiation */                  \
-            bool& raised = raised_both[g.ep_plain ? 0 : 1];                                                     \
-            if (!raised) {                                                                                      \
-                ICV_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                                  (int)kLdsPerCu));                                             \
-                raised = true;                                                                                  \
-            }                                                                                                   \
+            static bool raised[2][kMaxDevices] = {};         /* per instantiation and device */                \
+            const int st_ = allow_full_lds((const void*)kern, raised[g.ep_plain ? 0 : 1]);                      \
+            if (st_ != ICV_OK) return st_;                                                                      \
         }                                                                                                       \
         hipLaunchKernelGGL(kern, grid, dim3(256 * TEAMS), lds_bytes, s, a);                                     \
     } while (0)

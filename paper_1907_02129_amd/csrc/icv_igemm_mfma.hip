@@ -511,12 +511,9 @@ static int launch_one(const Geometry& g, IgemmArgs a, hipStream_t s)
         a.xcd_mode = 1;
     }
     if (lds_bytes > 64 * 1024) {
-        static bool raised = false;   // idempotent attribute; a race only repeats the call
-        if (!raised) {
-            ICV_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                              (int)kLdsPerCu));
-            raised = true;
-        }
+        static bool raised[kMaxDevices] = {};      // one array per instantiation of this function template
+        const int st = allow_full_lds((const void*)kern, raised);
+        if (st != ICV_OK) return st;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(threads), lds_bytes, s, a);
     ICV_HIP_CHECK(hipGetLastError());

@@ -12,7 +12,8 @@ enum PlanKind : int32_t {
     PLAN_INVALID = 0,
     PLAN_GENERIC = 1,   // vector-ALU kernel, any C, any dtype
     PLAN_MFMA = 2,      // tensor-core indirect GEMM, C a multiple of the k-granule
-    PLAN_MFMA_LOWC = 3  // tensor-core indirect GEMM for pixel rows of 8, 16 or 32 bytes (first-layer convolutions)
+    PLAN_MFMA_LOWC = 3, // tensor-core indirect GEMM for pixel rows of 8, 16 or 32 bytes (first-layer convolutions)
+    PLAN_MFMA_FREG = 4  // tensor-core indirect GEMM with the filter in registers and the input window in an LDS ring
 };
 
 // Output stage of icv_conv2d_nhwc_fused, as the kernels see it (icv_epilogue with the bias pointer typed by use).
@@ -28,15 +29,14 @@ struct EpilogueArgs {
 // per column, see output_bias).  `idx` counts elements of the output type.  All branches are uniform.
 __device__ inline void emit_output(void* out, int64_t idx, float v, const EpilogueArgs& e)
 {
-    v = fmaxf(v, e.relu ? 0.0f : -__builtin_inff());
+    if (e.relu) v = v > 0.0f ? v : 0.0f;      // a select, and only with ReLU: a NaN accumulator stays NaN otherwise
     if (e.out_kind == ICV_OUT_BF16) ((__bf16*)out)[idx] = (__bf16)v;     // hardware conversion: nearest, ties to even
     else ((float*)out)[idx] = v;
 }
 
 __device__ inline void emit_output(void* out, int64_t idx, int32_t v, const EpilogueArgs& e)
 {
-    const int32_t lo = e.relu ? 0 : INT32_MIN;
-    v = v > lo ? v : lo;
+    if (e.relu) v = v > 0 ? v : 0;
     if (e.out_kind == ICV_OUT_U8) {
         // clamp(rint((float)v * scale) + zero point, 0, 255); single-precision product, ties to even
         float r = rintf(__fmul_rn((float)v, e.scale));
@@ -86,6 +86,8 @@ struct Geometry {
                              // (short-row plan: > 0 when the buffer also holds the compact 16-bit entries)
     uint32_t zero_row_number;   // what the 16-bit entries hold for the zero row
     int32_t cc_major;        // 1: stage = chunk * T + tap (channel chunks outermost), 0: stage = tap * chunks + chunk
+    // filter-in-registers plan: column blocks per workgroup (1, 2, 4), row blocks per wavefront and pass, ring rows
+    int32_t freg_wn, freg_mb, freg_ring;
     const char* name;
     EpilogueArgs ep;         // output stage of this call (plain: no bias, no ReLU, accumulator type)
     bool ep_plain;
@@ -124,6 +126,10 @@ int launch_igemm_mfma(const icv_conv_params* p, const Geometry& g, const void* i
 int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                        const int32_t* ind, void* out, hipStream_t s);
 bool patch_variant_supported(int variant);
+int launch_igemm_freg(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
+                      const int32_t* ind, void* out, hipStream_t s);
+bool freg_shape_supported(int T, int KS);
+size_t freg_lds_bytes(int T, int KS, int PBK, int ring_rows);
 size_t patch_lds_bytes(int NR, int KCB, int ring, int cap_units, int ent_copies, int nbuf);
 int launch_igemm_lowc(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                       const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s);

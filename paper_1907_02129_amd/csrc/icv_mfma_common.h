@@ -38,6 +38,9 @@ __device__ inline typename Acc<I8>::type mfma32(const uint4& a, const uint4& b, 
 // [lds_base + 16*l, +16).  Inline assembly on purpose: the compiler does not see a memory instruction, so it
 // inserts no waits of its own for it, and the producers count outstanding copies themselves (wait_vmcnt).
 // A producer issues no other vector-memory instruction while copies are in flight.
+// M0 is written here without being listed as clobbered: the compiler treats it as a reserved register (naming it in
+// the clobber list is diagnosed as such), never keeps a value in it across other code, and writes it itself right
+// before each of its own instructions that read it.
 __device__ inline void copy16_global_to_lds(const void* gptr, uint32_t lds_base)
 {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n"
@@ -107,9 +110,8 @@ __device__ inline void store_tile_as(void* outp, const ACC (&acc)[MB][NB], int64
             return v;
         }
     };
-    OUT_ACC lo;
-    if constexpr (std::is_integral<OUT_ACC>::value) lo = FUSED && ep.relu ? 0 : INT32_MIN;
-    else lo = FUSED && ep.relu ? 0.0f : -__builtin_inff();
+    // ReLU as a select that runs only when asked for: without it a NaN accumulator stays NaN on every path
+    const bool relu = FUSED && ep.relu;
 #pragma unroll
     for (int i = 0; i < MB; i++)
 #pragma unroll
@@ -122,7 +124,7 @@ __device__ inline void store_tile_as(void* outp, const ACC (&acc)[MB][NB], int64
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     OUT_ACC v = (OUT_ACC)acc[i][j][r];
-                    if constexpr (FUSED) { v += bias; v = v > lo ? v : lo; }
+                    if constexpr (FUSED) { v += bias; if (relu) v = v > (OUT_ACC)0 ? v : (OUT_ACC)0; }
                     __builtin_nontemporal_store(convert(v), &o[(int64_t)(8 * (r >> 2) + (r & 3)) * out_stride]);
                 }
             } else {
@@ -130,7 +132,7 @@ __device__ inline void store_tile_as(void* outp, const ACC (&acc)[MB][NB], int64
                 for (int r = 0; r < 16; r++) {
                     const int64_t row = m_base + i * 32 + 8 * (r >> 2) + (r & 3);
                     OUT_ACC v = (OUT_ACC)acc[i][j][r];
-                    if constexpr (FUSED) { v += bias; v = v > lo ? v : lo; }
+                    if constexpr (FUSED) { v += bias; if (relu) v = v > (OUT_ACC)0 ? v : (OUT_ACC)0; }
                     if (row < M && col < K) out[row * out_stride + col] = convert(v);
                 }
             }
@@ -197,5 +199,19 @@ inline int device_cu_count()
 }
 
 constexpr size_t kLdsPerCu = 160 * 1024;
+
+// Lets `kern` use the whole LDS of a compute unit as dynamic shared memory.  The attribute belongs to the
+// (kernel, device) pair, so the caller keeps one flag array per kernel instantiation; the call is idempotent and a
+// race between threads only repeats it.
+constexpr int kMaxDevices = 64;
+inline int allow_full_lds(const void* kern, bool (&done)[kMaxDevices])
+{
+    int dev = 0;
+    const bool known = hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices;
+    if (known && done[dev]) return ICV_OK;
+    ICV_HIP_CHECK(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu));
+    if (known) done[dev] = true;
+    return ICV_OK;
+}
 
 }  // namespace icv

@@ -1,5 +1,6 @@
 // Set-up kernels: zero row, filter pre-pack, indirection build, and the im2col of the ablation path.
 #include "icv_internal.h"
+#include "icv_pixel_range.h"
 
 namespace icv {
 
@@ -74,9 +75,36 @@ __global__ void k_pack_filter_lowc(const uint8_t* src, uint8_t* dst, int K, int 
     *(uint2*)(dst + row * (int64_t)KP + b) = v;
 }
 
+// Filter-in-registers plan: [block of 32 output channels][fragment = tap * KS + step][lane][16 bytes], the operand
+// layout of the 32x32 MFMAs -- lane l holds bytes 32*step + 16*(l >> 5) .. +16 of kernel element `tap` of channel
+// 32*block + (l & 31) -- so that a wavefront loads a fragment with one coalesced 1 KB read.  Channels past K are zero.
+__global__ void k_pack_filter_frag(const uint8_t* src, uint8_t* dst, int K, int T, int KS, int64_t total_vec)
+{
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= total_vec) return;
+    const int lane = (int)(v & 63);
+    const int64_t fi = v >> 6;
+    const int f = (int)(fi % (T * KS));
+    const int cb = (int)(fi / (T * KS));
+    const int tap = f / KS, ks = f - tap * KS;
+    const int oc = cb * 32 + (lane & 31);
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (oc < K) val = *(const uint4*)(src + ((int64_t)oc * T + tap) * (KS * 32) + ks * 32 + (lane >> 5) * 16);
+    *(uint4*)(dst + v * 16) = val;
+}
+
 int launch_pack_filter(const icv_conv_params* p, const Geometry& g, const void* filt, void* packed, hipStream_t s)
 {
     const int64_t CB = (int64_t)p->C * g.elem_bytes;
+    if (g.kind == PLAN_MFMA_FREG) {
+        const int KS = g.KCB / 32;
+        const int64_t col_blocks = g.n_tiles * (g.NR / 32);
+        const int64_t total = col_blocks * g.T * KS * 64;
+        hipLaunchKernelGGL(k_pack_filter_frag, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                           (const uint8_t*)filt, (uint8_t*)packed, p->K, g.T, KS, total);
+        ICV_HIP_CHECK(hipGetLastError());
+        return ICV_OK;
+    }
     if (g.kind == PLAN_MFMA_LOWC) {
         const int64_t rows = g.n_tiles * g.NR, threads = rows * (g.KCB / 8);
         hipLaunchKernelGGL(k_pack_filter_lowc, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
@@ -211,8 +239,66 @@ __global__ __launch_bounds__(256) void k_build_indirection(IndArgs a)
     }
 }
 
+// Block form (filter-in-registers plan): per block of 32 consecutive output pixels one 16-byte record {base byte
+// offset, 0, base pixel, 0} -- the base is the closed-form lower bound of icv_pixel_range.h for the block's first
+// pixel, so a kernel can compute it without reading anything -- and per (kernel element, row) the entry as a 16-bit
+// pixel number counted from that base, 0xFFFF for the zero row (and for rows past M).  Physical order
+// [block][kernel element][32].  A wavefront builds one block: lane -> (kernel element l / 16 of a group of four,
+// rows 2 * (l % 16) and the next), so every store instruction writes 256 contiguous bytes.
+struct BlockIndArgs {
+    int4* rec;
+    uint16_t* ent;
+    RangeGeom q;
+    int64_t M;
+    uint32_t n_blocks;
+    int32_t T, stride_bytes;
+};
+
+__global__ __launch_bounds__(256) void k_build_block_indirection(BlockIndArgs a)
+{
+    const uint32_t blk = blockIdx.x * 4u + (threadIdx.x >> 6);
+    if (blk >= a.n_blocks) return;
+    const int lane = threadIdx.x & 63;
+    const int32_t base = lowest_pixel_from(a.q, decompose(a.q, blk * 32u));
+    if (lane == 0) a.rec[blk] = make_int4(base * a.stride_bytes, 0, base, 0);
+    const uint32_t m0 = blk * 32u + 2u * (uint32_t)(lane & 15);
+    OutPixel o[2];
+    bool live[2];
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+        live[j] = (int64_t)(m0 + j) < a.M;
+        o[j] = decompose(a.q, live[j] ? m0 + j : 0u);
+    }
+    uint32_t* dst = (uint32_t*)(a.ent + (int64_t)blk * a.T * 32) + lane;
+    for (int32_t tap = lane >> 4; tap < a.T; tap += 4) {
+        const int32_t ky = tap / a.q.S, kx = tap - ky * a.q.S;
+        uint32_t e[2];
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            const int32_t iy = o[j].oy * a.q.SY + ky * a.q.DY - a.q.PT;
+            const int32_t ix = o[j].ox * a.q.SX + kx * a.q.DX - a.q.PL;
+            const bool in = live[j] && (uint32_t)iy < (uint32_t)a.q.Hin && (uint32_t)ix < (uint32_t)a.q.Win;
+            e[j] = in ? (uint32_t)((o[j].n * a.q.Hin + iy) * a.q.Win + ix - base) : 0xFFFFu;
+        }
+        dst[(tap - (lane >> 4)) * 16] = e[0] | (e[1] << 16);
+    }
+}
+
 int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_t* ind, hipStream_t s)
 {
+    if (g.kind == PLAN_MFMA_FREG) {
+        BlockIndArgs b{};
+        b.rec = (int4*)ind;
+        b.ent = (uint16_t*)(b.rec + g.img_tiles);
+        b.q = RangeGeom{p->Hin, p->Win, g.Hout, g.Wout, p->SY, p->SX, p->DY, p->DX, p->PT, p->PL, p->R, p->S};
+        b.M = g.img_rows;
+        b.n_blocks = (uint32_t)g.img_tiles;
+        b.T = g.T;
+        b.stride_bytes = g.in_stride * g.elem_bytes;
+        hipLaunchKernelGGL(k_build_block_indirection, dim3((unsigned)((g.img_tiles + 3) / 4)), dim3(256), 0, s, b);
+        ICV_HIP_CHECK(hipGetLastError());
+        return ICV_OK;
+    }
     IndArgs a{};      // every field starts at zero; the ones this call uses are set below
     a.ind = ind;
     // a batch-independent buffer holds the entries of one image (batch index 0); img_rows = M otherwise

@@ -73,22 +73,9 @@ CONFIGS = {
 
 
 
-def _stored_channels(C: int) -> int:
-    """Channels as they are kept in memory for the 16-bit tensor-core kernels: 3 -> 4 (an 8-byte pixel); counts that
-    are neither a multiple of 32 nor 4, 8 or 16 are rounded up to a multiple of 32 (64-byte rows).  The padding
-    channels of input and filter hold zeros."""
-    if C == 3:
-        return 4
-    if C % 32 == 0 or C in (4, 8, 16):
-        return C
-    return -(-C // 32) * 32
-
-
 def _layer(model, tag, N, hw, C, K, k, stride, pad, seed, dtype="bf16"):
-    Cs = _stored_channels(C)
-    return ConvShape(f"{model}.{tag}", N, hw, hw, Cs, K, k, k, SY=stride, SX=stride, PT=pad, PL=pad, PB=pad, PR=pad,
-                     dtype=dtype, zero_point=128 if dtype == "u8i8" else 0, seed=seed,
-                     c_logical=C if Cs != C else 0)
+    return ConvShape(f"{model}.{tag}", N, hw, hw, C, K, k, k, SY=stride, SX=stride, PT=pad, PL=pad, PB=pad, PR=pad,
+                     dtype=dtype, zero_point=128 if dtype == "u8i8" else 0, seed=seed)
 
 
 def layer_type(s: ConvShape) -> str:

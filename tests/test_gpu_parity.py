@@ -11,6 +11,7 @@ import numpy as np
 import pytest
 import torch
 
+import icv_layout as layout
 import oracle
 from paper_1907_02129_amd import binding as icv
 from paper_1907_02129_amd.workloads import CONFIGS, ConvShape, make_tensors
@@ -45,6 +46,32 @@ def check_against_oracle(s: ConvShape, got: np.ndarray, x: np.ndarray, w: np.nda
     assert worst <= 1.0, f"{s.name}: error is {worst:.2f}x the fp32 accumulation bound"
 
 
+_ORACLE_CACHE = {}
+
+
+def oracle_accumulators(s: ConvShape, x, w):
+    """(accumulators, sum |x*w| or None) of a named benchmark shape, computed once per test session."""
+    if s.name not in _ORACLE_CACHE:
+        if s.dtype == "u8i8":
+            _ORACLE_CACHE[s.name] = (oracle.conv2d_u8i8(s, x, w, s.zero_point, centred=True), None)
+        else:
+            _ORACLE_CACHE[s.name] = oracle.conv2d_abs(s, x, w)
+    return _ORACLE_CACHE[s.name]
+
+
+def check_against_accumulators(s: ConvShape, got: np.ndarray, want, mag):
+    if s.dtype == "u8i8":
+        assert got.dtype == np.int32
+        assert np.array_equal(got, want), f"{s.name}: {(got != want).sum()} of {want.size} differ"
+        return
+    err = np.abs(got.astype(np.float64) - want)
+    rel = err.max() / np.abs(want).max()
+    assert rel <= TOL[s.dtype], f"{s.name}: max rel err {rel:.3e}"
+    bound = 2.0 * (s.R * s.S * s.C) * 2.0 ** -24 * mag + 1e-30
+    worst = (err / bound).max()
+    assert worst <= 1.0, f"{s.name}: error is {worst:.2f}x the fp32 accumulation bound"
+
+
 def run_indirect(s: ConvShape, x, w, plan=0, out_pixel_stride=0):
     xd, wd = icv.to_device(x), icv.to_device(w)
     buf = icv.prepare(s, wd, plan=plan, out_pixel_stride=out_pixel_stride)
@@ -72,8 +99,7 @@ def test_indirection_matches_oracle_entry_by_entry(name):
     ind = torch.full((icv.indirection_bytes(p) // 4,), 12345, dtype=torch.int32, device="cuda:0")
     icv.setup_indirection(p, ind)
     torch.cuda.synchronize()
-    buf = icv.ConvBuffers(p, Hout, Wout, None, None, ind, None)
-    got, tail = icv.logical_indirection(buf)
+    got, tail = layout.logical_indirection(p, ind, s.N * Hout * Wout)
     assert np.array_equal(got, oracle.indirection(s))
     assert np.all(tail == -1)                                   # rows past M read the zero row
 
@@ -95,7 +121,7 @@ def test_indirection_small_shapes(s):
     ind = torch.full((icv.indirection_bytes(p) // 4,), 12345, dtype=torch.int32, device="cuda:0")
     icv.setup_indirection(p, ind)
     torch.cuda.synchronize()
-    got, tail = icv.logical_indirection(icv.ConvBuffers(p, Hout, Wout, None, None, ind, None))
+    got, tail = layout.logical_indirection(p, ind, s.N * Hout * Wout)
     assert np.array_equal(got, oracle.indirection(s))
     assert np.all(tail == -1)
 
@@ -107,7 +133,7 @@ def test_benchmark_shape_matches_oracle(name):
     _say("conv", name, icv.plan_name(icv.make_params(s)))
     x, w = make_tensors(s)
     buf, xd = run_indirect(s, x, w)
-    check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+    check_against_accumulators(s, buf.output.cpu().numpy(), *oracle_accumulators(s, x, w))
 
 
 # ---------------------------------------------------------------- small shapes: several tiles, ragged tails
@@ -153,9 +179,9 @@ def test_small_shapes_match_oracle(s):
     check_against_oracle(s, buf.output.cpu().numpy(), x, w)
     if "lowc" in icv.plan_name(buf.p):
         # the short-row kernel reads compact 16-bit entries by default; plan bit 12 keeps it on the int32 offsets
-        assert icv.tile_ranges(buf) is not None
+        assert layout.tile_records(buf.p, buf.indirection) is not None
         buf32, _ = run_indirect(s, x, w, plan=1 << 12)
-        assert icv.tile_ranges(buf32) is None and icv.plan_name(buf32.p) == icv.plan_name(buf.p)
+        assert layout.tile_records(buf32.p, buf32.indirection) is None and icv.plan_name(buf32.p) == icv.plan_name(buf.p)
         assert torch.equal(buf32.output, buf.output)
 
 
@@ -289,7 +315,7 @@ def test_range_records_match_oracle_entries(s):
     x, w = make_tensors(s)
     buf = icv.prepare(s, icv.to_device(w), plan=2 << 12)
     torch.cuda.synchronize()
-    got = icv.tile_ranges(buf)
+    got = layout.tile_records(buf.p, buf.indirection)
     assert got is not None
     rec, rows = got
     mr = icv.indirection_index(buf.p, 0, 1)
@@ -314,6 +340,80 @@ def test_range_records_match_oracle_entries(s):
             assert zero.min() == zero.max() >= cap
         if blk.shape[0] < mr:
             assert np.all(rows[t, :, blk.shape[0]:] >= cap)
+
+
+# ---------------------------------------------------------------- filter in registers, input window in an LDS ring
+FREG = 3 << 12
+
+
+def _freg_shapes():
+    mk = ConvShape
+    q = dict(dtype="u8i8", zero_point=128)
+    return [
+        # 3x3 on 64-, 128- and 256-byte rows; K of one, two, four column blocks with tails; several passes per workgroup
+        mk("r_c32_k40", 2, 37, 41, 32, 40, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=301),
+        mk("r_c64_k64", 3, 29, 31, 64, 64, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=302),
+        mk("r_c128_k130", 2, 23, 19, 128, 130, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=303),
+        mk("r_c128_k300", 1, 17, 21, 128, 300, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=304),
+        mk("r_c64_k20", 2, 33, 18, 64, 20, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=305),
+        # stride 2, dilation, asymmetric and oversized padding, no padding, rows that wrap images
+        mk("r_s2", 2, 31, 29, 128, 72, 3, 3, SY=2, SX=2, PT=1, PL=1, PB=1, PR=1, seed=306),
+        mk("r_dil", 2, 24, 40, 64, 96, 3, 3, SY=1, SX=2, DY=2, DX=3, PT=2, PL=3, PB=2, PR=3, seed=307),
+        mk("r_valid", 5, 12, 12, 32, 64, 3, 3, seed=308),
+        mk("r_bigpad", 2, 9, 30, 64, 32, 3, 3, PT=5, PL=4, PB=6, PR=7, seed=309),
+        mk("r_bigpad_s3", 3, 7, 11, 64, 48, 3, 3, SY=3, SX=2, PT=4, PL=5, PB=5, PR=6, seed=310),
+        mk("r_tiny_images", 40, 3, 3, 64, 32, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=311),
+        mk("r_one_block", 1, 4, 5, 64, 16, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=312),
+        mk("r_stride_pad", 2, 14, 30, 32, 48, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=313),      # run with a pixel stride of 96
+        # 5x5 on 64-byte rows
+        mk("r_5x5", 2, 33, 35, 32, 64, 5, 5, PT=2, PL=2, PB=1, PR=1, seed=314),
+        mk("r_5x5_s2", 2, 40, 26, 32, 100, 5, 5, SY=2, SX=2, PT=2, PL=2, PB=2, PR=2, seed=315),
+        # uint8 x int8
+        mk("r_i8_c64", 2, 25, 27, 64, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=316, **q),
+        mk("r_i8_c256", 2, 15, 22, 256, 264, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=317, **q),
+        mk("r_i8_c128_s2", 3, 21, 18, 128, 64, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, seed=318, **q),
+        mk("r_i8_5x5", 1, 30, 30, 64, 40, 5, 5, PT=2, PL=2, PB=2, PR=2, seed=319, **q),
+    ]
+
+
+@pytest.mark.parametrize("s", _freg_shapes(), ids=lambda s: s.name)
+def test_filter_in_registers_kernel_matches_oracle(s):
+    stride = 96 if s.name == "r_stride_pad" else 0
+    x, w = make_tensors(s)
+    xp = x
+    if stride:
+        xp = np.zeros(x.shape[:-1] + (stride,), dtype=x.dtype)
+        xp[..., :s.C] = x
+        xp[..., s.C:] = 0x7fc0                                     # NaN bit patterns in the unused channels
+    p = icv.make_params(s, FREG, in_pixel_stride=stride)
+    name = icv.plan_name(p)
+    assert "freg" in name, name
+    _say("filter-in-registers", s.name, name)
+    buf = icv.prepare(s, icv.to_device(w), plan=FREG, in_pixel_stride=stride)
+    buf.output.fill_(-7)
+    icv.run(buf, icv.to_device(xp))
+    torch.cuda.synchronize()
+    check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+    # the buffer this plan builds: entry by entry the oracle's, and every block's base record is the closed-form
+    # lower end of the block's pixel range
+    got, tail = layout.logical_indirection(buf.p, buf.indirection, buf.M)
+    assert np.array_equal(got, oracle.indirection(s)) and np.all(tail == -1)
+    rec, _ = layout.tile_records(buf.p, buf.indirection)
+    esz = 1 if s.dtype == "u8i8" else 2
+    for b in range(rec.shape[0]):
+        first, _last = icv.row_pixel_range(buf.p, 32 * b, min(32 * b + 31, buf.M - 1))
+        assert rec[b, 2] == first and rec[b, 0] == first * (stride or s.C) * esz
+
+
+@pytest.mark.parametrize("s", [_freg_shapes()[i] for i in (1, 2, 5, 13, 16)], ids=lambda s: s.name)
+@pytest.mark.parametrize("relu,narrow", [(True, True), (False, False), (True, False)], ids=["relu_narrow", "linear_acc", "relu_acc"])
+def test_filter_in_registers_kernel_with_fused_output(s, relu, narrow):
+    x, w = make_tensors(s)
+    if s.dtype == "u8i8":
+        acc, mag = oracle.conv2d_u8i8(s, x, w, s.zero_point, centred=True), None
+    else:
+        acc, mag = oracle.conv2d_abs(s, x, w)
+    run_fused_case(s, x, w, acc, mag, relu, narrow, plan=FREG, out_pixel_stride=s.K + 8 if narrow else 0)
 
 
 # ---------------------------------------------------------------- 1x1 stride-1: plain GEMM on the input tensor
@@ -371,7 +471,8 @@ def test_batch_independent_buffer_matches_oracle(s):
     check_against_oracle(s, buf.output.cpu().numpy(), x, w)
     # the buffer is that of one image: entry by entry the oracle's entries of batch element 0
     one = s.with_(N=1)
-    got, pad = icv.logical_indirection(icv.prepare(one, icv.to_device(w), plan=PER_IMAGE))
+    built = icv.prepare(one, icv.to_device(w), plan=PER_IMAGE)
+    got, pad = layout.logical_indirection(built.p, built.indirection, built.M)
     assert np.array_equal(got, oracle.indirection(one)) and np.all(pad == -1)
     assert icv.indirection_bytes(buf.p) == icv.indirection_bytes(icv.make_params(one, plan=PER_IMAGE))
 
@@ -401,12 +502,18 @@ MODEL_LAYERS = resnet18_layers(2) + squeezenet10_layers(2)
 @pytest.mark.parametrize("s", MODEL_LAYERS, ids=lambda s: s.name)
 def test_model_layers_match_oracle(s):
     """Every distinct convolution of ResNet-18 and SqueezeNet 1.0 (section 3.1, Table 2) at batch 2, with the plan
-    the library picks and with the batch-independent buffer."""
-    x, w = make_tensors(s)
-    for plan in (0, PER_IMAGE):
-        _say("layer", s.name, icv.plan_name(icv.make_params(s, plan=plan)))
-        buf, xd = run_indirect(s, x, w, plan=plan)
-        check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+    the library picks and with the batch-independent buffer.  Channel counts the tensor-core kernels cannot address
+    (3; 48) run twice: stored padded with zeros, as the benchmark's sweep keeps them, and as they are (which takes
+    the vector-ALU kernel)."""
+    stored = icv.stored_for_tensor_cores(s)
+    for sh in ([stored, s] if stored is not s else [s]):
+        x, w = make_tensors(sh)
+        for plan in (0, PER_IMAGE):
+            name = icv.plan_name(icv.make_params(sh, plan=plan))
+            _say("layer", sh.name, "C", sh.C, name)
+            assert ("generic" in name) == (sh is not stored)
+            buf, xd = run_indirect(sh, x, w, plan=plan)
+            check_against_oracle(sh, buf.output.cpu().numpy(), x, w)
 
 
 # ---------------------------------------------------------------- grids with workgroups that find no tile
@@ -431,22 +538,11 @@ def test_tile_counts_that_are_not_a_multiple_of_eight(plan, tiles64):
 def test_batch_independent_buffer_with_fused_output_and_pixel_strides():
     s = ConvShape("bf_combo", 3, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=134)
     x, w = make_tensors(s)
-    rng = np.random.default_rng(5)
-    bias = rng.standard_normal(s.K).astype(np.float32)
     xs = np.zeros(x.shape[:-1] + (128,), dtype=x.dtype)
     xs[..., :s.C] = x
     xs[..., s.C:] = 0x7fc0                                      # NaN bit patterns in the unused channels
-    buf = icv.prepare(s, icv.to_device(w), plan=PER_IMAGE, in_pixel_stride=128, out_pixel_stride=100)
-    out = torch.full((s.N, buf.Hout, buf.Wout, 100), -7, dtype=torch.bfloat16, device="cuda:0")
-    bias_dev = torch.from_numpy(bias).cuda()
-    ep = icv.make_epilogue(bias_dev, True, icv.ICV_OUT_BF16)
-    icv.conv2d_nhwc_fused(buf.p, icv.to_device(xs), buf.packed, buf.indirection, buf.zero_row, ep, out)
-    torch.cuda.synchronize()
-    got = out.float().cpu().numpy()
-    want = oracle.epilogue(oracle.conv2d(s, x, w), bias.astype(np.float64), relu=True)
-    assert np.all(got[..., s.K:] == -7)                         # the pixel stride's padding is not written
-    err = np.abs(got[..., :s.K] - want).max() / np.abs(want).max()
-    assert err <= TOL["bf16"], err
+    acc, mag = oracle.conv2d_abs(s, x, w)
+    run_fused_case(s, x, w, acc, mag, True, True, plan=PER_IMAGE, in_pixel_stride=128, out_pixel_stride=100, x_stored=xs)
 
 
 # ---------------------------------------------------------------- one zero row for several operators
@@ -521,53 +617,50 @@ FUSED_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("s", FUSED_SHAPES, ids=lambda s: s.name)
-@pytest.mark.parametrize("relu", [False, True], ids=["linear", "relu"])
-@pytest.mark.parametrize("narrow", [False, True], ids=["acc_type", "narrow_out"])
-def test_fused_output_stage_matches_oracle(s, relu, narrow):
-    x, w = make_tensors(s)
+def run_fused_case(s, x, w, acc, mag, relu, narrow, plan=0, in_pixel_stride=0, out_pixel_stride=0, x_stored=None):
+    """One icv_conv2d_nhwc_fused call checked element by element: integer work bit-exact; float work within the
+    accumulation bound (any order), the bias add, and for a bfloat16 output one rounding to 8 significant bits."""
     rng = np.random.default_rng(s.seed + 500)
     quant = s.dtype == "u8i8"
-    buf = icv.prepare(s, icv.to_device(w))
+    buf = icv.prepare(s, icv.to_device(w), plan=plan, in_pixel_stride=in_pixel_stride, out_pixel_stride=out_pixel_stride)
     _say("fused", s.name, icv.plan_name(buf.p), "relu" if relu else "", "narrow" if narrow else "")
-    xd = icv.to_device(x)
+    xd = icv.to_device(x if x_stored is None else x_stored)
+    oshape = acc.shape[:-1] + (out_pixel_stride or s.K,)
     if quant:
-        acc = oracle.conv2d_u8i8(s, x, w, s.zero_point, centred=True)
         bias = rng.integers(-5000, 5000, size=s.K).astype(np.int32)
         want = oracle.epilogue(acc, bias, relu)
         scale, zp = float(np.float32(200.0 / np.abs(want).max())), 77
         bias_dev = icv.to_device(bias)
         ep = icv.make_epilogue(bias_dev, relu, icv.ICV_OUT_U8 if narrow else icv.ICV_OUT_ACC, scale, zp)
-        out = torch.full(want.shape, 201 if narrow else -7, dtype=torch.uint8 if narrow else torch.int32, device="cuda:0")
+        out = torch.full(oshape, 201 if narrow else -7, dtype=torch.uint8 if narrow else torch.int32, device="cuda:0")
         icv.conv2d_nhwc_fused(buf.p, xd, buf.packed, buf.indirection, buf.zero_row, ep, out)
         torch.cuda.synchronize()
         got = out.cpu().numpy()
+        assert np.all(got[..., s.K:] == (201 if narrow else -7))            # a pixel stride's padding is not written
+        got = got[..., :s.K]
         want = oracle.requantise_u8(want, scale, zp) if narrow else want
         assert np.array_equal(got, want), f"{(got != want).sum()} of {want.size} differ"      # integer work: bit-exact
         if narrow:
             assert got.min() == (zp if relu else 0) and got.max() == 255                         # the codes use the range, both clamps
         return
-    acc, mag = oracle.conv2d_abs(s, x, w)
     bias = (rng.standard_normal(s.K) * np.abs(acc).max() * 0.3).astype(np.float32)
     want = oracle.epilogue(acc, bias.astype(np.float64), relu)
-    if narrow and s.dtype == "f32":
-        narrow = False                    # bf16 output is offered for the float paths; exercise it on the fp32 kernel too
-        out_type = icv.ICV_OUT_BF16
-    else:
-        out_type = icv.ICV_OUT_BF16 if narrow else icv.ICV_OUT_ACC
+    # bf16 output is offered for the float paths, the fp32 kernel included
+    out_type = icv.ICV_OUT_BF16 if narrow else icv.ICV_OUT_ACC
     bias_dev = icv.to_device(bias)
     ep = icv.make_epilogue(bias_dev, relu, out_type)
-    out = torch.full(want.shape, 9.0, dtype=torch.bfloat16 if out_type == icv.ICV_OUT_BF16 else torch.float32, device="cuda:0")
+    out = torch.full(oshape, 9.0, dtype=torch.bfloat16 if out_type == icv.ICV_OUT_BF16 else torch.float32, device="cuda:0")
     icv.conv2d_nhwc_fused(buf.p, xd, buf.packed, buf.indirection, buf.zero_row, ep, out)
     torch.cuda.synchronize()
     if out_type == icv.ICV_OUT_BF16:
         got = _bf16_bits_to_f64(out.view(torch.int16).cpu().numpy().view(np.uint16))
     else:
         got = out.cpu().numpy().astype(np.float64)
+    assert np.all(got[..., s.K:] == 9.0)
+    got = got[..., :s.K]
     err = np.abs(got - want)
     # a bfloat16 output carries 8 significant bits whatever the inputs were: the bf16 bar applies to it
     assert err.max() / np.abs(want).max() <= (TOL["bf16"] if out_type == icv.ICV_OUT_BF16 else TOL[s.dtype])
-    # accumulation in fp32 (any order), the bias add, and for bf16 output one rounding to 8 significant bits
     n_terms = s.R * s.S * s.C + 1
     bound = 2.0 * n_terms * 2.0 ** -24 * (mag + np.abs(bias)[None, None, None, :]) + 1e-30
     if out_type == icv.ICV_OUT_BF16:
@@ -575,6 +668,28 @@ def test_fused_output_stage_matches_oracle(s, relu, narrow):
     assert (err / bound).max() <= 1.0
     if relu:
         assert got.min() == 0.0 and (got == 0).mean() > 0.05
+
+
+@pytest.mark.parametrize("s", FUSED_SHAPES, ids=lambda s: s.name)
+@pytest.mark.parametrize("relu", [False, True], ids=["linear", "relu"])
+@pytest.mark.parametrize("narrow", [False, True], ids=["acc_type", "narrow_out"])
+def test_fused_output_stage_matches_oracle(s, relu, narrow):
+    x, w = make_tensors(s)
+    if s.dtype == "u8i8":
+        acc, mag = oracle.conv2d_u8i8(s, x, w, s.zero_point, centred=True), None
+    else:
+        acc, mag = oracle.conv2d_abs(s, x, w)
+    run_fused_case(s, x, w, acc, mag, relu, narrow)
+
+
+@pytest.mark.parametrize("name", [n for n in CONFIGS if n != "cfg1_tiny_f32"])
+@pytest.mark.parametrize("relu,narrow", [(True, True), (False, False)], ids=["relu_narrow_out", "linear_acc_type"])
+def test_fused_output_stage_on_benchmark_shapes(name, relu, narrow):
+    """The fused instantiations of the very kernels the benchmark times, on the full-size shapes, every element."""
+    s = CONFIGS[name]
+    x, w = make_tensors(s)
+    acc, mag = oracle_accumulators(s, x, w)
+    run_fused_case(s, x, w, acc, mag, relu, narrow)
 
 
 def test_fused_with_nothing_to_fuse_equals_the_plain_call_and_rejects_bad_stages():
@@ -617,10 +732,8 @@ def test_padded_channel_layout():
     s4 = CONFIGS["cfg5b_7x7_s2"].with_(N=2, Hin=40, Win=36)
     x, w = make_tensors(s4)
     buf, xd = run_indirect(s4, x, w)
-    s3 = s4.with_(C=3)
-    want3 = oracle.conv2d(s3, x, np.ascontiguousarray(w[..., :3]))
-    got = buf.output.cpu().numpy().astype(np.float64)
-    assert np.abs(got - want3).max() / np.abs(want3).max() <= 1e-2
+    # the oracle on the three real channels (it reads the input with its pixel stride of 4)
+    check_against_oracle(s4.with_(C=3), buf.output.cpu().numpy(), x, np.ascontiguousarray(w[..., :3]))
 
 
 @pytest.mark.parametrize("name", ["cfg2_3x3_c64", "cfg3a_3x3_s2", "cfg4_int8_3x3", "cfg3c_5x5_asym", "cfg5b_7x7_s2"])
@@ -629,14 +742,15 @@ def test_im2col_gemm_ablation_agrees_with_indirect_path(name):
     s = CONFIGS[name].with_(N=2)
     _say("ablation", name)
     x, w = make_tensors(s)
-    buf, xd = run_indirect(s, x, w)
+    direct, xd = run_indirect(s, x, w)
+    buf = icv.prepare(s, icv.to_device(w), plan=1 << 12)          # the filter packed for the plain GEMM kernels
     out2, ws = run_im2col(s, buf, xd)
-    got1, got2 = buf.output.cpu().numpy(), out2.cpu().numpy()
+    got1, got2 = direct.output.cpu().numpy(), out2.cpu().numpy()
+    # each path is held to the per-element bound against the oracle (which also bounds their difference)
+    check_against_oracle(s, got1, x, w)
     check_against_oracle(s, got2, x, w)
     if s.dtype == "u8i8":
         assert np.array_equal(got1, got2)
-    else:
-        assert np.abs(got1 - got2).max() <= 2e-2 * np.abs(got1).max()
     # the patch matrix itself: row m, tap t holds the pixel row the indirection entry names
     M, T = buf.M, s.R * s.S
     esz = 1 if s.dtype == "u8i8" else 2
@@ -650,6 +764,20 @@ def test_im2col_gemm_ablation_agrees_with_indirect_path(name):
     fill = np.full(s.C * esz, s.zero_point if s.dtype == "u8i8" else 0, dtype=np.uint8)
     src = np.concatenate([xb, fill[None]], axis=0)
     assert np.array_equal(rows, src[ent])          # entry -1 indexes the appended fill row
+
+
+@pytest.mark.parametrize("s", [ConvShape("abl_img", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=151),
+                               ConvShape("abl_img_i8", 3, 15, 15, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=152),
+                               ConvShape("abl_img_lowc", 2, 30, 26, 4, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=153)],
+                         ids=lambda s: s.name)
+def test_im2col_gemm_ablation_with_the_batch_independent_plan(s):
+    """The ablation reads the filter as icv_pack_filter laid it out for the problem's plan, whatever tile that plan
+    chose: with plan bit 17 the tile is picked for a full chip, not for this small batch."""
+    x, w = make_tensors(s)
+    buf, xd = run_indirect(s, x, w, plan=(1 << 12) | PER_IMAGE)
+    check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+    out2, _ = run_im2col(s, buf, xd)
+    check_against_oracle(s, out2.cpu().numpy(), x, w)
 
 
 def test_small_generic_im2col_path():

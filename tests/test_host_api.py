@@ -44,12 +44,20 @@ def test_output_size_and_buffer_sizes(lib, name):
     assert (Hout, Wout) == oracle.out_extent(s)
     M, T = s.N * Hout * Wout, s.R * s.S
     nbytes = icv.indirection_bytes(p)
-    if "patch" in icv.plan_name(p) or "lowc" in icv.plan_name(p):   # a 16-byte range record per row tile follows
-        mr = icv.indirection_index(p, 0, 1)
-        tiles = -(-M // mr)
-        nbytes -= 16 * tiles + 2 * tiles * mr * T           # ... and the entries again as uint16 row numbers
-    assert nbytes % (4 * T) == 0 and nbytes >= 4 * M * T
-    assert nbytes < 4 * (M + 256) * T                       # padding is less than one row tile
+    # the layout the library reports accounts for every byte of the buffer: entries in the width the kernel reads,
+    # tile records, and the int32 form where it is kept beside a 2-byte form; padding is less than one row tile
+    L = icv.get_indirection_layout(p)
+    assert L.tile_rows in (32, 64, 128, 256) and L.tiles == -(-M // L.tile_rows)
+    n = L.tiles * L.tile_rows * T
+    parts = [(L.entries_at, n * L.entry_bytes)]
+    if L.record_bytes:
+        parts.append((L.records_at, L.tiles * L.record_bytes))
+    if L.int32_entries_at >= 0 and L.entry_bytes != 4:
+        parts.append((L.int32_entries_at, n * 4))
+    parts.sort()
+    assert parts[0][0] == 0 and all(a + b == c for (a, b), (c, _) in zip(parts, parts[1:]))
+    assert parts[-1][0] + parts[-1][1] == nbytes
+    assert (L.entry_bytes == 2) == (L.record_bytes == 16) and (L.records_at >= 0) == (L.record_bytes > 0)
     # the entries do not depend on the number of input channels (section 1.1); with the row staging fixed,
     # neither does the tile the library picks
     per_tap = 1 << 12
@@ -58,7 +66,11 @@ def test_output_size_and_buffer_sizes(lib, name):
     esz = {"f32": 4, "bf16": 2, "u8i8": 1}[s.dtype]
     assert icv.packed_filter_bytes(p) >= s.K * T * s.C * esz
     assert icv.zero_row_bytes(p) >= s.C * esz and icv.zero_row_bytes(p) % 16 == 0
-    assert icv.im2col_bytes(p) >= M * T * s.C * esz
+    # the ablation runs with a plan whose packed filter the plain GEMM kernels read
+    abl = icv.make_params(s, plan=per_tap)
+    assert icv.im2col_bytes(abl) >= M * T * s.C * esz
+    if "freg" in icv.plan_name(p):
+        assert icv.im2col_bytes(p) == 0
     assert icv.plan_name(p) != ""
 
 
@@ -103,7 +115,8 @@ def test_invalid_arguments_are_rejected(lib):
     assert _status(lib, s, R=80, PT=0, PB=0) == icv.ICV_ERR_INVALID_ARG             # kernel larger than input
     assert _status(lib, s, N=1 << 20) == icv.ICV_ERR_INVALID_ARG                    # input of 2 GiB or more
     assert _status(lib, s, plan=1 << 18) == icv.ICV_ERR_INVALID_ARG
-    assert _status(lib, s, plan=3 << 12) == icv.ICV_ERR_INVALID_ARG                 # no such row staging
+    assert _status(lib, s, plan=3 << 12) == icv.ICV_OK                              # filter in registers, forced
+    assert _status(lib, s, plan=3 << 12, R=7, S=7, PT=3, PL=3, PB=3, PR=3) == icv.ICV_ERR_UNSUPPORTED   # ... not for 7x7
     assert _status(lib, s, plan=2 | (13 << 4)) == icv.ICV_ERR_INVALID_ARG           # ring deeper than 12
     assert _status(lib, s, plan=2 | (1 << 4)) == icv.ICV_ERR_INVALID_ARG            # a ring needs two slots
     assert _status(lib, CONFIGS["cfg4_int8_3x3"], input_zero_point=300) == icv.ICV_ERR_INVALID_ARG
@@ -119,6 +132,8 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
     assert lib.icv_conv2d_nhwc(ctypes.byref(p), vp(0), vp(0), vp(0), vp(0), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
     assert lib.icv_pack_filter(ctypes.byref(p), vp(0), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
     assert lib.icv_init_zero_row(ctypes.byref(p), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
+    assert lib.icv_im2col(ctypes.byref(p), vp(0), vp(0), vp(0)) == icv.ICV_ERR_UNSUPPORTED     # plan without ablation
+    p = icv.make_params(CONFIGS["cfg2_3x3_c64"], plan=1 << 12)
     assert lib.icv_im2col(ctypes.byref(p), vp(0), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
     assert lib.icv_gemm_nhwc(ctypes.byref(p), vp(0), vp(0), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
     ep = icv.make_epilogue()
@@ -162,6 +177,53 @@ def _exact_span(shape, rows):
         if v.size:
             worst = max(worst, int(v.max() - v.min() + 1))
     return worst
+
+
+def test_row_pixel_range_brackets_every_window_of_output_pixels(lib):
+    """The sliding input window of the filter-in-registers kernel rests on two closed forms: a lower end that depends
+    on a window's first output pixel alone and an upper end that depends on its last one alone.  Brute force on the
+    oracle's entries: every valid entry of every window lies between them, both ends never move backwards, and the
+    window is never longer than icv_tile_span_bound says (which is what sizes the LDS ring)."""
+    import numpy as np
+    from oracle import direct_conv as oracle
+    from paper_1907_02129_amd.workloads import random_small_shape
+    rng = np.random.default_rng(11)
+    shapes = [random_small_shape(rng) for _ in range(200)]
+    # paddings beyond the kernel's reach, where the clamped ends differ from the unclipped positions
+    shapes += [random_small_shape(rng).with_(PT=int(rng.integers(0, 7)), PL=int(rng.integers(0, 7)),
+                                             PB=int(rng.integers(0, 7)), PR=int(rng.integers(0, 7))) for _ in range(150)]
+    shapes += [CONFIGS[n].with_(N=2) for n in ("cfg2_3x3_c64", "cfg3a_3x3_s2", "cfg3b_3x3_d2", "cfg3c_5x5_asym")]
+    attained_lo = attained_hi = 0
+    for shape in shapes:
+        p = icv.make_params(shape)
+        if not icv.plan_name(p):
+            continue                                    # the redrawn padding left no output pixel
+        ind = oracle.indirection(shape)
+        M = ind.shape[0]
+        valid = ind >= 0
+        lo_row = np.where(valid, ind, np.iinfo(np.int32).max).min(axis=1)       # per output pixel
+        hi_row = np.where(valid, ind, -1).max(axis=1)
+        # suffix minimum / prefix maximum: what "this pixel or any later (earlier) one" names
+        lo_from = np.minimum.accumulate(lo_row[::-1])[::-1]
+        hi_upto = np.maximum.accumulate(hi_row)
+        firsts = np.array([icv.row_pixel_range(p, m, m)[0] for m in range(M)])
+        lasts = np.array([icv.row_pixel_range(p, m, m)[1] for m in range(M)])
+        assert np.all(firsts <= lo_from), shape
+        assert np.all(lasts >= hi_upto), shape
+        assert np.all(np.diff(firsts) >= 0) and np.all(np.diff(lasts) >= 0), shape
+        assert firsts.min() >= 0 and lasts.max() <= shape.N * shape.Hin * shape.Win - 1
+        attained_lo += int(np.any(firsts == lo_from))
+        attained_hi += int(np.any(lasts == hi_upto))
+        for rows in (1, 3, 32, 64, 200):
+            if rows > M:
+                continue
+            span = lasts[rows - 1:] - firsts[:M - rows + 1] + 1
+            assert span.max() <= icv.tile_span_bound(p, rows), (shape, rows, int(span.max()))
+            f, l = icv.row_pixel_range(p, 0, rows - 1)
+            assert (f, l) == (firsts[0], lasts[rows - 1])
+    assert attained_lo > 250 and attained_hi > 250          # the ends are tight, not merely safe
+    p = icv.make_params(CONFIGS["cfg2_3x3_c64"])
+    assert lib.icv_row_pixel_range(ctypes.byref(p), 5, 4, None, None) == icv.ICV_ERR_INVALID_ARG
 
 
 def test_tile_span_bound_covers_every_tile(lib):
@@ -286,10 +348,12 @@ def test_random_plans_and_shapes_never_confuse_the_host_logic(lib):
         T = s.R * s.S
         rows = Hout * Wout * (1 if (plan >> 17) & 1 and not name.startswith("gemm_") else s.N)
         assert all(v > 0 for v in sizes)
-        assert sizes[0] >= 4 * rows * T and sizes[0] % 4 == 0
+        L = icv.get_indirection_layout(p)
+        assert sizes[0] >= L.entry_bytes * rows * T and sizes[0] % 4 == 0
         assert icv.indirection_index(p, 0, 0) == 0
         assert icv.indirection_index(p, rows - 1, T - 1) >= 0
         if T > 1:
             mr = icv.indirection_index(p, 0, 1)
-            assert mr in (64, 128, 256) and sizes[0] >= 4 * (-(-rows // mr) * mr) * T
+            assert mr == L.tile_rows and mr in (32, 64, 128, 256)
+            assert sizes[0] >= L.entry_bytes * (-(-rows // mr) * mr) * T
     assert {"generic", "mfma"} <= seen
