@@ -462,7 +462,7 @@ int icv_row_pixel_range(const icv_conv_params* p, int64_t m0, int64_t m1, int64_
     const int st = make_geometry(p, &g);
     if (st != ICV_OK) return st;
     if (m0 < 0 || m1 < m0 || m1 >= g.M || !first || !last) return ICV_ERR_INVALID_ARG;
-    const RangeGeom q{p->Hin, p->Win, g.Hout, g.Wout, p->SY, p->SX, p->DY, p->DX, p->PT, p->PL, p->R, p->S};
+    const RangeGeom q = make_range_geom(p->Hin, p->Win, g.Hout, g.Wout, p->SY, p->SX, p->DY, p->DX, p->PT, p->PL, p->R, p->S);
     *first = lowest_pixel_from(q, decompose(q, (uint32_t)m0));
     *last = highest_pixel_upto(q, decompose(q, (uint32_t)m1));
     return ICV_OK;

@@ -27,6 +27,7 @@
 //
 // uint8 activations: every A fragment is XORed with 0x80 (x -> x - 128 as a signed byte); the zero row holds 0x80.
 #include "icv_mfma_common.h"
+#include <utility>
 #include "icv_pixel_range.h"
 
 namespace icv {
@@ -45,6 +46,9 @@ struct FregArgs {
     int32_t stride_bytes;      // bytes between input pixels
     int32_t last_pixel;        // N*Hin*Win - 1
     uint32_t n_blocks;         // row blocks of 32 output pixels
+    uint32_t range_q, range_rem;   // n_blocks / n_ranges and the remainder: the first range_rem ranges get one block more
+    int32_t cg_shift;          // log2(n_cg), or -1 when n_cg is not a power of two
+    int32_t ranges_per_xcd;    // XCD mode: n_ranges / 8
     uint32_t ent_bytes;        // bytes of the entries (copies are clamped to them)
     int32_t n_cg;              // column groups of WN column blocks
     int32_t n_ranges;          // row ranges: workgroups per column group
@@ -62,6 +66,30 @@ __device__ inline typename Acc<I8>::type mfma_frag(const u32x4_t& a, const u32x4
     } else {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
     }
+}
+
+// A pointer the compiler can prove to be wavefront-uniform (the copies take their base address in scalar registers).
+template <typename P>
+__device__ inline const P* uniform_ptr(const P* p)
+{
+    const uint64_t v = (uint64_t)(uintptr_t)p;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    return (const P*)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), as straight-line code whatever the size of f:
+// the reduction below indexes registers with the step number, so it must never remain a loop (an unroll pragma is a
+// request that the compiler's size threshold may turn into a partial unroll, and the registers into scratch memory).
+template <typename F, int... I>
+__device__ __forceinline__ void static_steps_impl(F&& f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>()), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_steps(F&& f)
+{
+    static_steps_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>());
 }
 
 constexpr int freg_slot_bytes(int T, int PBK) { return 1024 + (PBK * T * 64 + 1023) / 1024 * 1024; }
@@ -89,23 +117,29 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lrow = lane & 31, lhalf = lane >> 5;
+    const uint8_t* const a_base = uniform_ptr(g.a);
+    const int4* const rec_base = uniform_ptr(g.rec);
+    const uint16_t* const ent_base = uniform_ptr(g.ent);
 
-    // ---- this workgroup's column group and row range
+    // ---- this workgroup's column group and row range (the host passes the quotients: a division costs this lone
+    // wavefront a few hundred cycles, and everything before the first copy is start-up latency)
     uint32_t cg, range;
     {
-        const uint32_t b = blockIdx.x, n_cg = (uint32_t)g.n_cg;
-        if (g.xcd_mode) {
-            const uint32_t x = b & 7, i = b >> 3, per_xcd = gridDim.x >> 3;
-            cg = i % n_cg;
-            range = x * (per_xcd / n_cg) + i / n_cg;
+        const uint32_t b = blockIdx.x, i = g.xcd_mode ? b >> 3 : b;
+        uint32_t j;
+        if (g.cg_shift >= 0) {
+            cg = i & ((1u << g.cg_shift) - 1u);
+            j = i >> g.cg_shift;
         } else {
-            cg = b % n_cg;
-            range = b / n_cg;
+            j = i / (uint32_t)g.n_cg;
+            cg = i - j * (uint32_t)g.n_cg;
         }
+        range = g.xcd_mode ? (b & 7u) * (uint32_t)g.ranges_per_xcd + j : j;
     }
     if (range >= (uint32_t)g.n_ranges) return;                    // the whole workgroup, before any barrier
-    const uint32_t rb_lo = (uint32_t)((uint64_t)range * g.n_blocks / (uint32_t)g.n_ranges);
-    const uint32_t rb_hi = (uint32_t)((uint64_t)(range + 1) * g.n_blocks / (uint32_t)g.n_ranges);
+    // the first range_rem ranges have range_q + 1 row blocks, the others range_q
+    const uint32_t rb_lo = range * g.range_q + (range < g.range_rem ? range : g.range_rem);
+    const uint32_t rb_hi = rb_lo + g.range_q + (range < g.range_rem ? 1u : 0u);
     const int n_pass = (int)((rb_hi - rb_lo + PBK - 1) / PBK);
     const uint32_t M = (uint32_t)g.M;
     const int32_t origin = lowest_pixel_from(g.q, decompose(g.q, rb_lo * 32u));       // pixel of ring row 0
@@ -120,60 +154,85 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
         const uint32_t pixels = top >= origin ? (uint32_t)(top - origin) + 1u : 1u;
         return (pixels * PP + 63u) / 64u;
     };
-    // copy u: ring pieces 64u .. 64u + 63 (one wavefront-wide 1 KB copy); lane -> (pixel, piece of its row)
-    auto copy_ring = [&](uint32_t u) {
-        const uint32_t gch = u * 64u + (uint32_t)lane;
-        const uint32_t ps = gch / PP;
-        uint32_t piece = gch - ps * PP;
-        if (piece > PP - 2) piece = PP - 2;                       // the padding piece repeats the last one
-        uint32_t pix = (uint32_t)origin + ps;
+    // Ring copies.  Copy u fills ring pieces 64u .. 64u + 63 (one wavefront-wide 1 KB copy); this wavefront issues
+    // u = wave, wave + 4, ...  Its state is carried from copy to copy with adds and compares only: the LDS address, and
+    // per lane the pixel (counted from the origin) and the piece of that pixel's row the lane moves.
+    const uint32_t ring_bytes = ring_chunks * 16u;
+    uint32_t cu = (uint32_t)wave;
+    uint32_t cdst = lds_base + (uint32_t)wave * 1024u;
+    uint32_t cps = ((uint32_t)wave * 64u + (uint32_t)lane) / PP;
+    uint32_t cpiece = ((uint32_t)wave * 64u + (uint32_t)lane) % PP;
+    auto copy_next = [&]() {
+        uint32_t pix = (uint32_t)origin + cps;
         if (pix > (uint32_t)g.last_pixel) pix = (uint32_t)g.last_pixel;      // never read past the tensor
-        const uint32_t dst = (uint32_t)__builtin_amdgcn_readfirstlane((int)(lds_base + ((u * 64u) % ring_chunks) * 16u));
-        copy16_global_to_lds(g.a, pix * (uint32_t)g.stride_bytes + piece * 16u, dst);
+        const uint32_t piece = cpiece > PP - 2 ? PP - 2 : cpiece;            // the padding piece repeats the last one
+        copy16_global_to_lds(a_base, pix * (uint32_t)g.stride_bytes + piece * 16u,
+                             (uint32_t)__builtin_amdgcn_readfirstlane((int)cdst));
+        cu += 4u;
+        cdst += 4096u;
+        if (cdst >= lds_base + ring_bytes) cdst -= ring_bytes;
+        cps += 256u / PP;
+        cpiece += 256u % PP;
+        if (cpiece >= (uint32_t)PP) { cpiece -= PP; cps += 1u; }
     };
-    // my share of everything pass k needs beyond what earlier passes brought in
-    auto issue_pass = [&](int k, uint32_t from, uint32_t upto) {
+    // block records and entries of pass k -> its slot
+    auto copy_entries = [&](int k) {
         const uint32_t slot = (uint32_t)__builtin_amdgcn_readfirstlane((int)(lds_base + slot_off + (uint32_t)(k & 1) * SLOT));
         const uint32_t blk0 = rb_lo + (uint32_t)k * PBK;
         if (wave == 0) {
             uint32_t blk = blk0 + (uint32_t)lane;
             if (blk > g.n_blocks - 1) blk = g.n_blocks - 1;
-            if (lane < PBK) copy16_global_to_lds(g.rec, blk * 16u, slot);
+            if (lane < PBK) copy16_global_to_lds(rec_base, blk * 16u, slot);
         }
+#pragma unroll
         for (int e = 0; e < ECOP; e++)
             if (((e + 1) & 3) == wave) {
                 uint32_t off = blk0 * (uint32_t)(T * 64) + (uint32_t)e * 1024u + (uint32_t)lane * 16u;
                 if (off > g.ent_bytes - 16u) off = g.ent_bytes - 16u;
-                copy16_global_to_lds(g.ent, off, slot + 1024u + (uint32_t)e * 1024u);
+                copy16_global_to_lds(ent_base, off, slot + 1024u + (uint32_t)e * 1024u);
             }
-        for (uint32_t u = from + ((uint32_t)wave - from) % 4u; u < upto; u += 4u) copy_ring(u);
     };
 
-    // ---- start-up: the first pass's window, this wavefront's filter block, the zero row
-    uint32_t issued = copies_upto_pass(0);
-    issue_pass(0, 0u, issued);
+    // ---- start-up: the windows of the first two passes and the zero row.  The filter is not loaded here: see below.
+    uint32_t upto_next = copies_upto_pass(n_pass > 1 ? 1 : 0);
+    copy_entries(0);
+    if (n_pass > 1) copy_entries(1);
+    while (cu < upto_next) copy_next();
     const int c = wave % WN, h = wave / WN;
-    u32x4_t B[NF];
+    // The kernel elements are walked in an order rotated by the row range: the sum does not care, and the workgroups
+    // -- which all read the same filter at the same time -- then ask the L2 channels for different lines at any one
+    // moment instead of queueing on the same ones.
+    int tap_of[T];
     {
-        const u32x4_t* wp = (const u32x4_t*)(g.w + ((size_t)(cg * WN + c) * NF) * 1024) + lane;
+        const int rot = (int)(range % (uint32_t)T);
 #pragma unroll
-        for (int f = 0; f < NF; f++) B[f] = wp[f * 64];
+        for (int j = 0; j < T; j++) tap_of[j] = j + rot < T ? j + rot : j + rot - T;
     }
+    u32x4_t B[NF];
+    const u32x4_t* const wp = (const u32x4_t*)(g.w + ((size_t)(cg * WN + c) * NF) * 1024) + lane;
+    auto load_filter = [&](int f) { B[f] = wp[(tap_of[f / KS] * KS + f % KS) * 64]; };
     for (int i = tid; i < PITCH / 4; i += 256) *(uint32_t*)(lds + zero_off + i * 4) = I8 ? 0x80808080u : 0u;
-    // the filter registers are final from here on: the compiler must not keep a wait for these loads inside the loop
-#pragma unroll
-    for (int f = 0; f < NF; f++) asm volatile("" : : "v"(B[f]));
+    if (n_pass > 2) upto_next = copies_upto_pass(2);
     wait_vmcnt<0>();
     __syncthreads();
 
     const int32_t col = (int32_t)(cg * WN + c) * 32 + lrow;
-    for (int k = 0; k < n_pass; k++) {
+    // One pass.  `first` (a compile-time tag) selects the copy of the body that runs once, for pass 0: it loads the
+    // filter fragments FD steps ahead of their first use, so the filter -- the largest thing a workgroup reads,
+    // through a 64 byte per clock L1 -- arrives spread over the first pass instead of delaying its start.  That copy
+    // issues no ring copies (the second pass's window was requested at start-up): the compiler's waits for the filter
+    // loads count every vector-memory operation of the wavefront, and a copy from HBM between them would stall the MFMAs.
+    constexpr int FD = 10;
+    auto run_pass = [&](int k, auto first) __attribute__((always_inline)) {
+        constexpr bool FIRST = decltype(first)::value;
         // the next pass's window: its copies land while this pass is multiplied (their ring rows and entry slot were
-        // last read in the pass before this one, which every wavefront has left)
-        if (k + 1 < n_pass) {
-            const uint32_t upto = copies_upto_pass(k + 1);
-            issue_pass(k + 1, issued, upto);
-            issued = upto > issued ? upto : issued;
+        // last read in the pass before this one, which every wavefront has left); the entries now, the ring copies one
+        // at a time between the MFMA steps below, where their address arithmetic costs nothing
+        const uint32_t upto = !FIRST && k + 1 < n_pass ? upto_next : 0u;
+        if (!FIRST && k + 1 < n_pass) copy_entries(k + 1);
+        if constexpr (FIRST) {
+#pragma unroll
+            for (int f = 0; f < FD && f < NF; f++) load_filter(f);
         }
 
         const uint8_t* slot = lds + slot_off + (k & 1) * SLOT;
@@ -188,47 +247,58 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[i][0][r] = 0;
 
-        // The reduction as one unrolled sequence of NF steps (kernel element tap = step / KS, 32-byte piece step % KS
-        // of its rows).  The wavefront is alone on its SIMD, so the latencies are hidden by software pipelining: a
-        // step's row numbers are read LA steps ahead, turned into LDS addresses LA - PF steps later, the A fragments
-        // are read PF steps ahead, and only then come the step's MFMAs.  The scheduling barriers keep the compiler
-        // from folding that order back into load-wait-multiply.
-        constexpr int PF = 2, LA = 4;
+        // The reduction as one unrolled sequence of NF steps (step st: kernel element tap_of[st / KS], 32-byte piece
+        // st % KS of its rows).  The wavefront is alone on its SIMD, so the latencies are hidden by software
+        // pipelining: a kernel element's row numbers are read LA + 1 steps before its first step, turned into LDS
+        // addresses PF + 1 steps before it, the A fragments are read PF steps ahead, and only then come the step's
+        // MFMAs.  The scheduling barriers keep the compiler from folding that order back into load-wait-multiply.
+        constexpr int PF = 3, LA = 6;
         uint32_t e16[T][MB], addr[T][MB];                      // few of them are live at any time
         u32x4_t af[PF + 1][MB];
-        auto read_rows = [&](int tap) {
+        auto read_rows = [&](int j) {
 #pragma unroll
-            for (int i = 0; i < MB; i++) e16[tap][i] = ent[(i * T + tap) * 32];
+            for (int i = 0; i < MB; i++) e16[j][i] = ent[(i * T + tap_of[j]) * 32];
         };
-        auto locate = [&](int tap) {
+        auto locate = [&](int j) {
 #pragma unroll
             for (int i = 0; i < MB; i++) {
-                const uint32_t row = (e16[tap][i] + (uint32_t)delta[i]) & ring_mask;
-                addr[tap][i] = (e16[tap][i] == 0xFFFFu ? zero_off : row * PITCH) + (uint32_t)lhalf * 16u;
+                const uint32_t row = (e16[j][i] + (uint32_t)delta[i]) & ring_mask;
+                addr[j][i] = (e16[j][i] == 0xFFFFu ? zero_off : __umul24(row, (uint32_t)PITCH)) + (uint32_t)lhalf * 16u;
             }
         };
         auto read_frags = [&](int st) {
 #pragma unroll
             for (int i = 0; i < MB; i++) af[st % (PF + 1)][i] = *(const u32x4_t*)(lds + addr[st / KS][i] + (st % KS) * 32);
         };
+        // before the first step: the rows of the kernel elements whose fragments are read within the first PF + 1
+        // steps are located here, those read within the first LA + 1 steps have their row numbers requested
 #pragma unroll
-        for (int tap = 0; tap * KS < LA && tap < T; tap++) read_rows(tap);
+        for (int j = 0; j * KS < LA + 1 && j < T; j++) read_rows(j);
 #pragma unroll
-        for (int tap = 0; tap * KS < LA && tap < T; tap++) locate(tap);
+        for (int j = 0; j * KS < PF + 1 && j < T; j++) locate(j);
 #pragma unroll
         for (int st = 0; st < PF && st < NF; st++) read_frags(st);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int st = 0; st < NF; st++) {
-            if ((st + LA) % KS == 0 && (st + LA) / KS < T) read_rows((st + LA) / KS);
-            if ((st + PF) % KS == 0 && (st + PF) / KS < T && (st + PF) >= LA) locate((st + PF) / KS);
+        static_steps<NF>([&](auto step) __attribute__((always_inline)) {
+            constexpr int st = decltype(step)::value;
             if (st + PF < NF) read_frags(st + PF);
+            if constexpr (FIRST) {
+                if (st + FD < NF) load_filter(st + FD);
+            }
 #pragma unroll
             for (int i = 0; i < MB; i++) acc[i][0] = mfma_frag<I8>(af[st % (PF + 1)][i], B[st], acc[i][0]);
+            // book-keeping behind the MFMAs, where it is free: the kernel element whose fragments the NEXT step starts
+            // to read is located now, row numbers are requested LA - PF steps before they are located
+            constexpr int jl = (st + 1 + PF) / KS, jr = (st + 1 + LA) / KS;
+            if ((st + 1 + PF) % KS == 0 && jl < T && jl * KS >= PF + 1) locate(jl);
+            if ((st + 1 + LA) % KS == 0 && jr < T && jr * KS >= LA + 1) read_rows(jr);
+            if (!FIRST && st % 2 == 1 && cu < upto) copy_next();
+            if (st == NF / 2 && k + 2 < n_pass && (!FIRST || n_pass > 2)) upto_next = copies_upto_pass(k + 2);
             __builtin_amdgcn_sched_barrier(0);
-        }
+        });
+        while (cu < upto) copy_next();                      // a window that jumped (an image boundary) has more
 
-        // my copies for the next pass (issued a pass ago) and the stores of the pass before this one
+        // my copies for the next pass (issued during this one) and the stores of the pass before this one
         wait_vmcnt<0>();
         const uint32_t blk = rb_lo + (uint32_t)k * PBK + (uint32_t)(h * MB);
         if (blk < rb_hi) {
@@ -241,7 +311,19 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
+    };
+    run_pass(0, std::true_type());
+    // The filter registers are final from here on.  Passing them through an empty statement tells the compiler that
+    // none of their loads is outstanding any more (the loop below then carries no wait for them) and says where each
+    // fragment lives: 4 * NF registers do not fit the 256 vector registers beside everything else, so all but the
+    // first FV fragments are kept in the accumulation registers, from which the MFMAs read them directly.
+    constexpr int FV = NF <= 36 ? NF : (NF <= 56 ? 28 : 20);
+#pragma unroll
+    for (int f = 0; f < NF; f++) {
+        if (f < FV) asm volatile("" : "+v"(B[f]));
+        else asm volatile("" : "+a"(B[f]));
     }
+    for (int k = 1; k < n_pass; k++) run_pass(k, std::false_type());
 }
 
 // ------------------------------------------------------------------ launch
@@ -298,7 +380,7 @@ int launch_igemm_freg(const icv_conv_params* p, const Geometry& g, const void* i
     a.rec = (const int4*)ind;
     a.ent = (const uint16_t*)(a.rec + g.img_tiles);
     a.out = out;
-    a.q = RangeGeom{p->Hin, p->Win, g.Hout, g.Wout, p->SY, p->SX, p->DY, p->DX, p->PT, p->PL, p->R, p->S};
+    a.q = make_range_geom(p->Hin, p->Win, g.Hout, g.Wout, p->SY, p->SX, p->DY, p->DX, p->PT, p->PL, p->R, p->S);
     a.M = g.M;
     a.K = p->K; a.out_stride = g.out_stride;
     a.stride_bytes = g.in_stride * g.elem_bytes;
@@ -318,6 +400,12 @@ int launch_igemm_freg(const icv_conv_params* p, const Geometry& g, const void* i
     a.xcd_mode = 0;
     if (ranges % 8 == 0) a.xcd_mode = 1;          // grid / 8 workgroups per XCD, a whole number of row ranges each
     a.n_ranges = (int32_t)ranges;
+    a.ranges_per_xcd = (int32_t)(ranges / 8);
+    a.range_q = (uint32_t)(a.n_blocks / ranges);
+    a.range_rem = (uint32_t)(a.n_blocks % ranges);
+    a.cg_shift = -1;
+    for (int sh = 0; sh < 16; sh++)
+        if ((1 << sh) == a.n_cg) a.cg_shift = sh;
     const size_t lds = freg_lds_bytes(T, KS, PBK, a.ring_rows);
     if (lds > kLdsPerCu || (a.ring_rows & (a.ring_rows - 1)) || a.ring_rows < 64) return ICV_ERR_UNSUPPORTED;
     const bool i8 = p->dtype == ICV_U8I8;

@@ -19,9 +19,37 @@
 
 namespace icv {
 
+// Division of a non-negative number below 2^31 by an invariant divisor, as a multiplication and a shift: with
+// sh = ceil(log2 d) and mul = ceil(2^(31 + sh) / d) (which fits 32 bits), floor(n / d) = (n * mul) >> (31 + sh) exactly.
+// The kernels divide output pixel numbers by Wout and Hout before they can issue their first load, and a hardware
+// division is some thirty dependent instructions.
+struct FastDiv {
+    uint32_t mul, shift, d;
+};
+
+inline FastDiv make_fast_div(uint32_t d)
+{
+    FastDiv f;
+    uint32_t sh = 0;
+    while ((1ull << sh) < d) ++sh;
+    f.mul = (uint32_t)(((1ull << (31 + sh)) + d - 1) / d);
+    f.shift = 31 + sh;
+    f.d = d;
+    return f;
+}
+
+ICV_HD inline uint32_t fast_div(uint32_t n, const FastDiv& f) { return (uint32_t)(((uint64_t)n * f.mul) >> f.shift); }
+
 struct RangeGeom {
     int32_t Hin, Win, Hout, Wout, SY, SX, DY, DX, PT, PL, R, S;
+    FastDiv by_wout, by_hout;
 };
+
+inline RangeGeom make_range_geom(int32_t Hin, int32_t Win, int32_t Hout, int32_t Wout, int32_t SY, int32_t SX, int32_t DY,
+                                 int32_t DX, int32_t PT, int32_t PL, int32_t R, int32_t S)
+{
+    return RangeGeom{Hin, Win, Hout, Wout, SY, SX, DY, DX, PT, PL, R, S, make_fast_div((uint32_t)Wout), make_fast_div((uint32_t)Hout)};
+}
 
 struct OutPixel {
     int32_t n, oy, ox;
@@ -29,10 +57,10 @@ struct OutPixel {
 
 ICV_HD inline OutPixel decompose(const RangeGeom& q, uint32_t m)
 {
-    const uint32_t row = m / (uint32_t)q.Wout;
+    const uint32_t row = fast_div(m, q.by_wout);
     OutPixel o;
     o.ox = (int32_t)(m - row * (uint32_t)q.Wout);
-    o.n = (int32_t)(row / (uint32_t)q.Hout);
+    o.n = (int32_t)fast_div(row, q.by_hout);
     o.oy = (int32_t)(row - (uint32_t)o.n * (uint32_t)q.Hout);
     return o;
 }

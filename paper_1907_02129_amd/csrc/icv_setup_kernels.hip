@@ -290,7 +290,7 @@ int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_
         BlockIndArgs b{};
         b.rec = (int4*)ind;
         b.ent = (uint16_t*)(b.rec + g.img_tiles);
-        b.q = RangeGeom{p->Hin, p->Win, g.Hout, g.Wout, p->SY, p->SX, p->DY, p->DX, p->PT, p->PL, p->R, p->S};
+        b.q = make_range_geom(p->Hin, p->Win, g.Hout, g.Wout, p->SY, p->SX, p->DY, p->DX, p->PT, p->PL, p->R, p->S);
         b.M = g.img_rows;
         b.n_blocks = (uint32_t)g.img_tiles;
         b.T = g.T;
