@@ -220,6 +220,20 @@ ICV_API int icv_gemm_nhwc(const icv_conv_params* p, const void* im2col_ws, const
 ICV_API int icv_conv2d_nhwc_im2col(const icv_conv_params* p, const void* input, const void* packed_filter,
                            void* im2col_ws, void* output, void* stream);
 
+/*
+ * icv_conv2d_nhwc_im2col for callers that cannot allocate device memory: code under HIP graph capture, serving loops
+ * and harnesses that forbid hipMalloc.  The patch matrix goes into a buffer that is part of the library's own device
+ * image (icv_static_workspace_bytes() bytes, 16 MiB, per GPU, held until the process ends) instead of a caller's
+ * workspace; the call itself allocates nothing and frees nothing.  The kernels and the results are those of
+ * icv_conv2d_nhwc_im2col.  ICV_ERR_UNSUPPORTED when icv_im2col_bytes(p) exceeds the buffer (or is 0: a plan without
+ * ablation).  All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU (different
+ * streams, or threads) race on it; calls on one stream are ordered and safe.  Nothing in the buffer needs clearing
+ * between calls: every byte a call reads, it has written before.
+ */
+ICV_API size_t icv_static_workspace_bytes(void);
+ICV_API int icv_conv2d_nhwc_im2col_static(const icv_conv_params* p, const void* input, const void* packed_filter,
+                                  void* output, void* stream);
+
 /* Name of the kernel variant icv_conv2d_nhwc would launch for p (static string; "" when invalid). */
 ICV_API const char* icv_plan_name(const icv_conv_params* p);
 

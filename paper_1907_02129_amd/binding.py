@@ -29,6 +29,7 @@ EXPORTS = (
     "icv_im2col_bytes", "icv_indirection_index", "icv_get_indirection_layout", "icv_row_pixel_range",
     "icv_tile_span_bound", "icv_init_zero_row", "icv_pack_filter",
     "icv_setup_indirection", "icv_conv2d_nhwc", "icv_conv2d_nhwc_fused", "icv_im2col", "icv_gemm_nhwc", "icv_conv2d_nhwc_im2col",
+    "icv_static_workspace_bytes", "icv_conv2d_nhwc_im2col_static",
     "icv_plan_name", "icv_status_string", "icv_last_hip_error",
 )
 
@@ -94,6 +95,8 @@ def load_library(path: str | None = None):
         "icv_im2col": (ctypes.c_int, [P, vp, vp, vp]),
         "icv_gemm_nhwc": (ctypes.c_int, [P, vp, vp, vp, vp]),
         "icv_conv2d_nhwc_im2col": (ctypes.c_int, [P, vp, vp, vp, vp, vp]),
+        "icv_static_workspace_bytes": (ctypes.c_size_t, []),
+        "icv_conv2d_nhwc_im2col_static": (ctypes.c_int, [P, vp, vp, vp, vp]),
         "icv_plan_name": (ctypes.c_char_p, [P]),
         "icv_status_string": (ctypes.c_char_p, [ctypes.c_int]),
         "icv_last_hip_error": (ctypes.c_int, []),
@@ -230,6 +233,15 @@ def gemm_nhwc(p, ws, packed_filter, output, stream=None):
 def conv2d_nhwc_im2col(p, input, packed_filter, ws, output, stream=None):
     _check(load_library().icv_conv2d_nhwc_im2col(ctypes.byref(p), _ptr(input), _ptr(packed_filter), _ptr(ws),
                                                  _ptr(output), _stream(stream)), "icv_conv2d_nhwc_im2col")
+
+
+def static_workspace_bytes() -> int:
+    return load_library().icv_static_workspace_bytes()
+
+
+def conv2d_nhwc_im2col_static(p, input, packed_filter, output, stream=None):
+    _check(load_library().icv_conv2d_nhwc_im2col_static(ctypes.byref(p), _ptr(input), _ptr(packed_filter), _ptr(output),
+                                                        _stream(stream)), "icv_conv2d_nhwc_im2col_static")
 
 
 # ---------------------------------------------------------------- convenience: buffers for one problem

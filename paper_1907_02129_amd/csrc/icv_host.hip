@@ -357,6 +357,28 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
 
 static bool aligned16(const void* ptr) { return ((uintptr_t)ptr & 15u) == 0; }
 
+// Workspace of icv_conv2d_nhwc_im2col_static: part of the device image, so no call ever allocates it.  Every GPU the
+// library runs on holds its own copy at its own address; in host code the array's name is only a handle for
+// hipGetSymbolAddress, never an address to pass to a kernel.
+constexpr size_t kStaticWorkspaceBytes = 16u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
+
+static int static_workspace(void** out)
+{
+    static void* address[64] = {};        // per device ordinal; a race between threads stores the same value twice
+    int dev = 0;
+    ICV_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return ICV_ERR_UNSUPPORTED;
+    if (!address[dev]) {
+        void* ptr = nullptr;
+        ICV_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return ICV_ERR_HIP;
+        address[dev] = ptr;
+    }
+    *out = address[dev];
+    return ICV_OK;
+}
+
 // The ablation path has no indirection buffer, so it tiles the whole batch as one image.  The tile, stage width and
 // stage order stay those of the problem's own plan (batch-independent buffer or not), because the packed filter the
 // caller passes was laid out by icv_pack_filter for exactly that plan.
@@ -582,6 +604,24 @@ int icv_conv2d_nhwc_im2col(const icv_conv_params* p, const void* input, const vo
     const int st = icv_im2col(p, input, im2col_ws, stream);
     if (st != ICV_OK) return st;
     return icv_gemm_nhwc(p, im2col_ws, packed_filter, output, stream);
+}
+
+size_t icv_static_workspace_bytes(void) { return kStaticWorkspaceBytes; }
+
+int icv_conv2d_nhwc_im2col_static(const icv_conv_params* p, const void* input, const void* packed_filter,
+                                  void* output, void* stream)
+{
+    const size_t need = icv_im2col_bytes(p);
+    if (need == 0) {
+        Geometry g;
+        const int st = make_geometry(p, &g);
+        return st != ICV_OK ? st : ICV_ERR_UNSUPPORTED;
+    }
+    if (need > kStaticWorkspaceBytes) return ICV_ERR_UNSUPPORTED;
+    void* ws = nullptr;
+    const int st = static_workspace(&ws);
+    if (st != ICV_OK) return st;
+    return icv_conv2d_nhwc_im2col(p, input, packed_filter, ws, output, stream);
 }
 
 const char* icv_plan_name(const icv_conv_params* p)
