@@ -207,7 +207,7 @@ def layer_sweep(icv, torch, N):
                    "kernel": icv.plan_name(pp), "ms": t_default, "TFLOPs": f / (t_default * 1e-3) / 1e12}
             # the Indirect GEMM primitive proper (rows gathered through the buffer) where the default is another
             # form of it; the ablation runs with the tile the library picks for a plain GEMM
-            pr_g = Problem(icv, torch, sh, sets=nsets, plan=1 << 12)
+            pr_g = Problem(icv, torch, sh, sets=nsets, plan=icv.PLAN_GATHER)
             t_gather = t_default
             if icv.plan_name(pr_g.p) != icv.plan_name(pp):
                 t_gather = graph_time(torch, pr_g.step, per_replay)
@@ -398,8 +398,8 @@ def main():
             row["indirection_GBps"] = ib / (ts * 1e-3) / 1e9
             if sh.dtype != "f32":
                 # the ablation and the per-element-gather variant run with the tile the library picks for them
-                # (plan bit 12: rows gathered per kernel element), not with the pixel-range plan's tile
-                pr_abl = Problem(icv, torch, sh, sets=min(len(pr.bufs), 12), plan=1 << 12)
+                # (the gather plan: rows fetched per kernel element), not with the pixel-range plan's tile
+                pr_abl = Problem(icv, torch, sh, sets=min(len(pr.bufs), 12), plan=icv.PLAN_GATHER)
                 if icv.plan_name(pr_abl.p) != icv.plan_name(pp):
                     row["per_element_gather_kernel"] = icv.plan_name(pr_abl.p)
                     row["per_element_gather_ms"] = pr_abl.time_quantiles(repeats=9, inner=40, warmup=3)[0]
@@ -409,8 +409,8 @@ def main():
                 row["gemm_only_ms"] = tg
                 row["speedup_vs_im2col_gemm"] = ta / m
             if sh.N > 1 and not icv.plan_name(pp).startswith("gemm_"):
-                # batch-independent indirection buffer (plan bit 17): one image's entries serve the whole batch
-                pr_img = Problem(icv, torch, sh, sets=min(len(pr.bufs), 12), plan=1 << 17)
+                # batch-independent indirection buffer (ICV_PLAN_PER_IMAGE): one image's entries serve the whole batch
+                pr_img = Problem(icv, torch, sh, sets=min(len(pr.bufs), 12), plan=icv.PLAN_PER_IMAGE)
                 row["per_image_buffer"] = {
                     "kernel": icv.plan_name(pr_img.p),
                     "ms": pr_img.time_quantiles(repeats=9, inner=40, warmup=3)[0],

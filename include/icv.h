@@ -63,21 +63,29 @@ typedef struct icv_conv_params {
     int32_t out_pixel_stride;  /* elements between output pixels; 0 means K (ldc of Listing 3)                 */
     int32_t dtype;             /* icv_dtype */
     int32_t input_zero_point;  /* ICV_U8I8 only: the value the zero row holds, 0..255 */
-    int32_t plan;              /* 0: the library picks kernel, tile and pipeline shape.  For tuning sweeps:
-                                  bits 0-3 kernel (1 vector ALU, 2.. tile variant), bits 4-7 LDS ring depth (2..12),
-                                  bits 8-9 workgroups per CU (1, 2), bits 10-11 stage width (1: 64 B, 2: 128 B),
-                                  bits 12-13 row staging (1: rows gathered per kernel element, 2: the tile's
-                                  input pixel range kept in LDS), bits 14-16 kernel elements per pipeline
-                                  stage of the latter.  All set-up calls and the conv call of one problem must use the same value.
-                                  Bit 17 (an option, not a tuning knob): batch-independent indirection buffer.  The
-                                  buffer then holds the entries of ONE image, offsets relative to that image's first
-                                  pixel, and row tiles never straddle two images; the kernels add n * Hin*Win*pixel
-                                  stride for image n.  Section 2.3 lists a change of batch size among the events that
-                                  force the buffer to be (partly) rebuilt; with this bit none is needed: a buffer
-                                  built with any N serves every N, and N plays no part in the choice of the tile
-                                  (the packed filter and zero row do not depend on N either).  The price is a
-                                  partial last tile per image instead of one per batch. */
+    int32_t plan;              /* 0: the library chooses.  Else one ICV_PLAN_* algorithm (bits 0-2), optionally or-ed
+                                  with ICV_PLAN_PER_IMAGE; all other bits must be 0.  All set-up calls and the conv
+                                  call of one problem must use the same value. */
 } icv_conv_params;
+
+/* plan, bits 0-2: the kernel family that computes the convolution (the library's choice when 0).
+ * ICV_ERR_UNSUPPORTED when the family does not cover the problem. */
+#define ICV_PLAN_VECTOR_ALU 1   /* fp32 vector-ALU kernel, no tensor cores: every dtype, every shape */
+#define ICV_PLAN_GATHER 2       /* tensor cores; each kernel element's rows fetched through their entries, one
+                                   element at a time: the Indirect GEMM of section 2.2 as printed, and the only
+                                   family whose packed filter the im2col + GEMM comparison path reads */
+#define ICV_PLAN_WINDOW 3       /* tensor cores; the input pixels a row tile names are copied to LDS once and
+                                   every kernel element reads them there */
+#define ICV_PLAN_FILTER_REGS 4  /* tensor cores; the filter stays in registers and the input slides through LDS
+                                   (3x3 on 128- and 256-byte pixel rows, 5x5 on 64-byte ones) */
+/* plan, bit 3: batch-independent indirection buffer.  The buffer then holds the entries of ONE image, offsets
+ * relative to that image's first pixel, and row tiles never straddle two images; the kernels add
+ * n * Hin*Win*pixel stride for image n.  Section 2.3 lists a change of batch size among the events that force the
+ * buffer to be (partly) rebuilt; with this bit none is needed: a buffer built with any N serves every N, and N
+ * plays no part in the choice of the tile (the packed filter and zero row do not depend on N either).  The price
+ * is a partial last tile per image instead of one per batch. */
+#define ICV_PLAN_PER_IMAGE 8
+
 
 /* Hout, Wout by the formula above.  ICV_ERR_INVALID_ARG when the parameters are not a valid problem. */
 ICV_API int icv_output_size(const icv_conv_params* p, int32_t* Hout, int32_t* Wout);
@@ -85,7 +93,7 @@ ICV_API int icv_output_size(const icv_conv_params* p, int32_t* Hout, int32_t* Wo
 /*
  * Buffer sizes in bytes (0 when the parameters are invalid).
  *  indirection  : int32 entries, M rounded up to whole row tiles, times R*S (independent of C, section 1.1;
- *                 with plan bit 17, M is Hout*Wout, one image's output pixels, whatever N is);
+ *                 with ICV_PLAN_PER_IMAGE, M is Hout*Wout, one image's output pixels, whatever N is);
  *                 kernels that keep a tile's input pixels in LDS, and the kernel for very short pixel rows
  *                 (which reads the entries in this compact form), append one 16-byte record per row tile,
  *                 {smallest valid entry of the tile, pixels from there to the largest one, 0, 0}, and then the
@@ -106,7 +114,7 @@ ICV_API size_t icv_im2col_bytes(const icv_conv_params* p);
  * entries of the indirection buffer (index in entries, see icv_get_indirection_layout).  The physical order is
  * [row tile][tap][row in tile], the order in which Listing 3 consumes pointers (*ppa++: all rows of the tile for one
  * tap, then the next tap).  Rows past M in the last tile name the zero row.  Returns -1 on invalid arguments.  With
- * plan bit 17 the buffer describes one image: m = oy*Wout + ox < Hout*Wout.
+ * ICV_PLAN_PER_IMAGE the buffer describes one image: m = oy*Wout + ox < Hout*Wout.
  */
 ICV_API int64_t icv_indirection_index(const icv_conv_params* p, int64_t m, int32_t tap);
 
@@ -164,7 +172,7 @@ ICV_API int icv_pack_filter(const icv_conv_params* p, const void* filter_krsc, v
  * paper's row pointer minus the tensor's base pointer.  Storing offsets keeps the buffer valid when the
  * input or zero-row pointers change (the paper's fourth invalidation rule then never applies); it must be
  * rebuilt only when the shape, stride, dilation, padding, pixel stride, element type or batch size change
- * (with plan bit 17 not even for the batch size: N is not read).
+ * (with ICV_PLAN_PER_IMAGE not even for the batch size: N is not read).
  * The input tensor must be smaller than 2 GiB (ICV_ERR_INVALID_ARG otherwise).
  *   indirection: icv_indirection_bytes() device.
  */

@@ -21,6 +21,9 @@ ICV_ERR_INVALID_ARG = -1
 ICV_ERR_UNSUPPORTED = -2
 ICV_ERR_HIP = -3
 ICV_F32, ICV_BF16, ICV_U8I8 = 0, 1, 2
+# icv_conv_params.plan: one algorithm, optionally or-ed with PLAN_PER_IMAGE (icv.h)
+PLAN_VECTOR_ALU, PLAN_GATHER, PLAN_WINDOW, PLAN_FILTER_REGS = 1, 2, 3, 4
+PLAN_PER_IMAGE = 8
 DTYPES = {"f32": ICV_F32, "bf16": ICV_BF16, "u8i8": ICV_U8I8}
 
 # every symbol include/icv.h declares

@@ -276,208 +276,12 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
     }
 }
 
-// Unified variant: no producer / consumer split.  Every wavefront copies its share of each stage and
-// multiplies its block of the tile; the address arithmetic of the next stage is ordinary code between the
-// copy burst and the next wait, so the compiler can spread it among the MFMAs of the current stage, and two
-// wavefronts per SIMD cover each other's LDS and issue latencies.  The ring, the entry prefetch, the tile list
-// and the per-stage barrier are those of the split kernel above.  Output stores share the vmcnt counter with
-// the copies here: after a tile's epilogue the next waits also drain those stores (safe, merely conservative).
-template <bool I8, int MR, int NR, int WM, int WN, int KCB, bool DIRECT, bool FUSED>
-__global__ __launch_bounds__(64 * WM * WN) void k_igemm_uni(IgemmArgs g)
-{
-    constexpr int NW = WM * WN;              // wavefronts; all copy and all multiply
-    constexpr int Q = KCB / 16;
-    constexpr int P = 256 / KCB;
-    constexpr int RPB = 1024 / KCB;
-    constexpr int A_VEC = MR * KCB / 1024 / NW;
-    constexpr int B_VEC = NR * KCB / 1024 / NW;
-    constexpr int LP = A_VEC + B_VEC;
-    constexpr int MRW = MR / WM, NRW = NR / WN;
-    constexpr int MB = MRW / 32, NB = NRW / 32;
-    constexpr int KSTEPS = KCB / 32;
-    constexpr int SLOT = (MR + NR) * KCB;
-    static_assert(A_VEC >= 1 && B_VEC >= 1 && MB >= 1 && NB >= 1, "tile too small for this wavefront split");
-    static_assert(A_VEC * NW * 1024 == MR * KCB && B_VEC * NW * 1024 == NR * KCB, "copies must divide evenly");
-    static_assert(4 * LP <= 63, "vmcnt is a 6-bit counter");
-    using acc_t = typename Acc<I8>::type;
-    using out_t = typename std::conditional<I8, int32_t, float>::type;
-
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
-    const int D = g.ring;
-    const int ent_base = D * SLOT;
-    const int ent_bytes = g.ent_copies * 1024;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const TileList tl = my_tiles(g.total_tiles, g.xcd_mode);
-    const int n_stages = g.n_stages;
-    const int64_t total_stages = tl.count * n_stages;
-
-    // ---- copy side (this wavefront is "producer" p = wave of NW)
-    const int p = wave;
-    const int lrow_in_blk = lane / Q;
-    int a_lane_off[A_VEC], a_row[A_VEC], b_src_off[B_VEC];
-#pragma unroll
-    for (int j = 0; j < A_VEC; j++) {
-        a_row[j] = (p * A_VEC + j) * RPB + lrow_in_blk;
-        a_lane_off[j] = ((lane % Q) ^ ((a_row[j] / P) % Q)) << 4;
-    }
-#pragma unroll
-    for (int j = 0; j < B_VEC; j++) {
-        const int row = (p * B_VEC + j) * RPB + lrow_in_blk;
-        b_src_off[j] = row * KCB + (((lane % Q) ^ ((row / P) % Q)) << 4);
-    }
-    auto fetch_entries = [&](int64_t k) {
-        if constexpr (!DIRECT) {
-            if (k >= tl.count) return;
-            const int64_t mt = (uint32_t)((tl.first + k * tl.step) / g.n_tiles) % g.img_tiles;          // tile of the buffer
-            const int32_t* src = g.ind + mt * ((int64_t)g.T * MR);
-            const uint32_t dst = lds_base + ent_base + (uint32_t)(k & 1) * ent_bytes;
-            const int n_chunks = g.T * MR / 4;
-            for (int u = p; u < g.ent_copies; u += NW) {
-                const int c = u * 64 + lane;
-                if (c < n_chunks) copy16_global_to_lds(src + c * 4, dst + u * 1024);
-            }
-        }
-    };
-    int64_t ik = 0;
-    int is = 0, itap = 0, icc = 0, islot = 0;
-    const uint8_t* wstage = nullptr;
-    const uint8_t* adirect[A_VEC];
-    const uint8_t* a_img = g.a;
-    auto enter_tile = [&]() {
-        if (ik >= tl.count) return;
-        const int64_t tile = tl.first + ik * tl.step;
-        const int32_t nt = (int32_t)(tile % g.n_tiles);
-        const int64_t mt = tile / g.n_tiles;
-        a_img = g.a + ((uint32_t)mt / g.img_tiles) * g.image_bytes;
-        wstage = g.w + ((int64_t)nt * n_stages) * (NR * KCB);
-        if constexpr (DIRECT) {
-#pragma unroll
-            for (int j = 0; j < A_VEC; j++) {
-                const int64_t row = mt * MR + a_row[j];
-                adirect[j] = g.a + (row < g.a_rows ? row : g.a_rows - 1) * g.row_stride_bytes;
-            }
-        }
-    };
-    enter_tile();
-    const uint8_t* asrc[A_VEC];
-    const uint8_t* bsrc = nullptr;
-    bool prepared = false;
-    auto prepare = [&]() {
-        prepared = ik < tl.count;
-        if (!prepared) return;
-        if constexpr (DIRECT) {
-            const int64_t koff = g.cc_major ? (int64_t)(is % g.T) * g.row_bytes + (int64_t)(is / g.T) * KCB
-                                            : (int64_t)is * KCB;
-#pragma unroll
-            for (int j = 0; j < A_VEC; j++)
-                asrc[j] = adirect[j] + koff + a_lane_off[j];
-        } else {
-            const int32_t* ent = (const int32_t*)(lds + ent_base + (int)(ik & 1) * ent_bytes) + itap * MR;
-            int32_t e[A_VEC];
-#pragma unroll
-            for (int j = 0; j < A_VEC; j++) e[j] = ent[a_row[j]];
-            const uint8_t* zsrc = g.zero_row + icc * KCB;
-            const uint8_t* abase = a_img + icc * KCB;
-#pragma unroll
-            for (int j = 0; j < A_VEC; j++) {
-                const uint32_t off = (uint32_t)(e[j] + a_lane_off[j]);
-                asrc[j] = e[j] < 0 ? zsrc + a_lane_off[j] : abase + off;
-            }
-        }
-        bsrc = wstage;
-        wstage += NR * KCB;
-        if (++icc == g.stages_per_tap) { icc = 0; ++itap; }
-        if (++is == n_stages) {
-            is = 0; itap = 0; icc = 0;
-            fetch_entries(ik + 2);
-            ++ik;
-            enter_tile();
-        }
-    };
-    auto issue = [&]() {
-        if (!prepared) return;
-        const uint32_t slot = lds_base + (uint32_t)islot * SLOT;
-#pragma unroll
-        for (int j = 0; j < A_VEC; j++) copy16_global_to_lds(asrc[j], slot + (p * A_VEC + j) * 1024);
-#pragma unroll
-        for (int j = 0; j < B_VEC; j++)
-            copy16_global_to_lds(bsrc + b_src_off[j], slot + MR * KCB + (p * B_VEC + j) * 1024);
-        islot = islot + 1 == D ? 0 : islot + 1;
-    };
-
-    // ---- multiply side
-    const int wm = wave / WN, wn = wave % WN;
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    const int swz = (lrow / P) % Q;
-    const uint32_t a_frag_base = (wm * MRW + lrow) * KCB;
-    const uint32_t b_frag_base = MR * KCB + (wn * NRW + lrow) * KCB;
-
-    fetch_entries(0);
-    fetch_entries(1);
-    wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();
-    prepare();
-    for (int q = 0; q < D - 1; q++) { issue(); prepare(); }
-
-    int cslot = 0;
-    int64_t q = 0;
-    for (int64_t k = 0; k < tl.count; k++) {
-        acc_t acc[MB][NB];
-#pragma unroll
-        for (int i = 0; i < MB; i++)
-#pragma unroll
-            for (int j = 0; j < NB; j++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) acc[i][j][r] = 0;
-
-        for (int s = 0; s < n_stages; s++, q++) {
-            const int64_t younger = total_stages - 1 - q;
-            wait_all_but_stages<LP>(younger < D - 2 ? (int)younger : D - 2);
-            __builtin_amdgcn_s_barrier();
-            issue();
-            prepare();
-            const uint8_t* S = lds + cslot * SLOT;
-            cslot = cslot + 1 == D ? 0 : cslot + 1;
-#pragma unroll
-            for (int ks = 0; ks < KSTEPS; ks++) {
-                const uint32_t coff = (uint32_t)(((2 * ks + lhalf) ^ swz) << 4);
-                uint4 af[MB], bf[NB];
-#pragma unroll
-                for (int i = 0; i < MB; i++) af[i] = *(const uint4*)(S + a_frag_base + i * 32 * KCB + coff);
-#pragma unroll
-                for (int j = 0; j < NB; j++) bf[j] = *(const uint4*)(S + b_frag_base + j * 32 * KCB + coff);
-#pragma unroll
-                for (int i = 0; i < MB; i++)
-#pragma unroll
-                    for (int j = 0; j < NB; j++) acc[i][j] = mfma32<I8>(af[i], bf[j], acc[i][j]);
-            }
-        }
-
-        const int64_t tile = tl.first + k * tl.step;
-        const int32_t nt = (int32_t)(tile % g.n_tiles);
-        const int64_t mt = tile / g.n_tiles;
-        const uint32_t img = (uint32_t)mt / g.img_tiles, t_img = (uint32_t)mt - img * g.img_tiles;
-        const int64_t img_row0 = (int64_t)img * g.img_rows;
-        const int64_t m_base = img_row0 + (int64_t)t_img * MR + wm * MRW + 4 * lhalf;
-        const int32_t n_base = nt * NR + wn * NRW + lrow;
-        const bool whole = (t_img + 1) * MR <= g.img_rows && (nt + 1) * NR <= g.K;     // no row or column tail
-        store_tile<FUSED, I8, MB, NB>(g.out, acc, img_row0 + g.img_rows, g.K, g.out_stride, m_base, n_base, whole, g.ep);
-    }
-    wait_vmcnt<0>();
-}
-
 // ------------------------------------------------------------------ launch
 template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool DIRECT, bool FUSED>
 static int launch_one(const Geometry& g, IgemmArgs a, hipStream_t s)
 {
     constexpr int threads = 64 * (WM * WN + NP);
-    void (*kern)(IgemmArgs);
-    if constexpr (NP == 0) kern = k_igemm_uni<I8, MR, NR, WM, WN, KCB, DIRECT, FUSED>;
-    else kern = k_igemm_mfma<I8, MR, NR, WM, WN, NP, KCB, DIRECT, FUSED>;
+    auto kern = k_igemm_mfma<I8, MR, NR, WM, WN, NP, KCB, DIRECT, FUSED>;
     constexpr size_t slot = (size_t)(MR + NR) * KCB;
     a.ent_copies = DIRECT ? 0 : (int32_t)(((size_t)g.T * MR * 4 + 1023) / 1024);
     const size_t ent = (size_t)2 * a.ent_copies * 1024;
@@ -537,11 +341,10 @@ static int launch_tile(const Geometry& g, const IgemmArgs& a, bool direct, hipSt
     if (g.KCB == 128) {
         return launch_pick<I8, MR, NR, WM, WN, NP, 128>(g, a, direct, s);
     }
-    if constexpr (NR * 64 / 1024 >= (NP == 0 ? WM * WN : NP)) {      // a 64-byte stage of the B tile must still split over the copying wavefronts
+    if constexpr (NR * 64 / 1024 >= NP) {      // a 64-byte stage of the B tile must still split over the copying wavefronts
         return launch_pick<I8, MR, NR, WM, WN, NP, 64>(g, a, direct, s);
     } else {
-        if constexpr (NP == 0) return ICV_ERR_UNSUPPORTED;
-        else return launch_pick<I8, MR, NR, WM, WN, 4, 64>(g, a, direct, s);
+        return launch_pick<I8, MR, NR, WM, WN, 4, 64>(g, a, direct, s);
     }
 }
 
@@ -551,18 +354,8 @@ static int launch_dtype(const Geometry& g, const IgemmArgs& a, bool direct, hipS
     switch (g.variant) {
         case 0: return launch_tile<I8, 128, 64, 2, 2, 4>(g, a, direct, s);
         case 1: return launch_tile<I8, 128, 128, 2, 2, 4>(g, a, direct, s);
-        case 2: return launch_tile<I8, 256, 64, 4, 1, 4>(g, a, direct, s);
         case 3: return launch_tile<I8, 256, 64, 4, 2, 8>(g, a, direct, s);
-        case 4: return launch_tile<I8, 256, 128, 2, 2, 4>(g, a, direct, s);
-        case 5: return launch_tile<I8, 64, 64, 2, 2, 4>(g, a, direct, s);
-        case 6: return launch_tile<I8, 256, 128, 4, 2, 8>(g, a, direct, s);
-        case 7: return launch_tile<I8, 128, 128, 4, 2, 8>(g, a, direct, s);
-        case 8: return launch_tile<I8, 256, 128, 4, 2, 4>(g, a, direct, s);
-        case 9: return launch_tile<I8, 128, 128, 2, 2, 8>(g, a, direct, s);
-        case 10: return launch_tile<I8, 256, 128, 4, 2, 0>(g, a, direct, s);
-        case 11: return launch_tile<I8, 128, 128, 4, 2, 0>(g, a, direct, s);
-        case 12: return launch_tile<I8, 256, 64, 4, 2, 0>(g, a, direct, s);
-        case 13: return launch_tile<I8, 128, 64, 4, 2, 0>(g, a, direct, s);
+        case 4: return launch_tile<I8, 64, 64, 2, 2, 4>(g, a, direct, s);
         default: return ICV_ERR_UNSUPPORTED;
     }
 }

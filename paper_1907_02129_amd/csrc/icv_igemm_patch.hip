@@ -462,15 +462,14 @@ static int launch_dtype(const Geometry& g, const PatchArgs& a, hipStream_t s)
         case 1: return launch_tile<I8, 128, 128, 2, 2>(g, a, s);
         case 2: return launch_tile<I8, 256, 64, 4, 1>(g, a, s);
         case 3: return launch_tile<I8, 256, 64, 4, 2>(g, a, s);
-        case 4: return launch_tile<I8, 256, 128, 2, 2>(g, a, s);
-        case 5: return launch_tile<I8, 64, 64, 2, 2>(g, a, s);
-        case 6: return launch_tile<I8, 256, 128, 4, 2>(g, a, s);
-        case 7: return launch_tile<I8, 128, 128, 4, 2>(g, a, s);
+        case 4: return launch_tile<I8, 64, 64, 2, 2>(g, a, s);
+        case 5: return launch_tile<I8, 256, 128, 4, 2>(g, a, s);
+        case 6: return launch_tile<I8, 128, 128, 4, 2>(g, a, s);
         default: return ICV_ERR_UNSUPPORTED;
     }
 }
 
-bool patch_variant_supported(int variant) { return variant >= 0 && variant <= 7; }
+bool patch_variant_supported(int variant) { return variant >= 0 && variant < kNumTileVariants; }
 
 int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                        const int32_t* ind, void* out, hipStream_t s)

@@ -141,6 +141,11 @@ struct TileVariant {
     int32_t MR, NR, WM, WN;
     const char* tag;
 };
+// Test hooks in icv_conv_params::plan above the public bits (icv.h says they must be 0; the library's own tests set
+// them to run every tile and pipeline shape on problems small enough for the CPU oracle): bits 8-11 tile
+// (1 + index into kTileVariants), bits 12-15 LDS ring depth of the gathering kernel (2..12), bits 16-17 workgroups
+// per compute unit (1, 2), bits 18-19 stage width (1: 64 bytes, 2: 128 bytes), bits 20-22 kernel elements per
+// pipeline stage of the pixel-range kernel.
 extern const TileVariant kTileVariants[];
 extern const int kNumTileVariants;
 

@@ -12,6 +12,7 @@ import pytest
 import torch
 
 import icv_layout as layout
+import plan_hooks as hooks
 import oracle
 from paper_1907_02129_amd import binding as icv
 from paper_1907_02129_amd.workloads import CONFIGS, ConvShape, make_tensors
@@ -178,9 +179,9 @@ def test_small_shapes_match_oracle(s):
     buf, xd = run_indirect(s, x, w)
     check_against_oracle(s, buf.output.cpu().numpy(), x, w)
     if "lowc" in icv.plan_name(buf.p):
-        # the short-row kernel reads compact 16-bit entries by default; plan bit 12 keeps it on the int32 offsets
+        # the short-row kernel reads compact 16-bit entries by default; the gather plan keeps it on the int32 offsets
         assert layout.tile_records(buf.p, buf.indirection) is not None
-        buf32, _ = run_indirect(s, x, w, plan=1 << 12)
+        buf32, _ = run_indirect(s, x, w, plan=icv.PLAN_GATHER)
         assert layout.tile_records(buf32.p, buf32.indirection) is None and icv.plan_name(buf32.p) == icv.plan_name(buf.p)
         assert torch.equal(buf32.output, buf.output)
 
@@ -217,37 +218,32 @@ def test_random_tensor_core_shapes_match_oracle(s):
     check_against_oracle(s, buf.output.cpu().numpy(), x, w)
 
 
-N_PLANS = 15    # plan 1 = vector ALU, 2.. = tensor-core tile variants
-
-
-PATCH_VARIANTS = (0, 1, 2, 3, 4, 5, 6, 7)     # tile variants the pixel-range kernel is instantiated for
-
-
-@pytest.mark.parametrize("staging", [0, 1, 2])
-@pytest.mark.parametrize("plan", range(1, N_PLANS + 1))
+@pytest.mark.parametrize("algo", [0, icv.PLAN_GATHER, icv.PLAN_WINDOW], ids=["auto", "gather", "window"])
+@pytest.mark.parametrize("tile", [None] + list(range(len(hooks.TILES))), ids=["vector_alu"] + hooks.TILES)
 @pytest.mark.parametrize("dtype", ["bf16", "u8i8"])
-def test_every_tile_variant(plan, dtype, staging):
-    if staging and plan == 1:
+def test_every_tile(tile, dtype, algo):
+    """Every tile of the tensor-core kernels (and the vector-ALU kernel) on shapes with row, column and channel tails."""
+    if tile is None and algo:
         pytest.skip("row staging is a property of the tensor-core kernels")
-    variant = plan - 2
-    plan |= staging << 12
+    plan = icv.PLAN_VECTOR_ALU if tile is None else algo | hooks.tile(tile)
     zp = 128 if dtype == "u8i8" else 0
     for s in (ConvShape("v_a", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype=dtype, zero_point=zp, seed=51),
               ConvShape("v_b", 1, 20, 33, 128, 200, 2, 3, SY=1, SX=2, PT=0, PL=1, PB=1, PR=1, dtype=dtype, zero_point=zp, seed=52),
               ConvShape("v_c", 3, 11, 9, 32 if dtype == "bf16" else 64, 33, 3, 3, DY=2, DX=1, PT=2, PL=1, PB=2, PR=1,
                         dtype=dtype, zero_point=zp, seed=53)):
-        _say("variant", plan, icv.plan_name(icv.make_params(s, plan=plan)), s.name)
+        _say("tile", plan, icv.plan_name(icv.make_params(s, plan=plan)), s.name)
         x, w = make_tensors(s)
         try:
             buf, xd = run_indirect(s, x, w, plan=plan)
         except icv.IcvError as e:
-            # a forced variant may decline a stage width it cannot split over its wavefronts -- loudly, not wrongly
-            row_bytes = s.C * (1 if dtype == "u8i8" else 2)
-            no_patch = staging == 2 and variant not in PATCH_VARIANTS
-            assert e.status == icv.ICV_ERR_UNSUPPORTED and (row_bytes % 128 != 0 or no_patch), (plan, s.name, e)
+            # the pixel-range kernel declines a tile whose range does not fit LDS -- loudly, not wrongly
+            assert e.status == icv.ICV_ERR_UNSUPPORTED and algo == icv.PLAN_WINDOW, (plan, s.name, e)
             continue
-        if staging == 2:
-            assert "patch" in icv.plan_name(buf.p)
+        name = icv.plan_name(buf.p)
+        if algo == icv.PLAN_WINDOW:
+            assert "patch" in name
+        if tile is not None and "generic" not in name and ("patch" in name or tile in hooks.GATHER_TILES):
+            assert hooks.TILES[tile] in name, name
         check_against_oracle(s, buf.output.cpu().numpy(), x, w)
 
 
@@ -276,14 +272,15 @@ def _patch_shapes():
 
 
 @pytest.mark.parametrize("s", _patch_shapes(), ids=lambda s: s.name)
-@pytest.mark.parametrize("knobs", [0, 2 << 4, 3 << 4, 5 << 4, 1 << 10, (2 << 4) | (1 << 10), 1 << 14, (3 << 14) | (1 << 10),
-                                   (5 << 14) | (2 << 4), 2 << 14, 2 << 8, (2 << 8) | (1 << 10) | (2 << 4), (2 << 8) | (2 << 14)],
+@pytest.mark.parametrize("knobs", [0, hooks.ring(2), hooks.ring(3), hooks.ring(5), hooks.KCB64, hooks.ring(2) | hooks.KCB64,
+                                   hooks.group(1), hooks.group(3) | hooks.KCB64, hooks.group(5) | hooks.ring(2), hooks.group(2),
+                                   hooks.per_cu(2), hooks.per_cu(2) | hooks.KCB64 | hooks.ring(2), hooks.per_cu(2) | hooks.group(2)],
                          ids=["auto", "ring2", "ring3", "ring5", "kcb64", "ring2_kcb64", "group1", "group3_kcb64",
                               "group5_ring2", "group2", "two_per_cu", "two_per_cu_kcb64_ring2", "two_per_cu_group2"])
-@pytest.mark.parametrize("tile", [0, 2, 5, 9], ids=["tile_auto", "128x64", "256x64", "128x128"])
+@pytest.mark.parametrize("tile", [0, hooks.tile(0), hooks.tile(3), hooks.tile(6)], ids=["tile_auto", "128x64", "256x64", "128x128"])
 def test_pixel_range_kernel_matches_oracle(s, knobs, tile):
-    # small shapes get the smallest tile when the library chooses; the larger ones are forced (plan bits 0-3)
-    plan = (2 << 12) | knobs | tile
+    # small shapes get the smallest tile when the library chooses; the larger ones are forced
+    plan = icv.PLAN_WINDOW | knobs | tile
     stride = 64 if s.name == "p_stride" else 0
     x, w = make_tensors(s)
     if stride:
@@ -313,7 +310,7 @@ def test_pixel_range_kernel_matches_oracle(s, knobs, tile):
 def test_range_records_match_oracle_entries(s):
     """Per row tile: smallest valid entry and pixel count up to the largest, from the oracle's entries."""
     x, w = make_tensors(s)
-    buf = icv.prepare(s, icv.to_device(w), plan=2 << 12)
+    buf = icv.prepare(s, icv.to_device(w), plan=icv.PLAN_WINDOW)
     torch.cuda.synchronize()
     got = layout.tile_records(buf.p, buf.indirection)
     assert got is not None
@@ -343,15 +340,15 @@ def test_range_records_match_oracle_entries(s):
 
 
 # ---------------------------------------------------------------- filter in registers, input window in an LDS ring
-FREG = 3 << 12
+FREG = icv.PLAN_FILTER_REGS
 
 
 def _freg_shapes():
     mk = ConvShape
     q = dict(dtype="u8i8", zero_point=128)
     return [
-        # 3x3 on 64-, 128- and 256-byte rows; K of one, two, four column blocks with tails; several passes per workgroup
-        mk("r_c32_k40", 2, 37, 41, 32, 40, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=301),
+        # 3x3 on 128- and 256-byte rows; K of one, two, four column blocks with tails; several passes per workgroup
+        mk("r_c64_k40", 2, 37, 41, 64, 40, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=301),
         mk("r_c64_k64", 3, 29, 31, 64, 64, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=302),
         mk("r_c128_k130", 2, 23, 19, 128, 130, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=303),
         mk("r_c128_k300", 1, 17, 21, 128, 300, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=304),
@@ -359,17 +356,17 @@ def _freg_shapes():
         # stride 2, dilation, asymmetric and oversized padding, no padding, rows that wrap images
         mk("r_s2", 2, 31, 29, 128, 72, 3, 3, SY=2, SX=2, PT=1, PL=1, PB=1, PR=1, seed=306),
         mk("r_dil", 2, 24, 40, 64, 96, 3, 3, SY=1, SX=2, DY=2, DX=3, PT=2, PL=3, PB=2, PR=3, seed=307),
-        mk("r_valid", 5, 12, 12, 32, 64, 3, 3, seed=308),
+        mk("r_valid", 5, 12, 12, 64, 64, 3, 3, seed=308),
         mk("r_bigpad", 2, 9, 30, 64, 32, 3, 3, PT=5, PL=4, PB=6, PR=7, seed=309),
         mk("r_bigpad_s3", 3, 7, 11, 64, 48, 3, 3, SY=3, SX=2, PT=4, PL=5, PB=5, PR=6, seed=310),
         mk("r_tiny_images", 40, 3, 3, 64, 32, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=311),
         mk("r_one_block", 1, 4, 5, 64, 16, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=312),
-        mk("r_stride_pad", 2, 14, 30, 32, 48, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=313),      # run with a pixel stride of 96
+        mk("r_stride_pad", 2, 14, 30, 64, 48, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=313),      # run with a pixel stride of 96
         # 5x5 on 64-byte rows
         mk("r_5x5", 2, 33, 35, 32, 64, 5, 5, PT=2, PL=2, PB=1, PR=1, seed=314),
         mk("r_5x5_s2", 2, 40, 26, 32, 100, 5, 5, SY=2, SX=2, PT=2, PL=2, PB=2, PR=2, seed=315),
         # uint8 x int8
-        mk("r_i8_c64", 2, 25, 27, 64, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=316, **q),
+        mk("r_i8_c128", 2, 25, 27, 128, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=316, **q),
         mk("r_i8_c256", 2, 15, 22, 256, 264, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=317, **q),
         mk("r_i8_c128_s2", 3, 21, 18, 128, 64, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, seed=318, **q),
         mk("r_i8_5x5", 1, 30, 30, 64, 40, 5, 5, PT=2, PL=2, PB=2, PR=2, seed=319, **q),
@@ -433,7 +430,7 @@ def test_pointwise_convolution_runs_as_gemm_on_the_input(s, pixel_stride):
         v = flat.reshape(-1, pixel_stride)
         v[:, :s.C] = x.reshape(-1, s.C)
         xp = flat
-    for plan in (0, 1 << 12):                                   # dispatch to the GEMM, and the gathered path for comparison
+    for plan in (0, icv.PLAN_GATHER):                           # dispatch to the GEMM, and the gathered path for comparison
         p = icv.make_params(s, plan, in_pixel_stride=pixel_stride)
         assert icv.plan_name(p).startswith("gemm_" if plan == 0 else "mfma_"), icv.plan_name(p)
         _say("pointwise", s.name, icv.plan_name(p), "pixel stride", pixel_stride)
@@ -448,7 +445,7 @@ def test_pointwise_convolution_runs_as_gemm_on_the_input(s, pixel_stride):
 
 
 # ---------------------------------------------------------------- batch-independent indirection buffer
-PER_IMAGE = 1 << 17
+PER_IMAGE = icv.PLAN_PER_IMAGE
 
 PER_IMAGE_SHAPES = [
     CONFIGS["cfg1_tiny_f32"].with_(N=3),                                                            # vector ALU
@@ -517,7 +514,8 @@ def test_model_layers_match_oracle(s):
 
 
 # ---------------------------------------------------------------- grids with workgroups that find no tile
-@pytest.mark.parametrize("plan", [0, 1 << 12, 2, 4, 7, (1 << 12) | 7], ids=["auto", "gathered", "128x64", "256x64_c4x1", "64x64", "64x64_gathered"])
+@pytest.mark.parametrize("plan", [0, icv.PLAN_GATHER, hooks.tile(0), hooks.tile(2), hooks.tile(4), icv.PLAN_GATHER | hooks.tile(4)],
+                         ids=["auto", "gathered", "128x64", "256x64_c4x1", "64x64", "64x64_gathered"])
 @pytest.mark.parametrize("tiles64", [9, 13, 23])
 def test_tile_counts_that_are_not_a_multiple_of_eight(plan, tiles64):
     """The XCD-aware tile order launches a multiple of 8 workgroups; with 9, 13 or 23 tiles of 64 rows (fewer of the
@@ -556,7 +554,7 @@ def test_one_zero_row_shared_by_operators_of_different_width():
     widest = max(shapes, key=lambda s: s.C)
     zero_row = torch.empty(icv.zero_row_bytes(icv.make_params(widest)), dtype=torch.uint8, device="cuda:0")
     icv.init_zero_row(icv.make_params(widest), zero_row)
-    for plan in (1 << 12, 1):                                  # gathered tensor-core kernel, vector-ALU kernel
+    for plan in (icv.PLAN_GATHER, icv.PLAN_VECTOR_ALU):        # gathered tensor-core kernel, vector-ALU kernel
         for s in shapes:
             x, w = make_tensors(s)
             buf = icv.prepare(s, icv.to_device(w), plan=plan)
@@ -743,7 +741,7 @@ def test_im2col_gemm_ablation_agrees_with_indirect_path(name):
     _say("ablation", name)
     x, w = make_tensors(s)
     direct, xd = run_indirect(s, x, w)
-    buf = icv.prepare(s, icv.to_device(w), plan=1 << 12)          # the filter packed for the plain GEMM kernels
+    buf = icv.prepare(s, icv.to_device(w), plan=icv.PLAN_GATHER)          # the filter packed for the plain GEMM kernels
     out2, ws = run_im2col(s, buf, xd)
     got1, got2 = direct.output.cpu().numpy(), out2.cpu().numpy()
     # each path is held to the per-element bound against the oracle (which also bounds their difference)
@@ -772,9 +770,9 @@ def test_im2col_gemm_ablation_agrees_with_indirect_path(name):
                          ids=lambda s: s.name)
 def test_im2col_gemm_ablation_with_the_batch_independent_plan(s):
     """The ablation reads the filter as icv_pack_filter laid it out for the problem's plan, whatever tile that plan
-    chose: with plan bit 17 the tile is picked for a full chip, not for this small batch."""
+    chose: with the batch-independent buffer the tile is picked for a full chip, not for this small batch."""
     x, w = make_tensors(s)
-    buf, xd = run_indirect(s, x, w, plan=(1 << 12) | PER_IMAGE)
+    buf, xd = run_indirect(s, x, w, plan=icv.PLAN_GATHER | PER_IMAGE)
     check_against_oracle(s, buf.output.cpu().numpy(), x, w)
     out2, _ = run_im2col(s, buf, xd)
     check_against_oracle(s, out2.cpu().numpy(), x, w)

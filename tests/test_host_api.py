@@ -8,6 +8,7 @@ import numpy as np
 import pytest
 
 import oracle
+import plan_hooks as hooks
 from paper_1907_02129_amd import binding as icv
 from paper_1907_02129_amd.workloads import CONFIGS, ConvShape, random_small_shape
 
@@ -60,7 +61,7 @@ def test_output_size_and_buffer_sizes(lib, name):
     assert (L.entry_bytes == 2) == (L.record_bytes == 16) and (L.records_at >= 0) == (L.record_bytes > 0)
     # the entries do not depend on the number of input channels (section 1.1); with the row staging fixed,
     # neither does the tile the library picks
-    per_tap = 1 << 12
+    per_tap = icv.PLAN_GATHER
     assert (icv.indirection_bytes(icv.make_params(s.with_(C=s.C * 2), plan=per_tap)) ==
             icv.indirection_bytes(icv.make_params(s, plan=per_tap))) or s.dtype == "f32"
     esz = {"f32": 4, "bf16": 2, "u8i8": 1}[s.dtype]
@@ -114,11 +115,17 @@ def test_invalid_arguments_are_rejected(lib):
     assert _status(lib, s, out_pixel_stride=8) == icv.ICV_ERR_INVALID_ARG           # stride < K
     assert _status(lib, s, R=80, PT=0, PB=0) == icv.ICV_ERR_INVALID_ARG             # kernel larger than input
     assert _status(lib, s, N=1 << 20) == icv.ICV_ERR_INVALID_ARG                    # input of 2 GiB or more
-    assert _status(lib, s, plan=1 << 18) == icv.ICV_ERR_INVALID_ARG
-    assert _status(lib, s, plan=3 << 12) == icv.ICV_OK                              # filter in registers, forced
-    assert _status(lib, s, plan=3 << 12, R=7, S=7, PT=3, PL=3, PB=3, PR=3) == icv.ICV_ERR_UNSUPPORTED   # ... not for 7x7
-    assert _status(lib, s, plan=2 | (13 << 4)) == icv.ICV_ERR_INVALID_ARG           # ring deeper than 12
-    assert _status(lib, s, plan=2 | (1 << 4)) == icv.ICV_ERR_INVALID_ARG            # a ring needs two slots
+    assert _status(lib, s, plan=5) == icv.ICV_ERR_INVALID_ARG                       # no such algorithm
+    assert _status(lib, s, plan=1 << 4) == icv.ICV_ERR_INVALID_ARG                  # bits that must be 0
+    assert _status(lib, s, plan=1 << 23) == icv.ICV_ERR_INVALID_ARG
+    assert _status(lib, s, plan=-1) == icv.ICV_ERR_INVALID_ARG
+    assert _status(lib, s, plan=icv.PLAN_FILTER_REGS) == icv.ICV_OK                 # filter in registers, forced
+    assert _status(lib, s, plan=icv.PLAN_FILTER_REGS | icv.PLAN_PER_IMAGE) == icv.ICV_ERR_UNSUPPORTED
+    assert _status(lib, s, plan=icv.PLAN_FILTER_REGS, R=7, S=7, PT=3, PL=3, PB=3, PR=3) == icv.ICV_ERR_UNSUPPORTED   # ... not for 7x7
+    assert _status(lib, s, plan=hooks.tile(0) | hooks.ring(13)) == icv.ICV_ERR_INVALID_ARG     # ring deeper than 12
+    assert _status(lib, s, plan=hooks.tile(0) | hooks.ring(1)) == icv.ICV_ERR_INVALID_ARG      # a ring needs two slots
+    assert _status(lib, s, plan=hooks.tile(7)) == icv.ICV_ERR_INVALID_ARG                      # seven tiles
+    assert _status(lib, s, plan=icv.PLAN_VECTOR_ALU | hooks.tile(0)) == icv.ICV_ERR_INVALID_ARG
     assert _status(lib, CONFIGS["cfg4_int8_3x3"], input_zero_point=300) == icv.ICV_ERR_INVALID_ARG
     assert lib.icv_output_size(None, None, None) == icv.ICV_ERR_INVALID_ARG
     assert icv.indirection_bytes(icv.make_params(s.with_(N=0))) == 0
@@ -132,8 +139,10 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
     assert lib.icv_conv2d_nhwc(ctypes.byref(p), vp(0), vp(0), vp(0), vp(0), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
     assert lib.icv_pack_filter(ctypes.byref(p), vp(0), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
     assert lib.icv_init_zero_row(ctypes.byref(p), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
-    assert lib.icv_im2col(ctypes.byref(p), vp(0), vp(0), vp(0)) == icv.ICV_ERR_UNSUPPORTED     # plan without ablation
-    p = icv.make_params(CONFIGS["cfg2_3x3_c64"], plan=1 << 12)
+    for name in ("cfg2_3x3_c64", "cfg3b_3x3_d2"):     # plans without ablation: a tile the GEMM lacks, filter in registers
+        q = icv.make_params(CONFIGS[name])
+        assert lib.icv_im2col(ctypes.byref(q), vp(0), vp(0), vp(0)) == icv.ICV_ERR_UNSUPPORTED and icv.im2col_bytes(q) == 0
+    p = icv.make_params(CONFIGS["cfg2_3x3_c64"], plan=icv.PLAN_GATHER)
     assert lib.icv_im2col(ctypes.byref(p), vp(0), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
     assert lib.icv_gemm_nhwc(ctypes.byref(p), vp(0), vp(0), vp(0), vp(0)) == icv.ICV_ERR_INVALID_ARG
     ep = icv.make_epilogue()
@@ -255,8 +264,8 @@ def test_tile_span_bound_covers_every_tile(lib):
 
 def test_range_records_are_counted_in_the_buffer_size(lib):
     s = CONFIGS["cfg2_3x3_c64"]
-    streamed = icv.make_params(s, plan=1 << 12)
-    patch = icv.make_params(s, plan=2 << 12)
+    streamed = icv.make_params(s, plan=icv.PLAN_GATHER)
+    patch = icv.make_params(s, plan=icv.PLAN_WINDOW)
     assert "patch" in icv.plan_name(patch) and "patch" not in icv.plan_name(streamed)
     mr = icv.indirection_index(patch, 0, 1)
     tiles = -(-(s.N * 56 * 56) // mr)
@@ -267,13 +276,13 @@ def test_range_records_are_counted_in_the_buffer_size(lib):
     # a single kernel element has nothing to re-use: rows are gathered per element
     assert "patch" not in icv.plan_name(icv.make_params(CONFIGS["cfg5a_1x1"]))
     # forcing the pixel-range kernel where it cannot run is an error, not a silent fallback
-    assert _status(lib, CONFIGS["cfg5a_1x1"], plan=2 << 12) == icv.ICV_ERR_UNSUPPORTED
+    assert _status(lib, CONFIGS["cfg5a_1x1"], plan=icv.PLAN_WINDOW) == icv.ICV_ERR_UNSUPPORTED
 
 
 def test_batch_independent_indirection_buffer_sizes(lib):
-    """Plan bit 17: the buffer describes one image, so its size does not depend on N (section 2.3 re-initialises
+    """ICV_PLAN_PER_IMAGE: the buffer describes one image, so its size does not depend on N (section 2.3 re-initialises
     the buffer when the batch grows; with one image per buffer there is nothing to re-initialise)."""
-    PER_IMAGE = 1 << 17
+    PER_IMAGE = icv.PLAN_PER_IMAGE
     for name in ("cfg2_3x3_c64", "cfg3c_5x5_asym", "cfg5b_7x7_s2", "cfg1_tiny_f32"):
         s = CONFIGS[name]
         one = icv.indirection_bytes(icv.make_params(s.with_(N=1), plan=PER_IMAGE))
@@ -336,7 +345,7 @@ def test_random_plans_and_shapes_never_confuse_the_host_logic(lib):
         dtype = ("f32", "bf16", "u8i8")[i % 3]
         s = random_small_shape(rng, dtype, c_mult=(1, 32, 64)[i % 3] if i % 2 else 4, max_hw=40, max_ck=4)
         s = s.with_(N=int(rng.integers(1, 40)))
-        plan = int(rng.integers(0, 1 << 18))
+        plan = int(rng.integers(0, 16)) | (int(rng.integers(0, 1 << 15)) << 8 if i % 4 else 0)
         p = icv.make_params(s, plan=plan)
         name = icv.plan_name(p)
         sizes = (icv.indirection_bytes(p), icv.packed_filter_bytes(p), icv.zero_row_bytes(p))
@@ -346,7 +355,7 @@ def test_random_plans_and_shapes_never_confuse_the_host_logic(lib):
         seen.add(name.split("_")[0])
         Hout, Wout = icv.output_size(p)
         T = s.R * s.S
-        rows = Hout * Wout * (1 if (plan >> 17) & 1 and not name.startswith("gemm_") else s.N)
+        rows = Hout * Wout * (1 if plan & icv.PLAN_PER_IMAGE and not name.startswith("gemm_") else s.N)
         assert all(v > 0 for v in sizes)
         L = icv.get_indirection_layout(p)
         assert sizes[0] >= L.entry_bytes * rows * T and sizes[0] % 4 == 0

@@ -11,7 +11,7 @@ from paper_1907_02129_amd import binding as icv
 from paper_1907_02129_amd.workloads import ConvShape, make_tensors
 
 pytestmark = pytest.mark.gpu
-GATHER = 1 << 12          # a plan whose packed filter the ablation's plain GEMM reads
+GATHER = icv.PLAN_GATHER          # a plan whose packed filter the ablation's plain GEMM reads
 
 
 def _both_ways(s):
@@ -53,7 +53,7 @@ def test_static_workspace_variant_rejects_what_does_not_fit():
         icv.conv2d_nhwc_im2col_static(p, out, out, out)
     assert e.value.status == icv.ICV_ERR_UNSUPPORTED
     # a plan without ablation (filter in registers) is refused the same way
-    p2 = icv.make_params(s.with_(N=1, Hin=20, Win=20), plan=3 << 12)
+    p2 = icv.make_params(s.with_(N=1, Hin=20, Win=20), plan=icv.PLAN_FILTER_REGS)
     with pytest.raises(icv.IcvError) as e:
         icv.conv2d_nhwc_im2col_static(p2, out, out, out)
     assert e.value.status == icv.ICV_ERR_UNSUPPORTED
