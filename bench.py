@@ -29,12 +29,24 @@ PEAK = {"bf16": 2500.0, "u8i8": 5000.0, "f32": 157.3}      # TFLOP/s (TOP/s), de
 HBM_PEAK_GBS = 8000.0
 LLC_BYTES = 256 << 20
 
-# HBM traffic of the dominant kernel per launch, bytes, measured with rocprofv3 --pmc (FETCH_SIZE and
-# WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None until measured.
-MEASURED_TRAFFIC = {
-    # profiles/igemm_cfg2_hbm_traffic.md: FETCH 7631.2 KiB x 1.99975 + WRITE 25139.0 KiB x 1.0
-    "cfg2_3x3_c64": int((7631.2 * 1.99975 + 25139.0) * 1024),
+# HBM traffic per launch recorded from rocprofv3 --pmc runs (one for FETCH_SIZE, one for WRITE_SIZE, KiB per dispatch,
+# each scaled by what the same counter reads for a 256 MiB copy; profiles/igemm_hbm_traffic.md holds the runs and the
+# command).  A constant recorded then, NOT measured by this run: it is reported only while the library still picks
+# the kernel it was recorded for.
+FETCH_SCALE, WRITE_SCALE = 1.99975, 1.0
+RECORDED_TRAFFIC = {
+    # workload: (kernel, FETCH_SIZE KiB, WRITE_SIZE KiB)
+    "cfg1_tiny_f32": ("generic_f32", 39.4, 2.0),
+    "cfg2_3x3_c64": ("mfma_bf16_256x64_c4x1_patch", 7630.7, 25122.1),
+    "cfg3a_3x3_s2": ("mfma_bf16_freg_w4m1", 15733.2, 25088.0),
+    "cfg3b_3x3_d2": ("mfma_bf16_freg_w4m2", 10121.3, 32771.1),
+    "cfg3c_5x5_asym": ("mfma_bf16_freg_w2m2", 6240.8, 24644.9),
+    "cfg4_int8_3x3": ("mfma_i8_128x128_c2x2_patch", 5926.5, 25088.0),
+    "cfg5a_1x1": ("gemm_bf16_256x64_c4x2_p8", 25302.6, 25101.3),
+    "cfg5b_7x7_s2": ("mfma_bf16_lowc_64x64", 32828.8, 100353.9),
 }
+TRAFFIC_SOURCE = "recorded constant from profiles/igemm_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE), not measured in this run"
+ALU_PEAK_F32 = 157.3          # TFLOP/s, fp32 vector ALUs: 256 CUs x 4 SIMDs x 32 lanes x 2 (FMA) x 2.4 GHz
 
 
 def flops(s, Hout, Wout, c=None):
@@ -46,6 +58,36 @@ def algorithmic_bytes(s, Hout, Wout):
     esz = {"f32": 4, "bf16": 2, "u8i8": 1}[s.dtype]
     M, T = s.N * Hout * Wout, s.R * s.S
     return s.N * s.Hin * s.Win * s.C * esz + s.K * T * s.C * esz + M * s.K * 4 + M * T * 4
+
+
+def roofline(s, Hout, Wout, ms, kernel, name, measured_peak=None):
+    """The roofline object of one shape: which of HBM time (algorithmic bytes at 8 TB/s) and arithmetic time (its
+    flops at the dtype's dense peak) is the longer bounds the kernel; `achieved` is that resource's rate at the
+    measured duration."""
+    fl = flops(s, Hout, Wout, getattr(s, "c_logical", 0) or None)
+    ab = algorithmic_bytes(s, Hout, Wout)
+    tensor = kernel.startswith(("mfma_", "gemm_"))
+    peak = PEAK[s.dtype] if tensor else ALU_PEAK_F32
+    if ab / (HBM_PEAK_GBS * 1e9) >= fl / (peak * 1e12):
+        r = {"bound": "hbm", "achieved": ab / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        r = {"bound": "mfma" if tensor else "alu", "achieved": fl / (ms * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s"}
+    r["frac"] = r["achieved"] / r["peak"]
+    r["algorithmic_bytes"] = ab
+    r["kernel"] = kernel
+    rec = RECORDED_TRAFFIC.get(name)
+    if rec and rec[0] == kernel:
+        r["traffic"] = int((rec[1] * FETCH_SCALE + rec[2] * WRITE_SCALE) * 1024)
+        r["traffic_source"] = TRAFFIC_SOURCE
+    else:
+        r["traffic"] = None
+        r["traffic_source"] = "none recorded for this kernel"
+    r["frac_of_hbm_peak"] = ab / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+    if tensor:
+        r["frac_of_mfma_peak"] = fl / (ms * 1e-3) / 1e12 / PEAK[s.dtype]
+        if measured_peak and measured_peak.get(s.dtype):
+            r["frac_of_measured_mfma_peak"] = fl / (ms * 1e-3) / 1e12 / measured_peak[s.dtype]
+    return r
 
 
 class Problem:
@@ -343,18 +385,9 @@ def main():
     t_setup = prob.time_setup()
     ind_bytes = icv.indirection_bytes(prob.p)      # everything the build writes: entries, range records, 16-bit form
 
-    abytes = algorithmic_bytes(s, Hout, Wout)
-    hbm_time = abytes / (HBM_PEAK_GBS * 1e9)
-    mfma_time = fl / (PEAK[s.dtype] * 1e12)
-    if hbm_time >= mfma_time:
-        roof = {"bound": "hbm", "achieved": abytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
-    else:
-        roof = {"bound": "mfma", "achieved": value, "peak": PEAK[s.dtype], "unit": "TFLOP/s"}
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = MEASURED_TRAFFIC.get(name)
-    roof["kernel"] = icv.plan_name(prob.p)
-    roof["algorithmic_bytes"] = abytes
-    roof["mfma_frac"] = value / PEAK[s.dtype]
+    # what the matrix cores of this device deliver on register operands alone, TFLOP/s (TOP/s)
+    measured_peak = {d: icv.measure_mfma_peak(d, 2) / 1e12 for d in ("bf16", "u8i8")}
+    roof = roofline(s, Hout, Wout, ms, icv.plan_name(prob.p), name, measured_peak)
 
     out = {
         "metric": "effective TFLOP/s (2*N*Hout*Wout*K*R*S*C / t)", "value": value, "unit": "TFLOP/s",
@@ -367,6 +400,8 @@ def main():
                    "kernel": icv.plan_name(prob.p)},
         "roofline": roof,
         "frac_of_mfma_peak": value / PEAK[s.dtype],
+        "mfma_peak_measured": {"bf16_TFLOPs": measured_peak["bf16"], "u8i8_TOPs": measured_peak["u8i8"],
+                               "how": "icv_measure_mfma_peak: register-only MFMA loop, 2 wavefronts per SIMD on every CU"},
         "wall_ms_per_step": wall_ms,
         "warm": {"ms_per_step": ms_warm, "value": fl / (ms_warm * 1e-3) / 1e12},
         "quantiles_ms": {"median": med, "q20": q20, "q80": q80, "repeats": 25, "launches_per_repeat": 20},
@@ -387,7 +422,8 @@ def main():
             row = {"kernel": icv.plan_name(pp), "ms": m, "q20": a, "q80": b, "TFLOPs": f / (m * 1e-3) / 1e12,
                    "frac_of_peak": f / (m * 1e-3) / 1e12 / PEAK[sh.dtype],
                    "GBps_algorithmic": ab / (m * 1e-3) / 1e9,
-                   "frac_of_hbm_peak": ab / (m * 1e-3) / 1e9 / HBM_PEAK_GBS}
+                   "frac_of_hbm_peak": ab / (m * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                   "roofline": roofline(sh, ho, wo, m, icv.plan_name(pp), nm, measured_peak)}
             if sh.dtype != "f32":
                 # the same launch with the fused output stage (bias + ReLU, 2- or 1-byte output elements)
                 pr.enable_fused()

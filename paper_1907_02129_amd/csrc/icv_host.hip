@@ -234,12 +234,13 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     }
     // Filter in registers, input window in an LDS ring: kernel sizes and row widths the kernel is instantiated for, a
     // whole-batch buffer, a window of two passes that fits LDS, 16-bit pixel numbers per 32-row block, and -- unless
-    // forced -- at least one full pass per workgroup and a filter block of 48 fragments or more: the larger the
+    // forced -- at least one full pass per workgroup and a bf16 filter block of 48 fragments or more: the larger the
     // block, the more LDS traffic the resident filter saves (measured: 6 to 18 % faster than the pixel-range kernel
-    // from 5x5 on 64-byte rows up, level with it or behind below that).
+    // from 5x5 on 64-byte rows up, level with it or behind below that and for uint8, whose MFMAs take half the time
+    // per byte and leave less to hide the filter load behind).
     int freg_wn = 0, freg_mb = 0, freg_ring = 0;
     if (p->dtype != ICV_F32 && !(p->dtype == ICV_U8I8 && p->input_zero_point != 128) && plan_kernel == 0 &&
-        (plan_staging == 3 || (plan_staging == 0 && T * (row_bytes / 32) >= 48)) && !plan_per_image && row_bytes % 32 == 0 &&
+        (plan_staging == 3 || (plan_staging == 0 && p->dtype == ICV_BF16 && T * (row_bytes / 32) >= 48)) && !plan_per_image && row_bytes % 32 == 0 &&
         stride_bytes % 16 == 0 && freg_shape_supported((int)T, (int)(row_bytes / 32)) &&
         tile_span_bound(p, Hout, Wout, 32) < 65535) {
         const int wn = p->K <= 32 ? 1 : (p->K <= 64 ? 2 : 4);
