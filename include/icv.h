@@ -92,14 +92,12 @@ ICV_API int icv_output_size(const icv_conv_params* p, int32_t* Hout, int32_t* Wo
 
 /*
  * Buffer sizes in bytes (0 when the parameters are invalid).
- *  indirection  : int32 entries, M rounded up to whole row tiles, times R*S (independent of C, section 1.1;
- *                 with ICV_PLAN_PER_IMAGE, M is Hout*Wout, one image's output pixels, whatever N is);
- *                 kernels that keep a tile's input pixels in LDS, and the kernel for very short pixel rows
- *                 (which reads the entries in this compact form), append one 16-byte record per row tile,
- *                 {smallest valid entry of the tile, pixels from there to the largest one, 0, 0}, and then the
- *                 entries once more, in the same order, as uint16 pixel numbers inside their tile's range
- *                 ((entry - smallest entry) / pixel stride; the zero row is 65535 for short pixel rows, else the number after the range's
- *                 LDS buffer)
+ *  indirection  : one entry per (output pixel, kernel element), M rounded up to whole row tiles, times R*S
+ *                 (independent of C, section 1.1; with ICV_PLAN_PER_IMAGE, M is Hout*Wout, one image's output
+ *                 pixels, whatever N is).  Entries are int32 byte offsets, or -- for the kernels that keep a
+ *                 tile's input pixels in LDS, and the kernel for very short pixel rows -- a 16-byte record per
+ *                 row tile followed by uint16 pixel numbers counted from the tile's base; only the form the plan's
+ *                 kernel reads is built.  icv_get_indirection_layout describes it.
  *  packed filter: the [K][R][S][C] filter re-laid as the tiles the GEMM kernel reads, K padded to the tile
  *  zero row     : C elements (section 2.3's explicit zero vector), rounded up to 16 bytes
  *  im2col       : the [M][R*S*C] patch matrix of the ablation path
@@ -126,8 +124,8 @@ ICV_API int64_t icv_indirection_index(const icv_conv_params* p, int64_t m, int32
  *                  every row tile has a 16-byte record {int32 base byte offset, int32 pixels from the base to the
  *                  tile's largest valid entry (0: not recorded), int32 base pixel index (0: not recorded), 0}, and
  *                  entry e names the pixel row at byte offset  base byte offset + e * pixel stride in bytes.
- * `entries_at` / `entry_bytes` describe the form the convolution kernel of this plan reads; plans that keep the
- * int32 form beside a 2-byte form report where it starts in `int32_entries_at` (-1: not built).
+ * `entries_at` / `entry_bytes` describe the form the convolution kernel of this plan reads, the only one built;
+ * `int32_entries_at` says where int32 entries start (0 for entry_bytes 4, -1 when they are not built).
  */
 typedef struct icv_indirection_layout {
     int32_t tile_rows;         /* output pixels per row tile */

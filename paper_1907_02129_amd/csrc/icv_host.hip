@@ -409,10 +409,10 @@ size_t icv_indirection_bytes(const icv_conv_params* p)
     Geometry g;
     if (make_geometry(p, &g) != ICV_OK) return 0;
     const size_t n = (size_t)g.img_tiles * g.MR * g.T;
-    // block form: a 16-byte record per block, then 16-bit entries
-    if (g.kind == PLAN_MFMA_FREG) return (size_t)g.img_tiles * 16 + n * sizeof(uint16_t);
-    // entries, then (pixel-range plans) one 16-byte range record per row tile and the entries as 16-bit row numbers
-    return n * sizeof(int32_t) + (g.patch_rows ? (size_t)g.img_tiles * 16 + n * sizeof(uint16_t) : 0);
+    // compact forms (block form of the filter-in-registers plan, range form of the pixel-range plans): a 16-byte
+    // record per block or row tile, then 16-bit entries; else int32 entries
+    if (g.kind == PLAN_MFMA_FREG || g.patch_rows) return (size_t)g.img_tiles * 16 + n * sizeof(uint16_t);
+    return n * sizeof(int32_t);
 }
 
 size_t icv_packed_filter_bytes(const icv_conv_params* p)
@@ -461,7 +461,7 @@ int icv_get_indirection_layout(const icv_conv_params* p, icv_indirection_layout*
         L->records_at = 0; L->entries_at = g.img_tiles * 16; L->int32_entries_at = -1;
     } else if (g.patch_rows) {
         L->entry_bytes = 2; L->zero_code = (int32_t)g.zero_row_number; L->record_bytes = 16;
-        L->int32_entries_at = 0; L->records_at = n * 4; L->entries_at = n * 4 + g.img_tiles * 16;
+        L->records_at = 0; L->entries_at = g.img_tiles * 16; L->int32_entries_at = -1;
     } else {
         L->entry_bytes = 4; L->zero_code = 0; L->record_bytes = 0;
         L->int32_entries_at = 0; L->records_at = -1; L->entries_at = 0;

@@ -329,7 +329,7 @@ int launch_igemm_lowc(const icv_conv_params* p, const Geometry& g, const void* i
     // the compact entries (range records, then 16-bit pixel numbers) follow the int32 entries in the buffer
     a.ranges = nullptr; a.rows = nullptr;
     if (!a_direct && g.patch_rows) {
-        a.ranges = (const int4*)(ind + g.img_tiles * g.MR * (int64_t)g.T);
+        a.ranges = (const int4*)ind;      // range records, then the 16-bit entries
         a.rows = (const uint16_t*)(a.ranges + g.img_tiles);
     }
     // 32-column blocks per workgroup: as many as fit beside the 64 gathered rows in half a compute unit's LDS

@@ -484,7 +484,7 @@ int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* 
     a.a = (const uint8_t*)input;
     a.w = (const uint8_t*)packed;
     // the buffer: int32 entries, then the tiles' range records, then the entries as 16-bit patch row numbers
-    a.ranges = (const int4*)(ind + g.img_tiles * g.MR * (int64_t)g.T);
+    a.ranges = (const int4*)ind;      // range records, then the 16-bit entries
     a.rows = (const uint16_t*)(a.ranges + g.img_tiles);
     a.image_bytes = g.image_bytes;
     a.img_tiles = (uint32_t)g.img_tiles;

@@ -134,108 +134,129 @@ int launch_pack_filter(const icv_conv_params* p, const Geometry& g, const void* 
 // Entry (m, tap): iy = oy*SY + ky*DY - PT, ix = ox*SX + kx*DX - PL (Listing 1's index arithmetic);
 // inside the input -> byte offset of pixel (n*Hin + iy)*Win + ix from the input base, else INT32_MIN (the
 // zero row).  Physical order [m tile][tap][MR].
-// A thread owns four consecutive rows m0..m0+3 of a tile and some of the taps, writing one int4 per tap:
-// neighbouring threads write neighbouring 16-byte pieces of a (tile, tap) run of MR*4 bytes.
+// A thread owns four consecutive rows m0..m0+3 of a tile and walks the kernel elements, writing one 16-byte (int32
+// entries) or 8-byte (16-bit entries) piece per element: the MR / 4 threads of a tile, neighbours in one wavefront,
+// write neighbouring pieces of a (tile, tap) run.
 struct IndArgs {
     int32_t* ind;
-    int64_t M, m_padded;
+    int64_t M;
     int32_t Hin, Win, Hout, Wout, R, S, SY, SX, DY, DX, PT, PL, MR, T;
     int32_t stride_bytes;   // bytes between input pixels
-    // compact form (plans that read it): range records, 16-bit entries, what those hold for the zero row, and
-    // log2 of the pixel stride in bytes (-1: not a power of two)
+    // compact form (plans that read it): range records, 16-bit entries, what those hold for the zero row
     int4* ranges;
     uint16_t* rows16;
     uint32_t zero_row_number;
-    int32_t stride_shift;
+    uint32_t n_tiles;
+    int32_t quad_shift;       // log2(MR / 4)
+    int32_t splits;           // threads that share a row quad's kernel elements (grid.y)
+    FastDiv by_wout, by_hout, by_s, by_dy, by_dx;
 };
 
 template <bool COMPACT>
 __global__ __launch_bounds__(256) void k_build_indirection(IndArgs a)
 {
-    // One workgroup per row tile.  Thread -> (four consecutive rows of the tile, group of kernel elements): the
-    // MR / 4 row quads times 256 / (MR / 4) element groups; a thread walks the elements tg, tg + groups, ...
-    __shared__ int32_t part[8];
-    const int64_t tile = blockIdx.x;
-    const int32_t mr4 = a.MR / 4;
-    const int32_t quad = threadIdx.x % mr4, tg = threadIdx.x / mr4, groups = 256 / mr4;
-    const int32_t r = 4 * quad;
-    const int64_t m0 = tile * a.MR + r;
-    // decompose the four rows
-    int32_t n[4], oy[4], ox[4];
+    // The kernel is bound by instruction issue, not by the bytes it writes (a wavefront instruction occupies its SIMD
+    // for four cycles), so a thread does everything that depends on its rows alone once and then walks all kernel
+    // elements (every splits-th one when a small problem is spread over more threads); divisions are multiply-shifts;
+    // and a tile's range comes from a closed form instead of a pass over its entries.
+    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
+    const uint32_t tile = t >> a.quad_shift, quad = t & ((1u << a.quad_shift) - 1u);
+    const int32_t split = (int32_t)blockIdx.y;
+    const bool active = tile < a.n_tiles;           // the others still take part in the shuffles below
+    const int32_t mr4 = 1 << a.quad_shift;
+    const int32_t r = 4 * (int32_t)quad;
+    const int64_t m0 = (int64_t)tile * a.MR + r;
+    // per row: iy = by + ky*DY, ix = bx + kx*DX, pixel = pb + iy*Win + ix
+    int32_t by[4], bx[4], pb[4];
     bool live[4];
     {
-        const uint32_t mm = (uint32_t)(m0 < a.M ? m0 : 0);
-        const uint32_t q = mm / (uint32_t)a.Wout;
+        const uint32_t mm = (uint32_t)(active && m0 < a.M ? m0 : 0);
+        const uint32_t q = fast_div(mm, a.by_wout);
         int32_t x = (int32_t)(mm - q * (uint32_t)a.Wout);
-        const uint32_t nn = q / (uint32_t)a.Hout;
+        const uint32_t nn = fast_div(q, a.by_hout);
         int32_t y = (int32_t)(q - nn * (uint32_t)a.Hout);
-        int32_t b = (int32_t)nn;
+        int32_t n = (int32_t)nn;
 #pragma unroll
         for (int j = 0; j < 4; j++) {
-            n[j] = b; oy[j] = y; ox[j] = x;
-            live[j] = m0 + j < a.M;
-            if (++x == a.Wout) { x = 0; if (++y == a.Hout) { y = 0; ++b; } }
+            by[j] = y * a.SY - a.PT; bx[j] = x * a.SX - a.PL; pb[j] = n * a.Hin * a.Win;
+            live[j] = active && m0 + j < a.M;
+            if (++x == a.Wout) { x = 0; if (++y == a.Hout) { y = 0; ++n; } }
         }
     }
-    auto entries = [&](int32_t tap, int32_t (&e)[4]) {
-        const int32_t ky = tap / a.S, kx = tap - ky * a.S;
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const int32_t iy = oy[j] * a.SY + ky * a.DY - a.PT;
-            const int32_t ix = ox[j] * a.SX + kx * a.DX - a.PL;
-            const bool in = live[j] && (uint32_t)iy < (uint32_t)a.Hin && (uint32_t)ix < (uint32_t)a.Win;
-            e[j] = in ? ((n[j] * a.Hin + iy) * a.Win + ix) * a.stride_bytes : INT32_MIN;
-        }
-    };
-    int4* dst = (int4*)(a.ind + tile * ((int64_t)a.T * a.MR) + r);
-    int32_t lo = INT32_MAX, hi = -1;          // smallest / largest valid entry seen by this thread
-    for (int32_t tap = tg; tap < a.T; tap += groups) {
-        int32_t e[4];
-        entries(tap, e);
-        dst[(int64_t)tap * mr4] = make_int4(e[0], e[1], e[2], e[3]);
-        if constexpr (COMPACT) {
-#pragma unroll
-            for (int j = 0; j < 4; j++)
-                if (e[j] >= 0) { lo = e[j] < lo ? e[j] : lo; hi = e[j] > hi ? e[j] : hi; }
-        }
-    }
+    int32_t first = 0;           // pixel the compact entries count from
     if constexpr (COMPACT) {
-        // The compact form of the same entries, in the same kernel (the entries are recomputed, which is cheaper
-        // than reading them back): the tile's range record -- its smallest valid entry and the number of pixels
-        // from there to the largest one, {0, 1} without any -- and every entry as a 16-bit pixel number inside that
-        // range, `zero_row_number` for the zero row.
-        for (int d = 32; d >= 1; d >>= 1) {
+        // The tile's range record: its smallest valid entry and the number of pixels from there to the largest one,
+        // {0, 1} without any.  A row's valid kernel elements are a rectangle ky_lo..ky_hi x kx_lo..kx_hi (iy depends
+        // on ky alone, ix on kx alone) and the entry grows with both, so the row's extremes sit in two corners.  The
+        // MR / 4 threads of a tile are neighbours in one wavefront: the tile's extremes are a few shuffles away.
+        int32_t lo = INT32_MAX, hi = -1;
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const int32_t ky_lo = by[j] < 0 ? (int32_t)fast_div((uint32_t)(-by[j] + a.DY - 1), a.by_dy) : 0;
+            const int32_t kx_lo = bx[j] < 0 ? (int32_t)fast_div((uint32_t)(-bx[j] + a.DX - 1), a.by_dx) : 0;
+            const int32_t room_y = a.Hin - 1 - by[j], room_x = a.Win - 1 - bx[j];
+            int32_t ky_hi = (int32_t)fast_div((uint32_t)(room_y < 0 ? 0 : room_y), a.by_dy);
+            int32_t kx_hi = (int32_t)fast_div((uint32_t)(room_x < 0 ? 0 : room_x), a.by_dx);
+            ky_hi = ky_hi < a.R - 1 ? ky_hi : a.R - 1;
+            kx_hi = kx_hi < a.S - 1 ? kx_hi : a.S - 1;
+            const bool any = live[j] && room_y >= 0 && room_x >= 0 && ky_lo <= ky_hi && kx_lo <= kx_hi;
+            const int32_t e_lo = pb[j] + (by[j] + ky_lo * a.DY) * a.Win + bx[j] + kx_lo * a.DX;
+            const int32_t e_hi = pb[j] + (by[j] + ky_hi * a.DY) * a.Win + bx[j] + kx_hi * a.DX;
+            lo = any && e_lo < lo ? e_lo : lo;
+            hi = any && e_hi > hi ? e_hi : hi;
+        }
+        for (int d = mr4 >> 1; d >= 1; d >>= 1) {
             const int32_t lo2 = __shfl_xor(lo, d, 64), hi2 = __shfl_xor(hi, d, 64);
             lo = lo2 < lo ? lo2 : lo;
             hi = hi2 > hi ? hi2 : hi;
         }
-        const int wave = threadIdx.x >> 6;
-        if ((threadIdx.x & 63) == 0) { part[wave] = lo; part[4 + wave] = hi; }
-        __syncthreads();
-#pragma unroll
-        for (int w = 0; w < 4; w++) {
-            lo = part[w] < lo ? part[w] : lo;
-            hi = part[4 + w] > hi ? part[4 + w] : hi;
-        }
-        const int32_t first = hi < 0 ? 0 : lo;
-        if (threadIdx.x == 0) {
-            const uint32_t span = hi < 0 ? 0u : (uint32_t)(hi - lo);
-            const uint32_t pixels = (a.stride_shift >= 0 ? span >> a.stride_shift : span / (uint32_t)a.stride_bytes) + 1;
-            a.ranges[tile] = make_int4(first, (int32_t)pixels, 0, 0);
-        }
-        uint2* dst16 = (uint2*)(a.rows16 + tile * ((int64_t)a.T * a.MR) + r);
-        for (int32_t tap = tg; tap < a.T; tap += groups) {
-            int32_t e[4];
-            entries(tap, e);
-            uint32_t q[4];
+        first = hi < 0 ? 0 : lo;
+        if (active && quad == 0 && split == 0)
+            a.ranges[tile] = make_int4(first * a.stride_bytes, hi < 0 ? 1 : hi - lo + 1, 0, 0);
+    }
+    if (!active) return;
+    // this thread's kernel elements split, split + splits, ... as (ky, kx)
+    int32_t ky = (int32_t)fast_div((uint32_t)split, a.by_s), kx = split - ky * a.S;
+    const int32_t step_y = (int32_t)fast_div((uint32_t)a.splits, a.by_s), step_x = a.splits - step_y * a.S;
+    // Four rows in one output row (the usual case) share iy and step through ix by SX: one pixel number per kernel
+    // element and four bounds checks instead of four full evaluations.
+    const bool flat = by[3] == by[0] && pb[3] == pb[0] && live[3];
+    const int64_t tile_at = (int64_t)tile * ((int64_t)a.T * a.MR) + r;
+    uint2* dst16 = COMPACT ? (uint2*)(a.rows16 + tile_at) + (int64_t)split * mr4 : nullptr;
+    int4* dst32 = COMPACT ? nullptr : (int4*)(a.ind + tile_at) + (int64_t)split * mr4;
+    const int64_t dst_step = (int64_t)a.splits * mr4;
+    for (int32_t tap = split; tap < a.T; tap += a.splits) {
+        const int32_t dy = ky * a.DY, dx = kx * a.DX;
+        int32_t e[4];
+        if (flat) {
+            const int32_t iy = by[0] + dy, ix0 = bx[0] + dx;
+            const bool in_y = (uint32_t)iy < (uint32_t)a.Hin;
+            const int32_t pixel0 = pb[0] + iy * a.Win + ix0 - first;
 #pragma unroll
             for (int j = 0; j < 4; j++) {
-                const uint32_t off = (uint32_t)(e[j] - first);
-                q[j] = e[j] < 0 ? a.zero_row_number
-                                : (a.stride_shift >= 0 ? off >> a.stride_shift : off / (uint32_t)a.stride_bytes);
+                const bool in = in_y && (uint32_t)(ix0 + j * a.SX) < (uint32_t)a.Win;
+                if constexpr (COMPACT) e[j] = in ? pixel0 + j * a.SX : (int32_t)a.zero_row_number;
+                else e[j] = in ? (pixel0 + j * a.SX) * a.stride_bytes : INT32_MIN;
             }
-            dst16[(int64_t)tap * mr4] = make_uint2(q[0] | (q[1] << 16), q[2] | (q[3] << 16));
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const int32_t iy = by[j] + dy, ix = bx[j] + dx;
+                const bool in = live[j] && (uint32_t)iy < (uint32_t)a.Hin && (uint32_t)ix < (uint32_t)a.Win;
+                const int32_t pixel = pb[j] + iy * a.Win + ix;
+                if constexpr (COMPACT) e[j] = in ? pixel - first : (int32_t)a.zero_row_number;
+                else e[j] = in ? pixel * a.stride_bytes : INT32_MIN;         // byte offsets, INT32_MIN for the zero row
+            }
         }
+        if constexpr (COMPACT) {
+            *dst16 = make_uint2((uint32_t)e[0] | ((uint32_t)e[1] << 16), (uint32_t)e[2] | ((uint32_t)e[3] << 16));
+            dst16 += dst_step;
+        } else {
+            *dst32 = make_int4(e[0], e[1], e[2], e[3]);
+            dst32 += dst_step;
+        }
+        kx += step_x; ky += step_y;
+        if (kx >= a.S) { kx -= a.S; ++ky; }
     }
 }
 
@@ -302,23 +323,33 @@ int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_
     IndArgs a{};      // every field starts at zero; the ones this call uses are set below
     a.ind = ind;
     // a batch-independent buffer holds the entries of one image (batch index 0); img_rows = M otherwise
-    a.M = g.img_rows; a.m_padded = g.img_tiles * g.MR;
+    a.M = g.img_rows;
     a.Hin = p->Hin; a.Win = p->Win; a.Hout = g.Hout; a.Wout = g.Wout;
     a.R = p->R; a.S = p->S; a.SY = p->SY; a.SX = p->SX; a.DY = p->DY; a.DX = p->DX;
     a.PT = p->PT; a.PL = p->PL; a.MR = g.MR; a.T = g.T;
     a.stride_bytes = g.in_stride * g.elem_bytes;
-    if (g.MR != 64 && g.MR != 128 && g.MR != 256) return ICV_ERR_UNSUPPORTED;         // MR / 4 must divide 256
-    if (g.img_tiles > 0x7fffffffll) return ICV_ERR_UNSUPPORTED;
-    const dim3 grid((unsigned)g.img_tiles);
-    a.ranges = nullptr; a.rows16 = nullptr; a.zero_row_number = 0; a.stride_shift = -1;
+    if (g.MR != 64 && g.MR != 128 && g.MR != 256) return ICV_ERR_UNSUPPORTED;         // a tile's threads share a wavefront
+    a.quad_shift = g.MR == 64 ? 4 : (g.MR == 128 ? 5 : 6);
+    const int64_t threads = g.img_tiles << a.quad_shift;
+    if (g.img_tiles > 0x7fffffffll || (threads + 255) / 256 > 0x7fffffffll) return ICV_ERR_UNSUPPORTED;
+    a.n_tiles = (uint32_t)g.img_tiles;
+    // A small problem has fewer row quads than the chip has lanes: the kernel elements of a quad are then shared
+    // among several threads, eight elements or more each.
+    int64_t splits = (65536 + threads - 1) / threads;
+    const int64_t most = (g.T + 7) / 8;
+    if (splits > most) splits = most;
+    if (splits < 1) splits = 1;
+    a.splits = (int32_t)splits;
+    const dim3 grid((unsigned)((threads + 255) / 256), (unsigned)splits);
+    a.ranges = nullptr; a.rows16 = nullptr; a.zero_row_number = 0;
+    a.by_wout = make_fast_div((uint32_t)g.Wout); a.by_hout = make_fast_div((uint32_t)g.Hout);
+    a.by_s = make_fast_div((uint32_t)p->S); a.by_dy = make_fast_div((uint32_t)p->DY); a.by_dx = make_fast_div((uint32_t)p->DX);
     if (g.patch_rows) {
-        // the range records and the 16-bit entries follow the int32 entries in the buffer
+        // the buffer holds the range records, then the 16-bit entries
         if (g.zero_row_number > 65535 || g.zero_row_number < (uint32_t)g.patch_rows) return ICV_ERR_UNSUPPORTED;
-        a.ranges = (int4*)(ind + a.m_padded * g.T);
+        a.ranges = (int4*)ind;
         a.rows16 = (uint16_t*)(a.ranges + g.img_tiles);
         a.zero_row_number = g.zero_row_number;
-        for (int sh = 0; sh < 31; sh++)
-            if ((1 << sh) == a.stride_bytes) a.stride_shift = sh;
         hipLaunchKernelGGL(k_build_indirection<true>, grid, dim3(256), 0, s, a);
     } else {
         hipLaunchKernelGGL(k_build_indirection<false>, grid, dim3(256), 0, s, a);
