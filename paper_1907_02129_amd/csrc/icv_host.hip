@@ -66,11 +66,12 @@ static const char* kFregNames[2][3][2] = {
 };
 // [dtype][tile]; the pixel-range kernel has every tile, the gathering kernel (and the plain GEMM it doubles as)
 // those with an empty name missing
-static const char* kPatchNames[2][7] = {
+static const char* kPatchNames[3][7] = {
     {"mfma_bf16_128x64_c2x2_patch", "mfma_bf16_128x128_c2x2_patch", "mfma_bf16_256x64_c4x1_patch", "mfma_bf16_256x64_c4x2_patch",
      "mfma_bf16_64x64_c2x2_patch", "mfma_bf16_256x128_c4x2_patch", "mfma_bf16_128x128_c4x2_patch"},
     {"mfma_i8_128x64_c2x2_patch", "mfma_i8_128x128_c2x2_patch", "mfma_i8_256x64_c4x1_patch", "mfma_i8_256x64_c4x2_patch",
      "mfma_i8_64x64_c2x2_patch", "mfma_i8_256x128_c4x2_patch", "mfma_i8_128x128_c4x2_patch"},
+    {"mfma_f32_128x64_c2x2_patch", "", "mfma_f32_256x64_c4x1_patch", "", "mfma_f32_64x64_c2x2_patch", "", "mfma_f32_128x128_c4x2_patch"},
 };
 static const char* kGemmNames[2][7] = {
     {"gemm_bf16_128x64_c2x2_p4", "gemm_bf16_128x128_c2x2_p4", "", "gemm_bf16_256x64_c4x2_p8", "gemm_bf16_64x64_c2x2_p4", "", ""},
@@ -138,7 +139,9 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     // ---- plan: which kernel, which tile
     const int64_t row_bytes = (int64_t)p->C * g->elem_bytes;        // bytes of one gathered A row
     const int64_t stride_bytes = (int64_t)g->in_stride * g->elem_bytes;
-    bool mfma_ok = p->dtype != ICV_F32 && row_bytes % 64 == 0 && stride_bytes % 16 == 0;
+    // fp32 tensors (section 3.1's own precision) run on the matrix cores through the pixel-range kernel alone
+    const bool f32 = p->dtype == ICV_F32;
+    bool mfma_ok = row_bytes % 64 == 0 && stride_bytes % 16 == 0;
     if (p->dtype == ICV_U8I8 && p->input_zero_point != 128) mfma_ok = false;   // x ^ 0x80 == x - 128 only
     if (plan_kernel == 1) mfma_ok = false;                                      // forced vector-ALU kernel
     int variant = -1;
@@ -146,7 +149,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     // LDS-resident pixel range: worthwhile when several kernel elements re-read the rows, possible when the pixel
     // stride is a power of two (entry -> LDS row is a shift) and two patch buffers fit beside the other buffers
     auto try_patch = [&](int v, bool need_two = false) {
-        if (plan_staging == 1 || T < 4 || !patch_variant_supported(v)) return false;
+        if (plan_staging == 1 || T < 4 || !patch_variant_supported(v) || (f32 && !patch_variant_supported_f32(v))) return false;
         if ((stride_bytes & (stride_bytes - 1)) != 0) return false;
         const TileVariant& tv = kTileVariants[v];
         if ((int64_t)tv.MR * T * 2 > 24 * 1024) return false;     // two tiles' row numbers (uint16) stay in LDS
@@ -222,7 +225,8 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
                 variant = order[first];
             }
         }
-        if (!patch_rows) {
+        if (!patch_rows && f32) mfma_ok = false;
+        if (!patch_rows && !f32) {
             // the gathering kernel has four of the tiles: 128 x 128 as 2 x 2 wavefronts (measured), 256 x 64 with
             // eight producer wavefronts, and 256-row tiles only when a tile's entries fit their LDS budget
             if (variant == 5 || variant == 6) variant = 1;
@@ -230,7 +234,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
             if (variant == 3 && (int64_t)256 * T * 4 > 24 * 1024) variant = 0;
         }
         // a workgroup keeps two tiles' worth of entries in LDS: 2 * MR*T int32 (plus padding)
-        if (!patch_rows && (int64_t)kTileVariants[variant].MR * T * 4 > 24 * 1024) mfma_ok = false;
+        if (mfma_ok && !patch_rows && (int64_t)kTileVariants[variant].MR * T * 4 > 24 * 1024) mfma_ok = false;
     }
     // Filter in registers, input window in an LDS ring: kernel sizes and row widths the kernel is instantiated for, a
     // whole-batch buffer, a window of two passes that fits LDS, 16-bit pixel numbers per 32-row block, and -- unless
@@ -314,7 +318,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         g->stages_per_tap = (int32_t)(row_bytes / g->KCB);
         g->taps_per_stage = 1;
         g->n_stages = g->T * g->stages_per_tap;
-        g->name = (patch_rows ? kPatchNames : kMfmaNames)[p->dtype == ICV_U8I8 ? 1 : 0][variant];
+        g->name = f32 ? kPatchNames[2][variant] : (patch_rows ? kPatchNames : kMfmaNames)[p->dtype == ICV_U8I8 ? 1 : 0][variant];
         // Section 3.2, closing paragraph: a 1x1 stride-1 convolution needs no im2col, the plain GEMM primitive has
         // the edge there and switching between the two primitives by convolution parameters is advised.  Its A matrix is the input tensor; the indirection buffer is built but not read.
         if (T == 1 && p->SY == 1 && p->SX == 1 && p->PT == 0 && p->PL == 0 && p->PB == 0 && p->PR == 0 &&
@@ -379,7 +383,7 @@ static int make_ablation_geometry(const icv_conv_params* p, Geometry* g)
     // the packed filter of the filter-in-registers plan is laid out for that kernel alone; the ablation takes a plan
     // whose filter and tile the plain GEMM kernel reads (ICV_PLAN_GATHER always is one)
     if (g->kind == PLAN_MFMA_FREG) return ICV_ERR_UNSUPPORTED;
-    if (g->kind == PLAN_MFMA && !kGemmNames[0][g->variant][0]) return ICV_ERR_UNSUPPORTED;      // a tile the GEMM lacks
+    if (g->kind == PLAN_MFMA && (!kGemmNames[0][g->variant][0] || p->dtype == ICV_F32)) return ICV_ERR_UNSUPPORTED;      // a tile, or a dtype, the GEMM lacks
     g->per_image = 0;
     g->img_rows = g->M;
     g->img_tiles = (g->M + g->MR - 1) / g->MR;

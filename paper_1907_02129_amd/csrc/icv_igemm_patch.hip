@@ -55,7 +55,7 @@ struct PatchArgs {
     EpilogueArgs ep;           // output stage (read by the FUSED instantiations only)
 };
 
-template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool FUSED>
+template <int DT, int MR, int NR, int WM, int WN, int NP, int KCB, bool FUSED>
 __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g)
 {
     constexpr int NC = WM * WN;
@@ -69,6 +69,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
     constexpr int BS = NR * KCB;             // bytes of one filter-tile slot
     static_assert(B_VEC >= 1 && B_VEC * NP * 1024 == NR * KCB, "filter tile must split over the producers");
     static_assert(MB >= 1 && NB >= 1, "tile too small for this wavefront split");
+    constexpr bool I8 = DT == ICV_U8I8;      // DT: the icv_dtype of input and filter
     using acc_t = typename Acc<I8>::type;
     using out_t = typename std::conditional<I8, int32_t, float>::type;
 
@@ -341,7 +342,10 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
 #pragma unroll
                             for (int i = 0; i < MB; i++)
 #pragma unroll
-                                for (int j = 0; j < NB; j++) acc[i][j] = mfma32<I8>(af[i], bf[j], acc[i][j]);
+                                for (int j = 0; j < NB; j++) {
+                                    if constexpr (DT == ICV_F32) acc[i][j] = mfma32_f32(af[i], bf[j], acc[i][j]);
+                                    else acc[i][j] = mfma32<I8>(af[i], bf[j], acc[i][j]);
+                                }
                         }
                         locate(en, last ? pb_next : pb);
                         entp = entn;
@@ -372,11 +376,11 @@ size_t patch_lds_bytes(int NR, int KCB, int ring, int cap_units, int ent_copies,
     return (size_t)ring * NR * KCB + (size_t)nbuf * (cap_units + 1) * 1024 + (size_t)nbuf * ent_copies * 1024;
 }
 
-template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool FUSED>
+template <int DT, int MR, int NR, int WM, int WN, int NP, int KCB, bool FUSED>
 static int launch_one(const Geometry& g, PatchArgs a, hipStream_t s)
 {
     constexpr int threads = 64 * (WM * WN + NP);
-    auto kern = k_igemm_patch<I8, MR, NR, WM, WN, NP, KCB, FUSED>;
+    auto kern = k_igemm_patch<DT, MR, NR, WM, WN, NP, KCB, FUSED>;
     a.ent_copies = (int32_t)(((size_t)a.T * MR * 2 + 1023) / 1024);
     a.cap_units = (int32_t)(((size_t)g.patch_rows * KCB + 1023) / 1024);
     // Kernel elements per stage: a stage should hold enough MFMAs (16 per consumer wavefront) to amortise its
@@ -444,32 +448,39 @@ static int launch_one(const Geometry& g, PatchArgs a, hipStream_t s)
     return ICV_OK;
 }
 
-template <bool I8, int MR, int NR, int WM, int WN>
+template <int DT, int MR, int NR, int WM, int WN>
 static int launch_tile(const Geometry& g, const PatchArgs& a, hipStream_t s)
 {
     if (g.KCB == 128)
-        return g.ep_plain ? launch_one<I8, MR, NR, WM, WN, 4, 128, false>(g, a, s)
-                          : launch_one<I8, MR, NR, WM, WN, 4, 128, true>(g, a, s);
-    return g.ep_plain ? launch_one<I8, MR, NR, WM, WN, 4, 64, false>(g, a, s)
-                      : launch_one<I8, MR, NR, WM, WN, 4, 64, true>(g, a, s);
+        return g.ep_plain ? launch_one<DT, MR, NR, WM, WN, 4, 128, false>(g, a, s)
+                          : launch_one<DT, MR, NR, WM, WN, 4, 128, true>(g, a, s);
+    return g.ep_plain ? launch_one<DT, MR, NR, WM, WN, 4, 64, false>(g, a, s)
+                      : launch_one<DT, MR, NR, WM, WN, 4, 64, true>(g, a, s);
 }
 
-template <bool I8>
+template <int DT>
 static int launch_dtype(const Geometry& g, const PatchArgs& a, hipStream_t s)
 {
     switch (g.variant) {
-        case 0: return launch_tile<I8, 128, 64, 2, 2>(g, a, s);
-        case 1: return launch_tile<I8, 128, 128, 2, 2>(g, a, s);
-        case 2: return launch_tile<I8, 256, 64, 4, 1>(g, a, s);
-        case 3: return launch_tile<I8, 256, 64, 4, 2>(g, a, s);
-        case 4: return launch_tile<I8, 64, 64, 2, 2>(g, a, s);
-        case 5: return launch_tile<I8, 256, 128, 4, 2>(g, a, s);
-        case 6: return launch_tile<I8, 128, 128, 4, 2>(g, a, s);
-        default: return ICV_ERR_UNSUPPORTED;
+        case 0: return launch_tile<DT, 128, 64, 2, 2>(g, a, s);
+        case 2: return launch_tile<DT, 256, 64, 4, 1>(g, a, s);
+        case 4: return launch_tile<DT, 64, 64, 2, 2>(g, a, s);
+        case 6: return launch_tile<DT, 128, 128, 4, 2>(g, a, s);
+        default: break;
     }
+    if constexpr (DT != ICV_F32) {      // fp32 tensors have the four tiles above
+        switch (g.variant) {
+            case 1: return launch_tile<DT, 128, 128, 2, 2>(g, a, s);
+            case 3: return launch_tile<DT, 256, 64, 4, 2>(g, a, s);
+            case 5: return launch_tile<DT, 256, 128, 4, 2>(g, a, s);
+            default: break;
+        }
+    }
+    return ICV_ERR_UNSUPPORTED;
 }
 
 bool patch_variant_supported(int variant) { return variant >= 0 && variant < kNumTileVariants; }
+bool patch_variant_supported_f32(int variant) { return variant == 0 || variant == 2 || variant == 4 || variant == 6; }
 
 int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                        const int32_t* ind, void* out, hipStream_t s)
@@ -498,7 +509,8 @@ int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* 
     a.n_tiles = (int32_t)g.n_tiles;
     a.ep = g.ep;
     a.ring = 0; a.G = 1; a.ent_copies = 0; a.cap_units = 0; a.a_share = 0; a.e_share = 0; a.nbuf = 2; a.xcd_mode = 0;
-    return p->dtype == ICV_U8I8 ? launch_dtype<true>(g, a, s) : launch_dtype<false>(g, a, s);
+    if (p->dtype == ICV_F32) return launch_dtype<ICV_F32>(g, a, s);
+    return p->dtype == ICV_U8I8 ? launch_dtype<ICV_U8I8>(g, a, s) : launch_dtype<ICV_BF16>(g, a, s);
 }
 
 }  // namespace icv

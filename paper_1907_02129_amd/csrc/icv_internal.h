@@ -126,6 +126,7 @@ int launch_igemm_mfma(const icv_conv_params* p, const Geometry& g, const void* i
 int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                        const int32_t* ind, void* out, hipStream_t s);
 bool patch_variant_supported(int variant);
+bool patch_variant_supported_f32(int variant);      // the tiles the pixel-range kernel has for fp32 tensors
 int launch_igemm_freg(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                       const int32_t* ind, void* out, hipStream_t s);
 bool freg_shape_supported(int T, int KS);

@@ -34,6 +34,19 @@ __device__ inline typename Acc<I8>::type mfma32(const uint4& a, const uint4& b, 
     }
 }
 
+// The same 16-byte fragments holding fp32 (section 3.1's own precision): four floats per lane and matrix, multiplied
+// as four 32x32x2 products.  Product j pairs element j of the lower half-wavefront (reduction index 4*piece + j, piece
+// even) with element j of the upper one (piece odd); the operands of A and B are paired alike, so the sum over the
+// four products is the sum over the eight reduction indices the two pieces hold.
+__device__ inline f32x16_t mfma32_f32(const uint4& a, const uint4& b, f32x16_t c)
+{
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.x), __builtin_bit_cast(float, b.x), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.y), __builtin_bit_cast(float, b.y), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.z), __builtin_bit_cast(float, b.z), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.w), __builtin_bit_cast(float, b.w), c, 0, 0, 0);
+    return c;
+}
+
 // 16-byte global -> LDS copy without a register stop: lane l of the wavefront writes LDS bytes
 // [lds_base + 16*l, +16).  Inline assembly on purpose: the compiler does not see a memory instruction, so it
 // inserts no waits of its own for it, and the producers count outstanding copies themselves (wait_vmcnt).

@@ -413,6 +413,55 @@ def test_filter_in_registers_kernel_with_fused_output(s, relu, narrow):
     run_fused_case(s, x, w, acc, mag, relu, narrow, plan=FREG, out_pixel_stride=s.K + 8 if narrow else 0)
 
 
+# ---------------------------------------------------------------- fp32 tensors on the matrix cores
+def _f32_mfma_shapes():
+    mk = lambda *a, **k: ConvShape(*a, dtype="f32", **k)
+    return [
+        mk("f_c64", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=401),
+        mk("f_c16", 3, 17, 15, 16, 40, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=402),             # 64-byte rows, K tail
+        mk("f_5x5_s2", 2, 31, 29, 32, 64, 5, 5, SY=2, SX=2, PT=2, PL=2, PB=1, PR=1, seed=403),
+        mk("f_dil", 2, 24, 40, 16, 130, 3, 3, SY=1, SX=2, DY=2, DX=3, PT=2, PL=3, PB=2, PR=3, seed=404),
+        mk("f_valid", 4, 12, 12, 32, 64, 3, 3, seed=405),
+        mk("f_stride", 2, 14, 14, 16, 48, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=406),          # run with a pixel stride of 32
+        mk("f_tiny", 1, 5, 6, 16, 16, 2, 2, PT=1, PL=1, seed=407),
+    ]
+
+
+@pytest.mark.parametrize("s", _f32_mfma_shapes(), ids=lambda s: s.name)
+@pytest.mark.parametrize("tile", [0, hooks.tile(0), hooks.tile(2), hooks.tile(6)], ids=["tile_auto", "128x64", "256x64", "128x128"])
+def test_fp32_tensors_on_the_matrix_cores(s, tile):
+    """fp32 input and filter (section 3.1's precision) through the pixel-range kernel's 32x32x2 fp32 products."""
+    stride = 32 if s.name == "f_stride" else 0
+    x, w = make_tensors(s)
+    xp = x
+    if stride:
+        xp = np.full(x.shape[:-1] + (stride,), np.nan, dtype=x.dtype)     # NaN in the unused channels
+        xp[..., :s.C] = x
+    p = icv.make_params(s, tile, in_pixel_stride=stride)
+    name = icv.plan_name(p)
+    if tile and "mfma_f32" not in name:
+        pytest.skip("this tile's pixel range does not fit LDS for the shape")
+    assert name.startswith("mfma_f32") and "patch" in name, name
+    _say("fp32 mfma", s.name, name)
+    buf = icv.prepare(s, icv.to_device(w), plan=tile, in_pixel_stride=stride)
+    buf.output.fill_(-7)
+    icv.run(buf, icv.to_device(xp))
+    torch.cuda.synchronize()
+    check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+    # the same problem on the vector ALUs agrees to the same bound, and plans without a pixel range fall back to them
+    assert icv.plan_name(icv.make_params(s, icv.PLAN_GATHER, in_pixel_stride=stride)).startswith("generic")
+    assert icv.im2col_bytes(p) == 0
+
+
+@pytest.mark.parametrize("s", _f32_mfma_shapes()[:3], ids=lambda s: s.name)
+@pytest.mark.parametrize("relu,narrow", [(True, True), (False, False)], ids=["relu_narrow", "linear_acc"])
+def test_fp32_tensors_on_the_matrix_cores_with_fused_output(s, relu, narrow):
+    x, w = make_tensors(s)
+    acc, mag = oracle.conv2d_abs(s, x, w)
+    assert icv.plan_name(icv.make_params(s)).startswith("mfma_f32")
+    run_fused_case(s, x, w, acc, mag, relu, narrow, out_pixel_stride=s.K + 8 if narrow else 0)
+
+
 # ---------------------------------------------------------------- 1x1 stride-1: plain GEMM on the input tensor
 @pytest.mark.parametrize("s", [
     ConvShape("g_exact", 2, 16, 16, 64, 64, 1, 1, seed=81),                        # M a multiple of every tile
