@@ -218,13 +218,18 @@ def test_random_tensor_core_shapes_match_oracle(s):
     check_against_oracle(s, buf.output.cpu().numpy(), x, w)
 
 
-@pytest.mark.parametrize("algo", [0, icv.PLAN_GATHER, icv.PLAN_WINDOW], ids=["auto", "gather", "window"])
-@pytest.mark.parametrize("tile", [None] + list(range(len(hooks.TILES))), ids=["vector_alu"] + hooks.TILES)
+def _tile_cases():
+    cases = [pytest.param(None, 0, id="vector_alu")]          # (row staging is a property of the tensor-core kernels)
+    for i, name in enumerate(hooks.TILES):
+        for algo, tag in ((0, "auto"), (icv.PLAN_GATHER, "gather"), (icv.PLAN_WINDOW, "window")):
+            cases.append(pytest.param(i, algo, id=f"{name}-{tag}"))
+    return cases
+
+
+@pytest.mark.parametrize("tile,algo", _tile_cases())
 @pytest.mark.parametrize("dtype", ["bf16", "u8i8"])
 def test_every_tile(tile, dtype, algo):
     """Every tile of the tensor-core kernels (and the vector-ALU kernel) on shapes with row, column and channel tails."""
-    if tile is None and algo:
-        pytest.skip("row staging is a property of the tensor-core kernels")
     plan = icv.PLAN_VECTOR_ALU if tile is None else algo | hooks.tile(tile)
     zp = 128 if dtype == "u8i8" else 0
     for s in (ConvShape("v_a", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype=dtype, zero_point=zp, seed=51),
@@ -292,7 +297,12 @@ def test_pixel_range_kernel_matches_oracle(s, knobs, tile):
     p = icv.make_params(s, plan, in_pixel_stride=stride)
     name = icv.plan_name(p)
     if tile and not name:
-        pytest.skip("this tile's pixel range (or row numbers) does not fit LDS for the shape")
+        # this tile's pixel range (or its row numbers) does not fit LDS for the shape: refused as a whole, loudly
+        assert icv.indirection_bytes(p) == 0 and icv.packed_filter_bytes(p) == 0
+        with pytest.raises(icv.IcvError) as e:
+            icv.prepare(s, icv.to_device(w), plan=plan, in_pixel_stride=stride)
+        assert e.value.status == icv.ICV_ERR_UNSUPPORTED
+        return
     assert "patch" in name, name
     _say("pixel-range", s.name, name, "knobs", knobs)
     buf = icv.prepare(s, icv.to_device(w), plan=plan, in_pixel_stride=stride)
@@ -440,7 +450,9 @@ def test_fp32_tensors_on_the_matrix_cores(s, tile):
     p = icv.make_params(s, tile, in_pixel_stride=stride)
     name = icv.plan_name(p)
     if tile and "mfma_f32" not in name:
-        pytest.skip("this tile's pixel range does not fit LDS for the shape")
+        # this tile's pixel range does not fit LDS for the shape: the vector-ALU kernel takes over
+        assert name == "generic_f32", name
+        return
     assert name.startswith("mfma_f32") and "patch" in name, name
     _say("fp32 mfma", s.name, name)
     buf = icv.prepare(s, icv.to_device(w), plan=tile, in_pixel_stride=stride)
