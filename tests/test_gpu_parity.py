@@ -137,6 +137,33 @@ def test_benchmark_shape_matches_oracle(name):
     check_against_accumulators(s, buf.output.cpu().numpy(), *oracle_accumulators(s, x, w))
 
 
+def _other_kernel_families():
+    """(shape, plan) pairs: each benchmark shape with every kernel family that covers it besides the library's choice
+    -- the families bench.py's comparison columns time at full size."""
+    out = []
+    try:
+        icv.load_library()
+    except (RuntimeError, OSError):
+        return out                  # no library at collection time: the fixture below reports it
+    for name, s in CONFIGS.items():
+        chosen = icv.plan_name(icv.make_params(s))
+        for plan, tag in ((icv.PLAN_GATHER, "gather"), (icv.PLAN_WINDOW, "window"), (icv.PLAN_FILTER_REGS, "filter_regs"),
+                          (icv.PLAN_PER_IMAGE, "per_image")):
+            other = icv.plan_name(icv.make_params(s, plan=plan))
+            if other and (other != chosen or plan in (icv.PLAN_PER_IMAGE, icv.PLAN_GATHER)) and not other.startswith("generic") and s.N > 1:
+                out.append(pytest.param(name, plan, id=f"{name}-{tag}"))
+    return out
+
+
+@pytest.mark.parametrize("name,plan", _other_kernel_families())
+def test_benchmark_shape_with_the_other_kernel_families(name, plan):
+    s = CONFIGS[name]
+    _say("conv", name, icv.plan_name(icv.make_params(s, plan=plan)))
+    x, w = make_tensors(s)
+    buf, xd = run_indirect(s, x, w, plan=plan)
+    check_against_accumulators(s, buf.output.cpu().numpy(), *oracle_accumulators(s, x, w))
+
+
 # ---------------------------------------------------------------- small shapes: several tiles, ragged tails
 def _small_shapes():
     out = []
