@@ -325,6 +325,7 @@ def main():
                     help="add the ResNet-18 / SqueezeNet 1.0 layer sweep at batch N (section 3.1, Table 2)")
     ap.add_argument("--workload", default=None, help="time another shape as the headline (tuning)")
     ap.add_argument("--plan", type=int, default=0)
+    ap.add_argument("--batch", type=int, default=0, help="with --workload / --traffic-probe: the shape at another batch size")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: a 256 MiB device copy (calibration) then 10 conv launches")
     args = ap.parse_args()
@@ -344,6 +345,9 @@ def main():
 
     name = args.workload or HEADLINE
     s = CONFIGS[name]
+    if args.batch > 0:
+        s = s.with_(N=args.batch)
+        name = f"{name}@N={args.batch}"
     if args.traffic_probe:
         # FETCH_SIZE / WRITE_SIZE calibration: a plain copy of known size (reads 256 MiB, writes 256 MiB),
         # then the conv kernel on rotating buffers; the counters of both are read from the same rocprofv3 run
