@@ -188,6 +188,40 @@ def _exact_span(shape, rows):
     return worst
 
 
+def test_output_pixel_decomposition_is_exact_up_to_the_largest_tensors(lib):
+    """The kernels split an output pixel number into (n, oy, ox) with a multiply and a shift instead of two divisions.
+    For a 1x1 unpadded stride-1 convolution output pixel m names input pixel m and nothing else, so the closed-form
+    window ends must both be m: checked at the ends, around every row and image boundary sampled, and at random m,
+    on extents up to the 2 GiB limit of the input (one uint8 channel) and on strided ones, where the decomposition
+    is visible through iy = oy*SY, ix = ox*SX."""
+    import numpy as np
+    rng = np.random.default_rng(5)
+    extents = [(1, 46340, 46340), (1, 3, 715827882), (1, 715827882, 3), (2047, 1024, 1024), (1, 1, 2147483647),
+               (7, 65537, 4681), (3, 1, 7), (5, 17, 1), (1 << 20, 1, 2047), (11, 9973, 19541)]
+    for N, H, W in extents:
+        s = ConvShape("big", N, H, W, 1, 1, 1, 1, dtype="u8i8", zero_point=128)
+        p = icv.make_params(s)
+        assert icv.output_size(p) == (H, W)
+        M = N * H * W
+        ms = {0, M - 1, M // 2}
+        for _ in range(40):
+            r = int(rng.integers(0, N * H))
+            ms.update(m for m in (r * W - 1, r * W, r * W + 1, r * W + W - 1) if 0 <= m < M)
+        ms.update(int(v) for v in rng.integers(0, M, size=200))
+        for m in ms:
+            assert icv.row_pixel_range(p, m, m) == (m, m), (N, H, W, m)
+    for N, Hin, Win, SY, SX in [(3, 20001, 30011, 2, 3), (1, 2, 1000000007, 1, 2), (5000, 301, 707, 3, 2)]:
+        s = ConvShape("big_s", N, Hin, Win, 1, 1, 1, 1, SY=SY, SX=SX, dtype="u8i8", zero_point=128)
+        p = icv.make_params(s)
+        Hout, Wout = icv.output_size(p)
+        M = N * Hout * Wout
+        for m in [0, M - 1] + [int(v) for v in rng.integers(0, M, size=300)]:
+            n, rem = divmod(m, Hout * Wout)
+            oy, ox = divmod(rem, Wout)
+            want = (n * Hin + oy * SY) * Win + ox * SX
+            assert icv.row_pixel_range(p, m, m) == (want, want), (N, Hin, Win, m)
+
+
 def test_row_pixel_range_brackets_every_window_of_output_pixels(lib):
     """The sliding input window of the filter-in-registers kernel rests on two closed forms: a lower end that depends
     on a window's first output pixel alone and an upper end that depends on its last one alone.  Brute force on the
