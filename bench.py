@@ -226,7 +226,7 @@ def graph_time(torch, step, per_replay, reps=9):
     return float(np.median(ts))
 
 
-def layer_sweep(icv, torch, N):
+def layer_sweep(icv, torch, N, dtype="bf16"):
     """The distinct convolutions of ResNet-18 and SqueezeNet 1.0 (the paper's section 3.1, "Models", Table 2) with
     synthetic data at batch N: the Indirect Convolution, the im2col + GEMM algorithm and its GEMM part alone, as in
     the paper's figures 3 and 4, and the geometric means by layer type of its Tables 3 and 4 (performance of the
@@ -236,7 +236,9 @@ def layer_sweep(icv, torch, N):
     layers, ratios = {}, {}
     for model, fn in (("resnet18", resnet18_layers), ("squeezenet10", squeezenet10_layers)):
         for sh in fn(N):
-            sh = icv.stored_for_tensor_cores(sh)       # 3 -> 4 and 48 -> 64 channels, zeros in the padding
+            if dtype != "bf16":
+                sh = sh.with_(dtype=dtype)
+            sh = icv.stored_for_tensor_cores(sh)       # bf16: 3 -> 4 and 48 -> 64 channels; fp32: 3 -> 16; zeros in the padding
             pp = icv.make_params(sh)
             ho, wo = icv.output_size(pp)
             nsets = min(sets_for_cold(sh, ho, wo), 12)
@@ -280,7 +282,7 @@ def layer_sweep(icv, torch, N):
         geo.setdefault(model, {})[cls] = {"layers": len(rs),
                                           "indirect_gemm_vs_gemm_primitive_pct": (float(g[0]) - 1) * 100,
                                           "indirect_vs_gemm_based_algorithm_pct": (float(g[1]) - 1) * 100}
-    return {"N": N, "layers": layers, "geomean_by_type": geo}
+    return {"N": N, "dtype": dtype, "layers": layers, "geomean_by_type": geo}
 
 
 def cpu_baseline(s, x, w, min_seconds=1.0, max_passes=20):
@@ -323,6 +325,8 @@ def main():
     ap.add_argument("--no-shapes", action="store_true", help="skip the per-shape table and the ablation")
     ap.add_argument("--sweep", type=int, default=0, metavar="N",
                     help="add the ResNet-18 / SqueezeNet 1.0 layer sweep at batch N (section 3.1, Table 2)")
+    ap.add_argument("--sweep-dtype", default="bf16", choices=["bf16", "f32"],
+                    help="tensor type of the layer sweep (f32: the paper's own precision, section 3.1)")
     ap.add_argument("--workload", default=None, help="time another shape as the headline (tuning)")
     ap.add_argument("--plan", type=int, default=0)
     ap.add_argument("--batch", type=int, default=0, help="with --workload / --traffic-probe: the shape at another batch size")
@@ -468,7 +472,7 @@ def main():
         out["shapes"] = shapes
 
     if args.sweep > 0:
-        out["layer_sweep"] = layer_sweep(icv, torch, args.sweep)
+        out["layer_sweep"] = layer_sweep(icv, torch, args.sweep, args.sweep_dtype)
 
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(s, prob.x_host, prob.w_host)

@@ -41,7 +41,7 @@ typedef enum {
 
 /* Element types: input/filter -> accumulator/output. */
 typedef enum {
-    ICV_F32 = 0,  /* float  x float    -> float  (MFMA where the pixel-range kernel applies, else vector ALU) */
+    ICV_F32 = 0,  /* float  x float    -> float  (MFMA when C is a multiple of 16, else vector ALU) */
     ICV_BF16 = 1, /* bf16   x bf16     -> float  (MFMA, fp32 accumulate)                 */
     ICV_U8I8 = 2  /* uint8  x int8     -> int32  (MFMA, out = sum (x - zero_point) * w)  */
 } icv_dtype;

@@ -302,18 +302,21 @@ def run(buf: ConvBuffers, input_dev: torch.Tensor) -> torch.Tensor:
 
 
 def stored_for_tensor_cores(shape):
-    """The shape as its tensors would be kept in memory for the 16-bit / 8-bit tensor-core kernels: 3 channels are
-    stored as 4 (an 8-byte pixel); counts that are neither 4, 8, 16 nor a multiple of 32 are rounded up to a
-    multiple of 32 (64-byte rows).  The padding channels of input and filter hold zeros and `c_logical` keeps the
-    real count (FLOPs are counted on it).  Shapes that need no padding are returned as they are; the unpadded shape
-    is always valid too and runs on the vector-ALU kernel."""
+    """The shape as its tensors would be kept in memory for the tensor-core kernels.  16-bit / 8-bit tensors: 3
+    channels are stored as 4 (an 8-byte pixel); counts that are neither 4, 8, 16 nor a multiple of 32 are rounded up
+    to a multiple of 32 (64-byte rows).  fp32 tensors: counts are rounded up to a multiple of 16 (64-byte rows).  The
+    padding channels of input and filter hold zeros and `c_logical` keeps the real count (FLOPs are counted on it).
+    Shapes that need no padding are returned as they are; the unpadded shape is always valid too and runs on the
+    vector-ALU kernel."""
     C = shape.C
-    if C == 3:
+    if shape.dtype == "f32":
+        Cs = -(-C // 16) * 16
+    elif C == 3:
         Cs = 4
     elif C % 32 == 0 or C in (4, 8, 16):
         Cs = C
     else:
         Cs = -(-C // 32) * 32
-    if Cs == C or shape.dtype == "f32":
+    if Cs == C:
         return shape
     return shape.with_(C=Cs, c_logical=C)

@@ -73,13 +73,15 @@ static const char* kPatchNames[3][7] = {
      "mfma_i8_64x64_c2x2_patch", "mfma_i8_256x128_c4x2_patch", "mfma_i8_128x128_c4x2_patch"},
     {"mfma_f32_128x64_c2x2_patch", "", "mfma_f32_256x64_c4x1_patch", "", "mfma_f32_64x64_c2x2_patch", "", "mfma_f32_128x128_c4x2_patch"},
 };
-static const char* kGemmNames[2][7] = {
+static const char* kGemmNames[3][7] = {
     {"gemm_bf16_128x64_c2x2_p4", "gemm_bf16_128x128_c2x2_p4", "", "gemm_bf16_256x64_c4x2_p8", "gemm_bf16_64x64_c2x2_p4", "", ""},
     {"gemm_i8_128x64_c2x2_p4", "gemm_i8_128x128_c2x2_p4", "", "gemm_i8_256x64_c4x2_p8", "gemm_i8_64x64_c2x2_p4", "", ""},
+    {"gemm_f32_128x64_c2x2_p4", "gemm_f32_128x128_c2x2_p4", "", "gemm_f32_256x64_c4x2_p8", "gemm_f32_64x64_c2x2_p4", "", ""},
 };
-static const char* kMfmaNames[2][7] = {
+static const char* kMfmaNames[3][7] = {
     {"mfma_bf16_128x64_c2x2_p4", "mfma_bf16_128x128_c2x2_p4", "", "mfma_bf16_256x64_c4x2_p8", "mfma_bf16_64x64_c2x2_p4", "", ""},
     {"mfma_i8_128x64_c2x2_p4", "mfma_i8_128x128_c2x2_p4", "", "mfma_i8_256x64_c4x2_p8", "mfma_i8_64x64_c2x2_p4", "", ""},
+    {"mfma_f32_128x64_c2x2_p4", "mfma_f32_128x128_c2x2_p4", "", "mfma_f32_256x64_c4x2_p8", "mfma_f32_64x64_c2x2_p4", "", ""},
 };
 
 static const int64_t kCusHost = 256;      // compute units the plan is chosen for (the launchers ask the device)
@@ -139,7 +141,8 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     // ---- plan: which kernel, which tile
     const int64_t row_bytes = (int64_t)p->C * g->elem_bytes;        // bytes of one gathered A row
     const int64_t stride_bytes = (int64_t)g->in_stride * g->elem_bytes;
-    // fp32 tensors (section 3.1's own precision) run on the matrix cores through the pixel-range kernel alone
+    // fp32 tensors (section 3.1's own precision) run on the matrix cores through the pixel-range kernel (four of its
+    // tiles) and the gathering kernel / plain GEMM
     const bool f32 = p->dtype == ICV_F32;
     bool mfma_ok = row_bytes % 64 == 0 && stride_bytes % 16 == 0;
     if (p->dtype == ICV_U8I8 && p->input_zero_point != 128) mfma_ok = false;   // x ^ 0x80 == x - 128 only
@@ -225,13 +228,14 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
                 variant = order[first];
             }
         }
-        if (!patch_rows && f32) mfma_ok = false;
-        if (!patch_rows && !f32) {
+        if (!patch_rows) {
             // the gathering kernel has four of the tiles: 128 x 128 as 2 x 2 wavefronts (measured), 256 x 64 with
             // eight producer wavefronts, and 256-row tiles only when a tile's entries fit their LDS budget
             if (variant == 5 || variant == 6) variant = 1;
             if (variant == 2) variant = 3;
             if (variant == 3 && (int64_t)256 * T * 4 > 24 * 1024) variant = 0;
+            // large kernels (7x7): 128-row tiles' entries do not fit either, 64-row tiles' do -- unless a tile was asked for
+            if (plan_kernel < 2 && (variant == 0 || variant == 1) && (int64_t)128 * T * 4 > 24 * 1024) variant = 4;
         }
         // a workgroup keeps two tiles' worth of entries in LDS: 2 * MR*T int32 (plus padding)
         if (mfma_ok && !patch_rows && (int64_t)kTileVariants[variant].MR * T * 4 > 24 * 1024) mfma_ok = false;
@@ -318,13 +322,14 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         g->stages_per_tap = (int32_t)(row_bytes / g->KCB);
         g->taps_per_stage = 1;
         g->n_stages = g->T * g->stages_per_tap;
-        g->name = f32 ? kPatchNames[2][variant] : (patch_rows ? kPatchNames : kMfmaNames)[p->dtype == ICV_U8I8 ? 1 : 0][variant];
+        const int name_row = f32 ? 2 : (p->dtype == ICV_U8I8 ? 1 : 0);
+        g->name = (patch_rows ? kPatchNames : kMfmaNames)[name_row][variant];
         // Section 3.2, closing paragraph: a 1x1 stride-1 convolution needs no im2col, the plain GEMM primitive has
         // the edge there and switching between the two primitives by convolution parameters is advised.  Its A matrix is the input tensor; the indirection buffer is built but not read.
         if (T == 1 && p->SY == 1 && p->SX == 1 && p->PT == 0 && p->PL == 0 && p->PB == 0 && p->PR == 0 &&
             plan_staging != 1) {
             g->gemm_on_input = 1;
-            g->name = kGemmNames[p->dtype == ICV_U8I8 ? 1 : 0][variant];
+            g->name = kGemmNames[name_row][variant];
         }
     } else {
         g->kind = PLAN_GENERIC;
@@ -383,7 +388,7 @@ static int make_ablation_geometry(const icv_conv_params* p, Geometry* g)
     // the packed filter of the filter-in-registers plan is laid out for that kernel alone; the ablation takes a plan
     // whose filter and tile the plain GEMM kernel reads (ICV_PLAN_GATHER always is one)
     if (g->kind == PLAN_MFMA_FREG) return ICV_ERR_UNSUPPORTED;
-    if (g->kind == PLAN_MFMA && (!kGemmNames[0][g->variant][0] || p->dtype == ICV_F32)) return ICV_ERR_UNSUPPORTED;      // a tile, or a dtype, the GEMM lacks
+    if (g->kind == PLAN_MFMA && !kGemmNames[0][g->variant][0]) return ICV_ERR_UNSUPPORTED;      // a tile the GEMM lacks
     g->per_image = 0;
     g->img_rows = g->M;
     g->img_tiles = (g->M + g->MR - 1) / g->MR;

@@ -59,7 +59,7 @@ struct IgemmArgs {
     EpilogueArgs ep;           // output stage (read by the FUSED instantiations only)
 };
 
-template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool DIRECT, bool FUSED>
+template <int DT, int MR, int NR, int WM, int WN, int NP, int KCB, bool DIRECT, bool FUSED>
 __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
 {
     constexpr int NC = WM * WN;              // consumer wavefronts; NP producer wavefronts follow them
@@ -77,6 +77,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
     static_assert(A_VEC * NP * 1024 == MR * KCB && B_VEC * NP * 1024 == NR * KCB, "copies must divide evenly");
     static_assert(4 * LP <= 63, "vmcnt is a 6-bit counter");
     static_assert((MR / NP) % RPB == 0, "a producer's rows are whole copy blocks");
+    constexpr bool I8 = DT == ICV_U8I8;      // DT: the icv_dtype of input and filter
     using acc_t = typename Acc<I8>::type;
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -258,7 +259,10 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
 #pragma unroll
                     for (int i = 0; i < MB; i++)
 #pragma unroll
-                        for (int j = 0; j < NB; j++) acc[i][j] = mfma32<I8>(af[i], bf[j], acc[i][j]);
+                        for (int j = 0; j < NB; j++) {
+                            if constexpr (DT == ICV_F32) acc[i][j] = mfma32_f32(af[i], bf[j], acc[i][j]);
+                            else acc[i][j] = mfma32<I8>(af[i], bf[j], acc[i][j]);
+                        }
                 }
             }
 
@@ -277,11 +281,11 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_mfma(IgemmArgs g)
 }
 
 // ------------------------------------------------------------------ launch
-template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB, bool DIRECT, bool FUSED>
+template <int DT, int MR, int NR, int WM, int WN, int NP, int KCB, bool DIRECT, bool FUSED>
 static int launch_one(const Geometry& g, IgemmArgs a, hipStream_t s)
 {
     constexpr int threads = 64 * (WM * WN + NP);
-    auto kern = k_igemm_mfma<I8, MR, NR, WM, WN, NP, KCB, DIRECT, FUSED>;
+    auto kern = k_igemm_mfma<DT, MR, NR, WM, WN, NP, KCB, DIRECT, FUSED>;
     constexpr size_t slot = (size_t)(MR + NR) * KCB;
     a.ent_copies = DIRECT ? 0 : (int32_t)(((size_t)g.T * MR * 4 + 1023) / 1024);
     const size_t ent = (size_t)2 * a.ent_copies * 1024;
@@ -325,37 +329,37 @@ static int launch_one(const Geometry& g, IgemmArgs a, hipStream_t s)
 }
 
 // picks the DIRECT (dense A) and FUSED (output stage) instantiation
-template <bool I8, int MR, int NR, int WM, int WN, int NP, int KCB>
+template <int DT, int MR, int NR, int WM, int WN, int NP, int KCB>
 static int launch_pick(const Geometry& g, const IgemmArgs& a, bool direct, hipStream_t s)
 {
     if (direct)
-        return g.ep_plain ? launch_one<I8, MR, NR, WM, WN, NP, KCB, true, false>(g, a, s)
-                          : launch_one<I8, MR, NR, WM, WN, NP, KCB, true, true>(g, a, s);
-    return g.ep_plain ? launch_one<I8, MR, NR, WM, WN, NP, KCB, false, false>(g, a, s)
-                      : launch_one<I8, MR, NR, WM, WN, NP, KCB, false, true>(g, a, s);
+        return g.ep_plain ? launch_one<DT, MR, NR, WM, WN, NP, KCB, true, false>(g, a, s)
+                          : launch_one<DT, MR, NR, WM, WN, NP, KCB, true, true>(g, a, s);
+    return g.ep_plain ? launch_one<DT, MR, NR, WM, WN, NP, KCB, false, false>(g, a, s)
+                      : launch_one<DT, MR, NR, WM, WN, NP, KCB, false, true>(g, a, s);
 }
 
-template <bool I8, int MR, int NR, int WM, int WN, int NP>
+template <int DT, int MR, int NR, int WM, int WN, int NP>
 static int launch_tile(const Geometry& g, const IgemmArgs& a, bool direct, hipStream_t s)
 {
     if (g.KCB == 128) {
-        return launch_pick<I8, MR, NR, WM, WN, NP, 128>(g, a, direct, s);
+        return launch_pick<DT, MR, NR, WM, WN, NP, 128>(g, a, direct, s);
     }
     if constexpr (NR * 64 / 1024 >= NP) {      // a 64-byte stage of the B tile must still split over the copying wavefronts
-        return launch_pick<I8, MR, NR, WM, WN, NP, 64>(g, a, direct, s);
+        return launch_pick<DT, MR, NR, WM, WN, NP, 64>(g, a, direct, s);
     } else {
-        return launch_pick<I8, MR, NR, WM, WN, 4, 64>(g, a, direct, s);
+        return launch_pick<DT, MR, NR, WM, WN, 4, 64>(g, a, direct, s);
     }
 }
 
-template <bool I8>
+template <int DT>
 static int launch_dtype(const Geometry& g, const IgemmArgs& a, bool direct, hipStream_t s)
 {
     switch (g.variant) {
-        case 0: return launch_tile<I8, 128, 64, 2, 2, 4>(g, a, direct, s);
-        case 1: return launch_tile<I8, 128, 128, 2, 2, 4>(g, a, direct, s);
-        case 3: return launch_tile<I8, 256, 64, 4, 2, 8>(g, a, direct, s);
-        case 4: return launch_tile<I8, 64, 64, 2, 2, 4>(g, a, direct, s);
+        case 0: return launch_tile<DT, 128, 64, 2, 2, 4>(g, a, direct, s);
+        case 1: return launch_tile<DT, 128, 128, 2, 2, 4>(g, a, direct, s);
+        case 3: return launch_tile<DT, 256, 64, 4, 2, 8>(g, a, direct, s);
+        case 4: return launch_tile<DT, 64, 64, 2, 2, 4>(g, a, direct, s);
         default: return ICV_ERR_UNSUPPORTED;
     }
 }
@@ -389,7 +393,8 @@ int launch_igemm_mfma(const icv_conv_params* p, const Geometry& g, const void* i
     a.ring = 0; a.ent_copies = 0; a.xcd_mode = 0;
     a.cc_major = g.cc_major; a.row_bytes = p->C * g.elem_bytes;
     a.ep = g.ep;
-    return p->dtype == ICV_U8I8 ? launch_dtype<true>(g, a, a_direct, s) : launch_dtype<false>(g, a, a_direct, s);
+    if (p->dtype == ICV_F32) return launch_dtype<ICV_F32>(g, a, a_direct, s);
+    return p->dtype == ICV_U8I8 ? launch_dtype<ICV_U8I8>(g, a, a_direct, s) : launch_dtype<ICV_BF16>(g, a, a_direct, s);
 }
 
 }  // namespace icv

@@ -476,20 +476,43 @@ def test_fp32_tensors_on_the_matrix_cores(s, tile):
         xp[..., :s.C] = x
     p = icv.make_params(s, tile, in_pixel_stride=stride)
     name = icv.plan_name(p)
-    if tile and "mfma_f32" not in name:
-        # this tile's pixel range does not fit LDS for the shape: the vector-ALU kernel takes over
-        assert name == "generic_f32", name
-        return
-    assert name.startswith("mfma_f32") and "patch" in name, name
+    if tile and "patch" not in name:
+        # this tile's pixel range does not fit LDS for the shape: rows are gathered per kernel element instead
+        assert name.startswith("mfma_f32"), name
+    else:
+        assert name.startswith("mfma_f32") and "patch" in name, name
     _say("fp32 mfma", s.name, name)
     buf = icv.prepare(s, icv.to_device(w), plan=tile, in_pixel_stride=stride)
     buf.output.fill_(-7)
     icv.run(buf, icv.to_device(xp))
     torch.cuda.synchronize()
     check_against_oracle(s, buf.output.cpu().numpy(), x, w)
-    # the same problem on the vector ALUs agrees to the same bound, and plans without a pixel range fall back to them
-    assert icv.plan_name(icv.make_params(s, icv.PLAN_GATHER, in_pixel_stride=stride)).startswith("generic")
-    assert icv.im2col_bytes(p) == 0
+    if tile == 0:
+        # the same problem with rows gathered per kernel element (section 2.2 as printed), in fp32 on the matrix cores too
+        g = icv.prepare(s, icv.to_device(w), plan=icv.PLAN_GATHER, in_pixel_stride=stride)
+        assert icv.plan_name(g.p).startswith("mfma_f32") and "patch" not in icv.plan_name(g.p)
+        g.output.fill_(-7)
+        icv.run(g, icv.to_device(xp))
+        torch.cuda.synchronize()
+        check_against_oracle(s, g.output.cpu().numpy(), x, w)
+
+
+def test_fp32_pointwise_convolution_and_ablation_on_the_matrix_cores():
+    """1x1 stride-1 in fp32 runs as the plain GEMM on the input; the im2col + GEMM comparison path runs in fp32 too."""
+    s = ConvShape("f_1x1", 3, 7, 11, 64, 72, 1, 1, dtype="f32", seed=411)
+    x, w = make_tensors(s)
+    assert icv.plan_name(icv.make_params(s)).startswith("gemm_f32")
+    buf, xd = run_indirect(s, x, w)
+    check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+    s = _f32_mfma_shapes()[0]
+    x, w = make_tensors(s)
+    buf = icv.prepare(s, icv.to_device(w), plan=icv.PLAN_GATHER)
+    ws = torch.empty(icv.im2col_bytes(buf.p), dtype=torch.uint8, device="cuda:0")
+    assert ws.numel() > 0
+    out = torch.full_like(buf.output, -7)
+    icv.conv2d_nhwc_im2col(buf.p, icv.to_device(x), buf.packed, ws, out)
+    torch.cuda.synchronize()
+    check_against_oracle(s, out.cpu().numpy(), x, w)
 
 
 @pytest.mark.parametrize("s", _f32_mfma_shapes()[:3], ids=lambda s: s.name)
