@@ -140,7 +140,8 @@ typedef struct icv_indirection_layout {
 ICV_API int icv_get_indirection_layout(const icv_conv_params* p, icv_indirection_layout* layout);
 
 /*
- * Closed-form bounds (host arithmetic) on the input pixels that the valid entries of output pixels m0..m1 name:
+ * Closed-form bounds (host arithmetic) on the input pixels that the valid entries (section 2.3; Listing 1's iy, ix)
+ * of output pixels m0..m1 name:
  * *first is not above any of them, *last not below (pixel indices (n*Hin + iy)*Win + ix of the whole tensor).  Both
  * are non-decreasing in m0 and m1, which is what lets a kernel keep a sliding window of input pixels while it walks
  * the output pixels in order.  last - first + 1 <= icv_tile_span_bound(p, m1 - m0 + 1).
