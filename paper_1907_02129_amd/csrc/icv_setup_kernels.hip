@@ -273,6 +273,7 @@ struct BlockIndArgs {
     int64_t M;
     uint32_t n_blocks;
     int32_t T, stride_bytes;
+    FastDiv by_s;
 };
 
 __global__ __launch_bounds__(256) void k_build_block_indirection(BlockIndArgs a)
@@ -291,8 +292,10 @@ __global__ __launch_bounds__(256) void k_build_block_indirection(BlockIndArgs a)
         o[j] = decompose(a.q, live[j] ? m0 + j : 0u);
     }
     uint32_t* dst = (uint32_t*)(a.ent + (int64_t)blk * a.T * 32) + lane;
+    // this lane's kernel elements lane / 16, + 4, ... as (ky, kx), stepped without a division per element
+    int32_t ky = (int32_t)fast_div((uint32_t)(lane >> 4), a.by_s), kx = (lane >> 4) - ky * a.q.S;
+    const int32_t step_y = (int32_t)fast_div(4u, a.by_s), step_x = 4 - step_y * a.q.S;
     for (int32_t tap = lane >> 4; tap < a.T; tap += 4) {
-        const int32_t ky = tap / a.q.S, kx = tap - ky * a.q.S;
         uint32_t e[2];
 #pragma unroll
         for (int j = 0; j < 2; j++) {
@@ -302,6 +305,8 @@ __global__ __launch_bounds__(256) void k_build_block_indirection(BlockIndArgs a)
             e[j] = in ? (uint32_t)((o[j].n * a.q.Hin + iy) * a.q.Win + ix - base) : 0xFFFFu;
         }
         dst[(tap - (lane >> 4)) * 16] = e[0] | (e[1] << 16);
+        kx += step_x; ky += step_y;
+        if (kx >= a.q.S) { kx -= a.q.S; ++ky; }
     }
 }
 
@@ -316,6 +321,7 @@ int launch_build_indirection(const icv_conv_params* p, const Geometry& g, int32_
         b.n_blocks = (uint32_t)g.img_tiles;
         b.T = g.T;
         b.stride_bytes = g.in_stride * g.elem_bytes;
+        b.by_s = make_fast_div((uint32_t)p->S);
         hipLaunchKernelGGL(k_build_block_indirection, dim3((unsigned)((g.img_tiles + 3) / 4)), dim3(256), 0, s, b);
         ICV_HIP_CHECK(hipGetLastError());
         return ICV_OK;
