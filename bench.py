@@ -471,6 +471,23 @@ def main():
             torch.cuda.empty_cache()
         out["shapes"] = shapes
 
+    if not args.no_shapes:
+        # The same kernels with enough work per launch for a steady state (batch 256): what they deliver once launch,
+        # start-up and the last stores are a small share of the run.
+        big = {}
+        for nm in ("cfg2_3x3_c64", "cfg3a_3x3_s2", "cfg3b_3x3_d2", "cfg4_int8_3x3"):
+            sh = CONFIGS[nm].with_(N=256)
+            pp = icv.make_params(sh)
+            ho, wo = icv.output_size(pp)
+            pr = Problem(icv, torch, sh, sets=2)
+            m = pr.time_quantiles(repeats=7, inner=10, warmup=3)[0]
+            f = flops(sh, ho, wo)
+            big[nm] = {"N": 256, "kernel": icv.plan_name(pp), "ms": m, "TFLOPs": f / (m * 1e-3) / 1e12,
+                       "roofline": roofline(sh, ho, wo, m, icv.plan_name(pp), nm + "@N=256", measured_peak)}
+            del pr
+            torch.cuda.empty_cache()
+        out["batch_256"] = big
+
     if args.sweep > 0:
         out["layer_sweep"] = layer_sweep(icv, torch, args.sweep, args.sweep_dtype)
 

@@ -248,7 +248,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     // per byte and leave less to hide the filter load behind).
     int freg_wn = 0, freg_mb = 0, freg_ring = 0;
     if (p->dtype != ICV_F32 && !(p->dtype == ICV_U8I8 && p->input_zero_point != 128) && plan_kernel == 0 &&
-        (plan_staging == 3 || (plan_staging == 0 && p->dtype == ICV_BF16 && T * (row_bytes / 32) >= 48)) && !plan_per_image && row_bytes % 32 == 0 &&
+        (plan_staging == 3 || (plan_staging == 0 && p->dtype == ICV_BF16)) && !plan_per_image && row_bytes % 32 == 0 &&
         stride_bytes % 16 == 0 && freg_shape_supported((int)T, (int)(row_bytes / 32)) &&
         tile_span_bound(p, Hout, Wout, 32) < 65535) {
         const int wn = p->K <= 32 ? 1 : (p->K <= 64 ? 2 : 4);
@@ -261,6 +261,9 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
             while (ring < need) ring *= 2;
             if (ring > (1 << 20) || freg_lds_bytes((int)T, (int)(row_bytes / 32), pbk, (int)ring) > 160 * 1024) continue;
             if (plan_staging != 3 && n_blocks < ranges * pbk) continue;
+            // smaller filter blocks (3x3 on 128-byte rows) only with 64 row blocks or more per workgroup, where the
+            // steady state decides (measured: cfg2's shape level at batch 128, 15-18 % faster at batch 256-512)
+            if (plan_staging != 3 && T * (row_bytes / 32) < 48 && n_blocks < 64 * ranges) continue;
             freg_wn = wn; freg_mb = mb; freg_ring = (int)ring;
         }
         if (!freg_mb && plan_staging == 3) return ICV_ERR_UNSUPPORTED;
