@@ -435,6 +435,10 @@ def main():
                    "GBps_algorithmic": ab / (m * 1e-3) / 1e9,
                    "frac_of_hbm_peak": ab / (m * 1e-3) / 1e9 / HBM_PEAK_GBS,
                    "roofline": roofline(sh, ho, wo, m, icv.plan_name(pp), nm, measured_peak)}
+            # the same launches replayed from a HIP graph: the GPU's time without the host's per-call cost (which is
+            # what "ms" shows for problems that take less than a launch through ctypes, cfg1)
+            nb = len(pr.bufs)
+            row["graph_replay_ms"] = graph_time(torch, pr.step, 2 * nb if nb >= 5 else 12)
             if sh.dtype != "f32" or row["kernel"].startswith("mfma_"):
                 # the same launch with the fused output stage (bias + ReLU, 2- or 1-byte output elements)
                 pr.enable_fused()
