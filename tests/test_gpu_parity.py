@@ -439,6 +439,50 @@ def test_filter_in_registers_kernel_matches_oracle(s):
         assert rec[b, 2] == first and rec[b, 0] == first * (stride or s.C) * esz
 
 
+def _random_freg_shapes(n=40):
+    """Random problems of the kinds the filter-in-registers kernel is built for (3x3 on 128- and 256-byte rows, 5x5 on
+    64-byte rows): any stride, dilation and padding, images from one pixel up, batches that end inside blocks."""
+    rng = np.random.default_rng(77)
+    out = []
+    while len(out) < n:
+        kind = len(out) % 4
+        dtype = "u8i8" if kind == 3 else "bf16"
+        if kind == 0:
+            R, C = 5, 32
+        else:
+            R, C = 3, int(rng.choice([64, 128])) * (2 if dtype == "u8i8" else 1)
+        DY, DX = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        SY, SX = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        PT, PL, PB, PR = (int(v) for v in rng.integers(0, 6, size=4))
+        Hin, Win = int(rng.integers(1, 30)), int(rng.integers(1, 45))
+        if Hin + PT + PB < DY * (R - 1) + 1 or Win + PL + PR < DX * (R - 1) + 1:
+            continue
+        out.append(ConvShape(f"rr{len(out)}_{dtype}_{R}x{R}_c{C}", int(rng.integers(1, 7)), Hin, Win, C, int(rng.integers(1, 150)),
+                             R, R, SY=SY, SX=SX, DY=DY, DX=DX, PT=PT, PL=PL, PB=PB, PR=PR, dtype=dtype,
+                             zero_point=128 if dtype == "u8i8" else 0, seed=2000 + len(out)))
+    return out
+
+
+@pytest.mark.parametrize("s", _random_freg_shapes(), ids=lambda s: s.name)
+def test_filter_in_registers_kernel_on_random_shapes(s):
+    p = icv.make_params(s, FREG)
+    name = icv.plan_name(p)
+    if not name:
+        # (a window of two passes that does not fit LDS: refused as a whole)
+        assert icv.indirection_bytes(p) == 0
+        return
+    assert "freg" in name, name
+    _say("filter-in-registers", s.name, name, s)
+    x, w = make_tensors(s)
+    buf = icv.prepare(s, icv.to_device(w), plan=FREG)
+    buf.output.fill_(-7)
+    icv.run(buf, icv.to_device(x))
+    torch.cuda.synchronize()
+    check_against_oracle(s, buf.output.cpu().numpy(), x, w)
+    got, tail = layout.logical_indirection(buf.p, buf.indirection, buf.M)
+    assert np.array_equal(got, oracle.indirection(s)) and np.all(tail == -1)
+
+
 @pytest.mark.parametrize("s", [_freg_shapes()[i] for i in (1, 2, 5, 13, 16)], ids=lambda s: s.name)
 @pytest.mark.parametrize("relu,narrow", [(True, True), (False, False), (True, False)], ids=["relu_narrow", "linear_acc", "relu_acc"])
 def test_filter_in_registers_kernel_with_fused_output(s, relu, narrow):
