@@ -4,7 +4,7 @@
 // It is Listing 3 with one output element per thread: for each kernel element load the row pointer from
 // the indirection buffer (entry = byte offset from the input base; < 0 -> the zero row), take the C-long dot product with the filter row,
 // accumulate.  A block is 4 output pixels x 64 output channels; the 64 lanes of a wavefront share the
-// A row (a broadcast read) and differ in the filter row.
+// A row (a broadcast read) and read neighbouring filter elements (the filter is packed with the output channels innermost).
 #include <type_traits>
 #include "icv_internal.h"
 
@@ -12,13 +12,14 @@ namespace icv {
 
 struct GenericArgs {
     const void* a;         // input tensor, or the im2col matrix when a_direct
-    const void* w;         // [K padded][T][C]
+    const void* w;         // [T * C][K padded]
     const int32_t* ind;    // [m tile][tap][64]
     const void* zero_row;
     void* out;
     int64_t M;
     int32_t K, T, C, in_stride, out_stride, zero_point, a_direct;
     int64_t img_rows, image_bytes;
+    int64_t kp;            // K padded: filter elements between two reduction indices
     EpilogueArgs ep;
 };
 
@@ -32,7 +33,7 @@ __global__ __launch_bounds__(256) void k_igemm_generic(GenericArgs g)
     const int32_t oc = blockIdx.y * 64 + (threadIdx.x & 63);
     if (m >= g.M || oc >= g.K) return;
     const TIn* in = (const TIn*)g.a;
-    const TW* w = (const TW*)g.w + (int64_t)oc * g.T * g.C;
+    const TW* w = (const TW*)g.w + oc;
     // batch-independent buffer: the entries are those of pixel m % img_rows, the rows they name lie in batch
     // element m / img_rows (img_rows = M and image_bytes = 0 otherwise)
     const int64_t img = m / g.img_rows, mi = m - img * g.img_rows;
@@ -47,12 +48,12 @@ __global__ __launch_bounds__(256) void k_igemm_generic(GenericArgs g)
             const int32_t e = ent[(int64_t)t * 64];
             row = e < 0 ? (const TIn*)g.zero_row : (const TIn*)(a_img + e);   // byte offset entry
         }
-        const TW* wr = w + (int64_t)t * g.C;
+        const TW* wr = w + (int64_t)t * g.C * g.kp;
         for (int32_t c = 0; c < g.C; c++) {
             if constexpr (std::is_integral<TAcc>::value) {
-                acc += ((int32_t)row[c] - g.zero_point) * (int32_t)wr[c];
+                acc += ((int32_t)row[c] - g.zero_point) * (int32_t)wr[c * g.kp];
             } else {
-                acc = fmaf(to_float(row[c]), to_float(wr[c]), acc);
+                acc = fmaf(to_float(row[c]), to_float(wr[c * g.kp]), acc);
             }
         }
     }
@@ -70,6 +71,7 @@ int launch_igemm_generic(const icv_conv_params* p, const Geometry& g, const void
     a.a_direct = a_direct ? 1 : 0;
     a.img_rows = a_direct ? g.M : g.img_rows;
     a.image_bytes = a_direct ? 0 : g.image_bytes;
+    a.kp = g.n_tiles * g.NR;
     a.ep = g.ep;
     const int64_t gx = (g.M + 3) / 4;
     if (gx > 0x7fffffffll || g.n_tiles > 65535) return ICV_ERR_UNSUPPORTED;

@@ -26,7 +26,7 @@ int launch_zero_row(const icv_conv_params* p, const Geometry& g, void* zero_row,
 //         tile's pixel range in LDS: the tile one pipeline stage of the GEMM kernel copies into LDS is one
 //         contiguous block.  Rows past K are zero.
 // One thread moves 16 bytes (KCB and C*elem are multiples of 16 for the tensor-core plans); the generic
-// plan (KCB == 0) keeps [K padded][T][C] and moves single elements.
+// plan (KCB == 0) transposes to [T * C][K padded] and moves single elements.
 struct PackArgs {
     const uint8_t* src;
     uint8_t* dst;
@@ -56,10 +56,15 @@ __global__ void k_pack_filter_vec(PackArgs a)
     *(uint4*)(a.dst + v * 16) = val;
 }
 
-__global__ void k_pack_filter_plain(const uint8_t* src, uint8_t* dst, int64_t valid_bytes, int64_t total_bytes)
+// Vector-ALU plan: [R*S*C][K padded], output channels innermost, so that the 64 lanes of a wavefront (64 neighbouring
+// output channels) read one contiguous run per reduction index.  One thread per element; channels past K are zero.
+template <typename T>
+__global__ void k_pack_filter_transposed(const T* src, T* dst, int K, int64_t red, int64_t kp)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < total_bytes) dst[i] = i < valid_bytes ? src[i] : (uint8_t)0;
+    if (i >= red * kp) return;
+    const int64_t r = i / kp, oc = i - r * kp;
+    dst[i] = oc < K ? src[oc * red + r] : (T)0;
 }
 
 // Low-C plan: [n tile][64][KP]; row oc is the filter's own [R][S][C] run followed by zeros up to KP bytes.
@@ -122,9 +127,14 @@ int launch_pack_filter(const icv_conv_params* p, const Geometry& g, const void* 
         a.total_vec = g.n_tiles * g.NR * (int64_t)g.T * CB / 16;
         hipLaunchKernelGGL(k_pack_filter_vec, dim3((unsigned)((a.total_vec + 255) / 256)), dim3(256), 0, s, a);
     } else {
-        const int64_t valid = (int64_t)p->K * g.T * CB, total = g.n_tiles * g.NR * (int64_t)g.T * CB;
-        hipLaunchKernelGGL(k_pack_filter_plain, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                           (const uint8_t*)filt, (uint8_t*)packed, valid, total);
+        const int64_t red = (int64_t)g.T * p->C, kp = g.n_tiles * g.NR, total = red * kp;
+        const dim3 grid((unsigned)((total + 255) / 256));
+        if (g.elem_bytes == 4)
+            hipLaunchKernelGGL(k_pack_filter_transposed<uint32_t>, grid, dim3(256), 0, s, (const uint32_t*)filt, (uint32_t*)packed, p->K, red, kp);
+        else if (g.elem_bytes == 2)
+            hipLaunchKernelGGL(k_pack_filter_transposed<uint16_t>, grid, dim3(256), 0, s, (const uint16_t*)filt, (uint16_t*)packed, p->K, red, kp);
+        else
+            hipLaunchKernelGGL(k_pack_filter_transposed<uint8_t>, grid, dim3(256), 0, s, (const uint8_t*)filt, (uint8_t*)packed, p->K, red, kp);
     }
     ICV_HIP_CHECK(hipGetLastError());
     return ICV_OK;
