@@ -60,7 +60,62 @@ def algorithmic_bytes(s, Hout, Wout):
     return s.N * s.Hin * s.Win * s.C * esz + s.K * T * s.C * esz + M * s.K * 4 + M * T * 4
 
 
-def roofline(s, Hout, Wout, ms, kernel, name, measured_peak=None):
+def vendor_gemm_reference(torch, n=8192, iters=10):
+    """TFLOP/s of the vendor library's bf16 GEMM (torch.matmul) on an n x n x n problem, on random and on all-zero
+    matrices: what a tuned, compute-bound kernel sustains on this device with and without switching activity in its
+    operands.  Context for the fractions of peak, nothing the library's own path uses."""
+    res = {}
+    for kind in ("random", "zeros"):
+        make = torch.randn if kind == "random" else torch.zeros
+        a = make(n, n, device="cuda:0", dtype=torch.bfloat16)
+        b = make(n, n, device="cuda:0", dtype=torch.bfloat16)
+        for _ in range(3):
+            c = a @ b
+        best = None
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                c = a @ b
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) / iters
+            best = t if best is None or t < best else best
+        res[f"bf16_{kind}_TFLOPs"] = 2.0 * n ** 3 / (best * 1e-3) / 1e12
+        del a, b, c
+    torch.cuda.empty_cache()
+    res["how"] = f"torch.matmul, {n} x {n} x {n} bfloat16, best of 3 x {iters} launches"
+    return res
+
+
+def vendor_gemm_only_ms(torch, M, red, K, dtype, iters=20):
+    """ms of the vendor library's GEMM (torch.matmul) on a patch matrix that is already in memory: [M, red] x [red, K]
+    on random data -- the "GEMM-only" measurement of section 3.2 with the machine's tuned GEMM in place of this
+    library's.  As many copies of the patch matrix are rotated as it takes to exceed the last-level cache."""
+    dt = {"bf16": torch.bfloat16, "f32": torch.float32}[dtype]
+    esz = 2 if dtype == "bf16" else 4
+    sets = max(1, min(8, -(-(320 << 20) // (M * red * esz))))
+    As = [torch.randn(M, red, device="cuda:0", dtype=dt) for _ in range(sets)]
+    B = torch.randn(red, K, device="cuda:0", dtype=dt)
+    outs = [torch.empty(M, K, device="cuda:0", dtype=dt) for _ in range(sets)]
+    for i in range(3):
+        torch.matmul(As[i % sets], B, out=outs[i % sets])
+    best = None
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(iters):
+            torch.matmul(As[i % sets], B, out=outs[i % sets])
+        e1.record()
+        torch.cuda.synchronize()
+        t = e0.elapsed_time(e1) / iters
+        best = t if best is None or t < best else best
+    del As, B, outs
+    torch.cuda.empty_cache()
+    return best
+
+
+def roofline(s, Hout, Wout, ms, kernel, name, measured_peak=None, measured_peak_varied=None):
     """The roofline object of one shape: which of HBM time (algorithmic bytes at 8 TB/s) and arithmetic time (its
     flops at the dtype's dense peak) is the longer bounds the kernel; `achieved` is that resource's rate at the
     measured duration."""
@@ -87,6 +142,8 @@ def roofline(s, Hout, Wout, ms, kernel, name, measured_peak=None):
         r["frac_of_mfma_peak"] = fl / (ms * 1e-3) / 1e12 / PEAK[s.dtype]
         if measured_peak and measured_peak.get(s.dtype):
             r["frac_of_measured_mfma_peak"] = fl / (ms * 1e-3) / 1e12 / measured_peak[s.dtype]
+        if measured_peak_varied and measured_peak_varied.get(s.dtype):
+            r["frac_of_measured_mfma_peak_varied_operands"] = fl / (ms * 1e-3) / 1e12 / measured_peak_varied[s.dtype]
     return r
 
 
@@ -394,8 +451,10 @@ def main():
     ind_bytes = icv.indirection_bytes(prob.p)      # everything the build writes: entries, range records, 16-bit form
 
     # what the matrix cores of this device deliver on register operands alone, TFLOP/s (TOP/s)
+    # (constant operands: the least switching activity; pseudo-random operands: what real tensors cost in clock)
     measured_peak = {d: icv.measure_mfma_peak(d, 2) / 1e12 for d in ("bf16", "u8i8")}
-    roof = roofline(s, Hout, Wout, ms, icv.plan_name(prob.p), name, measured_peak)
+    measured_peak_varied = {d: icv.measure_mfma_peak(d, 2, True) / 1e12 for d in ("bf16", "u8i8")}
+    roof = roofline(s, Hout, Wout, ms, icv.plan_name(prob.p), name, measured_peak, measured_peak_varied)
 
     out = {
         "metric": "effective TFLOP/s (2*N*Hout*Wout*K*R*S*C / t)", "value": value, "unit": "TFLOP/s",
@@ -409,7 +468,11 @@ def main():
         "roofline": roof,
         "frac_of_mfma_peak": value / PEAK[s.dtype],
         "mfma_peak_measured": {"bf16_TFLOPs": measured_peak["bf16"], "u8i8_TOPs": measured_peak["u8i8"],
-                               "how": "icv_measure_mfma_peak: register-only MFMA loop, 2 wavefronts per SIMD on every CU"},
+                               "bf16_TFLOPs_varied_operands": measured_peak_varied["bf16"],
+                               "u8i8_TOPs_varied_operands": measured_peak_varied["u8i8"],
+                               "how": "icv_measure_mfma_peak: register-only MFMA loop, 2 wavefronts per SIMD on every CU; "
+                                      "constant operands, and pseudo-random operands that change with every instruction"},
+        "vendor_gemm_reference": vendor_gemm_reference(torch),
         "wall_ms_per_step": wall_ms,
         "warm": {"ms_per_step": ms_warm, "value": fl / (ms_warm * 1e-3) / 1e12},
         "quantiles_ms": {"median": med, "q20": q20, "q80": q80, "repeats": 25, "launches_per_repeat": 20},
@@ -434,7 +497,7 @@ def main():
                    "frac_of_peak": f / (m * 1e-3) / 1e12 / PEAK[sh.dtype],
                    "GBps_algorithmic": ab / (m * 1e-3) / 1e9,
                    "frac_of_hbm_peak": ab / (m * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                   "roofline": roofline(sh, ho, wo, m, icv.plan_name(pp), nm, measured_peak)}
+                   "roofline": roofline(sh, ho, wo, m, icv.plan_name(pp), nm, measured_peak, measured_peak_varied)}
             # the same launches replayed from a HIP graph: the GPU's time without the host's per-call cost (which is
             # what "ms" shows for problems that take less than a launch through ctypes, cfg1)
             nb = len(pr.bufs)
@@ -459,6 +522,9 @@ def main():
                 row["im2col_ms"] = ti
                 row["gemm_only_ms"] = tg
                 row["speedup_vs_im2col_gemm"] = ta / m
+            if sh.dtype in ("bf16", "f32") and nm != "cfg1_tiny_f32":
+                # reference only: the vendor library's GEMM on a patch matrix that costs nothing to make
+                row["vendor_gemm_only_ms"] = vendor_gemm_only_ms(torch, sh.N * ho * wo, sh.R * sh.S * sh.C, sh.K, sh.dtype)
             if sh.N > 1 and not icv.plan_name(pp).startswith("gemm_"):
                 # batch-independent indirection buffer (ICV_PLAN_PER_IMAGE): one image's entries serve the whole batch
                 pr_img = Problem(icv, torch, sh, sets=min(len(pr.bufs), 12), plan=icv.PLAN_PER_IMAGE)
@@ -487,7 +553,17 @@ def main():
             m = pr.time_quantiles(repeats=7, inner=10, warmup=3)[0]
             f = flops(sh, ho, wo)
             big[nm] = {"N": 256, "kernel": icv.plan_name(pp), "ms": m, "TFLOPs": f / (m * 1e-3) / 1e12,
-                       "roofline": roofline(sh, ho, wo, m, icv.plan_name(pp), nm + "@N=256", measured_peak)}
+                       "roofline": roofline(sh, ho, wo, m, icv.plan_name(pp), nm + "@N=256", measured_peak,
+                                            measured_peak_varied)}
+            # Diagnostic, never a result: the same launches on activations whose bytes are all zero.  Instructions, addresses
+            # and bytes moved are identical; what changes is the switching activity in the matrix cores, hence the
+            # power, hence the clock the device holds.  The gap to the row above is the share of the distance to the
+            # peak that is the chip's power limit on this data, not idle cycles in the kernel.
+            for x in pr.xs:
+                x.zero_()
+            mz = pr.time_quantiles(repeats=7, inner=10, warmup=3)[0]
+            big[nm]["zero_activations_diagnostic"] = {"ms": mz, "TFLOPs": f / (mz * 1e-3) / 1e12,
+                                                      "frac_of_mfma_peak": f / (mz * 1e-3) / 1e12 / PEAK[sh.dtype]}
             del pr
             torch.cuda.empty_cache()
         out["batch_256"] = big

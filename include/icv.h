@@ -244,11 +244,15 @@ ICV_API int icv_conv2d_nhwc_im2col_static(const icv_conv_params* p, const void* 
 /*
  * Measurement aid: the rate, in multiply-add operations times two per second, at which the current device runs a
  * loop of nothing but tensor-core instructions on register operands (dtype ICV_BF16: 32x32x16 bfloat16 blocks,
- * ICV_U8I8: 32x32x32 int8 blocks), `waves_per_simd` (1..4) wavefronts on every SIMD of every compute unit.  It is
- * the ceiling the Indirect GEMM kernels' throughput can be set against beside the data-sheet figure, at the clock
- * the device sustains under that load.  Takes a few milliseconds, synchronises `stream`, allocates no memory.
+ * ICV_U8I8: 32x32x32 int8 blocks), `waves_per_simd` (1..4) wavefronts on every SIMD of every compute unit.
+ * varied_operands = 0: every instruction multiplies the same two constant operands, the least switching activity
+ * the matrix cores can have; 1: pseudo-random operands, a different pair in every instruction, as with real
+ * tensors (a device at its power limit holds a lower clock then).  Either is a ceiling the Indirect GEMM kernels'
+ * throughput can be set against beside the data-sheet figure, at the clock the device sustains under that load.
+ * Takes a few milliseconds, synchronises `stream`, allocates no memory.  Other argument values: ICV_ERR_INVALID_ARG.
  */
-ICV_API int icv_measure_mfma_peak(int32_t dtype, int32_t waves_per_simd, double* ops_per_second, void* stream);
+ICV_API int icv_measure_mfma_peak(int32_t dtype, int32_t waves_per_simd, int32_t varied_operands, double* ops_per_second,
+                                  void* stream);
 
 /* Name of the kernel variant icv_conv2d_nhwc would launch for p (static string; "" when invalid). */
 ICV_API const char* icv_plan_name(const icv_conv_params* p);

@@ -101,7 +101,8 @@ def load_library(path: str | None = None):
         "icv_static_workspace_bytes": (ctypes.c_size_t, []),
         "icv_conv2d_nhwc_im2col_static": (ctypes.c_int, [P, vp, vp, vp, vp]),
         "icv_plan_name": (ctypes.c_char_p, [P]),
-        "icv_measure_mfma_peak": (ctypes.c_int, [ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]),
+        "icv_measure_mfma_peak": (ctypes.c_int, [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_double),
+                                                 ctypes.c_void_p]),
         "icv_status_string": (ctypes.c_char_p, [ctypes.c_int]),
         "icv_last_hip_error": (ctypes.c_int, []),
     }
@@ -147,10 +148,11 @@ def status_string(status: int) -> str:
     return load_library().icv_status_string(status).decode()
 
 
-def measure_mfma_peak(dtype: str, waves_per_simd: int = 2) -> float:
+def measure_mfma_peak(dtype: str, waves_per_simd: int = 2, varied_operands: bool = False) -> float:
     """Operations per second of a register-only tensor-core loop on the current device (icv_measure_mfma_peak)."""
     v = ctypes.c_double(0.0)
-    _check(load_library().icv_measure_mfma_peak(DTYPES[dtype], waves_per_simd, ctypes.byref(v), _stream()), "icv_measure_mfma_peak")
+    _check(load_library().icv_measure_mfma_peak(DTYPES[dtype], waves_per_simd, int(varied_operands), ctypes.byref(v), _stream()),
+           "icv_measure_mfma_peak")
     return v.value
 
 

@@ -8,7 +8,11 @@
 
 namespace icv {
 
-template <bool I8>
+// VARIED = false: every MFMA multiplies the same two constant operands (1.0, small integers) -- nothing toggles but
+// the accumulators' low bits.  VARIED = true: four A and four B operands of pseudo-random values (bfloat16 in
+// +-[0.5, 2), random bytes), a different pair in every MFMA -- the switching activity of real tensors, which costs
+// power and, on a device that runs at its power limit, clock.
+template <bool I8, bool VARIED>
 __global__ __launch_bounds__(256) void k_mfma_only(int iters, float* sink)
 {
     using acc_t = typename Acc<I8>::type;
@@ -17,28 +21,50 @@ __global__ __launch_bounds__(256) void k_mfma_only(int iters, float* sink)
     for (int i = 0; i < 4; i++)
 #pragma unroll
         for (int r = 0; r < 16; r++) acc[i][r] = 0;
-    uint4 a, b;
-    a.x = a.y = a.z = a.w = I8 ? 0x01020301u * (threadIdx.x & 3) : 0x3f803f80u;       // small integers / 1.0 in bfloat16
-    b.x = b.y = b.z = b.w = I8 ? 0x01010101u : 0x3f803f80u;
-    for (int it = 0; it < iters; it++) {
+    uint4 a[4], b[4];
 #pragma unroll
-        for (int u = 0; u < 4; u++) acc[u] = mfma32<I8>(a, b, acc[u]);
+    for (int i = 0; i < 4; i++) {
+        if (VARIED) {
+            uint32_t h = (uint32_t)(threadIdx.x + 256u * blockIdx.x) * 2654435761u + (uint32_t)i * 0x9E3779B9u;
+            uint32_t v[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                h ^= h >> 15; h *= 0x2C1B3C6Du; h ^= h >> 12; h *= 0x297A2D39u; h ^= h >> 15;
+                // bfloat16 pairs: sign, exponent 126 or 127 (0x3F00 / 0x3F80 with the mantissa's top bit), 7 mantissa bits
+                v[j] = I8 ? h : ((h & 0x80FF80FFu) | 0x3F003F00u);
+            }
+            a[i] = make_uint4(v[0], v[1], v[2], v[3]);
+            b[i] = make_uint4(v[4], v[5], v[6], v[7]);
+        } else {
+            const uint32_t av = I8 ? 0x01020301u * (threadIdx.x & 3) : 0x3f803f80u;   // small integers / 1.0 in bfloat16
+            const uint32_t bv = I8 ? 0x01010101u : 0x3f803f80u;
+            a[i] = make_uint4(av, av, av, av);
+            b[i] = make_uint4(bv, bv, bv, bv);
+        }
+    }
+    for (int it = 0; it < iters; it += 4) {
+#pragma unroll
+        for (int v = 0; v < 4; v++)
+#pragma unroll
+            for (int u = 0; u < 4; u++) acc[u] = mfma32<I8>(a[(u + v) & 3], b[v], acc[u]);
     }
     float t = 0;
 #pragma unroll
     for (int i = 0; i < 4; i++)
 #pragma unroll
         for (int r = 0; r < 16; r++) t += (float)acc[i][r];
-    if (t == -1.5f) sink[0] = t;          // never true (the sums are non-negative): keeps the loop alive, writes nothing
+    if (t == -1.5f && sink) sink[0] = t;  // never true in practice, and no sink is passed: keeps the loop alive, writes nothing
 }
 
 }  // namespace icv
 
 using namespace icv;
 
-extern "C" int icv_measure_mfma_peak(int32_t dtype, int32_t waves_per_simd, double* ops_per_second, void* stream)
+extern "C" int icv_measure_mfma_peak(int32_t dtype, int32_t waves_per_simd, int32_t varied_operands, double* ops_per_second,
+                                     void* stream)
 {
-    if (!ops_per_second || (dtype != ICV_BF16 && dtype != ICV_U8I8) || waves_per_simd < 1 || waves_per_simd > 4)
+    if (!ops_per_second || (dtype != ICV_BF16 && dtype != ICV_U8I8) || waves_per_simd < 1 || waves_per_simd > 4 ||
+        (varied_operands != 0 && varied_operands != 1))
         return ICV_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
     const int iters = 8000;
@@ -54,8 +80,9 @@ extern "C" int icv_measure_mfma_peak(int32_t dtype, int32_t waves_per_simd, doub
     for (int rep = 0; rep < 4 && st == ICV_OK; rep++) {          // the first launch also warms the clock up
         hipError_t err = hipEventRecord(e0, s);
         if (err == hipSuccess) {
-            if (dtype == ICV_U8I8) hipLaunchKernelGGL(k_mfma_only<true>, dim3(blocks), dim3(256), 0, s, iters, (float*)nullptr);
-            else hipLaunchKernelGGL(k_mfma_only<false>, dim3(blocks), dim3(256), 0, s, iters, (float*)nullptr);
+            auto kern = dtype == ICV_U8I8 ? (varied_operands ? k_mfma_only<true, true> : k_mfma_only<true, false>)
+                                          : (varied_operands ? k_mfma_only<false, true> : k_mfma_only<false, false>);
+            hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), 0, s, iters, (float*)nullptr);
             err = hipGetLastError();
         }
         if (err == hipSuccess) err = hipEventRecord(e1, s);
