@@ -559,6 +559,13 @@ def main():
             # and bytes moved are identical; what changes is the switching activity in the matrix cores, hence the
             # power, hence the clock the device holds.  The gap to the row above is the share of the distance to the
             # peak that is the chip's power limit on this data, not idle cycles in the kernel.
+            # In between: the same tensors after a ReLU (negative values, or codes below the zero point, replaced by
+            # zero) -- what every convolution of the paper's two models but the first one reads.
+            for x in pr.xs:
+                x.clamp_(min=128 if sh.dtype == "u8i8" else 0)
+            mr = pr.time_quantiles(repeats=7, inner=10, warmup=3)[0]
+            big[nm]["relu_activations_diagnostic"] = {"ms": mr, "TFLOPs": f / (mr * 1e-3) / 1e12,
+                                                      "frac_of_mfma_peak": f / (mr * 1e-3) / 1e12 / PEAK[sh.dtype]}
             for x in pr.xs:
                 x.zero_()
             mz = pr.time_quantiles(repeats=7, inner=10, warmup=3)[0]

@@ -972,3 +972,18 @@ def test_runs_on_a_side_stream():
         icv.run(buf, xd)
     st.synchronize()
     assert torch.equal(want, buf.output)
+
+
+@pytest.mark.gpu
+def test_mfma_peak_measurement_is_plausible():
+    """The measured tensor-core ceilings: positive, below the data-sheet peak (a loop cannot beat the hardware), above a
+    tenth of it (every SIMD is multiplying), int8 about twice bf16, and toggling operands never faster than constant
+    ones beyond the run-to-run noise."""
+    for dtype, sheet in (("bf16", 2.5e15), ("u8i8", 5.0e15)):
+        const = icv.measure_mfma_peak(dtype, 2, False)
+        varied = icv.measure_mfma_peak(dtype, 2, True)
+        for r in (const, varied):
+            assert 0.1 * sheet < r < 1.02 * sheet, (dtype, r)
+        assert varied < 1.05 * const, (dtype, const, varied)
+    assert 1.5 < icv.measure_mfma_peak("u8i8", 2) / icv.measure_mfma_peak("bf16", 2) < 2.5
+

@@ -155,6 +155,16 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
         assert lib.icv_conv2d_nhwc_fused(ctypes.byref(p), a, a, a, a, ctypes.byref(bad), a, vp(0)) == icv.ICV_ERR_INVALID_ARG
 
 
+def test_mfma_peak_measurement_rejects_bad_arguments_before_any_launch(lib):
+    v = ctypes.c_double(-1.0)
+    vp = ctypes.c_void_p
+    F32, BF16 = icv.DTYPES["f32"], icv.DTYPES["bf16"]
+    for dtype, waves, varied in ((F32, 2, 0), (BF16, 0, 0), (BF16, 5, 0), (BF16, 2, 2), (BF16, 2, -1), (7, 1, 0)):
+        assert lib.icv_measure_mfma_peak(dtype, waves, varied, ctypes.byref(v), vp(0)) == icv.ICV_ERR_INVALID_ARG
+    assert lib.icv_measure_mfma_peak(BF16, 2, 0, None, vp(0)) == icv.ICV_ERR_INVALID_ARG
+    assert v.value == -1.0
+
+
 def test_status_strings(lib):
     assert icv.status_string(0) == "ok"
     assert "invalid" in icv.status_string(icv.ICV_ERR_INVALID_ARG)
