@@ -244,11 +244,12 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     // whole-batch buffer, a window of two passes that fits LDS, 16-bit pixel numbers per 32-row block, and -- unless
     // forced -- at least one full pass per workgroup and a bf16 filter block of 48 fragments or more: the larger the
     // block, the more LDS traffic the resident filter saves (measured: 6 to 18 % faster than the pixel-range kernel
-    // from 5x5 on 64-byte rows up, level with it or behind below that and for uint8, whose MFMAs take half the time
-    // per byte and leave less to hide the filter load behind).
+    // from 5x5 on 64-byte rows up, level with it or behind below that).  uint8, whose MFMAs take half the time per
+    // byte and leave less to hide the filter load behind, only from 16 row blocks per workgroup on (level with the
+    // pixel-range kernel at the benchmark's batch 32, 6-14 % faster at batch 128-256).
     int freg_wn = 0, freg_mb = 0, freg_ring = 0;
     if (p->dtype != ICV_F32 && !(p->dtype == ICV_U8I8 && p->input_zero_point != 128) && plan_kernel == 0 &&
-        (plan_staging == 3 || (plan_staging == 0 && p->dtype == ICV_BF16)) && !plan_per_image && row_bytes % 32 == 0 &&
+        (plan_staging == 3 || plan_staging == 0) && !plan_per_image && row_bytes % 32 == 0 &&
         stride_bytes % 16 == 0 && freg_shape_supported((int)T, (int)(row_bytes / 32)) &&
         tile_span_bound(p, Hout, Wout, 32) < 65535) {
         const int wn = p->K <= 32 ? 1 : (p->K <= 64 ? 2 : 4);
@@ -264,6 +265,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
             // smaller filter blocks (3x3 on 128-byte rows) only with 64 row blocks or more per workgroup, where the
             // steady state decides (measured: cfg2's shape level at batch 128, 15-18 % faster at batch 256-512)
             if (plan_staging != 3 && T * (row_bytes / 32) < 48 && n_blocks < 64 * ranges) continue;
+            if (plan_staging != 3 && p->dtype == ICV_U8I8 && n_blocks < 16 * ranges) continue;
             freg_wn = wn; freg_mb = mb; freg_ring = (int)ring;
         }
         if (!freg_mb && plan_staging == 3) return ICV_ERR_UNSUPPORTED;

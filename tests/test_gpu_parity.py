@@ -164,6 +164,20 @@ def test_benchmark_shape_with_the_other_kernel_families(name, plan):
     check_against_accumulators(s, buf.output.cpu().numpy(), *oracle_accumulators(s, x, w))
 
 
+@pytest.mark.parametrize("name", ["cfg2_3x3_c64", "cfg3a_3x3_s2", "cfg3b_3x3_d2", "cfg4_int8_3x3"])
+def test_batch_256_launches_on_sampled_images(name):
+    """The steady-state launches bench.py times (the benchmark shapes at batch 256, the library's own choice of kernel,
+    which differs from the one at the benchmark's batch): every output element of the first, the last and two inner
+    images against the oracle run on those images alone -- an image's output depends on no other image."""
+    s = CONFIGS[name].with_(N=256, name=name + "_n256")
+    _say("conv", s.name, icv.plan_name(icv.make_params(s)))
+    x, w = make_tensors(s)
+    buf, xd = run_indirect(s, x, w)
+    one = s.with_(N=1, name=s.name + "_one_image")
+    for n in (0, 97, 200, 255):
+        check_against_oracle(one, buf.output[n:n + 1].cpu().numpy(), x[n:n + 1], w)
+
+
 # ---------------------------------------------------------------- small shapes: several tiles, ragged tails
 def _small_shapes():
     out = []
