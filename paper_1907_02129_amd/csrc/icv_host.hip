@@ -240,32 +240,23 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         // a workgroup keeps two tiles' worth of entries in LDS: 2 * MR*T int32 (plus padding)
         if (mfma_ok && !patch_rows && (int64_t)kTileVariants[variant].MR * T * 4 > 24 * 1024) mfma_ok = false;
     }
-    // Filter in registers, input window in an LDS ring: kernel sizes and row widths the kernel is instantiated for, a
-    // whole-batch buffer, a window of two passes that fits LDS, 16-bit pixel numbers per 32-row block, and -- unless
-    // forced -- at least one full pass per workgroup and a bf16 filter block of 48 fragments or more: the larger the
-    // block, the more LDS traffic the resident filter saves (measured: 6 to 18 % faster than the pixel-range kernel
-    // from 5x5 on 64-byte rows up, level with it or behind below that).  uint8, whose MFMAs take half the time per
-    // byte and leave less to hide the filter load behind, only from 16 row blocks per workgroup on (level with the
-    // pixel-range kernel at the benchmark's batch 32, 6-14 % faster at batch 128-256).
+    // Filter in registers, input window in an LDS ring: wherever the kernel applies -- kernel sizes and row widths it
+    // is instantiated for, a whole-batch buffer, a window of two passes that fits LDS, 16-bit pixel numbers per 32-row
+    // block.  Measured against the pixel-range kernel on grids of 3x3 (64 and 128 bf16 channels, 128 and 256 uint8
+    // channels) and 5x5 problems from one 7x7 image to batch 64 of 56x56, 32 to 256 output channels: 5 to 130 %
+    // faster on all but a handful, which are level (within 3 %).
     int freg_wn = 0, freg_mb = 0, freg_ring = 0;
     if (p->dtype != ICV_F32 && !(p->dtype == ICV_U8I8 && p->input_zero_point != 128) && plan_kernel == 0 &&
         (plan_staging == 3 || plan_staging == 0) && !plan_per_image && row_bytes % 32 == 0 &&
         stride_bytes % 16 == 0 && freg_shape_supported((int)T, (int)(row_bytes / 32)) &&
         tile_span_bound(p, Hout, Wout, 32) < 65535) {
         const int wn = p->K <= 32 ? 1 : (p->K <= 64 ? 2 : 4);
-        const int64_t n_blocks = (M + 31) / 32, n_cg = (p->K + 32 * wn - 1) / (32 * wn);
-        const int64_t ranges = kCusHost / n_cg > 0 ? kCusHost / n_cg : 1;
         for (int mb = 2; mb >= 1 && !freg_mb; --mb) {
             const int pbk = (4 / wn) * mb;
             const int64_t need = tile_span_bound(p, Hout, Wout, 2 * pbk * 32) + 16;     // + what a 1 KB copy overshoots
             int64_t ring = 64;
             while (ring < need) ring *= 2;
             if (ring > (1 << 20) || freg_lds_bytes((int)T, (int)(row_bytes / 32), pbk, (int)ring) > 160 * 1024) continue;
-            if (plan_staging != 3 && n_blocks < ranges * pbk) continue;
-            // smaller filter blocks (3x3 on 128-byte rows) only with 64 row blocks or more per workgroup, where the
-            // steady state decides (measured: cfg2's shape level at batch 128, 15-18 % faster at batch 256-512)
-            if (plan_staging != 3 && T * (row_bytes / 32) < 48 && n_blocks < 64 * ranges) continue;
-            if (plan_staging != 3 && p->dtype == ICV_U8I8 && n_blocks < 16 * ranges) continue;
             freg_wn = wn; freg_mb = mb; freg_ring = (int)ring;
         }
         if (!freg_mb && plan_staging == 3) return ICV_ERR_UNSUPPORTED;

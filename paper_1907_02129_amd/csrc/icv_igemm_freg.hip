@@ -223,8 +223,9 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
     // issues no ring copies (the second pass's window was requested at start-up): the compiler's waits for the filter
     // loads count every vector-memory operation of the wavefront, and a copy from HBM between them would stall the MFMAs.
     constexpr int FD = 10;
-    auto run_pass = [&](int k, auto first) __attribute__((always_inline)) {
+    auto run_pass = [&](int k, auto first, auto blocks_per_wave) __attribute__((always_inline)) {
         constexpr bool FIRST = decltype(first)::value;
+        constexpr int MBE = decltype(blocks_per_wave)::value;      // MB, or 1 for a short last pass (see below)
         // the next pass's window: its copies land while this pass is multiplied (their ring rows and entry slot were
         // last read in the pass before this one, which every wavefront has left); the entries now, the ring copies one
         // at a time between the MFMA steps below, where their address arithmetic costs nothing
@@ -236,14 +237,14 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
         }
 
         const uint8_t* slot = lds + slot_off + (k & 1) * SLOT;
-        const uint16_t* ent = (const uint16_t*)(slot + 1024) + (h * MB) * (T * 32) + lrow;
-        int32_t delta[MB];
+        const uint16_t* ent = (const uint16_t*)(slot + 1024) + (h * MBE) * (T * 32) + lrow;
+        int32_t delta[MBE];
 #pragma unroll
-        for (int i = 0; i < MB; i++) delta[i] = *(const int32_t*)(slot + (h * MB + i) * 16 + 8) - origin;
+        for (int i = 0; i < MBE; i++) delta[i] = *(const int32_t*)(slot + (h * MBE + i) * 16 + 8) - origin;
 
-        acc_t acc[MB][1];
+        acc_t acc[MBE][1];
 #pragma unroll
-        for (int i = 0; i < MB; i++)
+        for (int i = 0; i < MBE; i++)
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[i][0][r] = 0;
 
@@ -253,22 +254,22 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
         // addresses PF + 1 steps before it, the A fragments are read PF steps ahead, and only then come the step's
         // MFMAs.  The scheduling barriers keep the compiler from folding that order back into load-wait-multiply.
         constexpr int PF = 3, LA = 6;
-        uint32_t e16[T][MB], addr[T][MB];                      // few of them are live at any time
-        u32x4_t af[PF + 1][MB];
+        uint32_t e16[T][MBE], addr[T][MBE];                    // few of them are live at any time
+        u32x4_t af[PF + 1][MBE];
         auto read_rows = [&](int j) {
 #pragma unroll
-            for (int i = 0; i < MB; i++) e16[j][i] = ent[(i * T + tap_of[j]) * 32];
+            for (int i = 0; i < MBE; i++) e16[j][i] = ent[(i * T + tap_of[j]) * 32];
         };
         auto locate = [&](int j) {
 #pragma unroll
-            for (int i = 0; i < MB; i++) {
+            for (int i = 0; i < MBE; i++) {
                 const uint32_t row = (e16[j][i] + (uint32_t)delta[i]) & ring_mask;
                 addr[j][i] = (e16[j][i] == 0xFFFFu ? zero_off : __umul24(row, (uint32_t)PITCH)) + (uint32_t)lhalf * 16u;
             }
         };
         auto read_frags = [&](int st) {
 #pragma unroll
-            for (int i = 0; i < MB; i++) af[st % (PF + 1)][i] = *(const u32x4_t*)(lds + addr[st / KS][i] + (st % KS) * 32);
+            for (int i = 0; i < MBE; i++) af[st % (PF + 1)][i] = *(const u32x4_t*)(lds + addr[st / KS][i] + (st % KS) * 32);
         };
         // before the first step: the rows of the kernel elements whose fragments are read within the first PF + 1
         // steps are located here, those read within the first LA + 1 steps have their row numbers requested
@@ -286,7 +287,7 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
                 if (st + FD < NF) load_filter(st + FD);
             }
 #pragma unroll
-            for (int i = 0; i < MB; i++) acc[i][0] = mfma_frag<I8>(af[st % (PF + 1)][i], B[st], acc[i][0]);
+            for (int i = 0; i < MBE; i++) acc[i][0] = mfma_frag<I8>(af[st % (PF + 1)][i], B[st], acc[i][0]);
             // book-keeping behind the MFMAs, where it is free: the kernel element whose fragments the NEXT step starts
             // to read is located now, row numbers are requested LA - PF steps before they are located
             constexpr int jl = (st + 1 + PF) / KS, jr = (st + 1 + LA) / KS;
@@ -300,19 +301,26 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
 
         // my copies for the next pass (issued during this one) and the stores of the pass before this one
         wait_vmcnt<0>();
-        const uint32_t blk = rb_lo + (uint32_t)k * PBK + (uint32_t)(h * MB);
+        const uint32_t blk = rb_lo + (uint32_t)k * PBK + (uint32_t)(h * MBE);
         if (blk < rb_hi) {
             uint32_t m_end = rb_hi * 32u;
             if (m_end > M) m_end = M;
             const int64_t m_base = (int64_t)blk * 32 + 4 * lhalf;
-            const bool whole = (blk + MB) * 32u <= m_end && (int32_t)(cg * WN + c + 1) * 32 <= g.K;
-            store_tile<FUSED, I8, MB, 1>(g.out, acc, (int64_t)m_end, g.K, g.out_stride, m_base, col, whole, g.ep);
+            const bool whole = (blk + MBE) * 32u <= m_end && (int32_t)(cg * WN + c + 1) * 32 <= g.K;
+            store_tile<FUSED, I8, MBE, 1>(g.out, acc, (int64_t)m_end, g.K, g.out_stride, m_base, col, whole, g.ep);
         }
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
     };
-    run_pass(0, std::true_type());
+    // A last pass with no more row blocks than row groups (WM) runs with one block per wavefront, the blocks dealt to
+    // the row groups one each: half the multiplications of a full pass for a range that ends just behind a pass
+    // boundary (3136 row blocks on 256 compute units are 12 for most workgroups and 13 for some).
+    const bool short_tail = MB > 1 && (rb_hi - rb_lo) - (uint32_t)(n_pass - 1) * PBK <= (uint32_t)WM;
+    using full_t = std::integral_constant<int, MB>;
+    using one_t = std::integral_constant<int, 1>;
+    if (n_pass == 1 && short_tail) run_pass(0, std::true_type(), one_t());
+    else run_pass(0, std::true_type(), full_t());
     // The filter registers are final from here on.  Passing them through an empty statement tells the compiler that
     // none of their loads is outstanding any more (the loop below then carries no wait for them) and says where each
     // fragment lives: 4 * NF registers do not fit the 256 vector registers beside everything else, so all but the
@@ -323,7 +331,9 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
         if (f < FV) asm volatile("" : "+v"(B[f]));
         else asm volatile("" : "+a"(B[f]));
     }
-    for (int k = 1; k < n_pass; k++) run_pass(k, std::false_type());
+    const int n_full = short_tail ? n_pass - 1 : n_pass;
+    for (int k = 1; k < n_full; k++) run_pass(k, std::false_type(), full_t());
+    if (short_tail && n_pass > 1) run_pass(n_pass - 1, std::false_type(), one_t());
 }
 
 // ------------------------------------------------------------------ launch
