@@ -376,7 +376,7 @@ static int launch_shape(const Geometry& g, const FregArgs& a, int64_t grid, size
     return ICV_ERR_UNSUPPORTED;
 }
 
-bool freg_shape_supported(int T, int KS) { return (T == 9 && (KS == 4 || KS == 8)) || (T == 25 && KS == 2); }
+bool freg_shape_supported(int T, int KS) { return (T == 9 && (KS == 2 || KS == 4 || KS == 8)) || (T == 25 && KS == 2); }
 
 int launch_igemm_freg(const icv_conv_params* p, const Geometry& g, const void* input, const void* packed,
                       const int32_t* ind, void* out, hipStream_t s)
@@ -424,6 +424,7 @@ int launch_igemm_freg(const icv_conv_params* p, const Geometry& g, const void* i
         return i8 ? launch_shape<true, T_, KS_>(g, a, grid, lds, s) : launch_shape<false, T_, KS_>(g, a, grid, lds, s);
     ICV_FREG_SHAPE(9, 8)
     ICV_FREG_SHAPE(9, 4)
+    ICV_FREG_SHAPE(9, 2)
     ICV_FREG_SHAPE(25, 2)
 #undef ICV_FREG_SHAPE
     return ICV_ERR_UNSUPPORTED;

@@ -421,6 +421,10 @@ def _freg_shapes():
         mk("r_i8_c256", 2, 15, 22, 256, 264, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=317, **q),
         mk("r_i8_c128_s2", 3, 21, 18, 128, 64, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, seed=318, **q),
         mk("r_i8_5x5", 1, 30, 30, 64, 40, 5, 5, PT=2, PL=2, PB=2, PR=2, seed=319, **q),
+        # 3x3 on 64-byte rows (appended: the fused-output test below picks shapes of this list by position)
+        mk("r_c32_k128", 2, 31, 27, 32, 128, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=320),
+        mk("r_c32_k40_s2", 3, 26, 19, 32, 40, 3, 3, SY=2, SX=2, PT=1, PL=1, PB=1, PR=1, seed=321),
+        mk("r_i8_c64", 2, 22, 33, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=322, **q),
     ]
 
 
@@ -453,9 +457,9 @@ def test_filter_in_registers_kernel_matches_oracle(s):
         assert rec[b, 2] == first and rec[b, 0] == first * (stride or s.C) * esz
 
 
-def _random_freg_shapes(n=40):
-    """Random problems of the kinds the filter-in-registers kernel is built for (3x3 on 128- and 256-byte rows, 5x5 on
-    64-byte rows): any stride, dilation and padding, images from one pixel up, batches that end inside blocks."""
+def _random_freg_shapes(n=60):
+    """Random problems of the kinds the filter-in-registers kernel is built for (3x3 on 64-, 128- and 256-byte rows, 5x5
+    on 64-byte rows): any stride, dilation and padding, images from one pixel up, batches that end inside blocks."""
     rng = np.random.default_rng(77)
     out = []
     while len(out) < n:
@@ -464,7 +468,7 @@ def _random_freg_shapes(n=40):
         if kind == 0:
             R, C = 5, 32
         else:
-            R, C = 3, int(rng.choice([64, 128])) * (2 if dtype == "u8i8" else 1)
+            R, C = 3, int(rng.choice([32, 64, 128])) * (2 if dtype == "u8i8" else 1)
         DY, DX = int(rng.integers(1, 4)), int(rng.integers(1, 4))
         SY, SX = int(rng.integers(1, 4)), int(rng.integers(1, 4))
         PT, PL, PB, PR = (int(v) for v in rng.integers(0, 6, size=4))
@@ -497,7 +501,7 @@ def test_filter_in_registers_kernel_on_random_shapes(s):
     assert np.array_equal(got, oracle.indirection(s)) and np.all(tail == -1)
 
 
-@pytest.mark.parametrize("s", [_freg_shapes()[i] for i in (1, 2, 5, 13, 16)], ids=lambda s: s.name)
+@pytest.mark.parametrize("s", [_freg_shapes()[i] for i in (1, 2, 5, 13, 16, 19)], ids=lambda s: s.name)
 @pytest.mark.parametrize("relu,narrow", [(True, True), (False, False), (True, False)], ids=["relu_narrow", "linear_acc", "relu_acc"])
 def test_filter_in_registers_kernel_with_fused_output(s, relu, narrow):
     x, w = make_tensors(s)
