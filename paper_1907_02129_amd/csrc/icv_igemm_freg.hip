@@ -46,6 +46,9 @@ struct FregArgs {
     int32_t stride_bytes;      // bytes between input pixels
     int32_t last_pixel;        // N*Hin*Win - 1
     uint32_t n_blocks;         // row blocks of 32 output pixels
+    uint32_t buf_blocks;       // row blocks the buffer describes: n_blocks, or those of one image (batch-independent buffer)
+    uint32_t img_pixels;       // batch-independent buffer: input pixels per image (its records count from image 0); else 0
+    FastDiv by_buf;            // division by buf_blocks
     uint32_t range_q, range_rem;   // n_blocks / n_ranges and the remainder: the first range_rem ranges get one block more
     int32_t cg_shift;          // log2(n_cg), or -1 when n_cg is not a power of two
     int32_t ranges_per_xcd;    // XCD mode: n_ranges / 8
@@ -179,15 +182,28 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
     auto copy_entries = [&](int k) {
         const uint32_t slot = (uint32_t)__builtin_amdgcn_readfirstlane((int)(lds_base + slot_off + (uint32_t)(k & 1) * SLOT));
         const uint32_t blk0 = rb_lo + (uint32_t)k * PBK;
-        if (wave == 0) {
-            uint32_t blk = blk0 + (uint32_t)lane;
+        // block number in the buffer: a batch-independent buffer holds the blocks of one image, and an image is a
+        // whole number of blocks
+        auto in_buffer = [&](uint32_t blk) {
             if (blk > g.n_blocks - 1) blk = g.n_blocks - 1;
-            if (lane < PBK) copy16_global_to_lds(rec_base, blk * 16u, slot);
+            return g.img_pixels ? blk - fast_div(blk, g.by_buf) * g.buf_blocks : blk;
+        };
+        if (wave == 0) {
+            if (lane < PBK) copy16_global_to_lds(rec_base, in_buffer(blk0 + (uint32_t)lane) * 16u, slot);
         }
 #pragma unroll
         for (int e = 0; e < ECOP; e++)
             if (((e + 1) & 3) == wave) {
-                uint32_t off = blk0 * (uint32_t)(T * 64) + (uint32_t)e * 1024u + (uint32_t)lane * 16u;
+                const uint32_t o = (uint32_t)e * 1024u + (uint32_t)lane * 16u;      // byte of the pass's entries
+                uint32_t off;
+                if (g.img_pixels) {
+                    // the pass's blocks need not follow each other in the buffer (the next image starts over at block 0);
+                    // a block's entries are T * 64 bytes, a multiple of the 16 bytes a lane moves
+                    const uint32_t b = o / (uint32_t)(T * 64);
+                    off = in_buffer(blk0 + b) * (uint32_t)(T * 64) + (o - b * (uint32_t)(T * 64));
+                } else {
+                    off = blk0 * (uint32_t)(T * 64) + o;
+                }
                 if (off > g.ent_bytes - 16u) off = g.ent_bytes - 16u;
                 copy16_global_to_lds(ent_base, off, slot + 1024u + (uint32_t)e * 1024u);
             }
@@ -240,7 +256,15 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
         const uint16_t* ent = (const uint16_t*)(slot + 1024) + (h * MBE) * (T * 32) + lrow;
         int32_t delta[MBE];
 #pragma unroll
-        for (int i = 0; i < MBE; i++) delta[i] = *(const int32_t*)(slot + (h * MBE + i) * 16 + 8) - origin;
+        for (int i = 0; i < MBE; i++) {
+            delta[i] = *(const int32_t*)(slot + (h * MBE + i) * 16 + 8) - origin;
+            if (g.img_pixels) {
+                // the record counts pixels from its image's first one: add the images before it
+                uint32_t b = rb_lo + (uint32_t)k * PBK + (uint32_t)(h * MBE + i);
+                if (b > g.n_blocks - 1) b = g.n_blocks - 1;
+                delta[i] += (int32_t)(fast_div(b, g.by_buf) * g.img_pixels);
+            }
+        }
 
         acc_t acc[MBE][1];
 #pragma unroll
@@ -395,7 +419,11 @@ int launch_igemm_freg(const icv_conv_params* p, const Geometry& g, const void* i
     a.K = p->K; a.out_stride = g.out_stride;
     a.stride_bytes = g.in_stride * g.elem_bytes;
     a.last_pixel = (int32_t)((int64_t)p->N * p->Hin * p->Win - 1);
-    a.n_blocks = (uint32_t)g.img_tiles;
+    a.n_blocks = (uint32_t)g.m_tiles;
+    a.buf_blocks = (uint32_t)g.img_tiles;
+    a.img_pixels = g.per_image ? (uint32_t)((int64_t)p->Hin * p->Win) : 0u;
+    a.by_buf = make_fast_div(a.buf_blocks);
+    if (g.per_image && g.img_rows % 32 != 0) return ICV_ERR_UNSUPPORTED;     // an image must be a whole number of blocks
     a.ent_bytes = (uint32_t)((size_t)g.img_tiles * T * 64);
     a.ring_rows = g.freg_ring;
     a.ep = g.ep;

@@ -630,13 +630,23 @@ PER_IMAGE_SHAPES = [
     ConvShape("b_i8", 3, 15, 15, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=106),
     ConvShape("b_tiny_images", 9, 3, 3, 64, 32, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=107),            # 9 pixels per image
     CONFIGS["cfg3c_5x5_asym"].with_(N=2),                                                           # 12321 = 48 * 256 + 33
+    # images of a whole number of 32-pixel blocks: the filter-in-registers kernel reads the one-image buffer
+    ConvShape("b_regs", 5, 16, 24, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=108),                 # 12 blocks per image
+    ConvShape("b_regs_s2", 3, 32, 32, 128, 130, 3, 3, SY=2, SX=2, PT=1, PL=1, PB=1, PR=1, seed=109),
+    ConvShape("b_regs_5x5", 3, 8, 12, 32, 64, 5, 5, PT=2, PL=2, PB=2, PR=2, seed=110),              # 3 blocks per image
+    ConvShape("b_regs_i8", 3, 16, 16, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=112),
+    ConvShape("b_regs_one_block_images", 9, 4, 8, 64, 32, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=113),  # a pass spans 4 images
+    ConvShape("b_regs_dil", 4, 16, 16, 64, 200, 3, 3, DY=2, DX=2, PT=2, PL=2, PB=2, PR=2, seed=114),
+    CONFIGS["cfg3b_3x3_d2"].with_(N=3),
 ]
 
 
 @pytest.mark.parametrize("s", PER_IMAGE_SHAPES, ids=lambda s: s.name)
 def test_batch_independent_buffer_matches_oracle(s):
     x, w = make_tensors(s)
-    _say("per-image", s.name, icv.plan_name(icv.make_params(s, plan=PER_IMAGE)))
+    name = icv.plan_name(icv.make_params(s, plan=PER_IMAGE))
+    _say("per-image", s.name, name)
+    assert ("freg" in name) == ("regs" in s.name or s.name.startswith("cfg3b"))
     buf, xd = run_indirect(s, x, w, plan=PER_IMAGE)
     check_against_oracle(s, buf.output.cpu().numpy(), x, w)
     # the buffer is that of one image: entry by entry the oracle's entries of batch element 0
@@ -650,17 +660,18 @@ def test_batch_independent_buffer_matches_oracle(s):
 def test_batch_independent_buffer_serves_any_batch_size():
     """Built once, used for batches of 1, 2 and 5 images without touching it (section 2.3: a batch-size increase
     only needs the entries of the new images; here there are none to add)."""
-    base = ConvShape("b_grow", 1, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=111)
-    big = base.with_(N=5)
-    x, w = make_tensors(big)
-    built = icv.prepare(base, icv.to_device(w), plan=PER_IMAGE)
-    for n in (1, 2, 5):
-        s = base.with_(N=n)
-        xs = np.ascontiguousarray(x[:n])
-        other = icv.prepare(s, icv.to_device(w), plan=PER_IMAGE)       # output, packed filter for this batch size
-        icv.conv2d_nhwc(other.p, icv.to_device(xs), other.packed, built.indirection, other.zero_row, other.output)
-        torch.cuda.synchronize()
-        check_against_oracle(s, other.output.cpu().numpy(), xs, w)
+    for base in (ConvShape("b_grow", 1, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=111),
+                 ConvShape("b_grow_regs", 1, 16, 24, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=115)):   # filter in registers
+        big = base.with_(N=5)
+        x, w = make_tensors(big)
+        built = icv.prepare(base, icv.to_device(w), plan=PER_IMAGE)
+        for n in (1, 2, 5):
+            s = base.with_(N=n)
+            xs = np.ascontiguousarray(x[:n])
+            other = icv.prepare(s, icv.to_device(w), plan=PER_IMAGE)       # output, packed filter for this batch size
+            icv.conv2d_nhwc(other.p, icv.to_device(xs), other.packed, built.indirection, other.zero_row, other.output)
+            torch.cuda.synchronize()
+            check_against_oracle(s, other.output.cpu().numpy(), xs, w)
 
 
 # ---------------------------------------------------------------- the paper's model layers
