@@ -77,8 +77,7 @@ typedef struct icv_conv_params {
 #define ICV_PLAN_WINDOW 3       /* tensor cores; the input pixels a row tile names are copied to LDS once and
                                    every kernel element reads them there */
 #define ICV_PLAN_FILTER_REGS 4  /* tensor cores; the filter stays in registers and the input slides through LDS
-                                   (3x3 on 64-, 128- and 256-byte pixel rows, 5x5 on 64-byte ones; with
-                                   ICV_PLAN_PER_IMAGE only when Hout*Wout is a multiple of 32) */
+                                   (3x3 on 64-, 128- and 256-byte pixel rows, 5x5 on 64-byte ones) */
 /* plan, bit 3: batch-independent indirection buffer.  The buffer then holds the entries of ONE image, offsets
  * relative to that image's first pixel, and row tiles never straddle two images; the kernels add
  * n * Hin*Win*pixel stride for image n.  Section 2.3 lists a change of batch size among the events that force the

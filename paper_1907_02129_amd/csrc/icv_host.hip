@@ -241,13 +241,12 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         if (mfma_ok && !patch_rows && (int64_t)kTileVariants[variant].MR * T * 4 > 24 * 1024) mfma_ok = false;
     }
     // Filter in registers, input window in an LDS ring: wherever the kernel applies -- kernel sizes and row widths it
-    // is instantiated for, a window of two passes that fits LDS, 16-bit pixel numbers per 32-row block, and with a
-    // batch-independent buffer images that are a whole number of blocks.  Measured against the pixel-range kernel on grids of 3x3 (64 and 128 bf16 channels, 128 and 256 uint8
+    // is instantiated for, a window of two passes that fits LDS, 16-bit pixel numbers per 32-row block.  Measured against the pixel-range kernel on grids of 3x3 (64 and 128 bf16 channels, 128 and 256 uint8
     // channels) and 5x5 problems from one 7x7 image to batch 64 of 56x56, 32 to 256 output channels: 5 to 130 %
     // faster on all but a handful, which are level (within 3 %).
     int freg_wn = 0, freg_mb = 0, freg_ring = 0;
     if (p->dtype != ICV_F32 && !(p->dtype == ICV_U8I8 && p->input_zero_point != 128) && plan_kernel == 0 &&
-        (plan_staging == 3 || plan_staging == 0) && (!plan_per_image || (Hout * Wout) % 32 == 0) && row_bytes % 32 == 0 &&
+        (plan_staging == 3 || plan_staging == 0) && row_bytes % 32 == 0 &&
         stride_bytes % 16 == 0 && freg_shape_supported((int)T, (int)(row_bytes / 32)) &&
         tile_span_bound(p, Hout, Wout, 32) < 65535) {
         const int wn = p->K <= 32 ? 1 : (p->K <= 64 ? 2 : 4);

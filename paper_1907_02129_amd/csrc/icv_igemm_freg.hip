@@ -48,6 +48,8 @@ struct FregArgs {
     uint32_t n_blocks;         // row blocks of 32 output pixels
     uint32_t buf_blocks;       // row blocks the buffer describes: n_blocks, or those of one image (batch-independent buffer)
     uint32_t img_pixels;       // batch-independent buffer: input pixels per image (its records count from image 0); else 0
+    uint32_t img_rows;         // batch-independent buffer: output pixels per image (an image is buf_blocks blocks, the last
+                               // one partly empty when this is not a multiple of 32); else unused
     FastDiv by_buf;            // division by buf_blocks
     uint32_t range_q, range_rem;   // n_blocks / n_ranges and the remainder: the first range_rem ranges get one block more
     int32_t cg_shift;          // log2(n_cg), or -1 when n_cg is not a power of two
@@ -145,15 +147,28 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
     const uint32_t rb_hi = rb_lo + g.range_q + (range < g.range_rem ? 1u : 0u);
     const int n_pass = (int)((rb_hi - rb_lo + PBK - 1) / PBK);
     const uint32_t M = (uint32_t)g.M;
-    const int32_t origin = lowest_pixel_from(g.q, decompose(g.q, rb_lo * 32u));       // pixel of ring row 0
+    // Output pixels of a row block.  With a whole-batch buffer block b holds pixels 32 b ... 32 b + 31 (the last block
+    // of the batch fewer).  With a batch-independent buffer every image starts a block of its own: block b is block
+    // b % buf_blocks of image b / buf_blocks, and the last block of an image is partly empty unless the image is a
+    // multiple of 32 pixels (its empty rows have zero-row entries and are never stored).
+    auto first_row = [&](uint32_t b) -> uint32_t {
+        if (!g.img_pixels) return b * 32u;
+        const uint32_t n = fast_div(b, g.by_buf);
+        return n * g.img_rows + (b - n * g.buf_blocks) * 32u;
+    };
+    auto end_row = [&](uint32_t b) -> uint32_t {           // one past the last output pixel of block b
+        if (!g.img_pixels) return (b + 1u) * 32u < M ? (b + 1u) * 32u : M;
+        const uint32_t n = fast_div(b, g.by_buf);
+        const uint32_t e = (b - n * g.buf_blocks + 1u) * 32u;
+        return n * g.img_rows + (e < g.img_rows ? e : g.img_rows);
+    };
+    const int32_t origin = lowest_pixel_from(g.q, decompose(g.q, first_row(rb_lo)));   // pixel of ring row 0
 
     // copies that must have been issued before pass k is multiplied: everything up to the highest pixel its rows name
     auto copies_upto_pass = [&](int k) -> uint32_t {
         uint32_t blk_end = rb_lo + (uint32_t)(k + 1) * PBK;
         if (blk_end > rb_hi) blk_end = rb_hi;
-        uint32_t m_end = blk_end * 32u;
-        if (m_end > M) m_end = M;
-        const int32_t top = highest_pixel_upto(g.q, decompose(g.q, m_end - 1u));
+        const int32_t top = highest_pixel_upto(g.q, decompose(g.q, end_row(blk_end - 1u) - 1u));
         const uint32_t pixels = top >= origin ? (uint32_t)(top - origin) + 1u : 1u;
         return (pixels * PP + 63u) / 64u;
     };
@@ -326,12 +341,24 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
         // my copies for the next pass (issued during this one) and the stores of the pass before this one
         wait_vmcnt<0>();
         const uint32_t blk = rb_lo + (uint32_t)k * PBK + (uint32_t)(h * MBE);
-        if (blk < rb_hi) {
+        const bool k_whole = (int32_t)(cg * WN + c + 1) * 32 <= g.K;
+        if (blk < rb_hi && !g.img_pixels) {
             uint32_t m_end = rb_hi * 32u;
             if (m_end > M) m_end = M;
             const int64_t m_base = (int64_t)blk * 32 + 4 * lhalf;
-            const bool whole = (blk + MBE) * 32u <= m_end && (int32_t)(cg * WN + c + 1) * 32 <= g.K;
+            const bool whole = (blk + MBE) * 32u <= m_end && k_whole;
             store_tile<FUSED, I8, MBE, 1>(g.out, acc, (int64_t)m_end, g.K, g.out_stride, m_base, col, whole, g.ep);
+        } else if (blk < rb_hi) {
+            // batch-independent buffer: consecutive blocks need not hold consecutive output pixels
+#pragma unroll
+            for (int i = 0; i < MBE; i++)
+                if (blk + (uint32_t)i < rb_hi) {
+                    const uint32_t m0 = first_row(blk + (uint32_t)i), m1 = end_row(blk + (uint32_t)i);
+                    acc_t one[1][1];
+                    one[0][0] = acc[i][0];
+                    store_tile<FUSED, I8, 1, 1>(g.out, one, (int64_t)m1, g.K, g.out_stride, (int64_t)m0 + 4 * lhalf, col,
+                                                m1 - m0 == 32u && k_whole, g.ep);
+                }
         }
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
@@ -422,8 +449,8 @@ int launch_igemm_freg(const icv_conv_params* p, const Geometry& g, const void* i
     a.n_blocks = (uint32_t)g.m_tiles;
     a.buf_blocks = (uint32_t)g.img_tiles;
     a.img_pixels = g.per_image ? (uint32_t)((int64_t)p->Hin * p->Win) : 0u;
+    a.img_rows = (uint32_t)g.img_rows;
     a.by_buf = make_fast_div(a.buf_blocks);
-    if (g.per_image && g.img_rows % 32 != 0) return ICV_ERR_UNSUPPORTED;     // an image must be a whole number of blocks
     a.ent_bytes = (uint32_t)((size_t)g.img_tiles * T * 64);
     a.ring_rows = g.freg_ring;
     a.ep = g.ep;

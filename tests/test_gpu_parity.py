@@ -630,7 +630,7 @@ PER_IMAGE_SHAPES = [
     ConvShape("b_i8", 3, 15, 15, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=106),
     ConvShape("b_tiny_images", 9, 3, 3, 64, 32, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=107),            # 9 pixels per image
     CONFIGS["cfg3c_5x5_asym"].with_(N=2),                                                           # 12321 = 48 * 256 + 33
-    # images of a whole number of 32-pixel blocks: the filter-in-registers kernel reads the one-image buffer
+    # the filter-in-registers kernel on the one-image buffer: images of a whole number of 32-pixel blocks
     ConvShape("b_regs", 5, 16, 24, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=108),                 # 12 blocks per image
     ConvShape("b_regs_s2", 3, 32, 32, 128, 130, 3, 3, SY=2, SX=2, PT=1, PL=1, PB=1, PR=1, seed=109),
     ConvShape("b_regs_5x5", 3, 8, 12, 32, 64, 5, 5, PT=2, PL=2, PB=2, PR=2, seed=110),              # 3 blocks per image
@@ -646,7 +646,6 @@ def test_batch_independent_buffer_matches_oracle(s):
     x, w = make_tensors(s)
     name = icv.plan_name(icv.make_params(s, plan=PER_IMAGE))
     _say("per-image", s.name, name)
-    assert ("freg" in name) == ("regs" in s.name or s.name.startswith("cfg3b"))
     buf, xd = run_indirect(s, x, w, plan=PER_IMAGE)
     check_against_oracle(s, buf.output.cpu().numpy(), x, w)
     # the buffer is that of one image: entry by entry the oracle's entries of batch element 0
