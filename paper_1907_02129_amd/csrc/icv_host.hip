@@ -58,7 +58,9 @@ int64_t tile_span_bound(const icv_conv_params* p, int64_t Hout, int64_t Wout, in
 static const char* kGenericNames[3] = {"generic_f32", "generic_bf16", "generic_u8i8"};
 static const char* kLowcNames[2] = {"mfma_bf16_lowc_64x64", "mfma_i8_lowc_64x64"};
 // filter in registers: [dtype][column blocks per workgroup 1, 2, 4][row blocks per wavefront and pass 1, 2]
-static const char* kFregNames[2][3][2] = {
+static const char* kFregNames[3][3][2] = {
+    {{"mfma_f32_freg_w1m1", "mfma_f32_freg_w1m2"}, {"mfma_f32_freg_w2m1", "mfma_f32_freg_w2m2"},
+     {"mfma_f32_freg_w4m1", "mfma_f32_freg_w4m2"}},
     {{"mfma_bf16_freg_w1m1", "mfma_bf16_freg_w1m2"}, {"mfma_bf16_freg_w2m1", "mfma_bf16_freg_w2m2"},
      {"mfma_bf16_freg_w4m1", "mfma_bf16_freg_w4m2"}},
     {{"mfma_i8_freg_w1m1", "mfma_i8_freg_w1m2"}, {"mfma_i8_freg_w2m1", "mfma_i8_freg_w2m2"},
@@ -241,11 +243,12 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         if (mfma_ok && !patch_rows && (int64_t)kTileVariants[variant].MR * T * 4 > 24 * 1024) mfma_ok = false;
     }
     // Filter in registers, input window in an LDS ring: wherever the kernel applies -- kernel sizes and row widths it
-    // is instantiated for, a window of two passes that fits LDS, 16-bit pixel numbers per 32-row block.  Measured against the pixel-range kernel on grids of 3x3 (64 and 128 bf16 channels, 128 and 256 uint8
-    // channels) and 5x5 problems from one 7x7 image to batch 64 of 56x56, 32 to 256 output channels: 5 to 130 %
-    // faster on all but a handful, which are level (within 3 %).
+    // is instantiated for, a window of two passes that fits LDS, 16-bit pixel numbers per 32-row block.  Measured
+    // against the pixel-range kernel on grids of 3x3 (64 and 128 bf16 channels, 128 and 256 uint8 channels) and 5x5
+    // problems from one 7x7 image to batch 64 of 56x56, 32 to 256 output channels: 5 to 130 % faster on all but a
+    // handful, which are level (within 3 %).
     int freg_wn = 0, freg_mb = 0, freg_ring = 0;
-    if (p->dtype != ICV_F32 && !(p->dtype == ICV_U8I8 && p->input_zero_point != 128) && plan_kernel == 0 &&
+    if (!(p->dtype == ICV_U8I8 && p->input_zero_point != 128) && plan_kernel == 0 &&
         (plan_staging == 3 || plan_staging == 0) && row_bytes % 32 == 0 &&
         stride_bytes % 16 == 0 && freg_shape_supported((int)T, (int)(row_bytes / 32)) &&
         tile_span_bound(p, Hout, Wout, 32) < 65535) {
@@ -279,7 +282,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
         g->taps_per_stage = 1;
         g->n_stages = g->T;
         g->zero_row_number = 0xFFFFu;
-        g->name = kFregNames[p->dtype == ICV_U8I8 ? 1 : 0][freg_wn == 4 ? 2 : freg_wn - 1][freg_mb - 1];
+        g->name = kFregNames[p->dtype][freg_wn == 4 ? 2 : freg_wn - 1][freg_mb - 1];
     } else if (lowc_ok) {
         g->kind = PLAN_MFMA_LOWC;
         g->variant = -1;

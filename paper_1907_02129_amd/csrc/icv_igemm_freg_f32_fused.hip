@@ -1,0 +1,11 @@
+// Filter-in-registers kernel: the instantiations for ICV_F32 tensors, fused output stage.
+#include "icv_igemm_freg_kernel.h"
+
+namespace icv {
+
+int launch_freg_f32_fused(const Geometry& g, const FregArgs& a, int64_t grid, size_t lds, int T, int KS, hipStream_t s)
+{
+    return launch_freg_instances<ICV_F32, true>(g, a, grid, lds, T, KS, s);
+}
+
+}  // namespace icv

@@ -425,6 +425,11 @@ def _freg_shapes():
         mk("r_c32_k128", 2, 31, 27, 32, 128, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=320),
         mk("r_c32_k40_s2", 3, 26, 19, 32, 40, 3, 3, SY=2, SX=2, PT=1, PL=1, PB=1, PR=1, seed=321),
         mk("r_i8_c64", 2, 22, 33, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=322, **q),
+        # fp32 tensors: 16, 32, 64 channels are 64-, 128-, 256-byte rows
+        mk("r_f32_c64", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="f32", seed=323),
+        mk("r_f32_c32_s2", 3, 26, 19, 32, 40, 3, 3, SY=2, SX=2, PT=1, PL=1, PB=1, PR=1, dtype="f32", seed=324),
+        mk("r_f32_c16_dil", 2, 24, 40, 16, 130, 3, 3, SY=1, SX=2, DY=2, DX=3, PT=2, PL=3, PB=2, PR=3, dtype="f32", seed=325),
+        mk("r_f32_5x5", 2, 33, 35, 16, 64, 5, 5, PT=2, PL=2, PB=1, PR=1, dtype="f32", seed=326),
     ]
 
 
@@ -451,7 +456,7 @@ def test_filter_in_registers_kernel_matches_oracle(s):
     got, tail = layout.logical_indirection(buf.p, buf.indirection, buf.M)
     assert np.array_equal(got, oracle.indirection(s)) and np.all(tail == -1)
     rec, _ = layout.tile_records(buf.p, buf.indirection)
-    esz = 1 if s.dtype == "u8i8" else 2
+    esz = {"u8i8": 1, "bf16": 2, "f32": 4}[s.dtype]
     for b in range(rec.shape[0]):
         first, _last = icv.row_pixel_range(buf.p, 32 * b, min(32 * b + 31, buf.M - 1))
         assert rec[b, 2] == first and rec[b, 0] == first * (stride or s.C) * esz
@@ -463,12 +468,13 @@ def _random_freg_shapes(n=60):
     rng = np.random.default_rng(77)
     out = []
     while len(out) < n:
-        kind = len(out) % 4
-        dtype = "u8i8" if kind == 3 else "bf16"
+        kind = len(out) % 5
+        dtype = "u8i8" if kind == 3 else ("f32" if kind == 4 else "bf16")
+        per_elem = {"u8i8": 2, "bf16": 1, "f32": 0.5}[dtype]       # channels per 2 bytes
         if kind == 0:
             R, C = 5, 32
         else:
-            R, C = 3, int(rng.choice([32, 64, 128])) * (2 if dtype == "u8i8" else 1)
+            R, C = 3, int(int(rng.choice([32, 64, 128])) * per_elem)
         DY, DX = int(rng.integers(1, 4)), int(rng.integers(1, 4))
         SY, SX = int(rng.integers(1, 4)), int(rng.integers(1, 4))
         PT, PL, PB, PR = (int(v) for v in rng.integers(0, 6, size=4))
@@ -501,7 +507,7 @@ def test_filter_in_registers_kernel_on_random_shapes(s):
     assert np.array_equal(got, oracle.indirection(s)) and np.all(tail == -1)
 
 
-@pytest.mark.parametrize("s", [_freg_shapes()[i] for i in (1, 2, 5, 13, 16, 19)], ids=lambda s: s.name)
+@pytest.mark.parametrize("s", [_freg_shapes()[i] for i in (1, 2, 5, 13, 16, 19, 22)], ids=lambda s: s.name)
 @pytest.mark.parametrize("relu,narrow", [(True, True), (False, False), (True, False)], ids=["relu_narrow", "linear_acc", "relu_acc"])
 def test_filter_in_registers_kernel_with_fused_output(s, relu, narrow):
     x, w = make_tensors(s)
@@ -527,9 +533,11 @@ def _f32_mfma_shapes():
 
 
 @pytest.mark.parametrize("s", _f32_mfma_shapes(), ids=lambda s: s.name)
-@pytest.mark.parametrize("tile", [0, hooks.tile(0), hooks.tile(2), hooks.tile(6)], ids=["tile_auto", "128x64", "256x64", "128x128"])
+@pytest.mark.parametrize("tile", [0, icv.PLAN_WINDOW, hooks.tile(0), hooks.tile(2), hooks.tile(6)],
+                         ids=["auto", "window_auto", "128x64", "256x64", "128x128"])
 def test_fp32_tensors_on_the_matrix_cores(s, tile):
-    """fp32 input and filter (section 3.1's precision) through the pixel-range kernel's 32x32x2 fp32 products."""
+    """fp32 input and filter (section 3.1's precision) through 32x32x2 fp32 products: the library's choice (the
+    filter-in-registers kernel where it applies), the pixel-range kernel with its own choice of tile and with each tile."""
     stride = 32 if s.name == "f_stride" else 0
     x, w = make_tensors(s)
     xp = x
@@ -538,8 +546,8 @@ def test_fp32_tensors_on_the_matrix_cores(s, tile):
         xp[..., :s.C] = x
     p = icv.make_params(s, tile, in_pixel_stride=stride)
     name = icv.plan_name(p)
-    if tile and "patch" not in name:
-        # this tile's pixel range does not fit LDS for the shape: rows are gathered per kernel element instead
+    if tile == 0 or (tile != icv.PLAN_WINDOW and "patch" not in name):
+        # (a forced tile whose pixel range does not fit LDS for the shape: rows are gathered per kernel element instead)
         assert name.startswith("mfma_f32"), name
     else:
         assert name.startswith("mfma_f32") and "patch" in name, name
