@@ -37,13 +37,13 @@ FETCH_SCALE, WRITE_SCALE = 1.99975, 1.0
 RECORDED_TRAFFIC = {
     # workload: (kernel, FETCH_SIZE KiB, WRITE_SIZE KiB)
     "cfg1_tiny_f32": ("generic_f32", 52.9, 2.0),
-    "cfg2_3x3_c64": ("mfma_bf16_freg_w2m2", 7675.6, 25095.3),
-    "cfg3a_3x3_s2": ("mfma_bf16_freg_w4m1", 15666.4, 25088.0),
-    "cfg3b_3x3_d2": ("mfma_bf16_freg_w4m2", 10144.9, 32777.5),
-    "cfg3c_5x5_asym": ("mfma_bf16_freg_w2m2", 6274.0, 24654.3),
-    "cfg4_int8_3x3": ("mfma_i8_freg_w4m2", 6008.8, 25090.7),
-    "cfg5a_1x1": ("gemm_bf16_256x64_c4x2_p8", 25305.3, 25109.4),
-    "cfg5b_7x7_s2": ("mfma_bf16_lowc_64x64", 32828.6, 100378.5),
+    "cfg2_3x3_c64": ("mfma_bf16_freg_w2m2", 7713.8, 25090.6),
+    "cfg3a_3x3_s2": ("mfma_bf16_freg_w4m1", 15740.5, 25088.0),
+    "cfg3b_3x3_d2": ("mfma_bf16_freg_w4m2", 10163.9, 32771.9),
+    "cfg3c_5x5_asym": ("mfma_bf16_freg_w2m2", 6317.0, 24648.8),
+    "cfg4_int8_3x3": ("mfma_i8_freg_w4m2", 6027.2, 25089.9),
+    "cfg5a_1x1": ("gemm_bf16_256x64_c4x2_p8", 25305.5, 25101.9),
+    "cfg5b_7x7_s2": ("mfma_bf16_lowc_64x64", 32829.0, 100363.7),
 }
 TRAFFIC_SOURCE = "recorded constant from profiles/igemm_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE), not measured in this run"
 ALU_PEAK_F32 = 157.3          # TFLOP/s, fp32 vector ALUs: 256 CUs x 4 SIMDs x 32 lanes x 2 (FMA) x 2.4 GHz
