@@ -516,6 +516,9 @@ def test_filter_in_registers_kernel_with_fused_output(s, relu, narrow):
     else:
         acc, mag = oracle.conv2d_abs(s, x, w)
     run_fused_case(s, x, w, acc, mag, relu, narrow, plan=FREG, out_pixel_stride=s.K + 8 if narrow else 0)
+    if relu and narrow:
+        # the same with the batch-independent buffer (images that end inside a block store through the guarded path)
+        run_fused_case(s, x, w, acc, mag, relu, narrow, plan=FREG | icv.PLAN_PER_IMAGE, out_pixel_stride=s.K + 8)
 
 
 # ---------------------------------------------------------------- fp32 tensors on the matrix cores
@@ -646,6 +649,7 @@ PER_IMAGE_SHAPES = [
     ConvShape("b_regs_one_block_images", 9, 4, 8, 64, 32, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=113),  # a pass spans 4 images
     ConvShape("b_regs_dil", 4, 16, 16, 64, 200, 3, 3, DY=2, DX=2, PT=2, PL=2, PB=2, PR=2, seed=114),
     CONFIGS["cfg3b_3x3_d2"].with_(N=3),
+    ConvShape("b_regs_f32", 3, 19, 23, 32, 72, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="f32", seed=116),   # 437 pixels per image
 ]
 
 
