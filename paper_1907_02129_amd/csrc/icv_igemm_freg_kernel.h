@@ -249,6 +249,16 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
     const u32x4_t* const wp = (const u32x4_t*)(g.w + ((size_t)(cg * WN + c) * NF) * 1024) + lane;
     auto load_filter = [&](int f) { B[f] = wp[(tap_of[f / KS] * KS + f % KS) * 64]; };
     for (int i = tid; i < PITCH / 4; i += 256) *(uint32_t*)(lds + zero_off + i * 4) = I8 ? 0x80808080u : 0u;
+    // Fused output stage: a lane's output channel is the same in every pass, so its bias is read once, here, where the
+    // start-up wait covers the load (read at the stores it would cost every pass a trip to L2), and added to the
+    // accumulators before they are handed to the output stage, which then gets no bias pointer.
+    using out_acc_t = typename std::conditional<I8, int32_t, float>::type;
+    out_acc_t lane_bias = 0;
+    EpilogueArgs ep = g.ep;
+    if constexpr (FUSED) {
+        lane_bias = output_bias<out_acc_t>(g.ep, (int32_t)(cg * WN + c) * 32 + lrow, g.K);
+        ep.bias = nullptr;
+    }
     if (n_pass > 2) upto_next = copies_upto_pass(2);
     wait_vmcnt<0>();
     __syncthreads();
@@ -348,12 +358,18 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
         wait_vmcnt<0>();
         const uint32_t blk = rb_lo + (uint32_t)k * PBK + (uint32_t)(h * MBE);
         const bool k_whole = (int32_t)(cg * WN + c + 1) * 32 <= g.K;
+        if constexpr (FUSED) {
+#pragma unroll
+            for (int i = 0; i < MBE; i++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) acc[i][0][r] += lane_bias;
+        }
         if (blk < rb_hi && !g.img_pixels) {
             uint32_t m_end = rb_hi * 32u;
             if (m_end > M) m_end = M;
             const int64_t m_base = (int64_t)blk * 32 + 4 * lhalf;
             const bool whole = (blk + MBE) * 32u <= m_end && k_whole;
-            store_tile<FUSED, I8, MBE, 1>(g.out, acc, (int64_t)m_end, g.K, g.out_stride, m_base, col, whole, g.ep);
+            store_tile<FUSED, I8, MBE, 1>(g.out, acc, (int64_t)m_end, g.K, g.out_stride, m_base, col, whole, ep);
         } else if (blk < rb_hi) {
             // batch-independent buffer: consecutive blocks need not hold consecutive output pixels
 #pragma unroll
@@ -363,7 +379,7 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
                     acc_t one[1][1];
                     one[0][0] = acc[i][0];
                     store_tile<FUSED, I8, 1, 1>(g.out, one, (int64_t)m1, g.K, g.out_stride, (int64_t)m0 + 4 * lhalf, col,
-                                                m1 - m0 == 32u && k_whole, g.ep);
+                                                m1 - m0 == 32u && k_whole, ep);
                 }
         }
         asm volatile("" ::: "memory");
