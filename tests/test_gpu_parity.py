@@ -650,6 +650,7 @@ PER_IMAGE_SHAPES = [
     ConvShape("b_regs_dil", 4, 16, 16, 64, 200, 3, 3, DY=2, DX=2, PT=2, PL=2, PB=2, PR=2, seed=114),
     CONFIGS["cfg3b_3x3_d2"].with_(N=3),
     ConvShape("b_regs_f32", 3, 19, 23, 32, 72, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="f32", seed=116),   # 437 pixels per image
+    ConvShape("b_window_c256", 3, 19, 23, 256, 72, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=117),            # pixel-range kernel
 ]
 
 
@@ -762,7 +763,8 @@ def test_one_zero_row_shared_by_operators_of_different_width():
 
 # ---------------------------------------------------------------- launches captured into a HIP graph
 @pytest.mark.parametrize("s", [
-    ConvShape("h_patch", 3, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=121),
+    ConvShape("h_regs", 3, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=121),
+    ConvShape("h_patch", 3, 19, 23, 256, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=126),
     ConvShape("h_gather", 2, 13, 17, 96, 40, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, seed=122),
     ConvShape("h_lowc", 2, 30, 26, 4, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=123),
     ConvShape("h_gemm", 2, 21, 13, 256, 64, 1, 1, seed=124),
@@ -776,6 +778,7 @@ def test_graph_replays_match_eager(s):
     check_against_oracle(s, buf.output.cpu().numpy(), x, w)
     eager = buf.output.clone()
     _say("graph", s.name, icv.plan_name(buf.p))
+    assert ("freg" in icv.plan_name(buf.p)) == (s.name in ("h_regs", "h_i8")) and ("patch" in icv.plan_name(buf.p)) == (s.name == "h_patch")
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
@@ -800,7 +803,7 @@ def _bf16_bits_to_f64(a: np.ndarray) -> np.ndarray:
 
 FUSED_SHAPES = [
     CONFIGS["cfg1_tiny_f32"],                                                                     # vector-ALU kernel
-    ConvShape("f_patch", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=91),               # pixel-range kernel
+    ConvShape("f_patch", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=91),               # filter in registers, then the pixel-range kernel
     ConvShape("f_gather", 2, 13, 17, 96, 40, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, seed=92),  # per-element gather
     ConvShape("f_gemm", 3, 7, 11, 128, 72, 1, 1, seed=93),                                        # GEMM on the input
     ConvShape("f_lowc", 2, 30, 26, 4, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=94),     # short rows
@@ -873,6 +876,10 @@ def test_fused_output_stage_matches_oracle(s, relu, narrow):
     else:
         acc, mag = oracle.conv2d_abs(s, x, w)
     run_fused_case(s, x, w, acc, mag, relu, narrow)
+    # where the library's choice is the filter-in-registers kernel, the pixel-range kernel's fused stage as well
+    window = icv.plan_name(icv.make_params(s, plan=icv.PLAN_WINDOW))
+    if window and window != icv.plan_name(icv.make_params(s)):
+        run_fused_case(s, x, w, acc, mag, relu, narrow, plan=icv.PLAN_WINDOW)
 
 
 @pytest.mark.parametrize("name", [n for n in CONFIGS if n != "cfg1_tiny_f32"])
