@@ -62,7 +62,9 @@ typedef struct icv_conv_params {
     int32_t in_pixel_stride;   /* elements between input pixels;  0 means C (section 2.3: input rows may be strided) */
     int32_t out_pixel_stride;  /* elements between output pixels; 0 means K (ldc of Listing 3)                 */
     int32_t dtype;             /* icv_dtype */
-    int32_t input_zero_point;  /* ICV_U8I8 only: the value the zero row holds, 0..255 */
+    int32_t input_zero_point;  /* ICV_U8I8 only: the value the zero row holds, 0..255.  Any value runs on the tensor
+                                  cores: they multiply (x - 128) * w, and the kernels add (128 - zero point) times
+                                  the output channel's filter sum, which icv_pack_filter computes once */
     int32_t plan;              /* 0: the library chooses.  Else one ICV_PLAN_* algorithm (bits 0-2), optionally or-ed
                                   with ICV_PLAN_PER_IMAGE; all other bits must be 0.  All set-up calls and the conv
                                   call of one problem must use the same value. */
@@ -98,7 +100,8 @@ ICV_API int icv_output_size(const icv_conv_params* p, int32_t* Hout, int32_t* Wo
  *                 tile's input pixels in LDS, and the kernel for very short pixel rows -- a 16-byte record per
  *                 row tile followed by uint16 pixel numbers counted from the tile's base; only the form the plan's
  *                 kernel reads is built.  icv_get_indirection_layout describes it.
- *  packed filter: the [K][R][S][C] filter re-laid as the tiles the GEMM kernel reads, K padded to the tile
+ *  packed filter: the [K][R][S][C] filter re-laid as the tiles the GEMM kernel reads, K padded to the tile; for
+ *                 ICV_U8I8 on the tensor cores followed by K int32 filter sums (the zero-point term, below)
  *  zero row     : C elements (section 2.3's explicit zero vector), rounded up to 16 bytes
  *  im2col       : the [M][R*S*C] patch matrix of the ablation path
  */

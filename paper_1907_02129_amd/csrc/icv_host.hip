@@ -26,6 +26,13 @@ static int64_t out_extent(int64_t in, int64_t lo, int64_t hi, int64_t dil, int64
     return span < 0 ? 0 : span / stride + 1;
 }
 
+// bytes of the packed filter proper (the uint8 tensor-core plans append the filter sums, Geometry::wsum_offset)
+static size_t packed_filter_base_bytes(const icv_conv_params* p, const Geometry& g)
+{
+    if (g.kind == PLAN_MFMA_LOWC) return (size_t)g.n_tiles * g.NR * g.KCB;
+    return (size_t)g.n_tiles * g.NR * g.T * p->C * g.elem_bytes;
+}
+
 int64_t tile_span_bound(const icv_conv_params* p, int64_t Hout, int64_t Wout, int64_t rows)
 {
     // Pixel index of entry (m, tap) before clipping: q(m) + ky*DY*Win + kx*DX with
@@ -86,7 +93,6 @@ static const char* kMfmaNames[3][7] = {
     {"mfma_f32_128x64_c2x2_p4", "mfma_f32_128x128_c2x2_p4", "", "mfma_f32_256x64_c4x2_p8", "mfma_f32_64x64_c2x2_p4", "", ""},
 };
 
-static const int64_t kCusHost = 256;      // compute units the plan is chosen for (the launchers ask the device)
 
 int make_geometry(const icv_conv_params* p, Geometry* g)
 {
@@ -138,6 +144,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     g->group = plan_group;
     g->gemm_on_input = 0;
     g->ep.bias = nullptr; g->ep.scale = 1.0f; g->ep.relu = 0; g->ep.out_kind = ICV_OUT_ACC; g->ep.out_zero_point = 0;
+    g->ep.wsum = nullptr; g->ep.zp_shift = 0;
     g->ep_plain = true;
 
     // ---- plan: which kernel, which tile
@@ -147,7 +154,6 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     // tiles) and the gathering kernel / plain GEMM
     const bool f32 = p->dtype == ICV_F32;
     bool mfma_ok = row_bytes % 64 == 0 && stride_bytes % 16 == 0;
-    if (p->dtype == ICV_U8I8 && p->input_zero_point != 128) mfma_ok = false;   // x ^ 0x80 == x - 128 only
     if (plan_kernel == 1) mfma_ok = false;                                      // forced vector-ALU kernel
     int variant = -1;
     int patch_rows = 0, patch_kcb = 0;
@@ -248,8 +254,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     // problems from one 7x7 image to batch 64 of 56x56, 32 to 256 output channels: 5 to 130 % faster on all but a
     // handful, which are level (within 3 %).
     int freg_wn = 0, freg_mb = 0, freg_ring = 0;
-    if (!(p->dtype == ICV_U8I8 && p->input_zero_point != 128) && plan_kernel == 0 &&
-        (plan_staging == 3 || plan_staging == 0) && row_bytes % 32 == 0 &&
+    if (plan_kernel == 0 && (plan_staging == 3 || plan_staging == 0) && row_bytes % 32 == 0 &&
         stride_bytes % 16 == 0 && freg_shape_supported((int)T, (int)(row_bytes / 32)) &&
         tile_span_bound(p, Hout, Wout, 32) < 65535) {
         const int wn = p->K <= 32 ? 1 : (p->K <= 64 ? 2 : 4);
@@ -268,7 +273,7 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     // very short rows (first-layer convolutions): the whole reduction of a tile is gathered at once
     const bool lowc_ok = p->dtype != ICV_F32 && plan_kernel == 0 &&
                          (row_bytes == 8 || row_bytes == 16 || row_bytes == 32) && stride_bytes % row_bytes == 0 &&
-                         T * row_bytes <= 608 && !(p->dtype == ICV_U8I8 && p->input_zero_point != 128);
+                         T * row_bytes <= 608;
     g->freg_wn = freg_wn; g->freg_mb = freg_mb; g->freg_ring = freg_ring;
     if (freg_mb) {
         g->kind = PLAN_MFMA_FREG;
@@ -349,6 +354,8 @@ int make_geometry(const icv_conv_params* p, Geometry* g)
     g->image_bytes = g->per_image ? (int64_t)p->Hin * p->Win * stride_bytes : 0;
     g->m_tiles = g->per_image ? g->img_tiles * p->N : g->img_tiles;
     g->n_tiles = (p->K + g->NR - 1) / g->NR;
+    // uint8 on the tensor cores: the filter sums of the zero-point term (EpilogueArgs) follow the packed filter
+    g->wsum_offset = p->dtype == ICV_U8I8 && g->kind != PLAN_GENERIC ? (int64_t)((packed_filter_base_bytes(p, *g) + 15) / 16 * 16) : -1;
     return ICV_OK;
 }
 
@@ -426,8 +433,8 @@ size_t icv_packed_filter_bytes(const icv_conv_params* p)
 {
     Geometry g;
     if (make_geometry(p, &g) != ICV_OK) return 0;
-    if (g.kind == PLAN_MFMA_LOWC) return (size_t)g.n_tiles * g.NR * g.KCB;
-    return (size_t)g.n_tiles * g.NR * g.T * p->C * g.elem_bytes;
+    if (g.wsum_offset >= 0) return (size_t)g.wsum_offset + ((size_t)p->K * 4 + 15) / 16 * 16;
+    return packed_filter_base_bytes(p, g);
 }
 
 size_t icv_zero_row_bytes(const icv_conv_params* p)
@@ -522,9 +529,15 @@ int icv_setup_indirection(const icv_conv_params* p, void* indirection, void* str
     return launch_build_indirection(p, g, (int32_t*)indirection, (hipStream_t)stream);
 }
 
-static int conv_common(const icv_conv_params* p, const Geometry& g, const void* a, const void* packed,
+static int conv_common(const icv_conv_params* p, Geometry g, const void* a, const void* packed,
                        const int32_t* ind, const void* zero_row, void* out, bool a_direct, hipStream_t s)
 {
+    if (g.wsum_offset >= 0 && p->input_zero_point != 128) {
+        // zero point other than 128: the output stage adds (128 - zp) * (the channel's filter sum)
+        g.ep.wsum = (const int32_t*)((const uint8_t*)packed + g.wsum_offset);
+        g.ep.zp_shift = 128 - p->input_zero_point;
+        g.ep_plain = false;
+    }
     if (g.kind == PLAN_MFMA_FREG) return a_direct ? ICV_ERR_UNSUPPORTED : launch_igemm_freg(p, g, a, packed, ind, out, s);
     if (g.kind == PLAN_MFMA && g.patch_rows && !a_direct) return launch_igemm_patch(p, g, a, packed, ind, out, s);
     if (g.kind == PLAN_MFMA)

@@ -48,6 +48,7 @@ int launch_igemm_freg(const icv_conv_params* p, const Geometry& g, const void* i
     a.ent_bytes = (uint32_t)((size_t)g.img_tiles * T * 64);
     a.ring_rows = g.freg_ring;
     a.ep = g.ep;
+    a.zero_fill = p->dtype == ICV_U8I8 ? 0x01010101u * (uint32_t)p->input_zero_point : 0u;
     const int WN = g.freg_wn, PBK = (4 / WN) * g.freg_mb;
     a.n_cg = (int32_t)g.n_tiles;
     // One workgroup per compute unit; the column groups share them.  A row range is at least one block.

@@ -60,6 +60,7 @@ struct FregArgs {
     int32_t n_ranges;          // row ranges: workgroups per column group
     int32_t xcd_mode;          // 1: XCD x (workgroups x, x + 8, ...) owns a contiguous run of row ranges, all column groups
     int32_t ring_rows;         // pixel rows of the ring, a power of two and a multiple of 64
+    uint32_t zero_fill;        // four bytes of the zero row: zeros, or the zero point of uint8 activations
     EpilogueArgs ep;
 };
 
@@ -248,7 +249,7 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
     u32x4_t B[NF];
     const u32x4_t* const wp = (const u32x4_t*)(g.w + ((size_t)(cg * WN + c) * NF) * 1024) + lane;
     auto load_filter = [&](int f) { B[f] = wp[(tap_of[f / KS] * KS + f % KS) * 64]; };
-    for (int i = tid; i < PITCH / 4; i += 256) *(uint32_t*)(lds + zero_off + i * 4) = I8 ? 0x80808080u : 0u;
+    for (int i = tid; i < PITCH / 4; i += 256) *(uint32_t*)(lds + zero_off + i * 4) = g.zero_fill;
     // Fused output stage: a lane's output channel is the same in every pass, so its bias is read once, here, where the
     // start-up wait covers the load (read at the stores it would cost every pass a trip to L2), and added to the
     // accumulators before they are handed to the output stage, which then gets no bias pointer.
@@ -258,6 +259,7 @@ __global__ __launch_bounds__(256) void k_igemm_freg(FregArgs g)
     if constexpr (FUSED) {
         lane_bias = output_bias<out_acc_t>(g.ep, (int32_t)(cg * WN + c) * 32 + lrow, g.K);
         ep.bias = nullptr;
+        ep.wsum = nullptr;         // (the zero-point term is part of lane_bias)
     }
     if (n_pass > 2) upto_next = copies_upto_pass(2);
     wait_vmcnt<0>();

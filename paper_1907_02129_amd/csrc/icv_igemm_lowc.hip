@@ -37,6 +37,7 @@ struct LowcArgs {
     int32_t col_blocks;     // 32-column blocks per workgroup (blockIdx.y selects the group)
     int32_t k_rows;         // rows of the packed filter (K padded to 64)
     int32_t direct;         // 1: `a` is the dense patch matrix [rows][KP] of the ablation path
+    uint32_t zero_fill;     // four bytes of the zero row: zeros, or the zero point of uint8 activations
     EpilogueArgs ep;
 };
 
@@ -205,11 +206,11 @@ __global__ __launch_bounds__(256 * TEAMS) void k_igemm_lowc(LowcArgs g)
         // and by the latency of its two dependent global loads (entries, then the rows they name), so this path
         // keeps both short: the wavefront's kernel elements tap0, tap0 + 4, ... are wavefront-uniform (scalar
         // branches and addresses), a row is loaded from base + 32-bit offset whether its entry is valid or not and
-        // replaced by the zero pattern afterwards (what the zero row holds: zeros, or the zero point 128 for uint8).
+        // replaced by the zero pattern afterwards (what the zero row holds: zeros, or the zero point for uint8).
         const int tap0 = __builtin_amdgcn_readfirstlane(tid >> 6);
         const int nb = (n_taps - tap0 + 3) / 4;                    // kernel elements of this wavefront, <= NB
         const uint32_t stride = (uint32_t)g.stride_bytes;
-        const uint32_t zfill = I8 ? 0x80808080u : 0u;
+        const uint32_t zfill = g.zero_fill;
         // entries (16-bit) and the byte offset they count from
         auto load_rows16 = [&](int64_t mt, uint32_t (&r)[NB], int32_t& first) __attribute__((always_inline)) {
             const uint32_t bt = per_image ? (uint32_t)mt % g.img_tiles : (uint32_t)mt;                   // tile of the buffer
@@ -325,6 +326,7 @@ int launch_igemm_lowc(const icv_conv_params* p, const Geometry& g, const void* i
     a.KP = g.KCB;
     a.direct = a_direct ? 1 : 0;
     a.ep = g.ep;
+    a.zero_fill = p->dtype == ICV_U8I8 ? 0x01010101u * (uint32_t)p->input_zero_point : 0u;
     a.stride_bytes = g.in_stride * g.elem_bytes;
     // the compact entries (range records, then 16-bit pixel numbers) follow the int32 entries in the buffer
     a.ranges = nullptr; a.rows = nullptr;

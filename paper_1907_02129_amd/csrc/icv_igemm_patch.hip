@@ -52,6 +52,7 @@ struct PatchArgs {
                                //    loaded between patches (for two workgroups per compute unit, which cover
                                //    each other's load bubbles)
     int32_t xcd_mode;
+    uint32_t zero_fill;        // four bytes of the zero row: zeros, or the zero point of uint8 activations
     EpilogueArgs ep;           // output stage (read by the FUSED instantiations only)
 };
 
@@ -277,9 +278,9 @@ __global__ __launch_bounds__(64 * (WM * WN + NP)) void k_igemm_patch(PatchArgs g
         const int bswz = (lrow / P) % Q;
         const uint32_t b_frag_base = (wn * NRW + lrow) * KCB;
 
-        // the zero row of both patch buffers (bytes that multiply as zero: 0x80 for centred uint8)
+        // the zero row of both patch buffers (zeros, or the zero point of uint8 activations)
         {
-            const uint32_t zv = I8 ? 0x80808080u : 0u;
+            const uint32_t zv = g.zero_fill;
             for (int i = tid; i < g.nbuf * 256; i += 64 * NC)
                 *(uint32_t*)(lds + patch_base + (i >> 8) * pbytes + zoff + (i & 255) * 4) = zv;
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -508,6 +509,7 @@ int launch_igemm_patch(const icv_conv_params* p, const Geometry& g, const void* 
     a.K = p->K; a.T = g.T; a.NCC = g.stages_per_tap; a.out_stride = g.out_stride;
     a.n_tiles = (int32_t)g.n_tiles;
     a.ep = g.ep;
+    a.zero_fill = p->dtype == ICV_U8I8 ? 0x01010101u * (uint32_t)p->input_zero_point : 0u;
     a.ring = 0; a.G = 1; a.ent_copies = 0; a.cap_units = 0; a.a_share = 0; a.e_share = 0; a.nbuf = 2; a.xcd_mode = 0;
     if (p->dtype == ICV_F32) return launch_dtype<ICV_F32>(g, a, s);
     return p->dtype == ICV_U8I8 ? launch_dtype<ICV_U8I8>(g, a, s) : launch_dtype<ICV_BF16>(g, a, s);

@@ -23,6 +23,13 @@ struct EpilogueArgs {
     int32_t relu;              // 0 / 1
     int32_t out_kind;          // ICV_OUT_ACC / ICV_OUT_BF16 / ICV_OUT_U8
     int32_t out_zero_point;
+    // uint8 activations with a zero point other than 128: the tensor-core kernels multiply (x - 128) * w (one XOR turns
+    // a uint8 into that signed byte), and sum (x - zp) * w = sum (x - 128) * w + (128 - zp) * sum w, so the output
+    // stage adds zp_shift * wsum[channel]: wsum holds each output channel's filter sum (icv_pack_filter writes it
+    // behind the packed filter), zp_shift = 128 - zp.  Padding reads the zero row, which holds zp, and so contributes
+    // (zp - 128) * w + (128 - zp) * w = 0.  Null / 0 otherwise.
+    const int32_t* wsum;
+    int32_t zp_shift;
 };
 
 // One output element through the output stage; `v` already includes the channel's bias (the caller reads it once
@@ -53,7 +60,9 @@ __device__ inline void emit_output(void* out, int64_t idx, int32_t v, const Epil
 template <typename T>
 __device__ inline T output_bias(const EpilogueArgs& e, int32_t col, int32_t K)
 {
-    return e.bias && col < K ? ((const T*)e.bias)[col] : (T)0;
+    T b = e.bias && col < K ? ((const T*)e.bias)[col] : (T)0;
+    if (e.wsum && col < K) b += (T)(e.zp_shift * e.wsum[col]);
+    return b;
 }
 
 // Geometry derived once per call from icv_conv_params (host side).
@@ -91,6 +100,7 @@ struct Geometry {
     const char* name;
     EpilogueArgs ep;         // output stage of this call (plain: no bias, no ReLU, accumulator type)
     bool ep_plain;
+    int64_t wsum_offset;  // uint8 tensor-core plans: byte offset of the K filter sums in the packed-filter buffer, else -1
 };
 
 // Upper bound on the number of consecutive input pixels spanned by the valid indirection entries of any

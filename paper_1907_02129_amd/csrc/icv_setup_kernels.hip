@@ -98,9 +98,28 @@ __global__ void k_pack_filter_frag(const uint8_t* src, uint8_t* dst, int K, int 
     *(uint4*)(dst + v * 16) = val;
 }
 
+// uint8 tensor-core plans: sums[k] = sum over the R*S*C filter elements of output channel k (the zero-point term of
+// EpilogueArgs).  One wavefront per channel.
+__global__ __launch_bounds__(256) void k_filter_channel_sums(const int8_t* filt_krsc, int32_t* sums, int K, int64_t per_channel)
+{
+    const int k = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (k >= K) return;
+    const int8_t* w = filt_krsc + (int64_t)k * per_channel;
+    int32_t acc = 0;
+    for (int64_t i = lane; i < per_channel; i += 64) acc += (int32_t)w[i];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+    if (lane == 0) sums[k] = acc;
+}
+
 int launch_pack_filter(const icv_conv_params* p, const Geometry& g, const void* filt, void* packed, hipStream_t s)
 {
     const int64_t CB = (int64_t)p->C * g.elem_bytes;
+    if (g.wsum_offset >= 0) {
+        hipLaunchKernelGGL(k_filter_channel_sums, dim3((unsigned)((p->K + 3) / 4)), dim3(256), 0, s, (const int8_t*)filt,
+                           (int32_t*)((uint8_t*)packed + g.wsum_offset), p->K, (int64_t)g.T * p->C);
+        ICV_HIP_CHECK(hipGetLastError());
+    }
     if (g.kind == PLAN_MFMA_FREG) {
         const int KS = g.KCB / 32;
         const int64_t col_blocks = g.n_tiles * (g.NR / 32);

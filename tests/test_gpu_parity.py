@@ -191,13 +191,13 @@ def _small_shapes():
     out.append(ConvShape("s_bf16_all_padding_rows", 1, 2, 2, 32, 16, 3, 3, DY=2, DX=2, PT=4, PL=4, PB=4, PR=4, seed=27))
     # int8
     out.append(ConvShape("s_i8_c64_k96", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=31))
-    out.append(ConvShape("s_i8_c192_k200", 1, 17, 9, 192, 200, 3, 3, DY=2, DX=2, PT=2, PL=2, PB=2, PR=2, dtype="u8i8", zero_point=128, seed=32))
+    out.append(ConvShape("s_i8_c192_k200", 1, 17, 9, 192, 200, 3, 3, DY=2, DX=2, PT=2, PL=2, PB=2, PR=2, dtype="u8i8", zero_point=9, seed=32))
     out.append(ConvShape("s_i8_c128_s2", 3, 14, 14, 128, 64, 5, 3, SY=2, SX=2, PT=2, PL=1, PB=2, PR=1, dtype="u8i8", zero_point=128, seed=33))
     # short pixel rows (8, 16, 32 bytes): the flattened-reduction tensor-core kernel
     out.append(ConvShape("s_bf16_c4_7x7", 2, 30, 26, 4, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=34))
     out.append(ConvShape("s_bf16_c8_3x3", 3, 13, 17, 8, 40, 3, 3, DY=2, DX=1, PT=2, PL=1, PB=2, PR=1, seed=35))
     out.append(ConvShape("s_bf16_c16_5x5", 1, 21, 9, 16, 64, 5, 5, SY=1, SX=2, PT=2, PL=2, PB=2, PR=2, seed=36))
-    out.append(ConvShape("s_i8_c8_5x5", 2, 11, 23, 8, 33, 5, 5, PT=2, PL=2, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=37))
+    out.append(ConvShape("s_i8_c8_5x5", 2, 11, 23, 8, 33, 5, 5, PT=2, PL=2, PB=1, PR=1, dtype="u8i8", zero_point=131, seed=37))
     out.append(ConvShape("s_i8_c32_3x3", 1, 16, 16, 32, 64, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=38))
     # ... with more filters than one workgroup keeps in LDS (several column groups, the last one narrower), and a
     # filter count that leaves a whole 32-column block of the 64-padded packed filter unused
@@ -205,7 +205,7 @@ def _small_shapes():
     out.append(ConvShape("s_i8_c8_5x5_k300", 1, 11, 23, 8, 300, 5, 5, PT=2, PL=2, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=40))
     out.append(ConvShape("s_bf16_c16_3x3_k96", 2, 13, 9, 16, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=45))
     out.append(ConvShape("s_bf16_c16_1x1_k33", 2, 13, 9, 16, 33, 1, 1, seed=46))
-    # vector-ALU fallback: odd channel counts, fp32, other zero points
+    # vector-ALU fallback: odd channel counts; and a zero point other than 128 (tensor cores: the filter-sum term)
     out.append(ConvShape("s_f32_odd", 2, 9, 10, 5, 7, 3, 3, SY=2, SX=1, PT=1, PL=2, PB=0, PR=1, dtype="f32", dist="uniform", seed=41))
     out.append(ConvShape("s_bf16_c3", 1, 12, 12, 3, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=42))
     out.append(ConvShape("s_i8_zp7", 1, 9, 9, 64, 16, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=7, seed=43))
@@ -272,11 +272,11 @@ def _tile_cases():
 def test_every_tile(tile, dtype, algo):
     """Every tile of the tensor-core kernels (and the vector-ALU kernel) on shapes with row, column and channel tails."""
     plan = icv.PLAN_VECTOR_ALU if tile is None else algo | hooks.tile(tile)
-    zp = 128 if dtype == "u8i8" else 0
-    for s in (ConvShape("v_a", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype=dtype, zero_point=zp, seed=51),
-              ConvShape("v_b", 1, 20, 33, 128, 200, 2, 3, SY=1, SX=2, PT=0, PL=1, PB=1, PR=1, dtype=dtype, zero_point=zp, seed=52),
+    zp = (128, 0, 201) if dtype == "u8i8" else (0, 0, 0)      # uint8: the tensor cores take any zero point
+    for s in (ConvShape("v_a", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype=dtype, zero_point=zp[0], seed=51),
+              ConvShape("v_b", 1, 20, 33, 128, 200, 2, 3, SY=1, SX=2, PT=0, PL=1, PB=1, PR=1, dtype=dtype, zero_point=zp[1], seed=52),
               ConvShape("v_c", 3, 11, 9, 32 if dtype == "bf16" else 64, 33, 3, 3, DY=2, DX=1, PT=2, PL=1, PB=2, PR=1,
-                        dtype=dtype, zero_point=zp, seed=53)):
+                        dtype=dtype, zero_point=zp[2], seed=53)):
         _say("tile", plan, icv.plan_name(icv.make_params(s, plan=plan)), s.name)
         x, w = make_tensors(s)
         try:
@@ -313,7 +313,7 @@ def _patch_shapes():
         mk("p_stride", 2, 14, 14, 32, 48, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=77),
         # int8, 256-byte rows
         mk("p_i8", 2, 15, 15, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=78),
-        mk("p_i8_s2", 2, 21, 18, 64, 64, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=79),
+        mk("p_i8_s2", 2, 21, 18, 64, 64, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=254, seed=79),
     ]
 
 
@@ -417,9 +417,9 @@ def _freg_shapes():
         mk("r_5x5", 2, 33, 35, 32, 64, 5, 5, PT=2, PL=2, PB=1, PR=1, seed=314),
         mk("r_5x5_s2", 2, 40, 26, 32, 100, 5, 5, SY=2, SX=2, PT=2, PL=2, PB=2, PR=2, seed=315),
         # uint8 x int8
-        mk("r_i8_c128", 2, 25, 27, 128, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=316, **q),
-        mk("r_i8_c256", 2, 15, 22, 256, 264, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=317, **q),
-        mk("r_i8_c128_s2", 3, 21, 18, 128, 64, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, seed=318, **q),
+        mk("r_i8_c128", 2, 25, 27, 128, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=316, dtype="u8i8", zero_point=0),
+        mk("r_i8_c256", 2, 15, 22, 256, 264, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=317, dtype="u8i8", zero_point=255),
+        mk("r_i8_c128_s2", 3, 21, 18, 128, 64, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, seed=318, dtype="u8i8", zero_point=77),
         mk("r_i8_5x5", 1, 30, 30, 64, 40, 5, 5, PT=2, PL=2, PB=2, PR=2, seed=319, **q),
         # 3x3 on 64-byte rows (appended: the fused-output test below picks shapes of this list by position)
         mk("r_c32_k128", 2, 31, 27, 32, 128, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=320),
@@ -483,7 +483,7 @@ def _random_freg_shapes(n=60):
             continue
         out.append(ConvShape(f"rr{len(out)}_{dtype}_{R}x{R}_c{C}", int(rng.integers(1, 7)), Hin, Win, C, int(rng.integers(1, 150)),
                              R, R, SY=SY, SX=SX, DY=DY, DX=DX, PT=PT, PL=PL, PB=PB, PR=PR, dtype=dtype,
-                             zero_point=128 if dtype == "u8i8" else 0, seed=2000 + len(out)))
+                             zero_point=int(rng.integers(0, 256)) if dtype == "u8i8" else 0, seed=2000 + len(out)))
     return out
 
 
@@ -602,7 +602,7 @@ def test_fp32_tensors_on_the_matrix_cores_with_fused_output(s, relu, narrow):
     ConvShape("g_exact", 2, 16, 16, 64, 64, 1, 1, seed=81),                        # M a multiple of every tile
     ConvShape("g_ragged", 3, 7, 11, 128, 72, 1, 1, seed=82),                       # M = 231: last tile mostly past M
     ConvShape("g_one_row", 1, 1, 1, 64, 200, 1, 1, seed=83),
-    ConvShape("g_i8", 2, 9, 13, 256, 96, 1, 1, dtype="u8i8", zero_point=128, seed=84),
+    ConvShape("g_i8", 2, 9, 13, 256, 96, 1, 1, dtype="u8i8", zero_point=5, seed=84),
 ], ids=lambda s: s.name)
 @pytest.mark.parametrize("pixel_stride", [0, 320])
 def test_pointwise_convolution_runs_as_gemm_on_the_input(s, pixel_stride):
@@ -638,14 +638,14 @@ PER_IMAGE_SHAPES = [
     ConvShape("b_gather", 4, 13, 17, 96, 40, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, seed=103),   # rows per element
     ConvShape("b_gather_1x1_s2", 3, 15, 15, 64, 64, 1, 1, SY=2, SX=2, seed=104),
     ConvShape("b_lowc", 3, 30, 26, 4, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=105),
-    ConvShape("b_i8", 3, 15, 15, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=106),
+    ConvShape("b_i8", 3, 15, 15, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=19, seed=106),
     ConvShape("b_tiny_images", 9, 3, 3, 64, 32, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=107),            # 9 pixels per image
     CONFIGS["cfg3c_5x5_asym"].with_(N=2),                                                           # 12321 = 48 * 256 + 33
     # the filter-in-registers kernel on the one-image buffer: images of a whole number of 32-pixel blocks
     ConvShape("b_regs", 5, 16, 24, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=108),                 # 12 blocks per image
     ConvShape("b_regs_s2", 3, 32, 32, 128, 130, 3, 3, SY=2, SX=2, PT=1, PL=1, PB=1, PR=1, seed=109),
     ConvShape("b_regs_5x5", 3, 8, 12, 32, 64, 5, 5, PT=2, PL=2, PB=2, PR=2, seed=110),              # 3 blocks per image
-    ConvShape("b_regs_i8", 3, 16, 16, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=112),
+    ConvShape("b_regs_i8", 3, 16, 16, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=200, seed=112),
     ConvShape("b_regs_one_block_images", 9, 4, 8, 64, 32, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=113),  # a pass spans 4 images
     ConvShape("b_regs_dil", 4, 16, 16, 64, 200, 3, 3, DY=2, DX=2, PT=2, PL=2, PB=2, PR=2, seed=114),
     CONFIGS["cfg3b_3x3_d2"].with_(N=3),
@@ -768,7 +768,7 @@ def test_one_zero_row_shared_by_operators_of_different_width():
     ConvShape("h_gather", 2, 13, 17, 96, 40, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, seed=122),
     ConvShape("h_lowc", 2, 30, 26, 4, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=123),
     ConvShape("h_gemm", 2, 21, 13, 256, 64, 1, 1, seed=124),
-    ConvShape("h_i8", 2, 15, 15, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=125),
+    ConvShape("h_i8", 2, 15, 15, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=64, seed=125),
 ], ids=lambda s: s.name)
 def test_graph_replays_match_eager(s):
     """The conv call is kernel launches only (no allocation, no memset, no synchronisation), so it can be captured;
@@ -807,9 +807,11 @@ FUSED_SHAPES = [
     ConvShape("f_gather", 2, 13, 17, 96, 40, 3, 3, SY=2, SX=1, PT=1, PL=1, PB=1, PR=1, seed=92),  # per-element gather
     ConvShape("f_gemm", 3, 7, 11, 128, 72, 1, 1, seed=93),                                        # GEMM on the input
     ConvShape("f_lowc", 2, 30, 26, 4, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=94),     # short rows
-    ConvShape("f_i8_patch", 2, 15, 15, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=95),
-    ConvShape("f_i8_lowc", 2, 11, 23, 8, 33, 5, 5, PT=2, PL=2, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=96),
-    ConvShape("f_i8_alu", 1, 9, 9, 64, 16, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=7, seed=97),
+    ConvShape("f_i8_patch", 2, 15, 15, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=3, seed=95),
+    ConvShape("f_i8_lowc", 2, 11, 23, 8, 33, 5, 5, PT=2, PL=2, PB=1, PR=1, dtype="u8i8", zero_point=250, seed=96),
+    ConvShape("f_i8_alu", 1, 9, 9, 5, 16, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=7, seed=97),
+    ConvShape("f_i8_zp0", 2, 13, 14, 64, 40, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=0, seed=99),   # after a ReLU
+    ConvShape("f_i8_gemm_zp", 2, 9, 13, 256, 96, 1, 1, dtype="u8i8", zero_point=17, seed=100),
 ]
 
 
@@ -825,7 +827,9 @@ def run_fused_case(s, x, w, acc, mag, relu, narrow, plan=0, in_pixel_stride=0, o
     if quant:
         bias = rng.integers(-5000, 5000, size=s.K).astype(np.int32)
         want = oracle.epilogue(acc, bias, relu)
-        scale, zp = float(np.float32(200.0 / np.abs(want).max())), 77
+        # (a scale at which both ends of the accumulators' range clamp, whichever way an input zero point skews them)
+        reach = float(min(want.max(), -want.min())) if want.min() < 0 < want.max() else float(np.abs(want).max())
+        scale, zp = float(np.float32(200.0 / reach)), 77
         bias_dev = icv.to_device(bias)
         ep = icv.make_epilogue(bias_dev, relu, icv.ICV_OUT_U8 if narrow else icv.ICV_OUT_ACC, scale, zp)
         out = torch.full(oshape, 201 if narrow else -7, dtype=torch.uint8 if narrow else torch.int32, device="cuda:0")
@@ -967,7 +971,7 @@ def test_im2col_gemm_ablation_agrees_with_indirect_path(name):
 
 
 @pytest.mark.parametrize("s", [ConvShape("abl_img", 2, 19, 23, 64, 96, 3, 3, PT=1, PL=1, PB=1, PR=1, seed=151),
-                               ConvShape("abl_img_i8", 3, 15, 15, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=128, seed=152),
+                               ConvShape("abl_img_i8", 3, 15, 15, 256, 80, 3, 3, PT=1, PL=1, PB=1, PR=1, dtype="u8i8", zero_point=41, seed=152),
                                ConvShape("abl_img_lowc", 2, 30, 26, 4, 70, 7, 7, SY=2, SX=2, PT=3, PL=3, PB=3, PR=3, seed=153)],
                          ids=lambda s: s.name)
 def test_im2col_gemm_ablation_with_the_batch_independent_plan(s):

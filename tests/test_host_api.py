@@ -176,6 +176,12 @@ def test_plans(lib):
     assert icv.plan_name(icv.make_params(CONFIGS["cfg1_tiny_f32"])).startswith("generic")
     assert icv.plan_name(icv.make_params(CONFIGS["cfg2_3x3_c64"])).startswith("mfma_bf16")
     assert icv.plan_name(icv.make_params(CONFIGS["cfg4_int8_3x3"])).startswith("mfma_i8")
+    # any uint8 zero point runs on the tensor cores; the packed filter then carries K int32 filter sums behind it
+    for zp in (0, 3, 255):
+        q = icv.make_params(CONFIGS["cfg4_int8_3x3"].with_(zero_point=zp))
+        assert icv.plan_name(q) == icv.plan_name(icv.make_params(CONFIGS["cfg4_int8_3x3"]))
+        assert icv.packed_filter_bytes(q) == 256 * 9 * 256 + 256 * 4
+    assert icv.packed_filter_bytes(icv.make_params(CONFIGS["cfg2_3x3_c64"])) == 64 * 9 * 64 * 2
     # 1x1 stride 1 without padding is a plain GEMM on the input tensor (section 3.2's advice to switch primitives)
     assert icv.plan_name(icv.make_params(CONFIGS["cfg5a_1x1"])).startswith("gemm_bf16")
     assert icv.plan_name(icv.make_params(CONFIGS["cfg5a_1x1"].with_(SX=2, SY=2))).startswith("mfma_bf16")
