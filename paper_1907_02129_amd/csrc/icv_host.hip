@@ -467,7 +467,6 @@ int icv_get_indirection_layout(const icv_conv_params* p, icv_indirection_layout*
     const int st = make_geometry(p, &g);
     if (st != ICV_OK) return st;
     if (!L) return ICV_ERR_INVALID_ARG;
-    const int64_t n = g.img_tiles * g.MR * (int64_t)g.T;
     L->tile_rows = g.MR;
     L->tiles = g.img_tiles;
     if (g.kind == PLAN_MFMA_FREG) {
